@@ -1,0 +1,103 @@
+/*
+ * CPU oracle for the Collage MCF-AdamW optimizer step (arXiv 2405.03637).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow,
+ * step-by-step restatement of what the paper's method computes, used only by
+ * the tests, the smoke check and the benchmark's cpu_baseline leg to judge the
+ * GPU library.  It shares no code with the GPU library and the GPU library
+ * never calls it.
+ *
+ * Conventions
+ *   bf16      : uint16_t holding the upper 16 bits of an IEEE binary32.
+ *   F(a o b)  : the paper's bf16 operation (Sec. 3.1): the operands are widened
+ *               exactly to fp32, ONE fp32 operation is done, and the result is
+ *               rounded once to bf16 with round-to-nearest-even.
+ *   R(f)      : fp32 -> bf16, round-to-nearest-even, NaN -> 0x7FC0.
+ *   B(x)      : fp64 -> bf16 in ONE rounding (not through float).
+ *
+ * Parity status: every function below is pinned by tests/test_oracle_*.py to
+ * values the paper prints, to exact rational arithmetic, to closed forms or to
+ * a textbook fp64 AdamW.  The bit-level choice of where roundings fall inside
+ * Algorithm 2 (one rounding per elementary operation, bf16 scalars, epsilon
+ * outside the square root) is a reading of the paper, which prints no worked
+ * AdamW step; that reading is the definition and is listed with the repository's
+ * design notes.
+ */
+#ifndef MCF_ORACLE_H
+#define MCF_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- rounding primitives (Sec. 3.1, Def. 3.1, App. A Table 7) ---- */
+uint16_t orc_R(float f);          /* fp32 -> bf16 RNE */
+uint16_t orc_B(double x);         /* fp64 -> bf16 RNE, single rounding */
+float    orc_widen(uint16_t h);   /* bf16 -> fp32, exact */
+void     orc_R_array(const float *f, uint16_t *out, uint64_t n);   /* R over an array */
+/* 1 if fp32 subnormals are neither flushed on input nor on output here. */
+int      orc_fp_env_ok(void);
+
+/* ---- one bf16 operation over arrays: out[i] = F(a[i] op b[i]) ----
+ * op: 0 add, 1 sub, 2 mul, 3 div, 4 sqrt (b ignored, may be NULL). */
+void orc_binop(int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n);
+
+/* ---- error-free transformations ---- */
+/* Thm 4.1: x = F(a+b), y = F(b - F(x-a)). */
+void orc_fast2sum(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *y, uint64_t n);
+/* Alg. 3 (TwoSum), six operations, no ordering assumption. */
+void orc_two_sum(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *y, uint64_t n);
+/* Alg. 1 (Grow): (x,y) <- Grow((x,y), a), in place. */
+void orc_grow(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n);
+/* Alg. 6 (TwoProdFMA): x = F(a*b), e = F(fma(a,b,-x)). */
+void orc_two_prod_fma(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *e, uint64_t n);
+/* Alg. 8 (Mul): (x,e) = (a1,a2)*(b1,b2), all arrays of length n. */
+void orc_mul_expansion(const uint16_t *a1, const uint16_t *a2, const uint16_t *b1, const uint16_t *b2,
+                       uint16_t *x, uint16_t *e, uint64_t n);
+
+/* ---- AdamW scalars (Alg. 2 line 1, Table 2, App. D "Scalar and Bias Correction") ---- */
+typedef struct { double lr, beta1, beta2, eps, weight_decay; } orc_hyper;
+typedef struct {
+  uint16_t b1;   /* B(beta1)            */
+  uint16_t c1;   /* B(1-beta1)          */
+  uint16_t b2;   /* B(beta2)   (first component of the beta2 expansion) */
+  uint16_t b2l;  /* B(beta2 - b2)  (second component; used by plus only) */
+  uint16_t c2;   /* B(1-beta2)          */
+  uint16_t bc1;  /* B(1-beta1^t)        */
+  uint16_t bc2;  /* B(1-beta2^t)        */
+  uint16_t e;    /* B(eps)              */
+  uint16_t lam;  /* B(weight_decay)     */
+  uint16_t na;   /* B(-lr)              */
+} orc_scalars;
+void orc_scalars_derive(const orc_hyper *h, uint64_t t, orc_scalars *out);
+
+/* ---- the step (Alg. 2 lines 8-13) ----
+ * variant 0 = Collage-light (option B), 1 = Collage-plus (option C; dv required).
+ * All state is updated in place.  delta_out, if not NULL, receives the bf16
+ * update Delta-theta of line 12 for every element.  nthreads >= 1 splits the
+ * elements evenly over that many host threads (elements are independent). */
+void orc_adamw_step(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t *v, uint16_t *dv,
+                    const uint16_t *grad, uint64_t n, int variant, const orc_hyper *h, uint64_t t,
+                    uint16_t *delta_out, int nthreads);
+
+/* ---- option D: bf16 theta/grad, fp32 m, v and master weights (Sec. 2.1, Table 1) ---- */
+void orc_fp32mw_step(uint16_t *theta, float *master, float *m, float *v, const uint16_t *grad,
+                     uint64_t n, const orc_hyper *h, uint64_t t, int nthreads);
+
+/* ---- effective descent quality (Def. 3.3, Eq. 2-3), fp64 ----
+ * delta      : intended update Delta-theta (bf16)
+ * th0,dth0   : parameter expansion before the step (dth0 may be NULL = 0)
+ * th1,dth1   : parameter expansion after the step  (dth1 may be NULL = 0)
+ * Adds this slice's contributions to s1 (sum delta*effective) and s2 (sum
+ * delta^2); orc_edq_finish turns the totals into EDQ = s1/sqrt(s2) (0 if s2=0). */
+void   orc_edq_accumulate(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0,
+                          const uint16_t *th1, const uint16_t *dth1, uint64_t n,
+                          double *s1, double *s2);
+double orc_edq_finish(double s1, double s2);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,227 @@
+"""ctypes binding of the CPU oracle (mcf_oracle.cpp).
+
+TEST INFRASTRUCTURE, NOT THE PRODUCT: only tests/, the smoke check and the
+benchmark's cpu_baseline leg may import this module.  The GPU library never
+does, and this module never imports the GPU package.
+
+bf16 arrays are numpy uint16 arrays (the upper half of an fp32 bit pattern).
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mcf_oracle.cpp")
+_LIB = os.path.join(_HERE, "libmcf_oracle.so")
+
+ADD, SUB, MUL, DIV, SQRT = 0, 1, 2, 3, 4
+LIGHT, PLUS = 0, 1
+
+
+def build(force=False):
+    """Compile the oracle with g++; one IEEE fp32 operation per written operation."""
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= max(
+            os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_HERE, "mcf_oracle.h"))):
+        return _LIB
+    cmd = ["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+           "-pthread", "-o", _LIB, _SRC]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class Hyper(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+                ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double)]
+
+
+class Scalars(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_uint16) for k in
+                ("b1", "c1", "b2", "b2l", "c2", "bc1", "bc2", "e", "lam", "na")]
+
+
+_u16p = ctypes.POINTER(ctypes.c_uint16)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_f64p = ctypes.POINTER(ctypes.c_double)
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    lib = ctypes.CDLL(build())
+    lib.orc_R.restype = ctypes.c_uint16
+    lib.orc_R.argtypes = [ctypes.c_float]
+    lib.orc_B.restype = ctypes.c_uint16
+    lib.orc_B.argtypes = [ctypes.c_double]
+    lib.orc_widen.restype = ctypes.c_float
+    lib.orc_widen.argtypes = [ctypes.c_uint16]
+    lib.orc_fp_env_ok.restype = ctypes.c_int
+    lib.orc_R_array.argtypes = [_f32p, _u16p, ctypes.c_uint64]
+    lib.orc_binop.argtypes = [ctypes.c_int, _u16p, _u16p, _u16p, ctypes.c_uint64]
+    for name in ("orc_fast2sum", "orc_two_sum", "orc_two_prod_fma"):
+        getattr(lib, name).argtypes = [_u16p, _u16p, _u16p, _u16p, ctypes.c_uint64]
+    lib.orc_grow.argtypes = [_u16p, _u16p, _u16p, ctypes.c_uint64]
+    lib.orc_mul_expansion.argtypes = [_u16p] * 6 + [ctypes.c_uint64]
+    lib.orc_scalars_derive.argtypes = [ctypes.POINTER(Hyper), ctypes.c_uint64, ctypes.POINTER(Scalars)]
+    lib.orc_adamw_step.argtypes = [_u16p] * 6 + [ctypes.c_uint64, ctypes.c_int, ctypes.POINTER(Hyper),
+                                                ctypes.c_uint64, _u16p, ctypes.c_int]
+    lib.orc_fp32mw_step.argtypes = [_u16p, _f32p, _f32p, _f32p, _u16p, ctypes.c_uint64,
+                                    ctypes.POINTER(Hyper), ctypes.c_uint64, ctypes.c_int]
+    lib.orc_edq_accumulate.argtypes = [_u16p] * 5 + [ctypes.c_uint64, _f64p, _f64p]
+    lib.orc_edq_finish.restype = ctypes.c_double
+    lib.orc_edq_finish.argtypes = [ctypes.c_double, ctypes.c_double]
+    _lib = lib
+    return lib
+
+
+def _u16(a, writable=False):
+    if a is None:
+        return None
+    assert isinstance(a, np.ndarray) and a.dtype == np.uint16 and a.flags["C_CONTIGUOUS"], "need contiguous uint16"
+    if writable:
+        assert a.flags["WRITEABLE"]
+    return a.ctypes.data_as(_u16p)
+
+
+def _f32(a):
+    assert isinstance(a, np.ndarray) and a.dtype == np.float32 and a.flags["C_CONTIGUOUS"] and a.flags["WRITEABLE"]
+    return a.ctypes.data_as(_f32p)
+
+
+def default_threads():
+    return max(1, len(os.sched_getaffinity(0)))
+
+
+# ---- scalar helpers -------------------------------------------------------
+def R(f):
+    """fp32 -> bf16 bits (RNE)."""
+    return int(_load().orc_R(float(np.float32(f))))
+
+
+def R_array(f):
+    """fp32 array -> bf16 bits (RNE)."""
+    f = np.ascontiguousarray(f, dtype=np.float32)
+    out = np.empty(f.shape, np.uint16)
+    _load().orc_R_array(f.ctypes.data_as(_f32p), _u16(out), f.size)
+    return out
+
+
+def B(x):
+    """fp64 -> bf16 bits in one rounding."""
+    return int(_load().orc_B(float(x)))
+
+
+def widen(h):
+    return float(_load().orc_widen(int(h)))
+
+
+def fp_env_ok():
+    return bool(_load().orc_fp_env_ok())
+
+
+# ---- array operations -----------------------------------------------------
+def binop(op, a, b=None):
+    a = np.ascontiguousarray(a, dtype=np.uint16)
+    if b is None:
+        b = a
+    b = np.ascontiguousarray(b, dtype=np.uint16)
+    assert a.shape == b.shape
+    out = np.empty_like(a)
+    _load().orc_binop(op, _u16(a), _u16(b), _u16(out), a.size)
+    return out
+
+
+def _pair_op(name, a, b):
+    a = np.ascontiguousarray(a, dtype=np.uint16)
+    b = np.ascontiguousarray(b, dtype=np.uint16)
+    assert a.shape == b.shape
+    x = np.empty_like(a)
+    y = np.empty_like(a)
+    getattr(_load(), name)(_u16(a), _u16(b), _u16(x), _u16(y), a.size)
+    return x, y
+
+
+def fast2sum(a, b):
+    return _pair_op("orc_fast2sum", a, b)
+
+
+def two_sum(a, b):
+    return _pair_op("orc_two_sum", a, b)
+
+
+def two_prod_fma(a, b):
+    return _pair_op("orc_two_prod_fma", a, b)
+
+
+def grow(x, y, a):
+    """Returns new (x, y); inputs are not modified."""
+    x = np.array(x, dtype=np.uint16, copy=True)
+    y = np.array(y, dtype=np.uint16, copy=True)
+    a = np.ascontiguousarray(a, dtype=np.uint16)
+    assert x.shape == y.shape == a.shape
+    _load().orc_grow(_u16(x), _u16(y), _u16(a), x.size)
+    return x, y
+
+
+def mul_expansion(a1, a2, b1, b2):
+    arrs = [np.ascontiguousarray(t, dtype=np.uint16) for t in (a1, a2, b1, b2)]
+    x = np.empty_like(arrs[0])
+    e = np.empty_like(arrs[0])
+    _load().orc_mul_expansion(*[_u16(t) for t in arrs], _u16(x), _u16(e), x.size)
+    return x, e
+
+
+def scalars(lr, beta1, beta2, eps, weight_decay, t):
+    h = Hyper(lr, beta1, beta2, eps, weight_decay)
+    s = Scalars()
+    _load().orc_scalars_derive(ctypes.byref(h), int(t), ctypes.byref(s))
+    return {k: getattr(s, k) for k, _ in Scalars._fields_}
+
+
+def adamw_step(theta, dtheta, m, v, dv, grad, variant, hyper, t, delta_out=None, nthreads=None):
+    """In-place Collage step over uint16 arrays.  hyper = (lr, beta1, beta2, eps, weight_decay)."""
+    n = theta.size
+    for arr in (dtheta, m, v, grad):
+        assert arr.size == n
+    if variant == PLUS:
+        assert dv is not None and dv.size == n
+    if delta_out is not None:
+        assert delta_out.size == n
+    h = Hyper(*hyper)
+    _load().orc_adamw_step(_u16(theta, True), _u16(dtheta, True), _u16(m, True), _u16(v, True),
+                           _u16(dv, True) if variant == PLUS else None, _u16(grad), n, int(variant),
+                           ctypes.byref(h), int(t), _u16(delta_out, True),
+                           int(nthreads or default_threads()))
+
+
+def fp32mw_step(theta, master, m, v, grad, hyper, t, nthreads=None):
+    n = theta.size
+    assert master.size == n and m.size == n and v.size == n and grad.size == n
+    h = Hyper(*hyper)
+    _load().orc_fp32mw_step(_u16(theta, True), _f32(master), _f32(m), _f32(v), _u16(grad), n,
+                            ctypes.byref(h), int(t), int(nthreads or default_threads()))
+
+
+class EdqAccumulator:
+    """Sums the two EDQ totals over any number of slices, then finishes."""
+
+    def __init__(self):
+        self.s1 = ctypes.c_double(0.0)
+        self.s2 = ctypes.c_double(0.0)
+
+    def add(self, delta, th0, dth0, th1, dth1):
+        n = delta.size
+        _load().orc_edq_accumulate(_u16(delta), _u16(th0), _u16(dth0), _u16(th1), _u16(dth1), n,
+                                   ctypes.byref(self.s1), ctypes.byref(self.s2))
+
+    def value(self):
+        return float(_load().orc_edq_finish(self.s1.value, self.s2.value))
+
+
+def edq(delta, th0, dth0, th1, dth1):
+    acc = EdqAccumulator()
+    acc.add(delta, th0, dth0, th1, dth1)
+    return acc.value()

@@ -1,0 +1,187 @@
+"""Seeded synthetic parameter sets and gradients, shaped like the paper's models.
+
+This module holds shapes and random-number plumbing only: none of the method's
+arithmetic lives here, so both the GPU library's callers and the CPU oracle's
+tests may draw their inputs from it.  Values are drawn in fp32 by torch's
+seeded generators on the requested device and cast to bf16 by torch
+(round-to-nearest-even); a CPU draw and a GPU draw with the same key are
+different streams, so a test draws once and copies.
+
+Shapes: GPT and OpenLLaMA layer counts and hidden sizes follow the paper's
+model table (App. E, Table 11); hyper-parameters follow Sec. 5 and App. E.2
+(beta1 0.9, beta2 0.95 or 0.999, weight decay 0.1).
+"""
+import torch
+
+# ---- hyper-parameters per workload: (lr, beta1, beta2, eps, weight_decay) ----
+HYPER_LIGHT = (3e-4, 0.9, 0.95, 1e-8, 0.1)
+HYPER_PLUS_1P3B = (1e-4, 0.9, 0.999, 1e-8, 0.1)
+HYPER_STRESS = (2.0 ** -20, 0.9, 0.999, 1e-8, 0.1)
+
+
+def gpt_shapes(n_layer, d, ffn, vocab, n_pos):
+    """GPT-2 style list: embeddings, per-layer {ln1, qkv, proj, ln2, fc, fc2} with biases, final ln."""
+    out = [("wte", vocab * d), ("wpe", n_pos * d)]
+    for l in range(n_layer):
+        p = f"h{l}."
+        out += [(p + "ln1.w", d), (p + "ln1.b", d),
+                (p + "qkv.w", d * 3 * d), (p + "qkv.b", 3 * d),
+                (p + "proj.w", d * d), (p + "proj.b", d),
+                (p + "ln2.w", d), (p + "ln2.b", d),
+                (p + "fc.w", d * ffn), (p + "fc.b", ffn),
+                (p + "fc2.w", ffn * d), (p + "fc2.b", d)]
+    out += [("ln_f.w", d), ("ln_f.b", d)]
+    return out
+
+
+def llama_shapes(n_layer, d, ffn, vocab):
+    """LLaMA style list: untied embedding and head, RMSNorm vectors, SwiGLU MLP, no biases."""
+    out = [("tok_emb", vocab * d)]
+    for l in range(n_layer):
+        p = f"l{l}."
+        out += [(p + "attn_norm", d), (p + "wq", d * d), (p + "wk", d * d), (p + "wv", d * d),
+                (p + "wo", d * d), (p + "ffn_norm", d), (p + "w_gate", d * ffn), (p + "w_up", d * ffn),
+                (p + "w_down", ffn * d)]
+    out += [("final_norm", d), ("lm_head", vocab * d)]
+    return out
+
+
+def _mix(*key):
+    """64-bit mix of an integer key tuple (splitmix-style), used only to derive generator seeds."""
+    x = 0x9E3779B97F4A7C15
+    for k in key:
+        x = (x ^ (int(k) & 0xFFFFFFFFFFFFFFFF)) & 0xFFFFFFFFFFFFFFFF
+        x = (x * 0xBF58476D1CE4E5B9) & 0xFFFFFFFFFFFFFFFF
+        x ^= x >> 31
+        x = (x * 0x94D049BB133111EB) & 0xFFFFFFFFFFFFFFFF
+        x ^= x >> 29
+    return x & 0x7FFFFFFFFFFFFFFF
+
+
+def _gen(device, *key):
+    g = torch.Generator(device=device)
+    g.manual_seed(_mix(*key))
+    return g
+
+
+def normal_bf16(n, std, key, device="cpu", mean=0.0, out=None):
+    """n draws of N(mean, std^2) in fp32, cast to bf16.  key = tuple of ints."""
+    g = _gen(device, *key)
+    x = torch.empty(n, dtype=torch.float32, device=device)
+    x.normal_(mean=float(mean), std=float(std), generator=g)
+    if out is None:
+        return x.to(torch.bfloat16)
+    out.copy_(x)           # copy_ casts with round-to-nearest-even
+    return out
+
+
+def uniform_f64(n, key):
+    """n uniforms in [0,1) on the CPU in fp64 (for per-tensor scales and lengths)."""
+    g = _gen("cpu", *key)
+    return torch.rand(n, dtype=torch.float64, generator=g)
+
+
+def stress_shapes(seed=0, total=64 * 1024 * 1024, n_tiny=4096, n_large=64):
+    """Precision-stress set: n_tiny tensors of 1..256 elements, interleaved among n_large
+    large tensors that share the remainder.  Returns [(name, numel)]."""
+    u = uniform_f64(n_tiny, (seed, 5, 1))
+    tiny = [1 + int(x * 256) for x in u.tolist()]
+    rest = total - sum(tiny)
+    base = rest // n_large
+    large = [base] * n_large
+    large[-1] += rest - base * n_large
+    out = []
+    per = n_tiny // n_large
+    ti = 0
+    for k in range(n_large):
+        out.append((f"big{k}", large[k]))
+        for _ in range(per):
+            out.append((f"tiny{ti}", tiny[ti]))
+            ti += 1
+    while ti < n_tiny:
+        out.append((f"tiny{ti}", tiny[ti]))
+        ti += 1
+    return out
+
+
+WORKLOADS = {
+    # name: (shape list builder, variant, hyper)
+    "flat_1m": (lambda: [("flat", 1 << 20)], "light", HYPER_LIGHT),
+    "gpt2_125m": (lambda: gpt_shapes(12, 768, 3072, 50257, 1024), "light", HYPER_LIGHT),
+    "gpt_1p3b": (lambda: gpt_shapes(24, 2048, 8192, 50304, 2048), "plus", HYPER_PLUS_1P3B),
+    "llama_7b": (lambda: llama_shapes(32, 4096, 11008, 32000), "light", HYPER_LIGHT),
+    "stress_64m": (lambda: stress_shapes(), "plus", HYPER_STRESS),
+}
+
+
+def shapes(name):
+    return WORKLOADS[name][0]()
+
+
+def total_params(shape_list):
+    return sum(n for _, n in shape_list)
+
+
+def grad_sigmas(name, shape_list, seed=0):
+    """Per-tensor gradient standard deviation."""
+    if name == "gpt_1p3b":
+        u = uniform_f64(len(shape_list), (seed, 3, 2))
+        return [10.0 ** (-5.0 + 3.0 * x) for x in u.tolist()]       # log-uniform in [1e-5, 1e-2]
+    return [1e-3] * len(shape_list)
+
+
+def layout(shape_list, misalign_tiny=False):
+    """Element offsets of each tensor inside one flat arena.
+
+    Large tensors start on 16-byte (8-element) boundaries.  With misalign_tiny,
+    tensors of at most 256 elements are packed back to back at whatever 2-byte
+    offset they land on, which exercises the unaligned head/tail handling."""
+    offs = []
+    cur = 0
+    for _, n in shape_list:
+        if not (misalign_tiny and n <= 256):
+            cur = (cur + 7) // 8 * 8
+        offs.append(cur)
+        cur += n
+    return offs, (cur + 7) // 8 * 8
+
+
+def init_theta(name, shape_list, offs, arena, seed=0):
+    """Fill arena (bf16, flat) with the initial parameters of the workload."""
+    dev = arena.device
+    if name == "stress_64m":
+        k = len(shape_list)
+        scale = [10.0 ** (-3.0 + 4.0 * x) for x in uniform_f64(k, (seed, 5, 3)).tolist()]
+        for i, ((_, n), o) in enumerate(zip(shape_list, offs)):
+            g = _gen(dev, seed, 5, 4, i)
+            u = torch.rand(n, dtype=torch.float32, device=dev, generator=g)
+            sgn = torch.where(torch.rand(n, dtype=torch.float32, device=dev, generator=g) < 0.5, -1.0, 1.0)
+            arena[o:o + n].copy_(sgn * scale[i] * (1.0 + 0.5 * u))
+        return
+    for i, ((_, n), o) in enumerate(zip(shape_list, offs)):
+        normal_bf16(n, 0.02, (seed, 0, i), device=dev, out=arena[o:o + n])
+
+
+def fill_grads(name, shape_list, offs, arena, step, seed=0, sigmas=None):
+    """Fill arena (bf16, flat) with the gradients of optimizer step `step` (1-based)."""
+    dev = arena.device
+    if sigmas is None:
+        sigmas = grad_sigmas(name, shape_list, seed)
+    for i, ((_, n), o) in enumerate(zip(shape_list, offs)):
+        mean = 0.0
+        if name == "stress_64m":
+            # steady drift: mean = sigma/2 with a per-tensor sign
+            mean = 0.5 * sigmas[i] * (1.0 if (_mix(seed, 5, 6, i) & 1) else -1.0)
+        normal_bf16(n, sigmas[i], (seed, 1, step, i), device=dev, mean=mean, out=arena[o:o + n])
+
+
+def expected_totals():
+    """Parameter totals the shape lists must reproduce."""
+    return {"flat_1m": 1 << 20, "gpt2_125m": 124_439_808, "gpt_1p3b": 1_315_819_520,
+            "llama_7b": 6_738_415_616, "stress_64m": 64 * 1024 * 1024}
+
+
+def bytes_per_param(kind):
+    """Algorithmic HBM bytes moved per parameter per step (state read + written, Table 1 turned into traffic)."""
+    return {"light": 18, "plus": 22, "fp32mw": 28}[kind]
+
