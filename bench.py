@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the Collage optimizer step on one MI355X.
+
+A step is one pass of the whole path (scalar preparation on the host, then the fused kernel:
+moments, bias correction, update, Grow of the parameter expansion) over every parameter of a
+LLaMA-7B-shaped set (291 tensors, 6,738,415,616 bf16 parameters), Collage-light, all state
+resident in HBM before the timed region.  Prints one JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama_7b] [--no-extras]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor peak
+
+# HBM traffic per parameter per step measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
+# what the same counters read for a plain copy of known size; see profiles/.  None = not measured yet.
+MEASURED_TRAFFIC_BYTES_PER_PARAM = {"light": None, "plus": None, "fp32mw": None}
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def time_steps(fn, steps, warmup):
+    """fn(t) enqueues one step on torch's current stream (the stream the library launches on)."""
+    import torch
+    for t in range(1, warmup + 1):
+        fn(t)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for t in range(warmup + 1, warmup + steps + 1):
+        fn(t)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, ev0.elapsed_time(ev1) / 1e3
+
+
+def build_light_or_plus(name, variant, dev):
+    import torch
+    from paper_2405_03637_amd import binding as mcf
+    from paper_2405_03637_amd import workloads as W
+    shapes = W.shapes(name)
+    offs, total = W.layout(shapes, misalign_tiny=(name == "stress_64m"))
+    z = lambda: torch.zeros(total, dtype=torch.bfloat16, device=dev)
+    st = {"theta": z(), "dtheta": z(), "m": z(), "v": z(), "grad": z()}
+    if variant == "plus":
+        st["dv"] = z()
+    W.init_theta(name, shapes, offs, st["theta"])
+    drift = W.stress_drift(shapes, offs, total, dev) if name == "stress_64m" else None
+    W.fill_grads(name, shapes, offs, st["grad"], 1, drift=drift)
+    tensors = [(st["theta"][o:o + n], st["dtheta"][o:o + n], st["m"][o:o + n], st["v"][o:o + n],
+                st["dv"][o:o + n] if variant == "plus" else None, st["grad"][o:o + n]) for (_, n), o in zip(shapes, offs)]
+    plan = mcf.Plan(tensors, mcf.PLUS if variant == "plus" else mcf.LIGHT)
+    return st, plan, W.total_params(shapes), len(shapes)
+
+
+def cpu_baseline(name, variant, hyper, sample=32 * 1024 * 1024, min_seconds=1.5):
+    """The oracle as it stands, on the host cores, over the first `sample` parameters of the workload."""
+    import numpy as np
+    import torch
+    from oracle import oracle as orc
+    from paper_2405_03637_amd import workloads as W
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import helpers as H
+    n = min(sample, W.total_params(W.shapes(name)))
+    theta = H.torch_to_u16(W.normal_bf16(n, 0.02, (0, 0, 0)))
+    z = lambda: np.zeros(n, np.uint16)
+    dth, m, v, dv = z(), z(), z(), (z() if variant == "plus" else None)
+    threads = orc.default_threads()
+    grads = [H.torch_to_u16(W.normal_bf16(n, 1e-3, (0, 1, t))) for t in (1, 2)]
+    orc.adamw_step(theta, dth, m, v, dv, grads[0], 1 if variant == "plus" else 0, hyper, 1, nthreads=threads)   # warm-up
+    steps, t0 = 0, time.perf_counter()
+    while steps < 2 or time.perf_counter() - t0 < min_seconds:
+        orc.adamw_step(theta, dth, m, v, dv, grads[steps & 1], 1 if variant == "plus" else 0, hyper, steps + 2, nthreads=threads)
+        steps += 1
+    el = time.perf_counter() - t0
+    return {"value": n * steps / el, "unit": "params/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {n} parameters of {name}, {steps} {variant} steps, {el:.2f} s wall on {threads} threads"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama_7b")
+    ap.add_argument("--variant", default=None, help="light or plus (default: the workload's own)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the plus / fp32-master / copy legs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the step is element-wise and shards with no "
+                 "communication); run with --gpus 1")
+
+    import torch
+    from paper_2405_03637_amd import binding as mcf
+    from paper_2405_03637_amd import workloads as W
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    mcf.lib()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    name = args.workload
+    variant = args.variant or W.WORKLOADS[name][1]
+    hyper = W.WORKLOADS[name][2]
+
+    log(f"bench: building {name} ({variant})")
+    st, plan, n_params, n_tensors = build_light_or_plus(name, variant, dev)
+    wall, gpu_s = time_steps(lambda t: plan.step(hyper, t), args.steps, args.warmup)
+    bpp = W.bytes_per_param(variant)
+    kern_s = gpu_s / args.steps
+    achieved = bpp * n_params / kern_s / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES_PER_PARAM.get(variant)
+    result = {
+        "metric": "MCF-AdamW params updated/sec and % of HBM roofline (GB/s) at 7B, 1 GPU",
+        "value": n_params * args.steps / wall,
+        "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic: theta~N(0,0.02), grad~N(0,1e-3) drawn on the GPU before the timed region; zero-initialised m, v, dtheta",
+        "config": {"workload": f"{name} Collage-{variant}: {n_tensors} tensors, {n_params} bf16 params, one launch per step",
+                   "params": n_params, "tensors": n_tensors, "variant": variant, "bytes_per_param": bpp},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": (traffic * n_params) if traffic else None,
+                     "kernel_ms": kern_s * 1e3, "algorithmic_bytes": bpp * n_params},
+    }
+    plan.destroy()
+
+    extras = {}
+    if not args.no_extras:
+        try:
+            # plain copy of one arena as the achievable streaming ceiling (reads n*2, writes n*2 bytes)
+            src, dst = st["theta"], st["grad"]
+            _, s = time_steps(lambda t: dst.copy_(src), 10, 2)
+            extras["copy_GBps"] = 4 * src.numel() * 10 / s / 1e9
+            del src, dst
+            other = "plus" if variant == "light" else "light"
+            st = None
+            torch.cuda.empty_cache()
+            st2, plan2, _, _ = build_light_or_plus(name, other, dev)
+            h2 = W.HYPER_PLUS_1P3B if other == "plus" else W.HYPER_LIGHT
+            _, s = time_steps(lambda t: plan2.step(h2, t), args.steps, args.warmup)
+            extras[f"{other}_GBps"] = W.bytes_per_param(other) * n_params * args.steps / s / 1e9
+            extras[f"{other}_ms"] = s / args.steps * 1e3
+            plan2.destroy()
+            # option D on the same shapes
+            shapes = W.shapes(name)
+            offs, total = W.layout(shapes, misalign_tiny=(name == "stress_64m"))
+            th, g = st2["theta"], st2["grad"]
+            st2 = None
+            torch.cuda.empty_cache()
+            master = th.float()
+            m32, v32 = torch.zeros_like(master), torch.zeros_like(master)
+            plan3 = mcf.Fp32MwPlan([(th[o:o + n], master[o:o + n], m32[o:o + n], v32[o:o + n], g[o:o + n])
+                                    for (_, n), o in zip(shapes, offs)])
+            _, s = time_steps(lambda t: plan3.step(W.HYPER_LIGHT, t), args.steps, args.warmup)
+            extras["fp32mw_GBps"] = W.bytes_per_param("fp32mw") * n_params * args.steps / s / 1e9
+            extras["fp32mw_ms"] = s / args.steps * 1e3
+            plan3.destroy()
+            del master, m32, v32, th, g
+        except Exception as e:       # the headline number above stands on its own
+            extras["error"] = repr(e)
+    st = None
+    torch.cuda.empty_cache()
+    if extras:
+        result["extras"] = extras
+        if "copy_GBps" in extras:
+            result["roofline"]["frac_of_copy"] = achieved / extras["copy_GBps"]
+
+    if not args.no_cpu:
+        log("bench: timing the CPU oracle")
+        result["cpu_baseline"] = cpu_baseline(name, variant, hyper)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,138 @@
+/*
+ * mcf.h - C ABI of the MI355X (gfx950) implementation of the Collage optimizer
+ * step (arXiv 2405.03637): AdamW with the weights and, optionally, Adam's
+ * second moment kept as two-component bf16 expansions (value, error).
+ *
+ * Number format and the single operation
+ *   bf16 is passed as uint16_t: the upper 16 bits of an IEEE binary32,
+ *   little endian.  Every arithmetic step is the paper's bf16 operation
+ *   F(a o b) (Sec. 3.1): operands widened exactly to fp32, one fp32 operation,
+ *   one round-to-nearest-even to bf16.  Subnormals are kept, infinities and
+ *   NaN follow IEEE 754; every NaN result is stored as 0x7FC0.
+ *
+ * Conventions for every entry point
+ *   - Returns MCF_OK (0) or a negative mcf_status.  No exceptions, no errno,
+ *     no logging.  Arguments are validated before the first HIP call, so the
+ *     argument errors below are reported even on a machine without a GPU.
+ *   - "device" pointers address HIP device memory of the current device and are
+ *     OWNED BY THE CALLER: the library never allocates, frees or keeps tensor
+ *     memory.  "host" pointers are ordinary process memory, read during the
+ *     call only.
+ *   - bf16 buffers need 2-byte alignment, fp32 buffers 4-byte, double buffers
+ *     8-byte (else MCF_ERR_ALIGN).  Any 2-byte alignment is accepted; 128-bit
+ *     accesses are used when all buffers of one tensor share the same offset
+ *     modulo 16 bytes, element-wise accesses otherwise.
+ *   - Updates are in place.  Buffers of different roles or tensors must not
+ *     overlap (not checked; the result is undefined if they do).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it and the call returns without waiting.
+ *   - The library owns only plan objects (a host struct, one device table and
+ *     one device buffer of reduction partials) between create and destroy.
+ *   - Calls on one plan must not overlap in time; distinct plans are independent.
+ */
+#ifndef MCF_H
+#define MCF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MCF_OK = 0,
+  MCF_ERR_NULL = -1,     /* a required pointer is NULL */
+  MCF_ERR_SIZE = -2,     /* a size is out of range (tensor longer than 2^35 elements, table too large) */
+  MCF_ERR_ALIGN = -3,    /* a pointer is not aligned to its element size */
+  MCF_ERR_VARIANT = -4,  /* variant is neither MCF_LIGHT nor MCF_PLUS, or an operation code is unknown */
+  MCF_ERR_STEP = -5,     /* step < 1 (the bias correction 1 - beta^0 would be zero) */
+  MCF_ERR_HYPER = -6,    /* a hyper-parameter is not finite, or beta not in [0,1), or lr/eps/weight_decay < 0 */
+  MCF_ERR_HIP = -7       /* a HIP runtime call failed (no device, out of memory, launch failure) */
+} mcf_status;
+
+/* Text for a status code; never NULL. */
+const char *mcf_status_string(int status);
+
+/* Alg. 2 line 1: learning rate alpha, beta1, beta2, epsilon, weight decay lambda.
+ * The library derives the bf16 scalars itself, in fp64, each cast once
+ * (App. D "Scalar and Bias Correction"): beta1, 1-beta1, beta2 (plus: its
+ * two-component expansion, Table 2), 1-beta2, 1-beta1^t, 1-beta2^t, eps,
+ * lambda, -alpha. */
+typedef struct { double lr, beta1, beta2, eps, weight_decay; } mcf_hyper;
+
+/* Sec. 4.2: light = expansion for the parameters only (option B, 10 bytes of state
+ * per parameter with the gradient); plus = also for the second moment (option C). */
+typedef enum { MCF_LIGHT = 0, MCF_PLUS = 1 } mcf_variant;
+
+/* One parameter tensor: flat, contiguous, n elements per buffer, all device memory.
+ * theta, dtheta: the parameter expansion (Alg. 2 lines 2-3); m, v: moments;
+ * dv: second component of v (MCF_PLUS only, ignored and may be NULL for MCF_LIGHT);
+ * grad: this step's gradient, read only. */
+typedef struct {
+  uint16_t *theta, *dtheta, *m, *v, *dv;
+  const uint16_t *grad;
+  uint64_t n;
+} mcf_tensor;
+
+typedef struct mcf_plan mcf_plan;
+
+/* Build the launch table for a list of tensors so that one kernel launch steps all of
+ * them, however many and however small.  `tensors` is a host array of `count` entries,
+ * copied; the device buffers it names must stay valid while the plan is used.  Tensors
+ * with n == 0 are allowed and skipped; count == 0 gives a plan whose step does nothing.
+ * Allocates device memory for the table (MCF_ERR_HIP if that fails). */
+int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, int variant);
+int mcf_plan_destroy(mcf_plan *plan);      /* NULL is accepted */
+/* Number of parameters the plan covers (0 for NULL). */
+uint64_t mcf_plan_params(const mcf_plan *plan);
+
+/* One optimizer step, Alg. 2 lines 8-13, over every tensor of the plan: one launch.
+ * step = t >= 1.  edq_dev: NULL, or a device pointer to 3 doubles that receive, in
+ * stream order, {EDQ, S1, S2} for this step over all parameters of the plan, where
+ * S1 = sum delta*effective, S2 = sum delta^2, EDQ = S1/sqrt(S2) (0 if S2 = 0)
+ * (Def. 3.3, Eq. 2-3, with the effective update taken on the value theta+dtheta). */
+int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *stream, double *edq_dev);
+
+/* The same step over a single flat tensor, no plan, no allocation.  n == 0 is a no-op. */
+int mcf_adamw_step_flat(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t *v, uint16_t *dv,
+                        const uint16_t *grad, uint64_t n, int variant, const mcf_hyper *hyper,
+                        uint64_t step, void *stream);
+
+/* ---- primitives (element-wise over n elements, device buffers) ---- */
+/* Thm 4.1 (Fast2Sum): x = F(a+b), y = F(b - F(x-a)); exact when |a| >= |b|. */
+int mcf_fast2sum(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *y, uint64_t n, void *stream);
+/* Alg. 3 (TwoSum): the same expansion in six operations, no ordering needed. */
+int mcf_two_sum(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *y, uint64_t n, void *stream);
+/* Alg. 1 (Grow): (x,y) <- Grow((x,y), a), in place. */
+int mcf_grow(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n, void *stream);
+/* Sec. 3.1: out = F(a op b) with op 0 add, 1 sub, 2 mul, 3 div, 4 sqrt(a) (b unused, may be NULL). */
+int mcf_bf16_op(int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n, void *stream);
+/* The rounding inside F: out = bf16(in), round-to-nearest-even, in = fp32 device buffer. */
+int mcf_round_f32(const float *in, uint16_t *out, uint64_t n, void *stream);
+
+/* Def. 3.3 as a stand-alone reduction: delta = intended update, (th0,dth0) the parameter
+ * before and (th1,dth1) after the step; dth0/dth1 may be NULL (plain bf16 parameters,
+ * Eq. 2 as printed).  edq_dev as in mcf_adamw_step.  scratch_dev: device buffer of at
+ * least mcf_edq_scratch_bytes(n) bytes, 8-byte aligned, used for reduction partials. */
+uint64_t mcf_edq_scratch_bytes(uint64_t n);
+int mcf_edq(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
+            const uint16_t *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev);
+
+/* ---- option D, the mixed-precision baseline the paper compares against (Sec. 2.1, Table 1):
+ * bf16 parameter and gradient, fp32 moments and fp32 master weight; plain fp32 AdamW with the
+ * same formula as Alg. 2 lines 8-12, master += delta, theta = bf16(master). ---- */
+typedef struct {
+  uint16_t *theta;          /* written only */
+  float *master, *m, *v;
+  const uint16_t *grad;
+  uint64_t n;
+} mcf_fp32mw_tensor;
+typedef struct mcf_fp32mw_plan mcf_fp32mw_plan;
+int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tensors, uint32_t count);
+int mcf_fp32mw_plan_destroy(mcf_fp32mw_plan *plan);
+int mcf_fp32mw_step(mcf_fp32mw_plan *plan, const mcf_hyper *hyper, uint64_t step, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

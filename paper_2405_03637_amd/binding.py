@@ -1,0 +1,221 @@
+"""Thin ctypes binding of libmcf_adamw.so: argument marshalling only.
+
+Every step of the optimizer path runs in the library's HIP kernels; torch is used by callers
+for device memory and streams.  Tensors are passed as torch tensors (bf16 viewed through
+their data_ptr) or as raw integer device addresses.  There is no CPU fallback: if the
+library cannot be loaded, importing symbols from it raises.
+"""
+import ctypes
+import os
+
+from . import build as _build
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+MCF_OK = 0
+MCF_ERR_NULL, MCF_ERR_SIZE, MCF_ERR_ALIGN, MCF_ERR_VARIANT, MCF_ERR_STEP, MCF_ERR_HYPER, MCF_ERR_HIP = \
+    -1, -2, -3, -4, -5, -6, -7
+LIGHT, PLUS = 0, 1
+OP_ADD, OP_SUB, OP_MUL, OP_DIV, OP_SQRT = 0, 1, 2, 3, 4
+
+
+class McfError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status} ({status_string(status)})")
+
+
+class Hyper(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+                ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double)]
+
+
+class Tensor(ctypes.Structure):
+    _fields_ = [("theta", ctypes.c_void_p), ("dtheta", ctypes.c_void_p), ("m", ctypes.c_void_p),
+                ("v", ctypes.c_void_p), ("dv", ctypes.c_void_p), ("grad", ctypes.c_void_p),
+                ("n", ctypes.c_uint64)]
+
+
+class Fp32Tensor(ctypes.Structure):
+    _fields_ = [("theta", ctypes.c_void_p), ("master", ctypes.c_void_p), ("m", ctypes.c_void_p),
+                ("v", ctypes.c_void_p), ("grad", ctypes.c_void_p), ("n", ctypes.c_uint64)]
+
+
+_lib = None
+_vp, _u64, _int = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int
+
+
+def lib():
+    """The loaded library.  Loads what is built; builds only if nothing is."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.LIB
+    if not os.path.exists(path):
+        _build.build()
+    L = ctypes.CDLL(path)
+    L.mcf_status_string.restype = ctypes.c_char_p
+    L.mcf_status_string.argtypes = [_int]
+    L.mcf_plan_create.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(Tensor), ctypes.c_uint32, _int]
+    L.mcf_plan_destroy.argtypes = [_vp]
+    L.mcf_plan_params.restype = _u64
+    L.mcf_plan_params.argtypes = [_vp]
+    L.mcf_adamw_step.argtypes = [_vp, ctypes.POINTER(Hyper), _u64, _vp, _vp]
+    L.mcf_adamw_step_flat.argtypes = [_vp] * 6 + [_u64, _int, ctypes.POINTER(Hyper), _u64, _vp]
+    L.mcf_fast2sum.argtypes = [_vp] * 4 + [_u64, _vp]
+    L.mcf_two_sum.argtypes = [_vp] * 4 + [_u64, _vp]
+    L.mcf_grow.argtypes = [_vp] * 3 + [_u64, _vp]
+    L.mcf_bf16_op.argtypes = [_int] + [_vp] * 3 + [_u64, _vp]
+    L.mcf_round_f32.argtypes = [_vp, _vp, _u64, _vp]
+    L.mcf_edq_scratch_bytes.restype = _u64
+    L.mcf_edq_scratch_bytes.argtypes = [_u64]
+    L.mcf_edq.argtypes = [_vp] * 5 + [_u64, _vp, _vp, _vp]
+    L.mcf_fp32mw_plan_create.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(Fp32Tensor), ctypes.c_uint32]
+    L.mcf_fp32mw_plan_destroy.argtypes = [_vp]
+    L.mcf_fp32mw_step.argtypes = [_vp, ctypes.POINTER(Hyper), _u64, _vp]
+    _lib = L
+    return L
+
+
+def status_string(status):
+    return lib().mcf_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != MCF_OK:
+        raise McfError(status, where)
+
+
+def _ptr(t):
+    """Device address of a torch tensor, an int address, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_contiguous(), "buffers must be contiguous"
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _hyper(h):
+    return h if isinstance(h, Hyper) else Hyper(*h)
+
+
+class Plan:
+    """mcf_plan over a list of (theta, dtheta, m, v, dv_or_None, grad) tensor tuples."""
+
+    def __init__(self, tensors, variant):
+        arr = (Tensor * max(1, len(tensors)))()
+        self._keep = tensors
+        for i, (th, dth, m, v, dv, g) in enumerate(tensors):
+            n = th.numel() if hasattr(th, "numel") else None
+            if n is None:
+                raise TypeError("pass torch tensors; use raw_plan for raw addresses")
+            arr[i] = Tensor(_ptr(th), _ptr(dth), _ptr(m), _ptr(v), _ptr(dv), _ptr(g), n)
+        self._h = _vp()
+        _check(lib().mcf_plan_create(ctypes.byref(self._h), arr, len(tensors), int(variant)), "mcf_plan_create")
+        self.variant = int(variant)
+
+    @classmethod
+    def raw(cls, entries, variant):
+        """entries: list of (theta, dtheta, m, v, dv, grad, n) integer device addresses."""
+        self = cls.__new__(cls)
+        arr = (Tensor * max(1, len(entries)))()
+        for i, e in enumerate(entries):
+            arr[i] = Tensor(*e)
+        self._keep = None
+        self._h = _vp()
+        _check(lib().mcf_plan_create(ctypes.byref(self._h), arr, len(entries), int(variant)), "mcf_plan_create")
+        self.variant = int(variant)
+        return self
+
+    @property
+    def params(self):
+        return int(lib().mcf_plan_params(self._h))
+
+    def step(self, hyper, t, stream=None, edq_out=None):
+        """One optimizer step.  edq_out: optional float64 device tensor of 3 elements {EDQ, S1, S2}."""
+        h = _hyper(hyper)
+        _check(lib().mcf_adamw_step(self._h, ctypes.byref(h), int(t), _stream(stream), _ptr(edq_out)), "mcf_adamw_step")
+
+    def destroy(self):
+        if self._h:
+            _check(lib().mcf_plan_destroy(self._h), "mcf_plan_destroy")
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+class Fp32MwPlan:
+    """mcf_fp32mw_plan over (theta_bf16, master_f32, m_f32, v_f32, grad_bf16) tuples."""
+
+    def __init__(self, tensors):
+        arr = (Fp32Tensor * max(1, len(tensors)))()
+        self._keep = tensors
+        for i, (th, w, m, v, g) in enumerate(tensors):
+            arr[i] = Fp32Tensor(_ptr(th), _ptr(w), _ptr(m), _ptr(v), _ptr(g), th.numel())
+        self._h = _vp()
+        _check(lib().mcf_fp32mw_plan_create(ctypes.byref(self._h), arr, len(tensors)), "mcf_fp32mw_plan_create")
+
+    def step(self, hyper, t, stream=None):
+        h = _hyper(hyper)
+        _check(lib().mcf_fp32mw_step(self._h, ctypes.byref(h), int(t), _stream(stream)), "mcf_fp32mw_step")
+
+    def destroy(self):
+        if self._h:
+            _check(lib().mcf_fp32mw_plan_destroy(self._h), "mcf_fp32mw_plan_destroy")
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def adamw_step_flat(theta, dtheta, m, v, dv, grad, variant, hyper, t, stream=None, n=None):
+    h = _hyper(hyper)
+    n = theta.numel() if n is None else n
+    _check(lib().mcf_adamw_step_flat(_ptr(theta), _ptr(dtheta), _ptr(m), _ptr(v), _ptr(dv), _ptr(grad), n,
+                                     int(variant), ctypes.byref(h), int(t), _stream(stream)), "mcf_adamw_step_flat")
+
+
+def fast2sum(a, b, x, y, stream=None):
+    _check(lib().mcf_fast2sum(_ptr(a), _ptr(b), _ptr(x), _ptr(y), a.numel(), _stream(stream)), "mcf_fast2sum")
+
+
+def two_sum(a, b, x, y, stream=None):
+    _check(lib().mcf_two_sum(_ptr(a), _ptr(b), _ptr(x), _ptr(y), a.numel(), _stream(stream)), "mcf_two_sum")
+
+
+def grow(x, y, a, stream=None):
+    _check(lib().mcf_grow(_ptr(x), _ptr(y), _ptr(a), x.numel(), _stream(stream)), "mcf_grow")
+
+
+def bf16_op(op, a, b, out, stream=None):
+    _check(lib().mcf_bf16_op(int(op), _ptr(a), _ptr(b), _ptr(out), a.numel(), _stream(stream)), "mcf_bf16_op")
+
+
+def round_f32(src, out, stream=None):
+    _check(lib().mcf_round_f32(_ptr(src), _ptr(out), src.numel(), _stream(stream)), "mcf_round_f32")
+
+
+def edq_scratch_bytes(n):
+    return int(lib().mcf_edq_scratch_bytes(int(n)))
+
+
+def edq(delta, th0, dth0, th1, dth1, scratch, out, stream=None):
+    _check(lib().mcf_edq(_ptr(delta), _ptr(th0), _ptr(dth0), _ptr(th1), _ptr(dth1), delta.numel(),
+                         _ptr(scratch), _stream(stream), _ptr(out)), "mcf_edq")

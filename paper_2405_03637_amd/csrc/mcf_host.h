@@ -1,0 +1,91 @@
+// Host-side preparation for the Collage step: argument checks and the bf16 scalars of
+// Alg. 2 (computed in fp64 and cast once, App. D "Scalar and Bias Correction").
+#pragma once
+#include <stdint.h>
+
+#include <cmath>
+#include <cstring>
+
+#include "../../include/mcf.h"
+#include "mcf_math.h"
+
+namespace mcfh {
+
+// fp64 -> bf16 with a single round-to-nearest-even, working on the double's fields:
+// the 53-bit significand is shifted right so that 8 bits (fewer in the subnormal range)
+// remain, and the discarded bits decide the rounding.
+inline uint16_t f64_to_bf16(double x) {
+  uint64_t u;
+  std::memcpy(&u, &x, 8);
+  const uint16_t sign = (uint16_t)((u >> 48) & 0x8000u);
+  const int ef = (int)((u >> 52) & 0x7ff);
+  const uint64_t frac = u & ((1ull << 52) - 1);
+  if (ef == 0x7ff) return frac ? (uint16_t)0x7fc0 : (uint16_t)(sign | 0x7f80);
+  if (ef == 0) return sign;                        // below 2^-1022: rounds to zero
+  const int e = ef - 1023;                         // value = sig * 2^(e-52)
+  const uint64_t sig = frac | (1ull << 52);
+  int shift = 45;                                  // normal: keep 8 of the 53 bits
+  if (e < -126) shift += -126 - e;                 // subnormal: coarser fixed spacing 2^-133
+  if (shift > 54) return sign;                     // less than a quarter of the least subnormal
+  const uint64_t q = sig >> shift;
+  const uint64_t rem = sig & ((1ull << shift) - 1);
+  const uint64_t half = 1ull << (shift - 1);
+  const uint64_t up = (rem > half || (rem == half && (q & 1))) ? 1 : 0;
+  uint32_t bits;
+  if (e >= -126) {
+    bits = (uint32_t)((e + 127) << 7) + (uint32_t)(q + up - 128);   // a carry moves into the exponent
+    if (bits >= 0x7f80u) bits = 0x7f80u;
+  } else {
+    bits = (uint32_t)(q + up);
+  }
+  return (uint16_t)(sign | bits);
+}
+
+inline float bf16_to_f32(uint16_t h) {
+  uint32_t u = (uint32_t)h << 16;
+  float f;
+  std::memcpy(&f, &u, 4);
+  return f;
+}
+
+inline int check_hyper(const mcf_hyper *h, uint64_t step) {
+  if (!h) return MCF_ERR_NULL;
+  if (step < 1) return MCF_ERR_STEP;
+  const double v[5] = {h->lr, h->beta1, h->beta2, h->eps, h->weight_decay};
+  for (double x : v)
+    if (!std::isfinite(x)) return MCF_ERR_HYPER;
+  if (h->lr < 0 || h->eps < 0 || h->weight_decay < 0) return MCF_ERR_HYPER;
+  if (h->beta1 < 0 || h->beta1 >= 1 || h->beta2 < 0 || h->beta2 >= 1) return MCF_ERR_HYPER;
+  return MCF_OK;
+}
+
+// Returns the scalars and whether the Fast arithmetic mode may be used with them: the two
+// bias corrections must be normal numbers in (0, 1] (so that dividing by them cannot shrink
+// a normal number into the subnormal range) and epsilon zero or a normal number of sane
+// size (so that sqrt(v)+eps is zero, or normal with a normal reciprocal).
+inline bool derive_scalars(const mcf_hyper &h, uint64_t step, mcfd::StepScalars &s) {
+  const double t = (double)step;
+  const uint16_t b1 = f64_to_bf16(h.beta1), c1 = f64_to_bf16(1.0 - h.beta1);
+  const uint16_t b2 = f64_to_bf16(h.beta2), c2 = f64_to_bf16(1.0 - h.beta2);
+  const uint16_t b2l = f64_to_bf16(h.beta2 - (double)bf16_to_f32(b2));
+  const uint16_t bc1 = f64_to_bf16(1.0 - std::pow(h.beta1, t));
+  const uint16_t bc2 = f64_to_bf16(1.0 - std::pow(h.beta2, t));
+  const uint16_t e = f64_to_bf16(h.eps), lam = f64_to_bf16(h.weight_decay), na = f64_to_bf16(-h.lr);
+  s.b1 = bf16_to_f32(b1);
+  s.c1 = bf16_to_f32(c1);
+  s.b2 = bf16_to_f32(b2);
+  s.b2l = bf16_to_f32(b2l);
+  s.c2 = bf16_to_f32(c2);
+  s.bc1 = bf16_to_f32(bc1);
+  s.bc2 = bf16_to_f32(bc2);
+  s.rbc1 = (float)(1.0 / (double)s.bc1);
+  s.rbc2 = (float)(1.0 / (double)s.bc2);
+  s.e = bf16_to_f32(e);
+  s.lam = bf16_to_f32(lam);
+  s.na = bf16_to_f32(na);
+  auto sane_bc = [](float x) { return x >= 0x1p-60f && x <= 1.0f; };
+  const bool eps_ok = (s.e == 0.0f) || (s.e >= 0x1p-100f && s.e <= 0x1p60f);
+  return sane_bc(s.bc1) && sane_bc(s.bc2) && eps_ok;
+}
+
+}  // namespace mcfh

@@ -1,0 +1,945 @@
+// Kernels, launch tables and the C ABI of the Collage optimizer step for gfx950.
+//
+// Work decomposition.  A tensor is cut into SLOTS of 8 consecutive bf16 (16 bytes per
+// stream) counted from the 16-byte boundary at or below its first element, so that a
+// slot is one 128-bit access per stream whatever the tensor's own alignment; the slots
+// that straddle the ends of the tensor are handled element by element.  A CHUNK is
+// kBlock*kUnroll consecutive slots of one tensor, done by one workgroup; lane l takes
+// slots l, l+kBlock, ... so each wave's access is one contiguous 1 KiB run per stream.
+// The chunk table {tensor, first slot} and the tensor descriptors live in device memory
+// and are wave-uniform, so they arrive through scalar loads into SGPRs; any number of
+// tensors of any size is one launch.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <cstdlib>
+#include <new>
+#include <type_traits>
+#include <vector>
+
+#include "../../include/mcf.h"
+#include "mcf_host.h"
+#include "mcf_math.h"
+
+namespace {
+
+using mcfd::ElemIO;
+using mcfd::P2;
+using mcfd::StepScalars;
+
+constexpr int kBlock = 256;
+#ifndef MCF_UNROLL
+#define MCF_UNROLL 2
+#endif
+constexpr int kUnroll = MCF_UNROLL;
+constexpr uint32_t kSlotsPerChunk = kBlock * kUnroll;
+constexpr uint64_t kMaxTensorElems = 1ull << 35;
+constexpr int kMaxStreams = 6;
+
+// Streams of the Collage step, in descriptor order.
+enum { S_TH = 0, S_DTH = 1, S_M = 2, S_V = 3, S_G = 4, S_DV = 5 };
+
+struct TensorDesc {
+  uint64_t p[kMaxStreams];   // element pointers (bf16), as integers
+  uint64_t n;                // elements
+  uint32_t phase;            // elements between the 16-byte boundary below p[0] and p[0]: 0..7
+  uint32_t scalar_only;      // 1: streams are not mutually aligned, every slot goes element by element
+};
+static_assert(sizeof(TensorDesc) == 64, "descriptor is one 64-byte scalar load");
+
+struct Chunk {
+  uint32_t tensor;
+  uint32_t slot0;
+};
+
+struct Slot {       // where one lane's 8 elements sit
+  uint64_t c0;      // aligned coordinate of the first element (multiple of 8)
+  bool any, full;
+};
+
+__device__ __forceinline__ Slot classify(const TensorDesc &d, uint64_t slot) {
+  Slot s;
+  s.c0 = slot * 8;
+  const uint64_t lo = d.phase, hi = d.phase + d.n;
+  s.any = (s.c0 + 8 > lo) && (s.c0 < hi);
+  s.full = (s.c0 >= lo) && (s.c0 + 8 <= hi) && !d.scalar_only;
+  return s;
+}
+
+// 128-bit access to elements [e0, e0+8) of the bf16 buffer at p.
+// The pointers are device-memory addresses, so the accesses are typed as global (address
+// space 1): global_load/global_store instead of the generic flat instructions.
+#define MCF_GLOBAL __attribute__((address_space(1)))
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+template <class T> __device__ __forceinline__ MCF_GLOBAL T *gptr(uint64_t p) { return (MCF_GLOBAL T *)p; }
+
+__device__ __forceinline__ void load_vec(uint64_t p, uint64_t e0, uint32_t (&w)[4]) {
+  const u32x4_t q = *gptr<const u32x4_t>(p + 2 * e0);
+  w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+}
+__device__ __forceinline__ void store_vec(uint64_t p, uint64_t e0, const uint32_t (&w)[4]) {
+  const u32x4_t q = {w[0], w[1], w[2], w[3]};
+  *gptr<u32x4_t>(p + 2 * e0) = q;
+}
+
+// Load the slot of stream `p` as 4 dwords (two bf16 each); elements outside the tensor read as 0.
+__device__ __forceinline__ void load_slot(uint64_t p, const TensorDesc &d, const Slot &s, uint32_t (&w)[4]) {
+  const MCF_GLOBAL uint16_t *base = gptr<const uint16_t>(p);
+  if (s.full) {
+    load_vec(p, s.c0 - d.phase, w);
+  } else {
+    const uint64_t lo = d.phase, hi = d.phase + d.n;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint64_t c = s.c0 + 2 * k;
+      uint32_t a = 0, b = 0;
+      if (c >= lo && c < hi) a = base[c - lo];
+      if (c + 1 >= lo && c + 1 < hi) b = base[c + 1 - lo];
+      w[k] = a | (b << 16);
+    }
+  }
+}
+
+__device__ __forceinline__ void store_slot(uint64_t p, const TensorDesc &d, const Slot &s, const uint32_t (&w)[4]) {
+  MCF_GLOBAL uint16_t *base = gptr<uint16_t>(p);
+  if (s.full) {
+    store_vec(p, s.c0 - d.phase, w);
+  } else {
+    const uint64_t lo = d.phase, hi = d.phase + d.n;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint64_t c = s.c0 + 2 * k;
+      if (c >= lo && c < hi) base[c - lo] = (uint16_t)(w[k] & 0xffffu);
+      if (c + 1 >= lo && c + 1 < hi) base[c + 1 - lo] = (uint16_t)(w[k] >> 16);
+    }
+  }
+}
+
+// ---------------------------------------------------------------- wave and block sums
+// Sum over the 64 lanes with DPP row operations, fixed order, result in every lane of
+// each 16-lane row; the four row sums are then read with v_readlane and added in order.
+template <int CTRL>
+__device__ __forceinline__ double dpp_add(double x) {
+  const int xl = __double2loint(x), xh = __double2hiint(x);
+  const int yl = __builtin_amdgcn_update_dpp(0, xl, CTRL, 0xF, 0xF, false);
+  const int yh = __builtin_amdgcn_update_dpp(0, xh, CTRL, 0xF, 0xF, false);
+  return x + __hiloint2double(yh, yl);
+}
+
+__device__ __forceinline__ double wave_sum(double x) {
+  x = dpp_add<0xB1>(x);    // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);    // quad_perm [2,3,0,1]
+  x = dpp_add<0x141>(x);   // row_half_mirror
+  x = dpp_add<0x140>(x);   // row_mirror
+  const int xl = __double2loint(x), xh = __double2hiint(x);
+  double r0 = __hiloint2double(__builtin_amdgcn_readlane(xh, 0), __builtin_amdgcn_readlane(xl, 0));
+  double r1 = __hiloint2double(__builtin_amdgcn_readlane(xh, 16), __builtin_amdgcn_readlane(xl, 16));
+  double r2 = __hiloint2double(__builtin_amdgcn_readlane(xh, 32), __builtin_amdgcn_readlane(xl, 32));
+  double r3 = __hiloint2double(__builtin_amdgcn_readlane(xh, 48), __builtin_amdgcn_readlane(xl, 48));
+  return ((r0 + r1) + r2) + r3;
+}
+
+// Sum of (a, b) over the workgroup; valid in thread 0.  All threads must call.
+__device__ __forceinline__ void block_sum2(double &a, double &b) {
+  __shared__ double sh[2 * (kBlock / 64)];
+  a = wave_sum(a);
+  b = wave_sum(b);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { sh[2 * wave] = a; sh[2 * wave + 1] = b; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double sa = sh[0], sb = sh[1];
+    for (int w = 1; w < kBlock / 64; ++w) { sa += sh[2 * w]; sb += sh[2 * w + 1]; }
+    a = sa; b = sb;
+  }
+}
+
+// Compile-time loop: f(integral_constant<int, J>) for J = LO .. HI-1.
+template <int LO, int HI, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+  if constexpr (LO < HI) {
+    f(std::integral_constant<int, LO>{});
+    static_for<LO + 1, HI>(f);
+  }
+}
+
+// ---------------------------------------------------------------- the step kernel
+// Hot path: one full slot, 8 elements of every stream held as 4 dwords each.  Returns true
+// when the Fast arithmetic mode asks for the slot to be recomputed in Exact mode.
+template <class M, int VARIANT, bool EDQ>
+__device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], uint32_t (&out)[kMaxStreams][4],
+                                         const StepScalars &sc, float &s1, float &s2) {
+  bool redo = false;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    ElemIO io;
+    io.th = mcfd::widen2(in[S_TH][k]);
+    io.dth = mcfd::widen2(in[S_DTH][k]);
+    io.m = mcfd::widen2(in[S_M][k]);
+    io.v = mcfd::widen2(in[S_V][k]);
+    io.g = mcfd::widen2(in[S_G][k]);
+    if (VARIANT == 1) io.dv = mcfd::widen2(in[S_DV][k]); else io.dv = {0.f, 0.f};
+    const P2 th0 = io.th, dth0 = io.dth;
+    P2 delta;
+    mcfd::adamw_pair<M, VARIANT>(io, sc, delta, redo);
+    out[S_TH][k] = mcfd::pack2(io.th);
+    out[S_DTH][k] = mcfd::pack2(io.dth);
+    out[S_M][k] = mcfd::pack2(io.m);
+    out[S_V][k] = mcfd::pack2(io.v);
+    if (VARIANT == 1) out[S_DV][k] = mcfd::pack2(io.dv);
+    if (EDQ) {
+      // effective update of the value theta+dtheta (Eq. 2); differences of neighbouring bf16 are exact
+      const float e_lo = (io.th.lo - th0.lo) + (io.dth.lo - dth0.lo);
+      const float e_hi = (io.th.hi - th0.hi) + (io.dth.hi - dth0.hi);
+      s1 = __builtin_fmaf(delta.lo, e_lo, s1);
+      s1 = __builtin_fmaf(delta.hi, e_hi, s1);
+      s2 = __builtin_fmaf(delta.lo, delta.lo, s2);
+      s2 = __builtin_fmaf(delta.hi, delta.hi, s2);
+    }
+  }
+  return redo;
+}
+
+// Cold path: one slot element by element in Exact mode, as a rolled loop so that it costs code
+// size once.  Serves the slots that straddle a tensor's ends, tensors whose buffers are not
+// mutually aligned, and slots the hot path asked to redo (their inputs are still in memory:
+// nothing of the slot has been stored yet).
+template <int VARIANT, bool EDQ>
+__device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, const StepScalars &sc, float &s1, float &s2) {
+  const uint64_t lo = d.phase, hi = d.phase + d.n;
+  MCF_GLOBAL uint16_t *th = gptr<uint16_t>(d.p[S_TH]);
+  MCF_GLOBAL uint16_t *dth = gptr<uint16_t>(d.p[S_DTH]);
+  MCF_GLOBAL uint16_t *m = gptr<uint16_t>(d.p[S_M]);
+  MCF_GLOBAL uint16_t *v = gptr<uint16_t>(d.p[S_V]);
+  MCF_GLOBAL uint16_t *dv = gptr<uint16_t>(d.p[S_DV]);
+  const MCF_GLOBAL uint16_t *g = gptr<const uint16_t>(d.p[S_G]);
+#pragma unroll 1
+  for (int k = 0; k < 8; ++k) {
+    const uint64_t c = c0 + k;
+    if (c < lo || c >= hi) continue;
+    const uint64_t e = c - lo;
+    ElemIO io;                       // the element rides in the low half of a pair
+    io.th = mcfd::widen2(th[e]);
+    io.dth = mcfd::widen2(dth[e]);
+    io.m = mcfd::widen2(m[e]);
+    io.v = mcfd::widen2(v[e]);
+    io.g = mcfd::widen2(g[e]);
+    if (VARIANT == 1) io.dv = mcfd::widen2(dv[e]); else io.dv = {0.f, 0.f};
+    const float th0 = io.th.lo, dth0 = io.dth.lo;
+    P2 delta;
+    bool unused = false;
+    mcfd::adamw_pair<mcfd::Exact, VARIANT>(io, sc, delta, unused);
+    th[e] = (uint16_t)(mcfd::fbits(io.th.lo) >> 16);
+    dth[e] = (uint16_t)(mcfd::fbits(io.dth.lo) >> 16);
+    m[e] = (uint16_t)(mcfd::fbits(io.m.lo) >> 16);
+    v[e] = (uint16_t)(mcfd::fbits(io.v.lo) >> 16);
+    if (VARIANT == 1) dv[e] = (uint16_t)(mcfd::fbits(io.dv.lo) >> 16);
+    if (EDQ) {
+      const float eff = (io.th.lo - th0) + (io.dth.lo - dth0);
+      s1 = __builtin_fmaf(delta.lo, eff, s1);
+      s2 = __builtin_fmaf(delta.lo, delta.lo, s2);
+    }
+  }
+}
+
+template <int VARIANT, bool FAST, bool EDQ, bool TABLE>
+__global__ void __launch_bounds__(kBlock)
+adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, TensorDesc flat,
+             StepScalars sc, double *__restrict__ partials) {
+  constexpr int NS = VARIANT == 1 ? 6 : 5;
+  using Mode = typename std::conditional<FAST, mcfd::Fast, mcfd::Exact>::type;
+  TensorDesc d;
+  uint64_t slot0;
+  if (TABLE) {
+    const Chunk c = chunks[blockIdx.x];
+    d = descs[c.tensor];
+    slot0 = c.slot0;
+  } else {
+    d = flat;
+    slot0 = (uint64_t)blockIdx.x * kSlotsPerChunk;
+  }
+
+  // Phase 1 issues every 128-bit load of the chunk, phase 2 computes and stores: the stores go to
+  // the buffers the loads read, so the compiler would not move a later slot's loads above them.
+  Slot slot[kUnroll];
+  uint32_t in[kUnroll][kMaxStreams][4];
+  static_for<0, kUnroll>([&](auto jc) {
+    constexpr int j = decltype(jc)::value;
+    slot[j] = classify(d, slot0 + (uint64_t)j * kBlock + threadIdx.x);
+    if (slot[j].full) {
+#pragma unroll
+      for (int s = 0; s < NS; ++s) load_vec(d.p[s], slot[j].c0 - d.phase, in[j][s]);
+    }
+  });
+
+  double acc1 = 0.0, acc2 = 0.0;
+  uint32_t cold = 0;          // bit j: slot j still has to go through the cold path
+  static_for<0, kUnroll>([&](auto jc) {
+    constexpr int j = decltype(jc)::value;
+    if (slot[j].full) {
+      uint32_t out[kMaxStreams][4];
+      float s1 = 0.f, s2 = 0.f;
+      if (hot_slot<Mode, VARIANT, EDQ>(in[j], out, sc, s1, s2)) {
+        cold |= 1u << j;
+      } else {
+        const uint64_t e0 = slot[j].c0 - d.phase;
+        store_vec(d.p[S_TH], e0, out[S_TH]);
+        store_vec(d.p[S_DTH], e0, out[S_DTH]);
+        store_vec(d.p[S_M], e0, out[S_M]);
+        store_vec(d.p[S_V], e0, out[S_V]);
+        if (VARIANT == 1) store_vec(d.p[S_DV], e0, out[S_DV]);
+        if (EDQ) { acc1 += (double)s1; acc2 += (double)s2; }
+      }
+    } else if (slot[j].any) {
+      cold |= 1u << j;
+    }
+  });
+  if (cold) {
+#pragma unroll 1
+    for (int j = 0; j < kUnroll; ++j) {
+      if (!((cold >> j) & 1u)) continue;
+      float s1 = 0.f, s2 = 0.f;
+      cold_slot<VARIANT, EDQ>(d, (slot0 + (uint64_t)j * kBlock + threadIdx.x) * 8, sc, s1, s2);
+      if (EDQ) { acc1 += (double)s1; acc2 += (double)s2; }
+    }
+  }
+  if (EDQ) {
+    block_sum2(acc1, acc2);
+    if (threadIdx.x == 0) { partials[2 * (uint64_t)blockIdx.x] = acc1; partials[2 * (uint64_t)blockIdx.x + 1] = acc2; }
+  }
+}
+
+// ---------------------------------------------------------------- EDQ reduction tail
+constexpr int kStage1Blocks = 1024;
+
+// Stage 1: block b sums partials [b*per, (b+1)*per) in a fixed order -> mid[b].
+__global__ void __launch_bounds__(kBlock)
+edq_stage1(const double *__restrict__ partials, uint64_t count, uint64_t per, double *__restrict__ mid) {
+  const uint64_t lo = (uint64_t)blockIdx.x * per;
+  uint64_t hi = lo + per;
+  if (hi > count) hi = count;
+  double a = 0.0, b = 0.0;
+  for (uint64_t i = lo + threadIdx.x; i < hi; i += kBlock) { a += partials[2 * i]; b += partials[2 * i + 1]; }
+  block_sum2(a, b);
+  if (threadIdx.x == 0) { mid[2 * blockIdx.x] = a; mid[2 * blockIdx.x + 1] = b; }
+}
+
+// Stage 2: one block sums mid[0..nmid) and writes {EDQ, S1, S2}.
+__global__ void __launch_bounds__(kBlock)
+edq_stage2(const double *__restrict__ mid, uint32_t nmid, double *__restrict__ out3) {
+  double a = 0.0, b = 0.0;
+  for (uint32_t i = threadIdx.x; i < nmid; i += kBlock) { a += mid[2 * i]; b += mid[2 * i + 1]; }
+  block_sum2(a, b);
+  if (threadIdx.x == 0) {
+    out3[0] = (b == 0.0) ? 0.0 : a / sqrt(b);
+    out3[1] = a;
+    out3[2] = b;
+  }
+}
+
+// ---------------------------------------------------------------- element-wise primitives
+enum PrimOp { P_FAST2SUM, P_TWOSUM, P_GROW, P_ADD, P_SUB, P_MUL, P_DIV, P_SQRT, P_EDQ };
+
+struct PrimArgs {
+  uint64_t p[kMaxStreams];
+  uint64_t n;
+  uint32_t phase, scalar_only;
+};
+
+template <class M, int OP>
+__device__ __forceinline__ void prim_words(const uint32_t (&in)[kMaxStreams][4], uint32_t (&out)[kMaxStreams][4],
+                                           bool &redo, float &s1, float &s2, bool has_d0, bool has_d1) {
+  using O = mcfd::Ops<M>;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    P2 a = mcfd::widen2(in[0][k]), b = mcfd::widen2(in[1][k]);
+    P2 x = {0.f, 0.f}, y = {0.f, 0.f};
+    if (OP == P_FAST2SUM) O::fast2sum(a, b, x, y);
+    if (OP == P_TWOSUM) O::two_sum(a, b, x, y);
+    if (OP == P_GROW) O::grow(a, b, mcfd::widen2(in[2][k]), x, y);          // streams: x, y, a
+    if (OP == P_ADD) x = O::add(a, b);
+    if (OP == P_SUB) x = O::sub(a, b);
+    if (OP == P_MUL) x = O::mul(a, b);
+    if (OP == P_DIV) {
+      if (M::kFast) {
+        // the reciprocal route needs |b| zero, infinite, NaN or within [2^-126, 2^126]
+        const float alo = __builtin_fabsf(b.lo), ahi = __builtin_fabsf(b.hi);
+        redo |= mcfd::is_subnormal(b.lo) | mcfd::is_subnormal(b.hi) | (alo > 0x1p126f && alo < __builtin_inff()) |
+                (ahi > 0x1p126f && ahi < __builtin_inff());
+      }
+      x = O::divg(a, b, redo);
+    }
+    if (OP == P_SQRT) {
+      if (M::kFast) redo |= mcfd::is_subnormal(a.lo) | mcfd::is_subnormal(a.hi);
+      x = O::sqrt(a, redo);
+    }
+    if (OP == P_EDQ) {
+      // streams: delta, th0, th1, dth0, dth1 ; fp32 differences of bf16 neighbours are exact
+      P2 th1 = mcfd::widen2(in[2][k]);
+      float e_lo = th1.lo - b.lo, e_hi = th1.hi - b.hi;
+      if (has_d0 | has_d1) {
+        P2 d0 = has_d0 ? mcfd::widen2(in[3][k]) : P2{0.f, 0.f};
+        P2 d1 = has_d1 ? mcfd::widen2(in[4][k]) : P2{0.f, 0.f};
+        e_lo += d1.lo - d0.lo;
+        e_hi += d1.hi - d0.hi;
+      }
+      s1 = __builtin_fmaf(a.lo, e_lo, s1);
+      s1 = __builtin_fmaf(a.hi, e_hi, s1);
+      s2 = __builtin_fmaf(a.lo, a.lo, s2);
+      s2 = __builtin_fmaf(a.hi, a.hi, s2);
+    }
+    if (M::kFast && OP != P_EDQ) redo |= mcfd::is_nan(x.lo) | mcfd::is_nan(x.hi) | mcfd::is_nan(y.lo) | mcfd::is_nan(y.hi);
+    out[0][k] = mcfd::pack2(x);
+    out[1][k] = mcfd::pack2(y);
+  }
+}
+
+// Stream layout per op (inputs first):   reads            writes
+//  FAST2SUM/TWOSUM: p0=a p1=b p2=x p3=y   0,1              out0->p2, out1->p3
+//  GROW:            p0=x p1=y p2=a        0,1,2            out0->p0, out1->p1
+//  ADD..SQRT:       p0=a p1=b p2=out      0,1 (sqrt: 0)    out0->p2
+//  EDQ:             p0=delta p1=th0 p2=th1 p3=dth0 p4=dth1  (reads only; partial sums out)
+template <int OP>
+__global__ void __launch_bounds__(kBlock) prim_kernel(PrimArgs a, uint32_t has_d0, uint32_t has_d1, double *__restrict__ partials) {
+  TensorDesc d;
+#pragma unroll
+  for (int s = 0; s < kMaxStreams; ++s) d.p[s] = a.p[s];
+  d.n = a.n; d.phase = a.phase; d.scalar_only = a.scalar_only;
+  const Slot s = classify(d, (uint64_t)blockIdx.x * kBlock + threadIdx.x);
+  double acc1 = 0.0, acc2 = 0.0;
+  if (s.any) {
+    uint32_t in[kMaxStreams][4] = {};
+    uint32_t out[kMaxStreams][4];
+    constexpr int nin = (OP == P_GROW) ? 3 : (OP == P_SQRT) ? 1 : 2;
+    if (OP == P_EDQ) {
+      load_slot(d.p[0], d, s, in[0]);
+      load_slot(d.p[1], d, s, in[1]);
+      load_slot(d.p[2], d, s, in[2]);
+      if (has_d0) load_slot(d.p[3], d, s, in[3]);
+      if (has_d1) load_slot(d.p[4], d, s, in[4]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < nin; ++k) load_slot(d.p[k], d, s, in[k]);
+    }
+    float s1 = 0.f, s2 = 0.f;
+    bool redo = false;
+    prim_words<mcfd::Fast, OP>(in, out, redo, s1, s2, has_d0, has_d1);
+    if (redo) {
+      bool unused = false;
+      s1 = 0.f; s2 = 0.f;
+      prim_words<mcfd::Exact, OP>(in, out, unused, s1, s2, has_d0, has_d1);
+    }
+    if (OP == P_FAST2SUM || OP == P_TWOSUM) { store_slot(d.p[2], d, s, out[0]); store_slot(d.p[3], d, s, out[1]); }
+    if (OP == P_GROW) { store_slot(d.p[0], d, s, out[0]); store_slot(d.p[1], d, s, out[1]); }
+    if (OP == P_ADD || OP == P_SUB || OP == P_MUL || OP == P_DIV || OP == P_SQRT) store_slot(d.p[2], d, s, out[0]);
+    acc1 = (double)s1; acc2 = (double)s2;
+  }
+  if (OP == P_EDQ) {
+    block_sum2(acc1, acc2);
+    if (threadIdx.x == 0) { partials[2 * (uint64_t)blockIdx.x] = acc1; partials[2 * (uint64_t)blockIdx.x + 1] = acc2; }
+  }
+}
+
+// fp32 -> bf16 over an array (the rounding inside F).  Two elements per lane.
+__global__ void __launch_bounds__(kBlock) round_kernel(const float *__restrict__ in, uint16_t *__restrict__ out, uint64_t n) {
+  const uint64_t i = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 2;
+  if (i >= n) return;
+  const float a = in[i];
+  const float b = (i + 1 < n) ? in[i + 1] : 0.f;
+  P2 r = mcfd::Fast::rnd({a, b});
+  if (mcfd::is_nan(a) | mcfd::is_nan(b)) r = mcfd::Exact::rnd({a, b});
+  out[i] = (uint16_t)(mcfd::fbits(r.lo) >> 16);
+  if (i + 1 < n) out[i + 1] = (uint16_t)(mcfd::fbits(r.hi) >> 16);
+}
+
+// ---------------------------------------------------------------- option D (fp32 master weights)
+struct Fp32Desc {
+  uint64_t theta, master, m, v, grad;   // pointers as integers
+  uint64_t n;
+  uint32_t phase, scalar_only;
+  uint64_t pad;
+};
+static_assert(sizeof(Fp32Desc) == 64, "descriptor is one 64-byte scalar load");
+
+struct Fp32Scalars { float b1, c1, b2, c2, bc1, bc2, e, lam, na; };
+
+__device__ __forceinline__ void fp32mw_elem(float g, float &m, float &v, float &w, const Fp32Scalars &s) {
+  const float t1 = s.b1 * m;
+  const float t2 = s.c1 * g;
+  const float m1 = t1 + t2;
+  const float g2 = g * g;
+  const float t3 = s.b2 * v;
+  const float t4 = s.c2 * g2;
+  const float v1 = t3 + t4;
+  const float mh = m1 / s.bc1;            // IEEE correctly rounded divide
+  const float vh = v1 / s.bc2;
+  const float dn = __builtin_sqrtf(vh) + s.e;
+  const float q = mh / dn;
+  const float dec = s.lam * w;
+  const float sum = q + dec;
+  const float delta = s.na * sum;
+  w = w + delta;
+  m = m1;
+  v = v1;
+}
+
+__global__ void __launch_bounds__(kBlock)
+fp32mw_kernel(const Fp32Desc *__restrict__ descs, const Chunk *__restrict__ chunks, Fp32Scalars sc) {
+  const Chunk c = chunks[blockIdx.x];
+  const Fp32Desc d = descs[c.tensor];
+  TensorDesc t;                       // reuse the slot classification
+  t.n = d.n; t.phase = d.phase; t.scalar_only = d.scalar_only;
+  MCF_GLOBAL uint16_t *theta = gptr<uint16_t>(d.theta);
+  const MCF_GLOBAL uint16_t *grad = gptr<const uint16_t>(d.grad);
+  MCF_GLOBAL float *master = gptr<float>(d.master);
+  MCF_GLOBAL float *mp = gptr<float>(d.m);
+  MCF_GLOBAL float *vp = gptr<float>(d.v);
+#pragma unroll
+  for (int j = 0; j < kUnroll; ++j) {
+    const Slot s = classify(t, (uint64_t)c.slot0 + (uint64_t)j * kBlock + threadIdx.x);
+    if (!s.any) continue;
+    if (s.full) {
+      const uint64_t e0 = s.c0 - d.phase;
+      typedef float f32x4_t __attribute__((ext_vector_type(4)));
+      uint32_t gw[4];
+      load_vec(d.grad, e0, gw);
+      const f32x4_t m0 = *(const MCF_GLOBAL f32x4_t *)(mp + e0), m1 = *(const MCF_GLOBAL f32x4_t *)(mp + e0 + 4);
+      const f32x4_t v0 = *(const MCF_GLOBAL f32x4_t *)(vp + e0), v1 = *(const MCF_GLOBAL f32x4_t *)(vp + e0 + 4);
+      const f32x4_t w0 = *(const MCF_GLOBAL f32x4_t *)(master + e0), w1 = *(const MCF_GLOBAL f32x4_t *)(master + e0 + 4);
+      float mm[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+      float vv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+      float ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+      uint32_t tw[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const P2 g = mcfd::widen2(gw[k]);
+        fp32mw_elem(g.lo, mm[2 * k], vv[2 * k], ww[2 * k], sc);
+        fp32mw_elem(g.hi, mm[2 * k + 1], vv[2 * k + 1], ww[2 * k + 1], sc);
+        tw[k] = mcfd::pack2(mcfd::Exact::rnd({ww[2 * k], ww[2 * k + 1]}));
+      }
+      *(MCF_GLOBAL f32x4_t *)(mp + e0) = f32x4_t{mm[0], mm[1], mm[2], mm[3]};
+      *(MCF_GLOBAL f32x4_t *)(mp + e0 + 4) = f32x4_t{mm[4], mm[5], mm[6], mm[7]};
+      *(MCF_GLOBAL f32x4_t *)(vp + e0) = f32x4_t{vv[0], vv[1], vv[2], vv[3]};
+      *(MCF_GLOBAL f32x4_t *)(vp + e0 + 4) = f32x4_t{vv[4], vv[5], vv[6], vv[7]};
+      *(MCF_GLOBAL f32x4_t *)(master + e0) = f32x4_t{ww[0], ww[1], ww[2], ww[3]};
+      *(MCF_GLOBAL f32x4_t *)(master + e0 + 4) = f32x4_t{ww[4], ww[5], ww[6], ww[7]};
+      store_vec(d.theta, e0, tw);
+    } else {
+      const uint64_t lo = d.phase, hi = d.phase + d.n;
+      for (int k = 0; k < 8; ++k) {
+        const uint64_t cc = s.c0 + k;
+        if (cc < lo || cc >= hi) continue;
+        const uint64_t e = cc - lo;
+        float m = mp[e], v = vp[e], w = master[e];
+        fp32mw_elem(mcfd::bitsf((uint32_t)grad[e] << 16), m, v, w, sc);
+        mp[e] = m; vp[e] = v; master[e] = w;
+        theta[e] = (uint16_t)(mcfd::fbits(mcfd::round_bits(w)) >> 16);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- host side
+#define MCF_HIP(call) do { if ((call) != hipSuccess) { (void)hipGetLastError(); return MCF_ERR_HIP; } } while (0)
+
+inline bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+// Alignment class of a set of bf16 pointers: common phase (elements above a 16-byte boundary)
+// or scalar_only when they disagree.
+inline void phase_of(const uint64_t *ptrs, int count, uint32_t &phase, uint32_t &scalar_only) {
+  phase = (uint32_t)((ptrs[0] & 15) >> 1);
+  scalar_only = 0;
+  for (int i = 1; i < count; ++i)
+    if ((ptrs[i] & 15) != (ptrs[0] & 15)) scalar_only = 1;
+  if (scalar_only) phase = 0;
+}
+
+inline uint64_t slots_of(uint64_t n, uint32_t phase) { return (n + phase + 7) / 8; }
+
+int check_tensor(const mcf_tensor &t, int variant) {
+  if (t.n == 0) return MCF_OK;
+  if (!t.theta || !t.dtheta || !t.m || !t.v || !t.grad) return MCF_ERR_NULL;
+  if (variant == MCF_PLUS && !t.dv) return MCF_ERR_NULL;
+  if (t.n > kMaxTensorElems) return MCF_ERR_SIZE;
+  if (misaligned(t.theta, 2) || misaligned(t.dtheta, 2) || misaligned(t.m, 2) || misaligned(t.v, 2) ||
+      misaligned(t.grad, 2) || (variant == MCF_PLUS && misaligned(t.dv, 2)))
+    return MCF_ERR_ALIGN;
+  return MCF_OK;
+}
+
+void fill_desc(const mcf_tensor &t, int variant, TensorDesc &d) {
+  d.p[S_TH] = (uint64_t)(uintptr_t)t.theta;
+  d.p[S_DTH] = (uint64_t)(uintptr_t)t.dtheta;
+  d.p[S_M] = (uint64_t)(uintptr_t)t.m;
+  d.p[S_V] = (uint64_t)(uintptr_t)t.v;
+  d.p[S_G] = (uint64_t)(uintptr_t)t.grad;
+  d.p[S_DV] = variant == MCF_PLUS ? (uint64_t)(uintptr_t)t.dv : d.p[S_V];
+  d.n = t.n;
+  phase_of(d.p, variant == MCF_PLUS ? 6 : 5, d.phase, d.scalar_only);
+}
+
+template <int VARIANT, bool TABLE>
+void launch_step(bool fast, bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs, const Chunk *chunks,
+                 const TensorDesc &flat, const StepScalars &sc, double *partials) {
+  const dim3 g(blocks), b(kBlock);
+  if (fast) {
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, 0, st, descs, chunks, flat, sc, partials);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, 0, st, descs, chunks, flat, sc, partials);
+  } else {
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, 0, st, descs, chunks, flat, sc, partials);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, 0, st, descs, chunks, flat, sc, partials);
+  }
+}
+
+// Reduce `count` pairs of partials to {EDQ, S1, S2}; mid holds 2*kStage1Blocks doubles.
+int launch_edq_tail(const double *partials, uint64_t count, double *mid, double *out3, hipStream_t st) {
+  uint64_t per = (count + kStage1Blocks - 1) / kStage1Blocks;
+  if (per == 0) per = 1;
+  const uint32_t nmid = (uint32_t)((count + per - 1) / per);
+  if (nmid) hipLaunchKernelGGL(edq_stage1, dim3(nmid), dim3(kBlock), 0, st, partials, count, per, mid);
+  hipLaunchKernelGGL(edq_stage2, dim3(1), dim3(kBlock), 0, st, mid, nmid, out3);
+  MCF_HIP(hipGetLastError());
+  return MCF_OK;
+}
+
+// MCF_FORCE_EXACT=1 in the environment routes every step through the Exact arithmetic mode.
+bool force_exact() {
+  static const bool v = [] { const char *e = getenv("MCF_FORCE_EXACT"); return e && e[0] == '1'; }();
+  return v;
+}
+
+}  // namespace
+
+struct mcf_plan {
+  int variant;
+  uint32_t n_tensors;
+  uint32_t n_chunks;
+  uint64_t n_params;
+  TensorDesc *d_descs;
+  Chunk *d_chunks;
+  double *d_partials;   // 2*n_chunks doubles, then 2*kStage1Blocks doubles
+};
+
+struct mcf_fp32mw_plan {
+  uint32_t n_chunks;
+  Fp32Desc *d_descs;
+  Chunk *d_chunks;
+};
+
+extern "C" {
+
+const char *mcf_status_string(int status) {
+  switch (status) {
+    case MCF_OK: return "ok";
+    case MCF_ERR_NULL: return "a required pointer is NULL";
+    case MCF_ERR_SIZE: return "a size is out of range";
+    case MCF_ERR_ALIGN: return "a pointer is not aligned to its element size";
+    case MCF_ERR_VARIANT: return "unknown variant or operation code";
+    case MCF_ERR_STEP: return "step must be at least 1";
+    case MCF_ERR_HYPER: return "hyper-parameter out of range";
+    case MCF_ERR_HIP: return "a HIP runtime call failed";
+    default: return "unknown status";
+  }
+}
+
+int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, int variant) {
+  if (!out) return MCF_ERR_NULL;
+  *out = nullptr;
+  if (count && !tensors) return MCF_ERR_NULL;
+  if (variant != MCF_LIGHT && variant != MCF_PLUS) return MCF_ERR_VARIANT;
+  for (uint32_t i = 0; i < count; ++i) {
+    const int rc = check_tensor(tensors[i], variant);
+    if (rc != MCF_OK) return rc;
+  }
+  std::vector<TensorDesc> descs;
+  std::vector<Chunk> chunks;
+  uint64_t params = 0;
+  for (uint32_t i = 0; i < count; ++i) {
+    if (tensors[i].n == 0) continue;
+    TensorDesc d;
+    fill_desc(tensors[i], variant, d);
+    const uint64_t slots = slots_of(d.n, d.phase);
+    const uint64_t nch = (slots + kSlotsPerChunk - 1) / kSlotsPerChunk;
+    if (chunks.size() + nch > 0x7fffffffull) return MCF_ERR_SIZE;
+    const uint32_t id = (uint32_t)descs.size();
+    descs.push_back(d);
+    for (uint64_t c = 0; c < nch; ++c) chunks.push_back(Chunk{id, (uint32_t)(c * kSlotsPerChunk)});
+    params += d.n;
+  }
+  mcf_plan *p = new (std::nothrow) mcf_plan();
+  if (!p) return MCF_ERR_HIP;
+  p->variant = variant;
+  p->n_tensors = (uint32_t)descs.size();
+  p->n_chunks = (uint32_t)chunks.size();
+  p->n_params = params;
+  p->d_descs = nullptr;
+  p->d_chunks = nullptr;
+  p->d_partials = nullptr;
+  if (p->n_chunks) {
+    bool ok = hipMalloc((void **)&p->d_descs, descs.size() * sizeof(TensorDesc)) == hipSuccess &&
+              hipMalloc((void **)&p->d_chunks, chunks.size() * sizeof(Chunk)) == hipSuccess &&
+              hipMalloc((void **)&p->d_partials, (2ull * p->n_chunks + 2ull * kStage1Blocks) * sizeof(double)) == hipSuccess &&
+              hipMemcpy(p->d_descs, descs.data(), descs.size() * sizeof(TensorDesc), hipMemcpyHostToDevice) == hipSuccess &&
+              hipMemcpy(p->d_chunks, chunks.data(), chunks.size() * sizeof(Chunk), hipMemcpyHostToDevice) == hipSuccess;
+    if (!ok) {
+      (void)hipGetLastError();
+      mcf_plan_destroy(p);
+      return MCF_ERR_HIP;
+    }
+  }
+  *out = p;
+  return MCF_OK;
+}
+
+int mcf_plan_destroy(mcf_plan *plan) {
+  if (!plan) return MCF_OK;
+  int rc = MCF_OK;
+  if (plan->d_descs && hipFree(plan->d_descs) != hipSuccess) rc = MCF_ERR_HIP;
+  if (plan->d_chunks && hipFree(plan->d_chunks) != hipSuccess) rc = MCF_ERR_HIP;
+  if (plan->d_partials && hipFree(plan->d_partials) != hipSuccess) rc = MCF_ERR_HIP;
+  delete plan;
+  return rc;
+}
+
+uint64_t mcf_plan_params(const mcf_plan *plan) { return plan ? plan->n_params : 0; }
+
+int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *stream, double *edq_dev) {
+  if (!plan) return MCF_ERR_NULL;
+  const int rc = mcfh::check_hyper(hyper, step);
+  if (rc != MCF_OK) return rc;
+  if (edq_dev && misaligned(edq_dev, 8)) return MCF_ERR_ALIGN;
+  StepScalars sc;
+  const bool fast = mcfh::derive_scalars(*hyper, step, sc) && !force_exact();
+  hipStream_t st = (hipStream_t)stream;
+  const TensorDesc none = {};
+  if (plan->n_chunks) {
+    if (plan->variant == MCF_PLUS)
+      launch_step<1, true>(fast, edq_dev != nullptr, plan->n_chunks, st, plan->d_descs, plan->d_chunks, none, sc, plan->d_partials);
+    else
+      launch_step<0, true>(fast, edq_dev != nullptr, plan->n_chunks, st, plan->d_descs, plan->d_chunks, none, sc, plan->d_partials);
+    MCF_HIP(hipGetLastError());
+  }
+  if (edq_dev) {
+    // with no chunks the tail sums nothing and writes zeros
+    return launch_edq_tail(plan->d_partials, plan->n_chunks, plan->d_partials + 2ull * plan->n_chunks, edq_dev, st);
+  }
+  return MCF_OK;
+}
+
+int mcf_adamw_step_flat(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t *v, uint16_t *dv,
+                        const uint16_t *grad, uint64_t n, int variant, const mcf_hyper *hyper,
+                        uint64_t step, void *stream) {
+  if (variant != MCF_LIGHT && variant != MCF_PLUS) return MCF_ERR_VARIANT;
+  const mcf_tensor t = {theta, dtheta, m, v, dv, grad, n};
+  int rc = check_tensor(t, variant);
+  if (rc != MCF_OK) return rc;
+  rc = mcfh::check_hyper(hyper, step);
+  if (rc != MCF_OK) return rc;
+  if (n == 0) return MCF_OK;
+  TensorDesc d;
+  fill_desc(t, variant, d);
+  const uint64_t nch = (slots_of(d.n, d.phase) + kSlotsPerChunk - 1) / kSlotsPerChunk;
+  StepScalars sc;
+  const bool fast = mcfh::derive_scalars(*hyper, step, sc) && !force_exact();
+  if (variant == MCF_PLUS) launch_step<1, false>(fast, false, (uint32_t)nch, (hipStream_t)stream, nullptr, nullptr, d, sc, nullptr);
+  else launch_step<0, false>(fast, false, (uint32_t)nch, (hipStream_t)stream, nullptr, nullptr, d, sc, nullptr);
+  MCF_HIP(hipGetLastError());
+  return MCF_OK;
+}
+
+static int prim_launch(int op, const void *p0, const void *p1, const void *p2, const void *p3, const void *p4,
+                       int nptr, uint64_t n, void *stream) {
+  const void *ps[5] = {p0, p1, p2, p3, p4};
+  PrimArgs a = {};
+  uint64_t al[5];
+  int na = 0;
+  for (int i = 0; i < nptr; ++i) {
+    a.p[i] = (uint64_t)(uintptr_t)ps[i];
+    if (ps[i]) {
+      if (misaligned(ps[i], 2)) return MCF_ERR_ALIGN;
+      al[na++] = a.p[i];
+    }
+  }
+  if (n > kMaxTensorElems) return MCF_ERR_SIZE;
+  a.n = n;
+  phase_of(al, na, a.phase, a.scalar_only);
+  const uint64_t slots = slots_of(n, a.phase);
+  const dim3 g((uint32_t)((slots + kBlock - 1) / kBlock)), b(kBlock);
+  hipStream_t st = (hipStream_t)stream;
+  switch (op) {
+    case P_FAST2SUM: hipLaunchKernelGGL(prim_kernel<P_FAST2SUM>, g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_TWOSUM: hipLaunchKernelGGL(prim_kernel<P_TWOSUM>, g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_GROW: hipLaunchKernelGGL(prim_kernel<P_GROW>, g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_ADD: hipLaunchKernelGGL(prim_kernel<P_ADD>, g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_SUB: hipLaunchKernelGGL(prim_kernel<P_SUB>, g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_MUL: hipLaunchKernelGGL(prim_kernel<P_MUL>, g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_DIV: hipLaunchKernelGGL(prim_kernel<P_DIV>, g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_SQRT: hipLaunchKernelGGL(prim_kernel<P_SQRT>, g, b, 0, st, a, 0u, 0u, nullptr); break;
+    default: return MCF_ERR_VARIANT;
+  }
+  MCF_HIP(hipGetLastError());
+  return MCF_OK;
+}
+
+int mcf_fast2sum(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *y, uint64_t n, void *stream) {
+  if (n == 0) return MCF_OK;
+  if (!a || !b || !x || !y) return MCF_ERR_NULL;
+  return prim_launch(P_FAST2SUM, a, b, x, y, nullptr, 4, n, stream);
+}
+
+int mcf_two_sum(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *y, uint64_t n, void *stream) {
+  if (n == 0) return MCF_OK;
+  if (!a || !b || !x || !y) return MCF_ERR_NULL;
+  return prim_launch(P_TWOSUM, a, b, x, y, nullptr, 4, n, stream);
+}
+
+int mcf_grow(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n, void *stream) {
+  if (n == 0) return MCF_OK;
+  if (!x || !y || !a) return MCF_ERR_NULL;
+  return prim_launch(P_GROW, x, y, a, nullptr, nullptr, 3, n, stream);
+}
+
+int mcf_bf16_op(int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n, void *stream) {
+  if (op < 0 || op > 4) return MCF_ERR_VARIANT;
+  if (n == 0) return MCF_OK;
+  if (!a || !out || (op != 4 && !b)) return MCF_ERR_NULL;
+  if (op == 4) b = a;
+  static const int map[5] = {P_ADD, P_SUB, P_MUL, P_DIV, P_SQRT};
+  return prim_launch(map[op], a, b, out, nullptr, nullptr, 3, n, stream);
+}
+
+int mcf_round_f32(const float *in, uint16_t *out, uint64_t n, void *stream) {
+  if (n == 0) return MCF_OK;
+  if (!in || !out) return MCF_ERR_NULL;
+  if (misaligned(in, 4) || misaligned(out, 2)) return MCF_ERR_ALIGN;
+  const uint64_t lanes = (n + 1) / 2;
+  const uint64_t blocks = (lanes + kBlock - 1) / kBlock;
+  if (blocks > 0x7fffffffull) return MCF_ERR_SIZE;
+  hipLaunchKernelGGL(round_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, in, out, n);
+  MCF_HIP(hipGetLastError());
+  return MCF_OK;
+}
+
+uint64_t mcf_edq_scratch_bytes(uint64_t n) {
+  const uint64_t blocks = (slots_of(n, 7) + kBlock - 1) / kBlock + 1;
+  return (2 * blocks + 2ull * kStage1Blocks) * sizeof(double);
+}
+
+int mcf_edq(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
+            const uint16_t *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev) {
+  if (!edq_dev) return MCF_ERR_NULL;
+  if (misaligned(edq_dev, 8)) return MCF_ERR_ALIGN;
+  if (n == 0) return launch_edq_tail(nullptr, 0, nullptr, edq_dev, (hipStream_t)stream);
+  if (!delta || !th0 || !th1 || !scratch_dev) return MCF_ERR_NULL;
+  if (misaligned(scratch_dev, 8)) return MCF_ERR_ALIGN;
+  double *partials = (double *)scratch_dev;
+  // stream order: delta, th0, th1, dth0, dth1 (absent second components are not read)
+  const void *ps[5] = {delta, th0, th1, dth0, dth1};
+  for (int i = 0; i < 5; ++i)
+    if (ps[i] && misaligned(ps[i], 2)) return MCF_ERR_ALIGN;
+  PrimArgs a = {};
+  uint64_t al[5];
+  int na = 0;
+  for (int i = 0; i < 5; ++i) {
+    a.p[i] = (uint64_t)(uintptr_t)ps[i];
+    if (ps[i]) al[na++] = a.p[i];
+  }
+  if (n > kMaxTensorElems) return MCF_ERR_SIZE;
+  a.n = n;
+  phase_of(al, na, a.phase, a.scalar_only);
+  const uint64_t blocks = (slots_of(n, a.phase) + kBlock - 1) / kBlock;
+  hipLaunchKernelGGL(prim_kernel<P_EDQ>, dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, a,
+                     dth0 ? 1u : 0u, dth1 ? 1u : 0u, partials);
+  MCF_HIP(hipGetLastError());
+  return launch_edq_tail(partials, blocks, partials + 2 * blocks, edq_dev, (hipStream_t)stream);
+}
+
+int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tensors, uint32_t count) {
+  if (!out) return MCF_ERR_NULL;
+  *out = nullptr;
+  if (count && !tensors) return MCF_ERR_NULL;
+  std::vector<Fp32Desc> descs;
+  std::vector<Chunk> chunks;
+  for (uint32_t i = 0; i < count; ++i) {
+    const mcf_fp32mw_tensor &t = tensors[i];
+    if (t.n == 0) continue;
+    if (!t.theta || !t.master || !t.m || !t.v || !t.grad) return MCF_ERR_NULL;
+    if (t.n > kMaxTensorElems) return MCF_ERR_SIZE;
+    if (misaligned(t.theta, 2) || misaligned(t.grad, 2) || misaligned(t.master, 4) || misaligned(t.m, 4) || misaligned(t.v, 4))
+      return MCF_ERR_ALIGN;
+  }
+  for (uint32_t i = 0; i < count; ++i) {
+    const mcf_fp32mw_tensor &t = tensors[i];
+    if (t.n == 0) continue;
+    Fp32Desc d = {};
+    d.theta = (uint64_t)(uintptr_t)t.theta;
+    d.master = (uint64_t)(uintptr_t)t.master;
+    d.m = (uint64_t)(uintptr_t)t.m;
+    d.v = (uint64_t)(uintptr_t)t.v;
+    d.grad = (uint64_t)(uintptr_t)t.grad;
+    d.n = t.n;
+    // 128-bit path: theta and grad share a phase, and each fp32 buffer is 16-byte aligned at the
+    // element that sits on theta's 16-byte boundary
+    const uint32_t ph = (uint32_t)((d.theta & 15) >> 1);
+    bool ok = (d.grad & 15) == (d.theta & 15);
+    const uint64_t f32s[3] = {d.master, d.m, d.v};
+    for (uint64_t f : f32s) ok = ok && (((f - 4ull * ph) & 15) == 0);
+    d.phase = ok ? ph : 0;
+    d.scalar_only = ok ? 0 : 1;
+    const uint64_t nch = (slots_of(d.n, d.phase) + kSlotsPerChunk - 1) / kSlotsPerChunk;
+    if (chunks.size() + nch > 0x7fffffffull) return MCF_ERR_SIZE;
+    const uint32_t id = (uint32_t)descs.size();
+    descs.push_back(d);
+    for (uint64_t c = 0; c < nch; ++c) chunks.push_back(Chunk{id, (uint32_t)(c * kSlotsPerChunk)});
+  }
+  mcf_fp32mw_plan *p = new (std::nothrow) mcf_fp32mw_plan();
+  if (!p) return MCF_ERR_HIP;
+  p->n_chunks = (uint32_t)chunks.size();
+  p->d_descs = nullptr;
+  p->d_chunks = nullptr;
+  if (p->n_chunks) {
+    bool ok = hipMalloc((void **)&p->d_descs, descs.size() * sizeof(Fp32Desc)) == hipSuccess &&
+              hipMalloc((void **)&p->d_chunks, chunks.size() * sizeof(Chunk)) == hipSuccess &&
+              hipMemcpy(p->d_descs, descs.data(), descs.size() * sizeof(Fp32Desc), hipMemcpyHostToDevice) == hipSuccess &&
+              hipMemcpy(p->d_chunks, chunks.data(), chunks.size() * sizeof(Chunk), hipMemcpyHostToDevice) == hipSuccess;
+    if (!ok) {
+      (void)hipGetLastError();
+      mcf_fp32mw_plan_destroy(p);
+      return MCF_ERR_HIP;
+    }
+  }
+  *out = p;
+  return MCF_OK;
+}
+
+int mcf_fp32mw_plan_destroy(mcf_fp32mw_plan *plan) {
+  if (!plan) return MCF_OK;
+  int rc = MCF_OK;
+  if (plan->d_descs && hipFree(plan->d_descs) != hipSuccess) rc = MCF_ERR_HIP;
+  if (plan->d_chunks && hipFree(plan->d_chunks) != hipSuccess) rc = MCF_ERR_HIP;
+  delete plan;
+  return rc;
+}
+
+int mcf_fp32mw_step(mcf_fp32mw_plan *plan, const mcf_hyper *hyper, uint64_t step, void *stream) {
+  if (!plan) return MCF_ERR_NULL;
+  const int rc = mcfh::check_hyper(hyper, step);
+  if (rc != MCF_OK) return rc;
+  if (!plan->n_chunks) return MCF_OK;
+  const double t = (double)step;
+  Fp32Scalars s;
+  s.b1 = (float)hyper->beta1;
+  s.c1 = (float)(1.0 - hyper->beta1);
+  s.b2 = (float)hyper->beta2;
+  s.c2 = (float)(1.0 - hyper->beta2);
+  s.bc1 = (float)(1.0 - std::pow(hyper->beta1, t));
+  s.bc2 = (float)(1.0 - std::pow(hyper->beta2, t));
+  s.e = (float)hyper->eps;
+  s.lam = (float)hyper->weight_decay;
+  s.na = (float)(-hyper->lr);
+  hipLaunchKernelGGL(fp32mw_kernel, dim3(plan->n_chunks), dim3(kBlock), 0, (hipStream_t)stream, plan->d_descs, plan->d_chunks, s);
+  MCF_HIP(hipGetLastError());
+  return MCF_OK;
+}
+
+}  // extern "C"

@@ -130,17 +130,18 @@ def grad_sigmas(name, shape_list, seed=0):
     return [1e-3] * len(shape_list)
 
 
-def layout(shape_list, misalign_tiny=False):
+def layout(shape_list, misalign_tiny=False, align=8):
     """Element offsets of each tensor inside one flat arena.
 
     Large tensors start on 16-byte (8-element) boundaries.  With misalign_tiny,
     tensors of at most 256 elements are packed back to back at whatever 2-byte
-    offset they land on, which exercises the unaligned head/tail handling."""
+    offset they land on, which exercises the unaligned head/tail handling;
+    align=1 packs every tensor that way."""
     offs = []
     cur = 0
     for _, n in shape_list:
         if not (misalign_tiny and n <= 256):
-            cur = (cur + 7) // 8 * 8
+            cur = (cur + align - 1) // align * align
         offs.append(cur)
         cur += n
     return offs, (cur + 7) // 8 * 8
@@ -162,17 +163,39 @@ def init_theta(name, shape_list, offs, arena, seed=0):
         normal_bf16(n, 0.02, (seed, 0, i), device=dev, out=arena[o:o + n])
 
 
-def fill_grads(name, shape_list, offs, arena, step, seed=0, sigmas=None):
-    """Fill arena (bf16, flat) with the gradients of optimizer step `step` (1-based)."""
-    dev = arena.device
-    if sigmas is None:
-        sigmas = grad_sigmas(name, shape_list, seed)
+def stress_drift(shape_list, offs, arena_len, device, seed=0, sigma=1e-3):
+    """Per-element gradient mean of the stress set: sigma/2 with a per-tensor sign (steady drift), fp32."""
+    drift = torch.zeros(arena_len, dtype=torch.float32, device=device)
     for i, ((_, n), o) in enumerate(zip(shape_list, offs)):
-        mean = 0.0
-        if name == "stress_64m":
-            # steady drift: mean = sigma/2 with a per-tensor sign
-            mean = 0.5 * sigmas[i] * (1.0 if (_mix(seed, 5, 6, i) & 1) else -1.0)
-        normal_bf16(n, sigmas[i], (seed, 1, step, i), device=dev, mean=mean, out=arena[o:o + n])
+        drift[o:o + n] = 0.5 * sigma * (1.0 if (_mix(seed, 5, 6, i) & 1) else -1.0)
+    return drift
+
+
+_CHUNK = 1 << 27     # elements drawn per call when filling a whole arena (bounds the fp32 temporary)
+
+
+def fill_grads(name, shape_list, offs, arena, step, seed=0, sigmas=None, drift=None):
+    """Fill arena (bf16, flat) with the gradients of optimizer step `step` (1-based).
+
+    Sets whose tensors share one sigma are drawn arena-wide (padding between tensors gets values
+    too; nobody reads them); the 1.3B set, with a sigma per tensor, is drawn tensor by tensor.
+    `drift` (stress set only) is the per-element mean from stress_drift()."""
+    dev = arena.device
+    if name == "gpt_1p3b":
+        if sigmas is None:
+            sigmas = grad_sigmas(name, shape_list, seed)
+        for i, ((_, n), o) in enumerate(zip(shape_list, offs)):
+            normal_bf16(n, sigmas[i], (seed, 1, step, i), device=dev, out=arena[o:o + n])
+        return
+    g = _gen(dev, seed, 1, step)
+    total = arena.numel()
+    for lo in range(0, total, _CHUNK):
+        hi = min(total, lo + _CHUNK)
+        x = torch.empty(hi - lo, dtype=torch.float32, device=dev)
+        x.normal_(mean=0.0, std=1e-3, generator=g)
+        if drift is not None:
+            x += drift[lo:hi]
+        arena[lo:hi].copy_(x)
 
 
 def expected_totals():

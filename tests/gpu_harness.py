@@ -1,0 +1,110 @@
+"""Shared machinery of the GPU parity tests: device arenas for one workload, the plan over them,
+seeded sampling of elements, and the oracle run over the sampled elements.
+
+Inputs (initial parameters, per-step gradients) come from paper_2405_03637_amd.workloads drawn on the
+GPU by torch; the sampled elements are copied to the host for the oracle.  No oracle input is ever
+taken from the library's outputs: the oracle carries its own state for the sampled elements from
+step 0 on.  The step is element-wise, so a sampled element's trajectory does not depend on the rest.
+"""
+import numpy as np
+import torch
+
+import helpers as H
+from oracle import oracle as orc
+from paper_2405_03637_amd import binding as mcf
+from paper_2405_03637_amd import workloads as W
+
+
+def sample_indices(shape_list, offs, full_below=16384, window=2048, n_random=2, seed=0):
+    """Arena element indices to check: small tensors entirely; of large ones the first and last
+    `window` elements (the unaligned head and the ragged tail) and n_random windows at random,
+    deliberately unaligned, offsets."""
+    rng = np.random.default_rng(seed)
+    parts = []
+    for (_, n), o in zip(shape_list, offs):
+        if n <= full_below:
+            parts.append(np.arange(o, o + n, dtype=np.int64))
+            continue
+        parts.append(np.arange(o, o + window, dtype=np.int64))
+        parts.append(np.arange(o + n - window, o + n, dtype=np.int64))
+        for _ in range(n_random):
+            s = int(rng.integers(window, n - 2 * window)) | 1
+            parts.append(np.arange(o + s, o + s + window, dtype=np.int64))
+    return np.unique(np.concatenate(parts))
+
+
+class Workload:
+    """Device state of one named workload and its plan."""
+
+    def __init__(self, name, device="cuda", misalign_tiny=False, seed=0, variant=None, shape_list=None, hyper=None,
+                 align=8):
+        self.name = name
+        self.shapes = shape_list if shape_list is not None else W.shapes(name)
+        vname = variant or W.WORKLOADS[name][1]
+        self.variant = mcf.PLUS if vname == "plus" else mcf.LIGHT
+        self.hyper = hyper or W.WORKLOADS[name][2]
+        self.offs, self.total = W.layout(self.shapes, misalign_tiny=misalign_tiny, align=align)
+        self.seed = seed
+        self.device = device
+        z = lambda: torch.zeros(self.total, dtype=torch.bfloat16, device=device)
+        self.theta, self.dtheta, self.m, self.v = z(), z(), z(), z()
+        self.dv = z() if self.variant == mcf.PLUS else None
+        self.grad = z()
+        W.init_theta(name, self.shapes, self.offs, self.theta, seed=seed)
+        self.drift = W.stress_drift(self.shapes, self.offs, self.total, device, seed) if name == "stress_64m" else None
+        self.sigmas = W.grad_sigmas(name, self.shapes, seed)
+        tensors = []
+        for (_, n), o in zip(self.shapes, self.offs):
+            sl = slice(o, o + n)
+            tensors.append((self.theta[sl], self.dtheta[sl], self.m[sl], self.v[sl],
+                            self.dv[sl] if self.dv is not None else None, self.grad[sl]))
+        self.plan = mcf.Plan(tensors, self.variant)
+        self.n_params = W.total_params(self.shapes)
+        assert self.plan.params == self.n_params
+
+    def state_names(self):
+        return ["theta", "dtheta", "m", "v"] + (["dv"] if self.dv is not None else [])
+
+    def new_grads(self, step):
+        W.fill_grads(self.name, self.shapes, self.offs, self.grad, step, seed=self.seed, sigmas=self.sigmas,
+                     drift=self.drift)
+
+    def gather(self, tensor, idx_dev):
+        return H.torch_to_u16(tensor[idx_dev])
+
+    def close(self):
+        self.plan.destroy()
+
+
+class SampledOracle:
+    """Oracle state for the sampled elements of a Workload, advanced in lock-step."""
+
+    def __init__(self, wl, idx):
+        self.wl = wl
+        self.idx = idx
+        self.idx_dev = torch.from_numpy(idx).to(wl.device)
+        self.state = {k: wl.gather(getattr(wl, k), self.idx_dev) for k in wl.state_names()}
+        # dtheta, m, v, dv start at zero by construction; theta is the generator's draw
+        for k in wl.state_names():
+            if k != "theta":
+                assert not self.state[k].any()
+
+    def step(self, t, want_delta=False):
+        g = self.wl.gather(self.wl.grad, self.idx_dev)
+        s = self.state
+        delta = np.empty(g.size, np.uint16) if want_delta else None
+        orc.adamw_step(s["theta"], s["dtheta"], s["m"], s["v"], s.get("dv"), g, self.wl.variant, self.wl.hyper, t,
+                       delta_out=delta)
+        return delta
+
+    def mismatches(self):
+        """{state name: number of sampled elements whose bits differ from the device}."""
+        out = {}
+        for k in self.wl.state_names():
+            dev = self.wl.gather(getattr(self.wl, k), self.idx_dev)
+            out[k] = int(np.count_nonzero(dev != self.state[k]))
+        return out
+
+
+def assert_bitwise(mism, where):
+    assert all(v == 0 for v in mism.values()), f"{where}: mismatching elements {mism}"

@@ -1,0 +1,140 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function
+include/mcf.h declares, and reports argument errors before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+from paper_2405_03637_amd import binding as mcf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HAS_GPU = torch.cuda.is_available()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "mcf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mcf_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    names = _declared()
+    assert {"mcf_adamw_step", "mcf_adamw_step_flat", "mcf_plan_create", "mcf_plan_destroy", "mcf_grow", "mcf_fast2sum",
+            "mcf_two_sum", "mcf_edq", "mcf_fp32mw_step", "mcf_bf16_op", "mcf_round_f32"} <= set(names)
+    lib = mcf.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    for code in range(0, -8, -1):
+        assert mcf.status_string(code) and mcf.status_string(code) != "unknown status"
+    assert mcf.status_string(-99) == "unknown status"
+
+
+def _hyper(**kw):
+    d = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    d.update(kw)
+    return mcf.Hyper(**d)
+
+
+FAKE = 0x10000      # an aligned, non-NULL address that is never dereferenced on these paths
+
+
+def _flat(theta=FAKE, dtheta=FAKE, m=FAKE, v=FAKE, dv=None, grad=FAKE, n=16, variant=0, hyper=None, step=1):
+    h = hyper or _hyper()
+    return mcf.lib().mcf_adamw_step_flat(theta, dtheta, m, v, dv, grad, n, variant, ctypes.byref(h), step, None)
+
+
+def test_flat_step_argument_errors():
+    assert _flat(theta=None) == mcf.MCF_ERR_NULL
+    assert _flat(grad=None) == mcf.MCF_ERR_NULL
+    assert _flat(variant=1, dv=None) == mcf.MCF_ERR_NULL
+    assert _flat(variant=2) == mcf.MCF_ERR_VARIANT
+    assert _flat(variant=-1) == mcf.MCF_ERR_VARIANT
+    assert _flat(m=FAKE + 1) == mcf.MCF_ERR_ALIGN
+    assert _flat(n=(1 << 35) + 1) == mcf.MCF_ERR_SIZE
+    assert _flat(step=0) == mcf.MCF_ERR_STEP
+    assert _flat(hyper=_hyper(beta1=1.0)) == mcf.MCF_ERR_HYPER
+    assert _flat(hyper=_hyper(beta2=-0.1)) == mcf.MCF_ERR_HYPER
+    assert _flat(hyper=_hyper(lr=float("nan"))) == mcf.MCF_ERR_HYPER
+    assert _flat(hyper=_hyper(eps=-1e-8)) == mcf.MCF_ERR_HYPER
+    assert _flat(hyper=_hyper(weight_decay=float("inf"))) == mcf.MCF_ERR_HYPER
+    assert mcf.lib().mcf_adamw_step_flat(FAKE, FAKE, FAKE, FAKE, None, FAKE, 16, 0, None, 1, None) == mcf.MCF_ERR_NULL
+    # an empty tensor is a no-op and never reaches the device, whatever the pointers
+    assert _flat(n=0, theta=None, grad=None) == mcf.MCF_OK
+
+
+def test_plan_argument_errors():
+    lib = mcf.lib()
+    h = ctypes.c_void_p()
+    one = (mcf.Tensor * 1)(mcf.Tensor(FAKE, FAKE, FAKE, FAKE, None, FAKE, 8))
+    assert lib.mcf_plan_create(None, one, 1, 0) == mcf.MCF_ERR_NULL
+    assert lib.mcf_plan_create(ctypes.byref(h), None, 1, 0) == mcf.MCF_ERR_NULL
+    assert lib.mcf_plan_create(ctypes.byref(h), one, 1, 7) == mcf.MCF_ERR_VARIANT
+    assert lib.mcf_plan_create(ctypes.byref(h), one, 1, 1) == mcf.MCF_ERR_NULL           # plus needs dv
+    bad = (mcf.Tensor * 1)(mcf.Tensor(FAKE, FAKE + 1, FAKE, FAKE, None, FAKE, 8))
+    assert lib.mcf_plan_create(ctypes.byref(h), bad, 1, 0) == mcf.MCF_ERR_ALIGN
+    big = (mcf.Tensor * 1)(mcf.Tensor(FAKE, FAKE, FAKE, FAKE, None, FAKE, (1 << 35) + 8))
+    assert lib.mcf_plan_create(ctypes.byref(h), big, 1, 0) == mcf.MCF_ERR_SIZE
+    assert not h.value
+    hy = _hyper()
+    assert lib.mcf_adamw_step(None, ctypes.byref(hy), 1, None, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_plan_destroy(None) == mcf.MCF_OK
+    assert lib.mcf_plan_params(None) == 0
+    # a plan over nothing needs no device memory and its step does nothing
+    assert lib.mcf_plan_create(ctypes.byref(h), None, 0, 0) == mcf.MCF_OK and h.value
+    assert lib.mcf_adamw_step(h, ctypes.byref(hy), 0, None, None) == mcf.MCF_ERR_STEP
+    assert lib.mcf_adamw_step(h, None, 1, None, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_adamw_step(h, ctypes.byref(hy), 1, None, FAKE + 4) == mcf.MCF_ERR_ALIGN
+    assert lib.mcf_adamw_step(h, ctypes.byref(hy), 1, None, None) == mcf.MCF_OK
+    assert lib.mcf_plan_destroy(h) == mcf.MCF_OK
+    empty = (mcf.Tensor * 2)(mcf.Tensor(None, None, None, None, None, None, 0), mcf.Tensor(None, None, None, None, None, None, 0))
+    assert lib.mcf_plan_create(ctypes.byref(h), empty, 2, 1) == mcf.MCF_OK
+    assert lib.mcf_plan_params(h) == 0
+    assert lib.mcf_plan_destroy(h) == mcf.MCF_OK
+
+
+@pytest.mark.skipif(HAS_GPU, reason="with a device the table allocation succeeds")
+def test_plan_create_without_device_reports_hip_error():
+    lib = mcf.lib()
+    h = ctypes.c_void_p()
+    one = (mcf.Tensor * 1)(mcf.Tensor(FAKE, FAKE, FAKE, FAKE, None, FAKE, 8))
+    assert lib.mcf_plan_create(ctypes.byref(h), one, 1, 0) == mcf.MCF_ERR_HIP
+    assert not h.value
+
+
+def test_primitive_argument_errors():
+    lib = mcf.lib()
+    assert lib.mcf_fast2sum(None, FAKE, FAKE, FAKE, 4, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_two_sum(FAKE, FAKE, FAKE, None, 4, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_grow(FAKE, None, FAKE, 4, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_fast2sum(FAKE + 1, FAKE, FAKE, FAKE, 4, None) == mcf.MCF_ERR_ALIGN
+    assert lib.mcf_grow(FAKE, FAKE, FAKE, (1 << 35) + 1, None) == mcf.MCF_ERR_SIZE
+    assert lib.mcf_fast2sum(None, None, None, None, 0, None) == mcf.MCF_OK
+    assert lib.mcf_bf16_op(5, FAKE, FAKE, FAKE, 4, None) == mcf.MCF_ERR_VARIANT
+    assert lib.mcf_bf16_op(0, FAKE, None, FAKE, 4, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_round_f32(FAKE + 2, FAKE, 4, None) == mcf.MCF_ERR_ALIGN
+    assert lib.mcf_round_f32(None, FAKE, 4, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_edq(FAKE, FAKE, None, FAKE, None, 4, FAKE, None, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_edq(FAKE, FAKE, None, FAKE, None, 4, None, None, FAKE) == mcf.MCF_ERR_NULL
+    assert lib.mcf_edq(FAKE, FAKE, None, FAKE + 1, None, 4, FAKE, None, FAKE) == mcf.MCF_ERR_ALIGN
+    assert lib.mcf_edq_scratch_bytes(0) >= 16 and lib.mcf_edq_scratch_bytes(1 << 30) > lib.mcf_edq_scratch_bytes(1 << 20)
+
+
+def test_fp32mw_argument_errors():
+    lib = mcf.lib()
+    h = ctypes.c_void_p()
+    one = (mcf.Fp32Tensor * 1)(mcf.Fp32Tensor(FAKE, FAKE, FAKE, None, FAKE, 8))
+    assert lib.mcf_fp32mw_plan_create(ctypes.byref(h), one, 1) == mcf.MCF_ERR_NULL
+    bad = (mcf.Fp32Tensor * 1)(mcf.Fp32Tensor(FAKE, FAKE + 2, FAKE, FAKE, FAKE, 8))
+    assert lib.mcf_fp32mw_plan_create(ctypes.byref(h), bad, 1) == mcf.MCF_ERR_ALIGN
+    assert lib.mcf_fp32mw_plan_create(None, one, 1) == mcf.MCF_ERR_NULL
+    hy = _hyper()
+    assert lib.mcf_fp32mw_step(None, ctypes.byref(hy), 1, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_fp32mw_plan_create(ctypes.byref(h), None, 0) == mcf.MCF_OK
+    assert lib.mcf_fp32mw_step(h, ctypes.byref(hy), 0, None) == mcf.MCF_ERR_STEP
+    assert lib.mcf_fp32mw_step(h, ctypes.byref(hy), 3, None) == mcf.MCF_OK
+    assert lib.mcf_fp32mw_plan_destroy(h) == mcf.MCF_OK

@@ -1,0 +1,403 @@
+"""GPU parity: the HIP library against the CPU oracle, bit for bit, through the C ABI.
+
+Bar: every bf16 state element identical (integer comparison of the bit patterns); EDQ within
+relative 1e-5 (fp64 reduction on both sides, different summation order).
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import helpers as H
+from gpu_harness import SampledOracle, Workload, assert_bitwise, sample_indices
+from oracle import oracle as orc
+from paper_2405_03637_amd import binding as mcf
+from paper_2405_03637_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _dev(u16):
+    return H.u16_to_torch(u16, DEV)
+
+
+# ------------------------------------------------------------------ rounding and single operations
+def test_round_f32_all_patterns():
+    """Every one of the 2^32 fp32 bit patterns through the library's rounding against the oracle's R."""
+    chunk = 1 << 26
+    out = torch.empty(chunk, dtype=torch.bfloat16, device=DEV)
+    for c in range(0, 1 << 32, chunk):
+        bits = torch.arange(c, c + chunk, dtype=torch.int64, device=DEV).to(torch.int32)   # wraps into the sign bit
+        mcf.round_f32(bits.view(torch.float32), out)
+        got = H.torch_to_u16(out)
+        want = orc.R_array(bits.cpu().numpy().view(np.float32))
+        bad = np.flatnonzero(got != want)
+        assert bad.size == 0, f"chunk {c:#x}: {bad.size} mismatches, first at {c + int(bad[0]):#x}"
+    _say("round: 2^32 patterns ok")
+
+
+@pytest.mark.parametrize("opname", ["add", "sub", "mul", "div", "sqrt"])
+def test_bf16_op_sweep(opname):
+    """Rows of the 2^16 x 2^16 operand table (all of it with MCF_FULL_SWEEP=1); sqrt: all 2^16 inputs.
+    Rows include zeros, subnormals, infinities and NaN patterns."""
+    op = {"add": 0, "sub": 1, "mul": 2, "div": 3, "sqrt": 4}[opname]
+    every = np.arange(1 << 16, dtype=np.uint16)
+    if opname == "sqrt":
+        a = _dev(every)
+        out = torch.empty_like(a)
+        mcf.bf16_op(op, a, None, out)
+        assert np.array_equal(H.torch_to_u16(out), orc.binop(op, every))
+        return
+    if os.environ.get("MCF_FULL_SWEEP") == "1":
+        rows = every
+    else:
+        rng = np.random.default_rng(30 + op)
+        rows = np.unique(np.concatenate([rng.integers(0, 1 << 16, 1024).astype(np.uint16),
+                                         np.array([0, 1, 0x7F, 0x80, 0x81, 0x3F80, 0x7F7F, 0x7F80, 0x7FC0, 0x8000, 0x8001,
+                                                   0xBF80, 0xFF80, 0xFFFF, 0x0100, 0x7E80, 0x7F00], np.uint16)]))
+    b = _dev(every)
+    out = torch.empty_like(b)
+    group = 64
+    for i in range(0, rows.size, group):
+        r = rows[i:i + group]
+        aa = np.repeat(r, every.size)
+        bb = np.tile(every, r.size)
+        a_d, b_d = _dev(aa), _dev(bb)
+        o_d = torch.empty_like(a_d)
+        mcf.bf16_op(op, a_d, b_d, o_d)
+        got = H.torch_to_u16(o_d)
+        want = orc.binop(op, aa, bb)
+        bad = np.flatnonzero(got != want)
+        assert bad.size == 0, f"{opname}: {bad.size} mismatches, first a={aa[bad[0]]:#06x} b={bb[bad[0]]:#06x} " \
+                              f"got={got[bad[0]]:#06x} want={want[bad[0]]:#06x}"
+    del out
+
+
+def _random_bf16(n, seed, special=True):
+    rng = np.random.default_rng(seed)
+    a = rng.integers(0, 1 << 16, n).astype(np.uint16)
+    k = n // 2
+    # half of the values in a narrow exponent band so that sums and differences really round
+    a[:k] = ((rng.integers(120, 134, k) << 7) | rng.integers(0, 128, k) | (rng.integers(0, 2, k) << 15)).astype(np.uint16)
+    if not special:
+        a[k:] = ((rng.integers(60, 190, n - k) << 7) | rng.integers(0, 128, n - k) | (rng.integers(0, 2, n - k) << 15)).astype(np.uint16)
+    return a
+
+
+@pytest.mark.parametrize("n,shift", [(1, 0), (7, 1), (64, 3), (1000, 5), (262144 + 13, 0), (262144 + 13, 7), (1 << 20, 0)])
+def test_primitives(n, shift):
+    """Fast2Sum, TwoSum and Grow on random bit patterns (NaN, infinities and subnormals included), with the
+    buffers starting `shift` elements past a 16-byte boundary so that head and tail go element by element."""
+    a, b, c = _random_bf16(n, 40), _random_bf16(n, 41), _random_bf16(n, 42)
+    pad = lambda u: _dev(np.concatenate([np.zeros(shift, np.uint16), u, np.zeros(8, np.uint16)]))
+    A, Bt, C = pad(a), pad(b), pad(c)
+    X, Y = torch.full_like(A, 7.0), torch.full_like(A, 7.0)
+    sl = slice(shift, shift + n)
+    guard = lambda t: (H.torch_to_u16(t[:shift]), H.torch_to_u16(t[shift + n:]))
+    before = guard(X)
+    mcf.fast2sum(A[sl], Bt[sl], X[sl], Y[sl])
+    wx, wy = orc.fast2sum(a, b)
+    assert np.array_equal(H.torch_to_u16(X[sl]), wx) and np.array_equal(H.torch_to_u16(Y[sl]), wy)
+    assert all(np.array_equal(p, q) for p, q in zip(before, guard(X)))            # nothing outside was touched
+    mcf.two_sum(A[sl], Bt[sl], X[sl], Y[sl])
+    wx, wy = orc.two_sum(a, b)
+    assert np.array_equal(H.torch_to_u16(X[sl]), wx) and np.array_equal(H.torch_to_u16(Y[sl]), wy)
+    mcf.grow(A[sl], Bt[sl], C[sl])
+    wx, wy = orc.grow(a, b, c)
+    assert np.array_equal(H.torch_to_u16(A[sl]), wx) and np.array_equal(H.torch_to_u16(Bt[sl]), wy)
+    assert np.array_equal(H.torch_to_u16(C[sl]), c)
+
+
+def test_primitives_mutually_misaligned_buffers():
+    n = 5000
+    a, b = _random_bf16(n, 43), _random_bf16(n, 44)
+    A = _dev(np.concatenate([np.zeros(1, np.uint16), a]))[1:]
+    Bt = _dev(np.concatenate([np.zeros(3, np.uint16), b]))[3:]
+    X = torch.empty(n + 2, dtype=torch.bfloat16, device=DEV)[2:]
+    Y = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    mcf.fast2sum(A, Bt, X, Y)
+    wx, wy = orc.fast2sum(a, b)
+    assert np.array_equal(H.torch_to_u16(X), wx) and np.array_equal(H.torch_to_u16(Y), wy)
+
+
+# ------------------------------------------------------------------ the step: small, exhaustive comparisons
+def _full_oracle_run(wl, steps, edq=False, check_each=True):
+    """Whole-state comparison after every step, oracle over every element."""
+    names = wl.state_names()
+    host = {k: H.torch_to_u16(getattr(wl, k)) for k in names}
+    edq_dev = torch.zeros(3, dtype=torch.float64, device=DEV) if edq else None
+    live = np.zeros(wl.total, bool)
+    for (_, n), o in zip(wl.shapes, wl.offs):
+        live[o:o + n] = True
+    for t in range(1, steps + 1):
+        wl.new_grads(t)
+        g = H.torch_to_u16(wl.grad)
+        before = {k: host[k].copy() for k in ("theta", "dtheta")} if edq else None
+        delta = np.zeros(wl.total, np.uint16) if edq else None
+        # the oracle steps the whole arena; padding between tensors is stepped too and then ignored
+        orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], host.get("dv"), g, wl.variant, wl.hyper, t,
+                       delta_out=delta)
+        wl.plan.step(wl.hyper, t, edq_out=edq_dev)
+        torch.cuda.synchronize()
+        if check_each or t == steps:
+            for k in names:
+                dev = H.torch_to_u16(getattr(wl, k))
+                bad = np.flatnonzero((dev != host[k]) & live)
+                assert bad.size == 0, f"{wl.name} step {t} {k}: {bad.size} mismatches, first at {int(bad[0])}: " \
+                                      f"got {dev[bad[0]]:#06x} want {host[k][bad[0]]:#06x}"
+                # padding is never written by the library
+                assert not dev[~live].any()
+                host[k][~live] = 0
+        if edq:
+            acc = orc.EdqAccumulator()
+            for (_, n), o in zip(wl.shapes, wl.offs):
+                sl = slice(o, o + n)
+                acc.add(delta[sl].copy(), before["theta"][sl].copy(), before["dtheta"][sl].copy(),
+                        host["theta"][sl].copy(), host["dtheta"][sl].copy())
+            want = acc.value()
+            got = edq_dev.cpu().numpy()
+            assert abs(got[0] - want) <= 1e-5 * abs(want), (t, got, want)
+            assert abs(got[1] - acc.s1.value) <= 1e-5 * abs(acc.s1.value) and abs(got[2] - acc.s2.value) <= 1e-5 * acc.s2.value
+            assert want > 0
+
+
+@pytest.mark.parametrize("variant", ["light", "plus"])
+def test_config1_flat_1m(variant):
+    """Config 1: one flat tensor of 2^20, 10 steps, every element after every step; plan and flat entry points."""
+    _say(f"config 1 {variant}")
+    wl = Workload("flat_1m", variant=variant)
+    _full_oracle_run(wl, 10, edq=True)
+    wl.close()
+    # the flat entry point on a fresh copy of the same inputs
+    wl = Workload("flat_1m", variant=variant)
+    host = {k: H.torch_to_u16(getattr(wl, k)) for k in wl.state_names()}
+    for t in range(1, 4):
+        wl.new_grads(t)
+        g = H.torch_to_u16(wl.grad)
+        orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], host.get("dv"), g, wl.variant, wl.hyper, t)
+        mcf.adamw_step_flat(wl.theta, wl.dtheta, wl.m, wl.v, wl.dv, wl.grad, wl.variant, wl.hyper, t)
+    for k in wl.state_names():
+        assert np.array_equal(H.torch_to_u16(getattr(wl, k)), host[k]), k
+    wl.close()
+
+
+@pytest.mark.parametrize("variant", ["light", "plus"])
+def test_many_small_and_ragged_tensors(variant):
+    """A few hundred tensors of 1..3000 elements packed back to back at odd offsets, plus three that span
+    several chunks with ragged tails: exercises the chunk table, heads, tails and tiny tensors."""
+    rng = np.random.default_rng(50)
+    sizes = [int(x) for x in rng.integers(1, 3000, 300)] + [1, 2, 7, 8, 9, 15, 16, 17, 4095, 4096, 4097, 8191, 8193,
+                                                            3 * 8192 + 5, 40_000, 100_003]
+    shapes = [(f"t{i}", n) for i, n in enumerate(sizes)]
+    for align in (1, 8):          # 1: every tensor starts wherever the previous one ended
+        wl = Workload("flat_1m", variant=variant, shape_list=shapes, misalign_tiny=True, align=align,
+                      hyper=W.HYPER_PLUS_1P3B if variant == "plus" else W.HYPER_LIGHT)
+        _full_oracle_run(wl, 5, edq=True)
+        wl.close()
+
+
+def test_mutually_misaligned_tensor_goes_elementwise():
+    n = 20_000
+    mk = lambda off: torch.zeros(n + 8, dtype=torch.bfloat16, device=DEV)[off:off + n]
+    th, dth, m, v, g = mk(0), mk(1), mk(2), mk(3), mk(5)
+    th.copy_(W.normal_bf16(n, 0.02, (9, 0), device=DEV))
+    plan = mcf.Plan([(th, dth, m, v, None, g)], mcf.LIGHT)
+    host = [H.torch_to_u16(t) for t in (th, dth, m, v)]
+    for t in range(1, 4):
+        g.copy_(W.normal_bf16(n, 1e-3, (9, 1, t), device=DEV))
+        orc.adamw_step(host[0], host[1], host[2], host[3], None, H.torch_to_u16(g), 0, W.HYPER_LIGHT, t)
+        plan.step(W.HYPER_LIGHT, t)
+    for h, d in zip(host, (th, dth, m, v)):
+        assert np.array_equal(h, H.torch_to_u16(d))
+    plan.destroy()
+
+
+@pytest.mark.parametrize("variant", ["light", "plus"])
+def test_special_values_take_the_exact_path(variant):
+    """State and gradients drawn from all bit patterns (NaN, infinities, zeros, subnormals, huge and tiny
+    values): the guarded fast arithmetic must hand these to the exact path and still match bit for bit."""
+    n = 1 << 18
+    shapes = [("a", n)]
+    wl = Workload("flat_1m", variant=variant, shape_list=shapes)
+    rnd = lambda s: _dev(_random_bf16(wl.total, s))
+    wl.theta.copy_(rnd(60)); wl.dtheta.copy_(rnd(61)); wl.m.copy_(rnd(62)); wl.v.copy_(rnd(63))
+    if wl.dv is not None:
+        wl.dv.copy_(rnd(64))
+    # v must mostly be non-negative to keep a share of the elements finite
+    wl.v[: n // 2].abs_()
+    host = {k: H.torch_to_u16(getattr(wl, k)) for k in wl.state_names()}
+    for t in range(1, 4):
+        wl.grad.copy_(rnd(70 + t))
+        g = H.torch_to_u16(wl.grad)
+        orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], host.get("dv"), g, wl.variant, wl.hyper, t)
+        wl.plan.step(wl.hyper, t)
+        for k in wl.state_names():
+            dev = H.torch_to_u16(getattr(wl, k))
+            bad = np.flatnonzero(dev != host[k])
+            assert bad.size == 0, f"step {t} {k}: {bad.size} mismatches, first {int(bad[0])}: got {dev[bad[0]]:#06x} want {host[k][bad[0]]:#06x}"
+    frac_nan = np.mean((host["theta"] & 0x7FFF) > 0x7F80)
+    assert 0.05 < frac_nan < 0.9999
+    wl.close()
+
+
+def test_tiny_magnitudes_subnormal_intermediates():
+    """Gradients around 1e-19..1e-22: v lands in and below the subnormal range, so quotients and roots meet
+    subnormal intermediates; beta close to 1 and huge/zero eps are covered through the hyper-parameters."""
+    n = 1 << 16
+    for hyper in [(1e-3, 0.9, 0.95, 1e-8, 0.1), (1e-3, 0.9, 0.999, 0.0, 0.0), (1e-3, 0.0, 0.0, 1e-30, 0.01),
+                  (1e-2, 0.99999, 0.9999999, 1e-8, 0.1)]:
+        wl = Workload("flat_1m", variant="plus", shape_list=[("a", n)], hyper=hyper)
+        host = {k: H.torch_to_u16(getattr(wl, k)) for k in wl.state_names()}
+        rng = np.random.default_rng(80)
+        for t in range(1, 5):
+            scale = 10.0 ** rng.uniform(-24, -17, wl.total)
+            gq = H.np_round_f64_to_bf16(rng.standard_normal(wl.total) * scale)
+            gq[::97] = 0
+            wl.grad.copy_(_dev(gq))
+            orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], host["dv"], gq, 1, hyper, t)
+            wl.plan.step(hyper, t)
+            for k in wl.state_names():
+                dev = H.torch_to_u16(getattr(wl, k))
+                bad = np.flatnonzero(dev != host[k])
+                assert bad.size == 0, f"hyper {hyper} step {t} {k}: {bad.size} mismatches"
+        wl.close()
+
+
+def test_checkpoint_resume_is_bitwise():
+    """State is the tensors plus t: 6 steps equal 3 steps, a new plan, 3 more steps."""
+    a = Workload("flat_1m", variant="plus", shape_list=[("x", 50_001), ("y", 333)], misalign_tiny=True)
+    b = Workload("flat_1m", variant="plus", shape_list=[("x", 50_001), ("y", 333)], misalign_tiny=True)
+    for t in range(1, 7):
+        a.new_grads(t)
+        b.grad.copy_(a.grad)
+        a.plan.step(a.hyper, t)
+        if t == 4:
+            b.plan.destroy()
+            tensors = [(b.theta[o:o + n], b.dtheta[o:o + n], b.m[o:o + n], b.v[o:o + n], b.dv[o:o + n], b.grad[o:o + n])
+                       for (_, n), o in zip(b.shapes, b.offs)]
+            b.plan = mcf.Plan(tensors, b.variant)
+        b.plan.step(b.hyper, t)
+    for k in a.state_names():
+        assert torch.equal(getattr(a, k), getattr(b, k))
+    a.close(); b.close()
+
+
+def test_edq_standalone():
+    n = 300_007
+    rng = np.random.default_rng(90)
+    th0 = H.np_round_f64_to_bf16(rng.standard_normal(n))
+    delta = H.np_round_f64_to_bf16(rng.standard_normal(n) * 1e-3)
+    dth0 = np.zeros(n, np.uint16)
+    th1, dth1 = orc.grow(th0, dth0, delta)
+    plain = orc.binop(orc.ADD, th0, delta)
+    out = torch.zeros(3, dtype=torch.float64, device=DEV)
+    scratch = torch.empty(mcf.edq_scratch_bytes(n) // 8, dtype=torch.float64, device=DEV)
+    mcf.edq(_dev(delta), _dev(th0), _dev(dth0), _dev(th1), _dev(dth1), scratch, out)
+    want = orc.edq(delta, th0, dth0, th1, dth1)
+    assert abs(out[0].item() - want) <= 1e-5 * abs(want)
+    mcf.edq(_dev(delta), _dev(th0), None, _dev(plain), None, scratch, out)      # Eq. 2 as printed: plain bf16
+    want = orc.edq(delta, th0, None, plain, None)
+    assert abs(out[0].item() - want) <= 1e-5 * abs(want)
+
+
+# ------------------------------------------------------------------ option D
+def test_fp32_master_baseline():
+    shapes = [("a", 100_003), ("b", 77), ("c", 8192 * 3)]
+    offs, total = W.layout(shapes)
+    th = torch.zeros(total, dtype=torch.bfloat16, device=DEV)
+    W.init_theta("flat_1m", shapes, offs, th)
+    master = th.float()
+    m = torch.zeros(total, dtype=torch.float32, device=DEV)
+    v = torch.zeros_like(m)
+    g = torch.zeros_like(th)
+    plan = mcf.Fp32MwPlan([(th[o:o + n], master[o:o + n], m[o:o + n], v[o:o + n], g[o:o + n]) for (_, n), o in zip(shapes, offs)])
+    h_th, h_w, h_m, h_v = H.torch_to_u16(th), master.cpu().numpy().copy(), m.cpu().numpy().copy(), v.cpu().numpy().copy()
+    for t in range(1, 6):
+        W.fill_grads("flat_1m", shapes, offs, g, t)
+        orc.fp32mw_step(h_th, h_w, h_m, h_v, H.torch_to_u16(g), W.HYPER_LIGHT, t)
+        plan.step(W.HYPER_LIGHT, t)
+    live = np.zeros(total, bool)
+    for (_, n), o in zip(shapes, offs):
+        live[o:o + n] = True
+    for name, host, dev in (("master", h_w, master), ("m", h_m, m), ("v", h_v, v)):
+        d = dev.cpu().numpy()
+        assert np.array_equal(d.view(np.uint32)[live], host.view(np.uint32)[live]), name
+    assert np.array_equal(H.torch_to_u16(th)[live], h_th[live])
+    plan.destroy()
+
+
+# ------------------------------------------------------------------ the paper-shaped configurations
+def _sampled_run(name, steps, check_at, full_first_step=False, misalign_tiny=False, edq_first=False):
+    _say(f"{name}: allocating")
+    wl = Workload(name, misalign_tiny=misalign_tiny)
+    idx = sample_indices(wl.shapes, wl.offs)
+    so = SampledOracle(wl, idx)
+    _say(f"{name}: {wl.n_params} params in {len(wl.shapes)} tensors, {idx.size} sampled")
+    full = None
+    if full_first_step:
+        full = {k: H.torch_to_u16(getattr(wl, k)) for k in wl.state_names()}
+    edq_dev = torch.zeros(3, dtype=torch.float64, device=DEV) if edq_first else None
+    for t in range(1, steps + 1):
+        wl.new_grads(t)
+        so.step(t)
+        if t == 1 and full_first_step:
+            g = H.torch_to_u16(wl.grad)
+            before = (full["theta"].copy(), full["dtheta"].copy()) if edq_first else None
+            delta = np.zeros(wl.total, np.uint16) if edq_first else None
+            orc.adamw_step(full["theta"], full["dtheta"], full["m"], full["v"], full.get("dv"), g, wl.variant, wl.hyper, 1,
+                           delta_out=delta)
+            wl.plan.step(wl.hyper, 1, edq_out=edq_dev)
+            live = np.zeros(wl.total, bool)
+            for (_, n), o in zip(wl.shapes, wl.offs):
+                live[o:o + n] = True
+            for k in wl.state_names():
+                dev = H.torch_to_u16(getattr(wl, k))
+                nbad = int(np.count_nonzero((dev != full[k]) & live))
+                assert nbad == 0, f"{name} step 1 {k}: {nbad} of {wl.n_params} differ"
+            if edq_first:
+                acc = orc.EdqAccumulator()
+                for (_, n), o in zip(wl.shapes, wl.offs):
+                    sl = slice(o, o + n)
+                    acc.add(delta[sl].copy(), before[0][sl].copy(), before[1][sl].copy(), full["theta"][sl].copy(),
+                            full["dtheta"][sl].copy())
+                got = edq_dev.cpu().numpy()
+                assert abs(got[0] - acc.value()) <= 1e-5 * abs(acc.value()), (got, acc.value())
+                _say(f"{name}: step 1 EDQ {got[0]:.9e} oracle {acc.value():.9e}")
+            full = None
+            _say(f"{name}: step 1 whole state ok")
+        else:
+            wl.plan.step(wl.hyper, t)
+        if t in check_at:
+            assert_bitwise(so.mismatches(), f"{name} step {t}")
+            _say(f"{name}: step {t} sampled state ok")
+    wl.close()
+
+
+def test_config2_gpt2_125m():
+    """Config 2: 148 tensors, 124,439,808 parameters, light, 100 steps.  Whole state at step 1, then the
+    sampled elements (all small tensors, heads, tails and random windows of the large ones)."""
+    _sampled_run("gpt2_125m", 100, {1, 2, 10, 50, 100}, full_first_step=True)
+
+
+def test_config3_gpt_1p3b_plus_edq():
+    """Config 3: 292 tensors, 1,315,819,520 parameters, plus, 20 steps, per-tensor gradient scales.
+    Whole state and the fused EDQ at step 1 (oracle over every element), sampled elements afterwards."""
+    _sampled_run("gpt_1p3b", 20, {1, 2, 5, 10, 20}, full_first_step=True, edq_first=True)
+
+
+def test_config4_llama_7b():
+    """Config 4: 291 tensors, 6,738,415,616 parameters, light, 10 steps, in the launch configuration the
+    benchmark times.  Sampled elements only (the oracle computes each one independently)."""
+    _sampled_run("llama_7b", 10, {1, 2, 5, 10})
+
+
+def test_config5_stress_64m():
+    """Config 5: 64 Mi parameters incl. 4096 tensors of 1..256 elements at odd offsets, plus, lr = 2^-20,
+    1000 steps.  Every tiny tensor and windows of the large ones are followed by the oracle."""
+    _sampled_run("stress_64m", 1000, {1, 10, 100, 500, 1000}, misalign_tiny=True)
