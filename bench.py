@@ -21,8 +21,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor peak
 
 # HBM traffic per parameter per step measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
-# what the same counters read for a plain copy of known size; see profiles/.  None = not measured yet.
-MEASURED_TRAFFIC_BYTES_PER_PARAM = {"light": None, "plus": None, "fp32mw": None}
+# what the same counters read for a plain copy of known size (FETCH_SIZE x2.0000, WRITE_SIZE x1.0000);
+# the figures and commands are in profiles/*_llama_7b.md.  None = not measured.
+MEASURED_TRAFFIC_BYTES_PER_PARAM = {"light": 18.250, "plus": 22.250, "fp32mw": 29.389}
 
 
 def log(msg):
@@ -144,8 +145,9 @@ def main():
         try:
             # plain copy of one arena as the achievable streaming ceiling (reads n*2, writes n*2 bytes)
             src, dst = st["theta"], st["grad"]
-            _, s = time_steps(lambda t: dst.copy_(src), 10, 2)
-            extras["copy_GBps"] = 4 * src.numel() * 10 / s / 1e9
+            nb = src.numel() // 8 * 8
+            _, s = time_steps(lambda t: mcf.stream_copy(dst[:nb], src[:nb]), 10, 2)
+            extras["copy_GBps"] = 4 * nb * 10 / s / 1e9
             del src, dst
             other = "plus" if variant == "light" else "light"
             st = None

@@ -132,6 +132,13 @@ int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tenso
 int mcf_fp32mw_plan_destroy(mcf_fp32mw_plan *plan);
 int mcf_fp32mw_step(mcf_fp32mw_plan *plan, const mcf_hyper *hyper, uint64_t step, void *stream);
 
+/* ---- measurement aid: a plain 128-bit copy of `bytes` bytes (multiple of 16, both pointers 16-byte
+ * aligned device memory, not overlapping) in the step kernel's launch shape.  It is the streaming
+ * ceiling the step's bandwidth is reported against and the known-size transfer used to calibrate
+ * profiler byte counters (the step moves 18 or 22 bytes per parameter: Table 1's state, read and
+ * written, plus the gradient). ---- */
+int mcf_stream_copy(void *dst, const void *src, uint64_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

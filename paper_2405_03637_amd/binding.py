@@ -50,9 +50,12 @@ def lib():
     global _lib
     if _lib is not None:
         return _lib
-    path = _build.LIB
+    path = os.environ.get("MCF_LIBRARY") or _build.LIB        # MCF_LIBRARY: load another build of the library
     if not os.path.exists(path):
         _build.build()
+    # torch owns the process's HIP runtime (device memory, streams): load it first so that this
+    # library binds to the same libamdhip64 instead of bringing in a second copy
+    import torch  # noqa: F401
     L = ctypes.CDLL(path)
     L.mcf_status_string.restype = ctypes.c_char_p
     L.mcf_status_string.argtypes = [_int]
@@ -73,6 +76,7 @@ def lib():
     L.mcf_fp32mw_plan_create.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(Fp32Tensor), ctypes.c_uint32]
     L.mcf_fp32mw_plan_destroy.argtypes = [_vp]
     L.mcf_fp32mw_step.argtypes = [_vp, ctypes.POINTER(Hyper), _u64, _vp]
+    L.mcf_stream_copy.argtypes = [_vp, _vp, _u64, _vp]
     _lib = L
     return L
 
@@ -219,3 +223,8 @@ def edq_scratch_bytes(n):
 def edq(delta, th0, dth0, th1, dth1, scratch, out, stream=None):
     _check(lib().mcf_edq(_ptr(delta), _ptr(th0), _ptr(dth0), _ptr(th1), _ptr(dth1), delta.numel(),
                          _ptr(scratch), _stream(stream), _ptr(out)), "mcf_edq")
+
+
+def stream_copy(dst, src, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _check(lib().mcf_stream_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "mcf_stream_copy")
