@@ -551,57 +551,79 @@ __device__ __forceinline__ void fp32mw_elem(float g, float &m, float &v, float &
   v = v1;
 }
 
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
 __global__ void __launch_bounds__(kStepBlock) MCF_STEP_ATTR
 fp32mw_kernel(const Fp32Desc *__restrict__ descs, const Chunk *__restrict__ chunks, Fp32Scalars sc) {
   const Chunk c = chunks[blockIdx.x];
   const Fp32Desc d = descs[c.tensor];
-  TensorDesc t;                       // reuse the slot classification
-  t.n = d.n; t.phase = d.phase; t.scalar_only = d.scalar_only;
   MCF_GLOBAL uint16_t *theta = gptr<uint16_t>(d.theta);
   const MCF_GLOBAL uint16_t *grad = gptr<const uint16_t>(d.grad);
   MCF_GLOBAL float *master = gptr<float>(d.master);
   MCF_GLOBAL float *mp = gptr<float>(d.m);
   MCF_GLOBAL float *vp = gptr<float>(d.v);
-#pragma unroll
+  const uint64_t c_lo = (uint64_t)c.slot0 * 8, c_hi = c_lo + 8ull * kSlotsPerChunk;
+  const bool interior = !d.scalar_only && c_lo >= d.phase && c_hi <= d.phase + d.n;      // wave-uniform
+  if (interior) {
+    // Every access of the wave is one contiguous run: in pass h lane l takes the 4 elements
+    // [h*4*kStepBlock + 4l, +4) of the chunk, i.e. 16 bytes of each fp32 buffer and 8 bytes of each
+    // bf16 buffer, so a wave reads 1 KiB (fp32) or 512 B (bf16) per instruction with no gaps.
+    constexpr int kPasses = 2 * kUnroll;
+    u32x2_t gw[kPasses];
+    f32x4_t mm[kPasses], vv[kPasses], ww[kPasses];
+    static_for<0, kPasses>([&](auto hc) {
+      constexpr int h = decltype(hc)::value;
+      const uint64_t e0 = (c_lo - d.phase) + (uint64_t)h * 4 * kStepBlock + 4 * threadIdx.x;
+#if MCF_NT_LOAD
+      gw[h] = __builtin_nontemporal_load((const MCF_GLOBAL u32x2_t *)(grad + e0));
+#else
+      gw[h] = *(const MCF_GLOBAL u32x2_t *)(grad + e0);
+#endif
+      mm[h] = load_f4(mp + e0);
+      vv[h] = load_f4(vp + e0);
+      ww[h] = load_f4(master + e0);
+    });
+    static_for<0, kPasses>([&](auto hc) {
+      constexpr int h = decltype(hc)::value;
+      const uint64_t e0 = (c_lo - d.phase) + (uint64_t)h * 4 * kStepBlock + 4 * threadIdx.x;
+      const P2 g0 = mcfd::widen2(gw[h].x), g1 = mcfd::widen2(gw[h].y);
+      float m[4] = {mm[h].x, mm[h].y, mm[h].z, mm[h].w};
+      float v[4] = {vv[h].x, vv[h].y, vv[h].z, vv[h].w};
+      float w[4] = {ww[h].x, ww[h].y, ww[h].z, ww[h].w};
+      fp32mw_elem(g0.lo, m[0], v[0], w[0], sc);
+      fp32mw_elem(g0.hi, m[1], v[1], w[1], sc);
+      fp32mw_elem(g1.lo, m[2], v[2], w[2], sc);
+      fp32mw_elem(g1.hi, m[3], v[3], w[3], sc);
+      store_f4(mp + e0, f32x4_t{m[0], m[1], m[2], m[3]});
+      store_f4(vp + e0, f32x4_t{v[0], v[1], v[2], v[3]});
+      store_f4(master + e0, f32x4_t{w[0], w[1], w[2], w[3]});
+      const u32x2_t tw = {mcfd::pack2(mcfd::Exact::rnd({w[0], w[1]})), mcfd::pack2(mcfd::Exact::rnd({w[2], w[3]}))};
+#if MCF_NT_STORE
+      __builtin_nontemporal_store(tw, (MCF_GLOBAL u32x2_t *)(theta + e0));
+#else
+      *(MCF_GLOBAL u32x2_t *)(theta + e0) = tw;
+#endif
+    });
+    return;
+  }
+  // Chunks at a tensor's ends, and tensors whose buffers are not mutually aligned: slot by slot,
+  // element by element where a slot is not whole.
+  TensorDesc t;
+  t.n = d.n; t.phase = d.phase; t.scalar_only = d.scalar_only;
+#pragma unroll 1
   for (int j = 0; j < kUnroll; ++j) {
     const Slot s = classify(t, (uint64_t)c.slot0 + (uint64_t)j * kStepBlock + threadIdx.x);
     if (!s.any) continue;
-    if (s.full) {
-      const uint64_t e0 = s.c0 - d.phase;
-      uint32_t gw[4];
-      load_vec(d.grad, e0, gw);
-      const f32x4_t m0 = load_f4(mp + e0), m1 = load_f4(mp + e0 + 4);
-      const f32x4_t v0 = load_f4(vp + e0), v1 = load_f4(vp + e0 + 4);
-      const f32x4_t w0 = load_f4(master + e0), w1 = load_f4(master + e0 + 4);
-      float mm[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
-      float vv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-      float ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-      uint32_t tw[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const P2 g = mcfd::widen2(gw[k]);
-        fp32mw_elem(g.lo, mm[2 * k], vv[2 * k], ww[2 * k], sc);
-        fp32mw_elem(g.hi, mm[2 * k + 1], vv[2 * k + 1], ww[2 * k + 1], sc);
-        tw[k] = mcfd::pack2(mcfd::Exact::rnd({ww[2 * k], ww[2 * k + 1]}));
-      }
-      store_f4(mp + e0, f32x4_t{mm[0], mm[1], mm[2], mm[3]});
-      store_f4(mp + e0 + 4, f32x4_t{mm[4], mm[5], mm[6], mm[7]});
-      store_f4(vp + e0, f32x4_t{vv[0], vv[1], vv[2], vv[3]});
-      store_f4(vp + e0 + 4, f32x4_t{vv[4], vv[5], vv[6], vv[7]});
-      store_f4(master + e0, f32x4_t{ww[0], ww[1], ww[2], ww[3]});
-      store_f4(master + e0 + 4, f32x4_t{ww[4], ww[5], ww[6], ww[7]});
-      store_vec(d.theta, e0, tw);
-    } else {
-      const uint64_t lo = d.phase, hi = d.phase + d.n;
-      for (int k = 0; k < 8; ++k) {
-        const uint64_t cc = s.c0 + k;
-        if (cc < lo || cc >= hi) continue;
-        const uint64_t e = cc - lo;
-        float m = mp[e], v = vp[e], w = master[e];
-        fp32mw_elem(mcfd::bitsf((uint32_t)grad[e] << 16), m, v, w, sc);
-        mp[e] = m; vp[e] = v; master[e] = w;
-        theta[e] = (uint16_t)(mcfd::fbits(mcfd::round_bits(w)) >> 16);
-      }
+    const uint64_t lo = d.phase, hi = d.phase + d.n;
+#pragma unroll 1
+    for (int k = 0; k < 8; ++k) {
+      const uint64_t cc = s.c0 + k;
+      if (cc < lo || cc >= hi) continue;
+      const uint64_t e = cc - lo;
+      float m = mp[e], v = vp[e], w = master[e];
+      fp32mw_elem(mcfd::bitsf((uint32_t)grad[e] << 16), m, v, w, sc);
+      mp[e] = m; vp[e] = v; master[e] = w;
+      theta[e] = (uint16_t)(mcfd::fbits(mcfd::round_bits(w)) >> 16);
     }
   }
 }

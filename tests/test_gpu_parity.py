@@ -333,19 +333,26 @@ def test_fp32_master_baseline():
 
 
 # ------------------------------------------------------------------ the paper-shaped configurations
-def _sampled_run(name, steps, check_at, full_first_step=False, misalign_tiny=False, edq_first=False):
+def _sampled_run(name, steps, check_at, full_first_step=False, misalign_tiny=False, edq_first=False, drift=False):
     _say(f"{name}: allocating")
     wl = Workload(name, misalign_tiny=misalign_tiny)
     idx = sample_indices(wl.shapes, wl.offs)
     so = SampledOracle(wl, idx)
     _say(f"{name}: {wl.n_params} params in {len(wl.shapes)} tensors, {idx.size} sampled")
+    if drift:
+        theta0 = H.u16_to_f64(so.state["theta"])
+        ideal = theta0.copy()                       # theta_0 + sum of the updates, in fp64
+        plain = so.state["theta"].copy()            # the same updates added with plain bf16 addition (Eq. 1)
     full = None
     if full_first_step:
         full = {k: H.torch_to_u16(getattr(wl, k)) for k in wl.state_names()}
     edq_dev = torch.zeros(3, dtype=torch.float64, device=DEV) if edq_first else None
     for t in range(1, steps + 1):
         wl.new_grads(t)
-        so.step(t)
+        delta = so.step(t, want_delta=drift)
+        if drift:
+            ideal += H.u16_to_f64(delta)
+            plain = orc.binop(orc.ADD, plain, delta)
         if t == 1 and full_first_step:
             g = H.torch_to_u16(wl.grad)
             before = (full["theta"].copy(), full["dtheta"].copy()) if edq_first else None
@@ -376,6 +383,21 @@ def _sampled_run(name, steps, check_at, full_first_step=False, misalign_tiny=Fal
         if t in check_at:
             assert_bitwise(so.mismatches(), f"{name} step {t}")
             _say(f"{name}: step {t} sampled state ok")
+    if drift:
+        # Drift of the DEVICE's expansion against the exact sum of the updates it was given (Sec. 4: Grow keeps
+        # what plain bf16 addition loses).  Each Grow loses at most half an ulp of the second component,
+        # i.e. at most 2^-16 of |theta| per step; plain bf16 never moves because every update is below ulp/2.
+        got = H.u16_to_f64(wl.gather(wl.theta, so.idx_dev)) + H.u16_to_f64(wl.gather(wl.dtheta, so.idx_dev))
+        rel = np.abs(got - ideal) / np.abs(theta0)
+        moved = np.abs(ideal - theta0) / np.abs(theta0)
+        rel_plain = np.abs(H.u16_to_f64(plain) - ideal) / np.abs(theta0)
+        _say(f"{name}: drift after {steps} steps: max {rel.max():.3e} rms {np.sqrt(np.mean(rel ** 2)):.3e} of |theta0|; "
+             f"travelled median {np.median(moved):.3e}; plain bf16: max {rel_plain.max():.3e} rms "
+             f"{np.sqrt(np.mean(rel_plain ** 2)):.3e}, unchanged {np.mean(plain == H.np_round_f64_to_bf16(theta0)):.3f}")
+        assert rel.max() <= steps * 2.0 ** -16
+        assert np.sqrt(np.mean(rel ** 2)) <= 8 * np.sqrt(steps) * 2.0 ** -17
+        assert np.mean(plain == H.np_round_f64_to_bf16(theta0)) > 0.99          # lost arithmetic, Def. 3.2
+        assert np.sqrt(np.mean(rel ** 2)) < 0.05 * np.sqrt(np.mean(rel_plain ** 2))
     wl.close()
 
 
@@ -400,4 +422,30 @@ def test_config4_llama_7b():
 def test_config5_stress_64m():
     """Config 5: 64 Mi parameters incl. 4096 tensors of 1..256 elements at odd offsets, plus, lr = 2^-20,
     1000 steps.  Every tiny tensor and windows of the large ones are followed by the oracle."""
-    _sampled_run("stress_64m", 1000, {1, 10, 100, 500, 1000}, misalign_tiny=True)
+    _sampled_run("stress_64m", 1000, {1, 10, 100, 500, 1000}, misalign_tiny=True, drift=True)
+
+
+def test_flat_tensor_longer_than_2_pow_32():
+    """One flat tensor of 2^32 + 70,001 elements through the flat entry point (64-bit element offsets):
+    windows at the start, across the 2^32 boundary and at the ragged end are followed by the oracle."""
+    n = (1 << 32) + 70_001
+    _say("flat > 2^32: allocating")
+    z = lambda: torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    st = {"theta": z(), "dtheta": z(), "m": z(), "v": z()}
+    grad = z()
+    W.fill_grads("flat_1m", [("x", n)], [0], st["theta"], 0)          # any seeded bf16 values do
+    st["theta"].mul_(20.0)
+    w = 4096
+    idx = np.unique(np.concatenate([np.arange(0, w), np.arange((1 << 31) - w, (1 << 31) + w),
+                                    np.arange((1 << 32) - w, (1 << 32) + w), np.arange(n - w, n)]).astype(np.int64))
+    idx_dev = torch.from_numpy(idx).to(DEV)
+    host = {k: H.torch_to_u16(v[idx_dev]) for k, v in st.items()}
+    for t in range(1, 4):
+        W.fill_grads("flat_1m", [("x", n)], [0], grad, t)
+        orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], None, H.torch_to_u16(grad[idx_dev]), 0,
+                       W.HYPER_LIGHT, t)
+        mcf.adamw_step_flat(st["theta"], st["dtheta"], st["m"], st["v"], None, grad, mcf.LIGHT, W.HYPER_LIGHT, t)
+    for k, v in st.items():
+        assert np.array_equal(H.torch_to_u16(v[idx_dev]), host[k]), k
+    # and the step really ran everywhere: m is non-zero wherever the gradient is
+    assert int(torch.count_nonzero(st["m"]).item()) > 0.99 * n
