@@ -137,8 +137,8 @@ inline void adamw_element(uint16_t &theta, uint16_t &dtheta, uint16_t &m, uint16
   /* line 9: the increment (1-beta2)*g^2 */
   uint16_t inc = Fmul(s.c2, Fmul(g, g));
   uint16_t v_new;
-  if (variant == 0) {
-    /* light: v <- beta2*v + (1-beta2)*g^2 */
+  if (variant != 1) {
+    /* light (and the plain-bf16 and Kahan baselines): v <- beta2*v + (1-beta2)*g^2 */
     v_new = Fadd(Fmul(s.b2, v), inc);
   } else {
     /* plus: (v,dv) <- Grow(Mul((b2,b2l),(v,dv)), (1-beta2)*g^2) */
@@ -159,11 +159,23 @@ inline void adamw_element(uint16_t &theta, uint16_t &dtheta, uint16_t &m, uint16
   uint16_t decay = Fmul(s.lam, theta);
   uint16_t delta = Fmul(s.na, Fadd(ratio, decay));
 
-  /* line 13: (theta,dtheta) <- Grow((theta,dtheta), delta) */
-  Pair th = grow(Pair{theta, dtheta}, delta);
-
-  theta = th.hi;
-  dtheta = th.lo;
+  if (variant == 2) {
+    /* option A, Eq. 1: theta <- F(theta + delta); nothing else is kept */
+    theta = Fadd(theta, delta);
+  } else if (variant == 3) {
+    /* Kahan summation (App. B): the auxiliary variable c (stored in dtheta) is first added to
+     * the update, the sum is added to the parameter, and what that addition lost becomes the new c:
+     * c <- F(u - F(theta_new - theta_old)) */
+    uint16_t u = Fadd(delta, dtheta);
+    uint16_t theta_new = Fadd(theta, u);
+    dtheta = Fsub(u, Fsub(theta_new, theta));
+    theta = theta_new;
+  } else {
+    /* line 13: (theta,dtheta) <- Grow((theta,dtheta), delta) */
+    Pair th = grow(Pair{theta, dtheta}, delta);
+    theta = th.hi;
+    dtheta = th.lo;
+  }
   m = m_new;
   v = v_new;
   if (delta_out) *delta_out = delta;
@@ -297,9 +309,10 @@ void orc_adamw_step(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t *v,
   orc_scalars s;
   derive_scalars(*h, t, s);
   parallel_ranges(n, nthreads, [=](uint64_t lo, uint64_t hi) {
+    uint16_t unused = 0;
     for (uint64_t i = lo; i < hi; ++i)
-      adamw_element(theta[i], dtheta[i], m[i], v[i], variant ? &dv[i] : nullptr, grad[i], variant, s,
-                    delta_out ? &delta_out[i] : nullptr);
+      adamw_element(theta[i], variant == 2 ? unused : dtheta[i], m[i], v[i], variant == 1 ? &dv[i] : nullptr,
+                    grad[i], variant, s, delta_out ? &delta_out[i] : nullptr);
   });
 }
 
@@ -322,8 +335,10 @@ void orc_fp32mw_step(uint16_t *theta, float *master, float *m, float *v, const u
 }
 
 void orc_edq_accumulate(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0,
-                        const uint16_t *th1, const uint16_t *dth1, uint64_t n, double *s1, double *s2) {
+                        const uint16_t *th1, const uint16_t *dth1, uint64_t n, double *s1, double *s2,
+                        uint64_t *lost) {
   double a1 = 0.0, a2 = 0.0;
+  uint64_t nl = 0;
   for (uint64_t i = 0; i < n; ++i) {
     double d = (double)W(delta[i]);
     double before = (double)W(th0[i]) + (dth0 ? (double)W(dth0[i]) : 0.0);
@@ -331,9 +346,11 @@ void orc_edq_accumulate(const uint16_t *delta, const uint16_t *th0, const uint16
     double effective = after - before;           /* Eq. 2, extended to the expansion's value */
     a1 += d * effective;
     a2 += d * d;
+    if (d != 0.0 && effective == 0.0) nl += 1;  /* lost arithmetic (Def. 3.2): a non-zero update that changed nothing */
   }
   *s1 += a1;
   *s2 += a2;
+  if (lost) *lost += nl;
 }
 
 double orc_edq_finish(double s1, double s2) {

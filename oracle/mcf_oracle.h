@@ -74,7 +74,9 @@ typedef struct {
 void orc_scalars_derive(const orc_hyper *h, uint64_t t, orc_scalars *out);
 
 /* ---- the step (Alg. 2 lines 8-13) ----
- * variant 0 = Collage-light (option B), 1 = Collage-plus (option C; dv required).
+ * variant 0 = Collage-light (option B), 1 = Collage-plus (option C; dv required),
+ *         2 = plain bf16 (option A: line 13 is theta <- F(theta + delta), Eq. 1; dtheta unused, may be NULL),
+ *         3 = Kahan-compensated bf16 (App. B; dtheta holds the Kahan variable c).
  * All state is updated in place.  delta_out, if not NULL, receives the bf16
  * update Delta-theta of line 12 for every element.  nthreads >= 1 splits the
  * elements evenly over that many host threads (elements are independent). */
@@ -91,10 +93,13 @@ void orc_fp32mw_step(uint16_t *theta, float *master, float *m, float *v, const u
  * th0,dth0   : parameter expansion before the step (dth0 may be NULL = 0)
  * th1,dth1   : parameter expansion after the step  (dth1 may be NULL = 0)
  * Adds this slice's contributions to s1 (sum delta*effective) and s2 (sum
- * delta^2); orc_edq_finish turns the totals into EDQ = s1/sqrt(s2) (0 if s2=0). */
+ * delta^2); orc_edq_finish turns the totals into EDQ = s1/sqrt(s2) (0 if s2=0).
+ * lost, if not NULL, is increased by the number of elements with a non-zero update
+ * whose value did not change (lost arithmetic, Def. 3.2; the "imprecision
+ * percentage" of the BERT case study is this count over n). */
 void   orc_edq_accumulate(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0,
                           const uint16_t *th1, const uint16_t *dth1, uint64_t n,
-                          double *s1, double *s2);
+                          double *s1, double *s2, uint64_t *lost /* may be NULL */);
 double orc_edq_finish(double s1, double s2);
 
 #ifdef __cplusplus

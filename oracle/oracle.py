@@ -17,7 +17,7 @@ _SRC = os.path.join(_HERE, "mcf_oracle.cpp")
 _LIB = os.path.join(_HERE, "libmcf_oracle.so")
 
 ADD, SUB, MUL, DIV, SQRT = 0, 1, 2, 3, 4
-LIGHT, PLUS = 0, 1
+LIGHT, PLUS, BF16, KAHAN = 0, 1, 2, 3
 
 
 def build(force=False):
@@ -70,7 +70,7 @@ def _load():
                                                 ctypes.c_uint64, _u16p, ctypes.c_int]
     lib.orc_fp32mw_step.argtypes = [_u16p, _f32p, _f32p, _f32p, _u16p, ctypes.c_uint64,
                                     ctypes.POINTER(Hyper), ctypes.c_uint64, ctypes.c_int]
-    lib.orc_edq_accumulate.argtypes = [_u16p] * 5 + [ctypes.c_uint64, _f64p, _f64p]
+    lib.orc_edq_accumulate.argtypes = [_u16p] * 5 + [ctypes.c_uint64, _f64p, _f64p, ctypes.POINTER(ctypes.c_uint64)]
     lib.orc_edq_finish.restype = ctypes.c_double
     lib.orc_edq_finish.argtypes = [ctypes.c_double, ctypes.c_double]
     _lib = lib
@@ -184,14 +184,14 @@ def scalars(lr, beta1, beta2, eps, weight_decay, t):
 def adamw_step(theta, dtheta, m, v, dv, grad, variant, hyper, t, delta_out=None, nthreads=None):
     """In-place Collage step over uint16 arrays.  hyper = (lr, beta1, beta2, eps, weight_decay)."""
     n = theta.size
-    for arr in (dtheta, m, v, grad):
+    for arr in (m, v, grad) + (() if variant == BF16 else (dtheta,)):
         assert arr.size == n
     if variant == PLUS:
         assert dv is not None and dv.size == n
     if delta_out is not None:
         assert delta_out.size == n
     h = Hyper(*hyper)
-    _load().orc_adamw_step(_u16(theta, True), _u16(dtheta, True), _u16(m, True), _u16(v, True),
+    _load().orc_adamw_step(_u16(theta, True), None if variant == BF16 else _u16(dtheta, True), _u16(m, True), _u16(v, True),
                            _u16(dv, True) if variant == PLUS else None, _u16(grad), n, int(variant),
                            ctypes.byref(h), int(t), _u16(delta_out, True),
                            int(nthreads or default_threads()))
@@ -211,11 +211,12 @@ class EdqAccumulator:
     def __init__(self):
         self.s1 = ctypes.c_double(0.0)
         self.s2 = ctypes.c_double(0.0)
+        self.lost = ctypes.c_uint64(0)
 
     def add(self, delta, th0, dth0, th1, dth1):
         n = delta.size
         _load().orc_edq_accumulate(_u16(delta), _u16(th0), _u16(dth0), _u16(th1), _u16(dth1), n,
-                                   ctypes.byref(self.s1), ctypes.byref(self.s2))
+                                   ctypes.byref(self.s1), ctypes.byref(self.s2), ctypes.byref(self.lost))
 
     def value(self):
         return float(_load().orc_edq_finish(self.s1.value, self.s2.value))

@@ -1,0 +1,127 @@
+"""Pins for the oracle's two comparison strategies that share the Collage chain: plain bf16
+(option A, Eq. 1) and Kahan-compensated bf16 (App. B "Kahan Summation", App. D "Equivalence"),
+and for the lost-update counter (Def. 3.2; the imprecision percentage of the BERT case study).
+
+Each is checked as a composition of primitives that are pinned on their own (single bf16
+operations, Fast2Sum), against the behaviour the paper states, and by brute force.
+"""
+from fractions import Fraction
+
+import numpy as np
+
+import helpers as H
+from paper_2405_03637_amd import workloads as W
+
+
+def _state(n, seed, theta_std=0.02):
+    theta = H.torch_to_u16(W.normal_bf16(n, theta_std, (seed, 200)))
+    z = lambda: np.zeros(n, np.uint16)
+    return dict(theta=theta, dtheta=z(), m=z(), v=z())
+
+
+def _grads(n, seed, t, std=1e-3, mean=0.0):
+    return H.torch_to_u16(W.normal_bf16(n, std, (seed, 201, t), mean=mean))
+
+
+def test_plain_bf16_is_the_light_chain_with_one_rounded_addition(orc):
+    """Option A differs from Collage-light only in line 13: theta <- F(theta + delta) (Eq. 1)."""
+    n = 30_000
+    hyper = (1e-2, 0.9, 0.95, 1e-8, 0.1)
+    a, b = _state(n, 1), _state(n, 1)
+    for t in range(1, 6):
+        g = _grads(n, 1, t)
+        da, db = np.empty(n, np.uint16), np.empty(n, np.uint16)
+        theta_before = a["theta"].copy()
+        orc.adamw_step(a["theta"], None, a["m"], a["v"], None, g, orc.BF16, hyper, t, delta_out=da)
+        # the update depends on theta (weight decay), so feed light the same theta
+        b["theta"][:] = theta_before
+        b["dtheta"][:] = 0
+        orc.adamw_step(b["theta"], b["dtheta"], b["m"], b["v"], None, g, orc.LIGHT, hyper, t, delta_out=db)
+        assert np.array_equal(da, db) and np.array_equal(a["m"], b["m"]) and np.array_equal(a["v"], b["v"])
+        assert np.array_equal(a["theta"], orc.binop(orc.ADD, theta_before, da))
+
+
+def test_plain_bf16_loses_small_updates_collage_keeps_them(orc):
+    """Sec. 3.2: when |delta| <= ulp(theta)/2 the bf16 parameter does not move at all; the expansion does."""
+    n, steps = 4096, 200
+    hyper = (2.0 ** -16, 0.9, 0.95, 1e-8, 0.0)
+    plain, light = _state(n, 2, theta_std=1.0), _state(n, 2, theta_std=1.0)
+    big = np.abs(H.u16_to_f64(plain["theta"])) > 0.01        # |delta| ~ 1.5e-5 < ulp/2 there
+    th0 = plain["theta"].copy()
+    for t in range(1, steps + 1):
+        g = _grads(n, 2, t, mean=1e-3)
+        orc.adamw_step(plain["theta"], None, plain["m"], plain["v"], None, g, orc.BF16, hyper, t)
+        orc.adamw_step(light["theta"], light["dtheta"], light["m"], light["v"], None, g, orc.LIGHT, hyper, t)
+    assert np.array_equal(plain["theta"][big], th0[big])
+    moved = (H.u16_to_f64(light["theta"]) + H.u16_to_f64(light["dtheta"])) - H.u16_to_f64(th0)
+    assert np.all(moved[big] < -0.5 * steps * hyper[0])      # steady positive gradients push theta down
+
+
+def test_kahan_step_is_fast2sum_of_theta_and_compensated_update(orc):
+    """App. D "Equivalence" (i): the Kahan variable is the error term of Fast2Sum(theta, u), u = F(delta + c)."""
+    n = 30_000
+    hyper = (1e-3, 0.9, 0.95, 1e-8, 0.1)
+    st = _state(n, 3, theta_std=1.0)
+    for t in range(1, 8):
+        g = _grads(n, 3, t)
+        d = np.empty(n, np.uint16)
+        th0, c0 = st["theta"].copy(), st["dtheta"].copy()
+        orc.adamw_step(st["theta"], st["dtheta"], st["m"], st["v"], None, g, orc.KAHAN, hyper, t, delta_out=d)
+        u = orc.binop(orc.ADD, d, c0)
+        x, y = orc.fast2sum(th0, u)
+        assert np.array_equal(st["theta"], x) and np.array_equal(st["dtheta"], y)
+        ok = np.abs(H.u16_to_f64(th0)) >= np.abs(H.u16_to_f64(u))
+        exact = H.u16_to_f64(th0) + H.u16_to_f64(u)
+        assert np.array_equal((H.u16_to_f64(x) + H.u16_to_f64(y))[ok], exact[ok])
+
+
+def test_kahan_and_collage_light_follow_the_same_trajectory(orc):
+    """App. D "Equivalence": with |theta| >> |delta| both keep theta_0 + sum(delta) to the resolution of the
+    second component, and stay within a few of its ulps of each other."""
+    n, steps = 8192, 300
+    hyper = (2.0 ** -16, 0.9, 0.95, 1e-8, 0.1)
+    k, l = _state(n, 4, theta_std=1.0), _state(n, 4, theta_std=1.0)
+    th0 = H.u16_to_f64(k["theta"])
+    big = np.abs(th0) > 0.05
+    ideal = th0.copy()
+    for t in range(1, steps + 1):
+        g = _grads(n, 4, t, mean=5e-4)
+        d = np.empty(n, np.uint16)
+        orc.adamw_step(k["theta"], k["dtheta"], k["m"], k["v"], None, g, orc.KAHAN, hyper, t, delta_out=d)
+        orc.adamw_step(l["theta"], l["dtheta"], l["m"], l["v"], None, g, orc.LIGHT, hyper, t)
+        ideal += H.u16_to_f64(d)
+    vk = H.u16_to_f64(k["theta"]) + H.u16_to_f64(k["dtheta"])
+    vl = H.u16_to_f64(l["theta"]) + H.u16_to_f64(l["dtheta"])
+    assert np.all(np.abs(vk - ideal)[big] <= steps * 2.0 ** -16 * np.abs(th0)[big])
+    # weight decay makes the two delta streams differ slightly once the first components differ; the values agree
+    assert np.median(np.abs(vk - vl)[big] / np.abs(ideal - th0)[big]) < 2.0 ** -6
+    assert np.all(np.abs(vk - vl)[big] <= steps * 2.0 ** -15 * np.abs(th0)[big])
+
+
+def test_lost_update_counter(orc):
+    u = lambda vals: np.array([orc.B(v) for v in vals], np.uint16)
+    theta = u([200.0, -300.0, 1.0, 4.0, 0.5])
+    delta = u([0.1, 0.2, 0.25, 0.0, -2.0 ** -12])
+    new = orc.binop(orc.ADD, theta, delta)
+    acc = orc.EdqAccumulator()
+    acc.add(delta, theta, None, new, None)
+    # 200+0.1 and -300+0.2 are lost (Sec. 3.1 Remark), 1+0.25 is not, a zero update is not counted, 0.5-2^-12 is lost
+    assert acc.lost.value == 3
+    # with the expansion nothing is lost
+    th1, d1 = orc.grow(theta, np.zeros(5, np.uint16), delta)
+    acc = orc.EdqAccumulator()
+    acc.add(delta, theta, np.zeros(5, np.uint16), th1, d1)
+    assert acc.lost.value == 0
+    # brute force on random data
+    rng = np.random.default_rng(5)
+    n = 3000
+    th = H.np_round_f64_to_bf16(rng.standard_normal(n))
+    de = H.np_round_f64_to_bf16(rng.standard_normal(n) * 10.0 ** rng.uniform(-6, -1, n))
+    de[::17] = 0
+    nw = orc.binop(orc.ADD, th, de)
+    want = sum(1 for a, b, c in zip(th.tolist(), de.tolist(), nw.tolist())
+               if H.bf16_bits_to_fraction(b) != 0 and H.bf16_bits_to_fraction(c) == H.bf16_bits_to_fraction(a))
+    acc = orc.EdqAccumulator()
+    acc.add(de, th, None, nw, None)
+    assert acc.lost.value == want and 0 < want < n
+    assert Fraction(want, n) > Fraction(1, 10)
