@@ -54,15 +54,17 @@ def build_light_or_plus(name, variant, dev):
     shapes = W.shapes(name)
     offs, total = W.layout(shapes, misalign_tiny=(name == "stress_64m"))
     z = lambda: torch.zeros(total, dtype=torch.bfloat16, device=dev)
-    st = {"theta": z(), "dtheta": z(), "m": z(), "v": z(), "grad": z()}
+    st = {"theta": z(), "m": z(), "v": z(), "grad": z()}
+    if variant != "bf16":
+        st["dtheta"] = z()
     if variant == "plus":
         st["dv"] = z()
     W.init_theta(name, shapes, offs, st["theta"])
     drift = W.stress_drift(shapes, offs, total, dev) if name == "stress_64m" else None
     W.fill_grads(name, shapes, offs, st["grad"], 1, drift=drift)
-    tensors = [(st["theta"][o:o + n], st["dtheta"][o:o + n], st["m"][o:o + n], st["v"][o:o + n],
+    tensors = [(st["theta"][o:o + n], st["dtheta"][o:o + n] if variant != "bf16" else None, st["m"][o:o + n], st["v"][o:o + n],
                 st["dv"][o:o + n] if variant == "plus" else None, st["grad"][o:o + n]) for (_, n), o in zip(shapes, offs)]
-    plan = mcf.Plan(tensors, mcf.PLUS if variant == "plus" else mcf.LIGHT)
+    plan = mcf.Plan(tensors, {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN}[variant])
     return st, plan, W.total_params(shapes), len(shapes)
 
 
@@ -149,15 +151,18 @@ def main():
             _, s = time_steps(lambda t: mcf.stream_copy(dst[:nb], src[:nb]), 10, 2)
             extras["copy_GBps"] = 4 * nb * 10 / s / 1e9
             del src, dst
-            other = "plus" if variant == "light" else "light"
             st = None
-            torch.cuda.empty_cache()
-            st2, plan2, _, _ = build_light_or_plus(name, other, dev)
-            h2 = W.HYPER_PLUS_1P3B if other == "plus" else W.HYPER_LIGHT
-            _, s = time_steps(lambda t: plan2.step(h2, t), args.steps, args.warmup)
-            extras[f"{other}_GBps"] = W.bytes_per_param(other) * n_params * args.steps / s / 1e9
-            extras[f"{other}_ms"] = s / args.steps * 1e3
-            plan2.destroy()
+            for other in ("plus", "light", "kahan", "bf16"):      # the other strategies on the same shapes
+                if other == variant:
+                    continue
+                st2 = None
+                torch.cuda.empty_cache()
+                st2, plan2, _, _ = build_light_or_plus(name, other, dev)
+                h2 = W.HYPER_PLUS_1P3B if other == "plus" else W.HYPER_LIGHT
+                _, s = time_steps(lambda t: plan2.step(h2, t), args.steps, args.warmup)
+                extras[f"{other}_GBps"] = W.bytes_per_param(other) * n_params * args.steps / s / 1e9
+                extras[f"{other}_ms"] = s / args.steps * 1e3
+                plan2.destroy()
             # option D on the same shapes
             shapes = W.shapes(name)
             offs, total = W.layout(shapes, misalign_tiny=(name == "stress_64m"))

@@ -44,7 +44,7 @@ typedef enum {
   MCF_ERR_NULL = -1,     /* a required pointer is NULL */
   MCF_ERR_SIZE = -2,     /* a size is out of range (tensor longer than 2^35 elements, table too large) */
   MCF_ERR_ALIGN = -3,    /* a pointer is not aligned to its element size */
-  MCF_ERR_VARIANT = -4,  /* variant is neither MCF_LIGHT nor MCF_PLUS, or an operation code is unknown */
+  MCF_ERR_VARIANT = -4,  /* variant is not one of mcf_variant, or an operation code is unknown */
   MCF_ERR_STEP = -5,     /* step < 1 (the bias correction 1 - beta^0 would be zero) */
   MCF_ERR_HYPER = -6,    /* a hyper-parameter is not finite, or beta not in [0,1), or lr/eps/weight_decay < 0 */
   MCF_ERR_HIP = -7       /* a HIP runtime call failed (no device, out of memory, launch failure) */
@@ -61,12 +61,17 @@ const char *mcf_status_string(int status);
 typedef struct { double lr, beta1, beta2, eps, weight_decay; } mcf_hyper;
 
 /* Sec. 4.2: light = expansion for the parameters only (option B, 10 bytes of state
- * per parameter with the gradient); plus = also for the second moment (option C). */
-typedef enum { MCF_LIGHT = 0, MCF_PLUS = 1 } mcf_variant;
+ * per parameter with the gradient); plus = also for the second moment (option C).
+ * The other two are the paper's comparison strategies on the same chain (lines 8-12
+ * unchanged): MCF_BF16 = plain bf16, option A, line 13 is Eq. 1 theta <- F(theta + delta);
+ * MCF_KAHAN = Kahan-compensated bf16 (App. B): u = F(delta + c), theta' = F(theta + u),
+ * c <- F(u - F(theta' - theta)), with c kept in dtheta. */
+typedef enum { MCF_LIGHT = 0, MCF_PLUS = 1, MCF_BF16 = 2, MCF_KAHAN = 3 } mcf_variant;
 
 /* One parameter tensor: flat, contiguous, n elements per buffer, all device memory.
- * theta, dtheta: the parameter expansion (Alg. 2 lines 2-3); m, v: moments;
- * dv: second component of v (MCF_PLUS only, ignored and may be NULL for MCF_LIGHT);
+ * theta, dtheta: the parameter expansion (Alg. 2 lines 2-3; MCF_KAHAN: the Kahan variable;
+ * MCF_BF16: unused, may be NULL); m, v: moments;
+ * dv: second component of v (MCF_PLUS only, otherwise ignored and may be NULL);
  * grad: this step's gradient, read only. */
 typedef struct {
   uint16_t *theta, *dtheta, *m, *v, *dv;
@@ -87,10 +92,12 @@ int mcf_plan_destroy(mcf_plan *plan);      /* NULL is accepted */
 uint64_t mcf_plan_params(const mcf_plan *plan);
 
 /* One optimizer step, Alg. 2 lines 8-13, over every tensor of the plan: one launch.
- * step = t >= 1.  edq_dev: NULL, or a device pointer to 3 doubles that receive, in
- * stream order, {EDQ, S1, S2} for this step over all parameters of the plan, where
+ * step = t >= 1.  edq_dev: NULL, or a device pointer to 4 doubles that receive, in
+ * stream order, {EDQ, S1, S2, LOST} for this step over all parameters of the plan, where
  * S1 = sum delta*effective, S2 = sum delta^2, EDQ = S1/sqrt(S2) (0 if S2 = 0)
- * (Def. 3.3, Eq. 2-3, with the effective update taken on the value theta+dtheta). */
+ * (Def. 3.3, Eq. 2-3, with the effective update taken on the value theta+dtheta; on theta
+ * alone for MCF_BF16), and LOST = the number of parameters with delta != 0 whose value did
+ * not change (lost arithmetic, Def. 3.2; LOST/n is the imprecision percentage of Sec. 5.1). */
 int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *stream, double *edq_dev);
 
 /* The same step over a single flat tensor, no plan, no allocation.  n == 0 is a no-op. */

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 MCF_OK = 0
 MCF_ERR_NULL, MCF_ERR_SIZE, MCF_ERR_ALIGN, MCF_ERR_VARIANT, MCF_ERR_STEP, MCF_ERR_HYPER, MCF_ERR_HIP = \
     -1, -2, -3, -4, -5, -6, -7
-LIGHT, PLUS = 0, 1
+LIGHT, PLUS, BF16, KAHAN = 0, 1, 2, 3
 OP_ADD, OP_SUB, OP_MUL, OP_DIV, OP_SQRT = 0, 1, 2, 3, 4
 
 
@@ -146,7 +146,7 @@ class Plan:
         return int(lib().mcf_plan_params(self._h))
 
     def step(self, hyper, t, stream=None, edq_out=None):
-        """One optimizer step.  edq_out: optional float64 device tensor of 3 elements {EDQ, S1, S2}."""
+        """One optimizer step.  edq_out: optional float64 device tensor of 4 elements {EDQ, S1, S2, LOST}."""
         h = _hyper(hyper)
         _check(lib().mcf_adamw_step(self._h, ctypes.byref(h), int(t), _stream(stream), _ptr(edq_out)), "mcf_adamw_step")
 

@@ -187,19 +187,20 @@ __device__ __forceinline__ double wave_sum(double x) {
   return ((r0 + r1) + r2) + r3;
 }
 
-// Sum of (a, b) over the workgroup; valid in thread 0.  All threads must call.
+// Sum of (a, b, c) over the workgroup; valid in thread 0.  All threads must call.
 template <int THREADS = kBlock>
-__device__ __forceinline__ void block_sum2(double &a, double &b) {
-  __shared__ double sh[2 * (THREADS / 64)];
+__device__ __forceinline__ void block_sum3(double &a, double &b, double &c) {
+  __shared__ double sh[3 * (THREADS / 64)];
   a = wave_sum(a);
   b = wave_sum(b);
+  c = wave_sum(c);
   const int wave = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) { sh[2 * wave] = a; sh[2 * wave + 1] = b; }
+  if ((threadIdx.x & 63) == 0) { sh[3 * wave] = a; sh[3 * wave + 1] = b; sh[3 * wave + 2] = c; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    double sa = sh[0], sb = sh[1];
-    for (int w = 1; w < THREADS / 64; ++w) { sa += sh[2 * w]; sb += sh[2 * w + 1]; }
-    a = sa; b = sb;
+    double sa = sh[0], sb = sh[1], sc = sh[2];
+    for (int w = 1; w < THREADS / 64; ++w) { sa += sh[3 * w]; sb += sh[3 * w + 1]; sc += sh[3 * w + 2]; }
+    a = sa; b = sb; c = sc;
   }
 }
 
@@ -212,38 +213,71 @@ __device__ __forceinline__ void static_for(F &&f) {
   }
 }
 
+// ---------------------------------------------------------------- effective descent quality
+// Per-lane totals of Def. 3.3: s1 = sum delta*effective, s2 = sum delta^2, and the number of lost
+// updates (Def. 3.2: delta != 0 but the value did not change).  The effective update is taken on
+// the value theta+dtheta (Eq. 2 when there is no second component), in fp64 so that "did not
+// change" is decided exactly.
+struct EdqAcc {
+  double s1, s2;
+  uint32_t lost;
+};
+
+__device__ __forceinline__ void edq_add(EdqAcc &a, float delta, float th0, float dth0, float th1, float dth1) {
+  const double d = (double)delta;
+  const double eff = ((double)th1 + (double)dth1) - ((double)th0 + (double)dth0);
+  a.s1 = __builtin_fma(d, eff, a.s1);
+  a.s2 = __builtin_fma(d, d, a.s2);
+  a.lost += (d != 0.0 && eff == 0.0) ? 1u : 0u;
+}
+
+constexpr int kEdqVals = 3;              // doubles per partial: s1, s2, lost
+
+// One partial per workgroup.  All threads must call.
+template <int THREADS>
+__device__ __forceinline__ void edq_store_partial(const EdqAcc &a, double *__restrict__ partials, uint64_t index) {
+  double s1 = a.s1, s2 = a.s2, lost = (double)a.lost;
+  block_sum3<THREADS>(s1, s2, lost);
+  if (threadIdx.x == 0) {
+    partials[kEdqVals * index] = s1;
+    partials[kEdqVals * index + 1] = s2;
+    partials[kEdqVals * index + 2] = lost;
+  }
+}
+
 // ---------------------------------------------------------------- the step kernel
+template <int VARIANT> struct StepStreams {
+  static constexpr bool kDth = VARIANT != mcfd::V_BF16;      // second component of theta / Kahan variable
+  static constexpr bool kDv = VARIANT == mcfd::V_PLUS;       // second component of v
+};
+
 // Hot path: one full slot, 8 elements of every stream held as 4 dwords each.  Returns true
 // when the Fast arithmetic mode asks for the slot to be recomputed in Exact mode.
 template <class M, int VARIANT, bool EDQ>
 __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], uint32_t (&out)[kMaxStreams][4],
-                                         const StepScalars &sc, float &s1, float &s2) {
+                                         const StepScalars &sc, EdqAcc &acc) {
+  using SS = StepStreams<VARIANT>;
   bool redo = false;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     ElemIO io;
     io.th = mcfd::widen2(in[S_TH][k]);
-    io.dth = mcfd::widen2(in[S_DTH][k]);
+    if (SS::kDth) io.dth = mcfd::widen2(in[S_DTH][k]); else io.dth = {0.f, 0.f};
     io.m = mcfd::widen2(in[S_M][k]);
     io.v = mcfd::widen2(in[S_V][k]);
     io.g = mcfd::widen2(in[S_G][k]);
-    if (VARIANT == 1) io.dv = mcfd::widen2(in[S_DV][k]); else io.dv = {0.f, 0.f};
+    if (SS::kDv) io.dv = mcfd::widen2(in[S_DV][k]); else io.dv = {0.f, 0.f};
     const P2 th0 = io.th, dth0 = io.dth;
     P2 delta;
     mcfd::adamw_pair<M, VARIANT>(io, sc, delta, redo);
     out[S_TH][k] = mcfd::pack2(io.th);
-    out[S_DTH][k] = mcfd::pack2(io.dth);
+    if (SS::kDth) out[S_DTH][k] = mcfd::pack2(io.dth);
     out[S_M][k] = mcfd::pack2(io.m);
     out[S_V][k] = mcfd::pack2(io.v);
-    if (VARIANT == 1) out[S_DV][k] = mcfd::pack2(io.dv);
+    if (SS::kDv) out[S_DV][k] = mcfd::pack2(io.dv);
     if (EDQ) {
-      // effective update of the value theta+dtheta (Eq. 2); differences of neighbouring bf16 are exact
-      const float e_lo = (io.th.lo - th0.lo) + (io.dth.lo - dth0.lo);
-      const float e_hi = (io.th.hi - th0.hi) + (io.dth.hi - dth0.hi);
-      s1 = __builtin_fmaf(delta.lo, e_lo, s1);
-      s1 = __builtin_fmaf(delta.hi, e_hi, s1);
-      s2 = __builtin_fmaf(delta.lo, delta.lo, s2);
-      s2 = __builtin_fmaf(delta.hi, delta.hi, s2);
+      edq_add(acc, delta.lo, th0.lo, dth0.lo, io.th.lo, io.dth.lo);
+      edq_add(acc, delta.hi, th0.hi, dth0.hi, io.th.hi, io.dth.hi);
     }
   }
   return redo;
@@ -254,7 +288,8 @@ __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], u
 // mutually aligned, and slots the hot path asked to redo (their inputs are still in memory:
 // nothing of the slot has been stored yet).
 template <int VARIANT, bool EDQ>
-__device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, const StepScalars &sc, float &s1, float &s2) {
+__device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, const StepScalars &sc, EdqAcc &acc) {
+  using SS = StepStreams<VARIANT>;
   const uint64_t lo = d.phase, hi = d.phase + d.n;
   MCF_GLOBAL uint16_t *th = gptr<uint16_t>(d.p[S_TH]);
   MCF_GLOBAL uint16_t *dth = gptr<uint16_t>(d.p[S_DTH]);
@@ -269,25 +304,21 @@ __device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, cons
     const uint64_t e = c - lo;
     ElemIO io;                       // the element rides in the low half of a pair
     io.th = mcfd::widen2(th[e]);
-    io.dth = mcfd::widen2(dth[e]);
+    if (SS::kDth) io.dth = mcfd::widen2(dth[e]); else io.dth = {0.f, 0.f};
     io.m = mcfd::widen2(m[e]);
     io.v = mcfd::widen2(v[e]);
     io.g = mcfd::widen2(g[e]);
-    if (VARIANT == 1) io.dv = mcfd::widen2(dv[e]); else io.dv = {0.f, 0.f};
+    if (SS::kDv) io.dv = mcfd::widen2(dv[e]); else io.dv = {0.f, 0.f};
     const float th0 = io.th.lo, dth0 = io.dth.lo;
     P2 delta;
     bool unused = false;
     mcfd::adamw_pair<mcfd::Exact, VARIANT>(io, sc, delta, unused);
     th[e] = (uint16_t)(mcfd::fbits(io.th.lo) >> 16);
-    dth[e] = (uint16_t)(mcfd::fbits(io.dth.lo) >> 16);
+    if (SS::kDth) dth[e] = (uint16_t)(mcfd::fbits(io.dth.lo) >> 16);
     m[e] = (uint16_t)(mcfd::fbits(io.m.lo) >> 16);
     v[e] = (uint16_t)(mcfd::fbits(io.v.lo) >> 16);
-    if (VARIANT == 1) dv[e] = (uint16_t)(mcfd::fbits(io.dv.lo) >> 16);
-    if (EDQ) {
-      const float eff = (io.th.lo - th0) + (io.dth.lo - dth0);
-      s1 = __builtin_fmaf(delta.lo, eff, s1);
-      s2 = __builtin_fmaf(delta.lo, delta.lo, s2);
-    }
+    if (SS::kDv) dv[e] = (uint16_t)(mcfd::fbits(io.dv.lo) >> 16);
+    if (EDQ) edq_add(acc, delta.lo, th0, dth0, io.th.lo, io.dth.lo);
   }
 }
 
@@ -295,7 +326,7 @@ template <int VARIANT, bool FAST, bool EDQ, bool TABLE>
 __global__ void __launch_bounds__(kStepBlock) MCF_STEP_ATTR
 adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, TensorDesc flat,
              StepScalars sc, double *__restrict__ partials, uint32_t n_chunks) {
-  constexpr int NS = VARIANT == 1 ? 6 : 5;
+  using SS = StepStreams<VARIANT>;
   using Mode = typename std::conditional<FAST, mcfd::Fast, mcfd::Exact>::type;
   TensorDesc d;
   uint64_t slot0;
@@ -324,28 +355,33 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
     constexpr int j = decltype(jc)::value;
     slot[j] = classify(d, slot0 + (uint64_t)j * kStepBlock + threadIdx.x);
     if (slot[j].full) {
-#pragma unroll
-      for (int s = 0; s < NS; ++s) load_vec(d.p[s], slot[j].c0 - d.phase, in[j][s]);
+      const uint64_t e0 = slot[j].c0 - d.phase;
+      load_vec(d.p[S_TH], e0, in[j][S_TH]);
+      if (SS::kDth) load_vec(d.p[S_DTH], e0, in[j][S_DTH]);
+      load_vec(d.p[S_M], e0, in[j][S_M]);
+      load_vec(d.p[S_V], e0, in[j][S_V]);
+      load_vec(d.p[S_G], e0, in[j][S_G]);
+      if (SS::kDv) load_vec(d.p[S_DV], e0, in[j][S_DV]);
     }
   });
 
-  double acc1 = 0.0, acc2 = 0.0;
+  EdqAcc acc = {0.0, 0.0, 0u};
   uint32_t cold = 0;          // bit j: slot j still has to go through the cold path
   static_for<0, kUnroll>([&](auto jc) {
     constexpr int j = decltype(jc)::value;
     if (slot[j].full) {
       uint32_t out[kMaxStreams][4];
-      float s1 = 0.f, s2 = 0.f;
-      if (hot_slot<Mode, VARIANT, EDQ>(in[j], out, sc, s1, s2)) {
+      EdqAcc local = {0.0, 0.0, 0u};
+      if (hot_slot<Mode, VARIANT, EDQ>(in[j], out, sc, local)) {
         cold |= 1u << j;
       } else {
         const uint64_t e0 = slot[j].c0 - d.phase;
         store_vec(d.p[S_TH], e0, out[S_TH]);
-        store_vec(d.p[S_DTH], e0, out[S_DTH]);
+        if (SS::kDth) store_vec(d.p[S_DTH], e0, out[S_DTH]);
         store_vec(d.p[S_M], e0, out[S_M]);
         store_vec(d.p[S_V], e0, out[S_V]);
-        if (VARIANT == 1) store_vec(d.p[S_DV], e0, out[S_DV]);
-        if (EDQ) { acc1 += (double)s1; acc2 += (double)s2; }
+        if (SS::kDv) store_vec(d.p[S_DV], e0, out[S_DV]);
+        if (EDQ) { acc.s1 += local.s1; acc.s2 += local.s2; acc.lost += local.lost; }
       }
     } else if (slot[j].any) {
       cold |= 1u << j;
@@ -355,15 +391,12 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
 #pragma unroll 1
     for (int j = 0; j < kUnroll; ++j) {
       if (!((cold >> j) & 1u)) continue;
-      float s1 = 0.f, s2 = 0.f;
-      cold_slot<VARIANT, EDQ>(d, (slot0 + (uint64_t)j * kStepBlock + threadIdx.x) * 8, sc, s1, s2);
-      if (EDQ) { acc1 += (double)s1; acc2 += (double)s2; }
+      EdqAcc local = {0.0, 0.0, 0u};
+      cold_slot<VARIANT, EDQ>(d, (slot0 + (uint64_t)j * kStepBlock + threadIdx.x) * 8, sc, local);
+      if (EDQ) { acc.s1 += local.s1; acc.s2 += local.s2; acc.lost += local.lost; }
     }
   }
-  if (EDQ) {
-    block_sum2<kStepBlock>(acc1, acc2);
-    if (threadIdx.x == 0) { partials[2 * (uint64_t)chunk_id] = acc1; partials[2 * (uint64_t)chunk_id + 1] = acc2; }
-  }
+  if (EDQ) edq_store_partial<kStepBlock>(acc, partials, chunk_id);
 }
 
 // ---------------------------------------------------------------- EDQ reduction tail
@@ -375,22 +408,27 @@ edq_stage1(const double *__restrict__ partials, uint64_t count, uint64_t per, do
   const uint64_t lo = (uint64_t)blockIdx.x * per;
   uint64_t hi = lo + per;
   if (hi > count) hi = count;
-  double a = 0.0, b = 0.0;
-  for (uint64_t i = lo + threadIdx.x; i < hi; i += kBlock) { a += partials[2 * i]; b += partials[2 * i + 1]; }
-  block_sum2(a, b);
-  if (threadIdx.x == 0) { mid[2 * blockIdx.x] = a; mid[2 * blockIdx.x + 1] = b; }
+  double a = 0.0, b = 0.0, c = 0.0;
+  for (uint64_t i = lo + threadIdx.x; i < hi; i += kBlock) {
+    a += partials[kEdqVals * i];
+    b += partials[kEdqVals * i + 1];
+    c += partials[kEdqVals * i + 2];
+  }
+  block_sum3(a, b, c);
+  if (threadIdx.x == 0) { mid[kEdqVals * blockIdx.x] = a; mid[kEdqVals * blockIdx.x + 1] = b; mid[kEdqVals * blockIdx.x + 2] = c; }
 }
 
-// Stage 2: one block sums mid[0..nmid) and writes {EDQ, S1, S2}.
+// Stage 2: one block sums mid[0..nmid) and writes {EDQ, S1, S2, lost}.
 __global__ void __launch_bounds__(kBlock)
-edq_stage2(const double *__restrict__ mid, uint32_t nmid, double *__restrict__ out3) {
-  double a = 0.0, b = 0.0;
-  for (uint32_t i = threadIdx.x; i < nmid; i += kBlock) { a += mid[2 * i]; b += mid[2 * i + 1]; }
-  block_sum2(a, b);
+edq_stage2(const double *__restrict__ mid, uint32_t nmid, double *__restrict__ out4) {
+  double a = 0.0, b = 0.0, c = 0.0;
+  for (uint32_t i = threadIdx.x; i < nmid; i += kBlock) { a += mid[kEdqVals * i]; b += mid[kEdqVals * i + 1]; c += mid[kEdqVals * i + 2]; }
+  block_sum3(a, b, c);
   if (threadIdx.x == 0) {
-    out3[0] = (b == 0.0) ? 0.0 : a / sqrt(b);
-    out3[1] = a;
-    out3[2] = b;
+    out4[0] = (b == 0.0) ? 0.0 : a / sqrt(b);
+    out4[1] = a;
+    out4[2] = b;
+    out4[3] = c;
   }
 }
 
@@ -405,7 +443,7 @@ struct PrimArgs {
 
 template <class M, int OP>
 __device__ __forceinline__ void prim_words(const uint32_t (&in)[kMaxStreams][4], uint32_t (&out)[kMaxStreams][4],
-                                           bool &redo, float &s1, float &s2, bool has_d0, bool has_d1) {
+                                           bool &redo, EdqAcc &acc, uint32_t valid) {
   using O = mcfd::Ops<M>;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
@@ -431,19 +469,11 @@ __device__ __forceinline__ void prim_words(const uint32_t (&in)[kMaxStreams][4],
       x = O::sqrt(a, redo);
     }
     if (OP == P_EDQ) {
-      // streams: delta, th0, th1, dth0, dth1 ; fp32 differences of bf16 neighbours are exact
-      P2 th1 = mcfd::widen2(in[2][k]);
-      float e_lo = th1.lo - b.lo, e_hi = th1.hi - b.hi;
-      if (has_d0 | has_d1) {
-        P2 d0 = has_d0 ? mcfd::widen2(in[3][k]) : P2{0.f, 0.f};
-        P2 d1 = has_d1 ? mcfd::widen2(in[4][k]) : P2{0.f, 0.f};
-        e_lo += d1.lo - d0.lo;
-        e_hi += d1.hi - d0.hi;
-      }
-      s1 = __builtin_fmaf(a.lo, e_lo, s1);
-      s1 = __builtin_fmaf(a.hi, e_hi, s1);
-      s2 = __builtin_fmaf(a.lo, a.lo, s2);
-      s2 = __builtin_fmaf(a.hi, a.hi, s2);
+      // streams: delta, th0, th1, dth0, dth1 (absent second components were loaded as zeros);
+      // elements outside the tensor are skipped so that they cannot count as lost updates
+      const P2 th1 = mcfd::widen2(in[2][k]), d0 = mcfd::widen2(in[3][k]), d1 = mcfd::widen2(in[4][k]);
+      if (valid & (1u << (2 * k))) edq_add(acc, a.lo, b.lo, d0.lo, th1.lo, d1.lo);
+      if (valid & (1u << (2 * k + 1))) edq_add(acc, a.hi, b.hi, d0.hi, th1.hi, d1.hi);
     }
     if (M::kFast && OP != P_EDQ) redo |= mcfd::is_nan(x.lo) | mcfd::is_nan(x.hi) | mcfd::is_nan(y.lo) | mcfd::is_nan(y.hi);
     out[0][k] = mcfd::pack2(x);
@@ -463,38 +493,36 @@ __global__ void __launch_bounds__(kBlock) prim_kernel(PrimArgs a, uint32_t has_d
   for (int s = 0; s < kMaxStreams; ++s) d.p[s] = a.p[s];
   d.n = a.n; d.phase = a.phase; d.scalar_only = a.scalar_only;
   const Slot s = classify(d, (uint64_t)blockIdx.x * kBlock + threadIdx.x);
-  double acc1 = 0.0, acc2 = 0.0;
+  EdqAcc acc = {0.0, 0.0, 0u};
   if (s.any) {
     uint32_t in[kMaxStreams][4] = {};
     uint32_t out[kMaxStreams][4];
     constexpr int nin = (OP == P_GROW) ? 3 : (OP == P_SQRT) ? 1 : 2;
+    uint32_t valid = 0xffu;              // which of the slot's 8 elements belong to the tensor
     if (OP == P_EDQ) {
       load_slot(d.p[0], d, s, in[0]);
       load_slot(d.p[1], d, s, in[1]);
       load_slot(d.p[2], d, s, in[2]);
       if (has_d0) load_slot(d.p[3], d, s, in[3]);
       if (has_d1) load_slot(d.p[4], d, s, in[4]);
+      valid = 0;
+      for (int k = 0; k < 8; ++k)
+        if (s.c0 + k >= d.phase && s.c0 + k < d.phase + d.n) valid |= 1u << k;
     } else {
 #pragma unroll
       for (int k = 0; k < nin; ++k) load_slot(d.p[k], d, s, in[k]);
     }
-    float s1 = 0.f, s2 = 0.f;
     bool redo = false;
-    prim_words<mcfd::Fast, OP>(in, out, redo, s1, s2, has_d0, has_d1);
+    prim_words<mcfd::Fast, OP>(in, out, redo, acc, valid);
     if (redo) {
       bool unused = false;
-      s1 = 0.f; s2 = 0.f;
-      prim_words<mcfd::Exact, OP>(in, out, unused, s1, s2, has_d0, has_d1);
+      prim_words<mcfd::Exact, OP>(in, out, unused, acc, valid);
     }
     if (OP == P_FAST2SUM || OP == P_TWOSUM) { store_slot(d.p[2], d, s, out[0]); store_slot(d.p[3], d, s, out[1]); }
     if (OP == P_GROW) { store_slot(d.p[0], d, s, out[0]); store_slot(d.p[1], d, s, out[1]); }
     if (OP == P_ADD || OP == P_SUB || OP == P_MUL || OP == P_DIV || OP == P_SQRT) store_slot(d.p[2], d, s, out[0]);
-    acc1 = (double)s1; acc2 = (double)s2;
   }
-  if (OP == P_EDQ) {
-    block_sum2(acc1, acc2);
-    if (threadIdx.x == 0) { partials[2 * (uint64_t)blockIdx.x] = acc1; partials[2 * (uint64_t)blockIdx.x + 1] = acc2; }
-  }
+  if (OP == P_EDQ) edq_store_partial<kBlock>(acc, partials, blockIdx.x);
 }
 
 // fp32 -> bf16 over an array (the rounding inside F).  Two elements per lane.
@@ -645,26 +673,31 @@ inline void phase_of(const uint64_t *ptrs, int count, uint32_t &phase, uint32_t 
 
 inline uint64_t slots_of(uint64_t n, uint32_t phase) { return (n + phase + 7) / 8; }
 
+inline bool known_variant(int v) { return v == MCF_LIGHT || v == MCF_PLUS || v == MCF_BF16 || v == MCF_KAHAN; }
+
 int check_tensor(const mcf_tensor &t, int variant) {
   if (t.n == 0) return MCF_OK;
-  if (!t.theta || !t.dtheta || !t.m || !t.v || !t.grad) return MCF_ERR_NULL;
-  if (variant == MCF_PLUS && !t.dv) return MCF_ERR_NULL;
+  const bool need_dth = variant != MCF_BF16, need_dv = variant == MCF_PLUS;
+  if (!t.theta || !t.m || !t.v || !t.grad) return MCF_ERR_NULL;
+  if ((need_dth && !t.dtheta) || (need_dv && !t.dv)) return MCF_ERR_NULL;
   if (t.n > kMaxTensorElems) return MCF_ERR_SIZE;
-  if (misaligned(t.theta, 2) || misaligned(t.dtheta, 2) || misaligned(t.m, 2) || misaligned(t.v, 2) ||
-      misaligned(t.grad, 2) || (variant == MCF_PLUS && misaligned(t.dv, 2)))
+  if (misaligned(t.theta, 2) || misaligned(t.m, 2) || misaligned(t.v, 2) || misaligned(t.grad, 2) ||
+      (need_dth && misaligned(t.dtheta, 2)) || (need_dv && misaligned(t.dv, 2)))
     return MCF_ERR_ALIGN;
   return MCF_OK;
 }
 
+// Streams a variant does not use point at theta (v for dv): they are never accessed and do
+// not disturb the alignment class.
 void fill_desc(const mcf_tensor &t, int variant, TensorDesc &d) {
   d.p[S_TH] = (uint64_t)(uintptr_t)t.theta;
-  d.p[S_DTH] = (uint64_t)(uintptr_t)t.dtheta;
+  d.p[S_DTH] = variant != MCF_BF16 ? (uint64_t)(uintptr_t)t.dtheta : d.p[S_TH];
   d.p[S_M] = (uint64_t)(uintptr_t)t.m;
   d.p[S_V] = (uint64_t)(uintptr_t)t.v;
   d.p[S_G] = (uint64_t)(uintptr_t)t.grad;
   d.p[S_DV] = variant == MCF_PLUS ? (uint64_t)(uintptr_t)t.dv : d.p[S_V];
   d.n = t.n;
-  phase_of(d.p, variant == MCF_PLUS ? 6 : 5, d.phase, d.scalar_only);
+  phase_of(d.p, 6, d.phase, d.scalar_only);
 }
 
 template <int VARIANT, bool TABLE>
@@ -684,7 +717,18 @@ void launch_step(bool fast, bool edq, uint32_t blocks, hipStream_t st, const Ten
   }
 }
 
-// Reduce `count` pairs of partials to {EDQ, S1, S2}; mid holds 2*kStage1Blocks doubles.
+template <bool TABLE>
+void launch_variant(int variant, bool fast, bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs,
+                    const Chunk *chunks, const TensorDesc &flat, const StepScalars &sc, double *partials) {
+  switch (variant) {
+    case MCF_PLUS: launch_step<mcfd::V_PLUS, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
+    case MCF_BF16: launch_step<mcfd::V_BF16, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
+    case MCF_KAHAN: launch_step<mcfd::V_KAHAN, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
+    default: launch_step<mcfd::V_LIGHT, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
+  }
+}
+
+// Reduce `count` partials (kEdqVals doubles each) to {EDQ, S1, S2, lost}; mid holds kEdqVals*kStage1Blocks doubles.
 int launch_edq_tail(const double *partials, uint64_t count, double *mid, double *out3, hipStream_t st) {
   uint64_t per = (count + kStage1Blocks - 1) / kStage1Blocks;
   if (per == 0) per = 1;
@@ -739,7 +783,7 @@ int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, i
   if (!out) return MCF_ERR_NULL;
   *out = nullptr;
   if (count && !tensors) return MCF_ERR_NULL;
-  if (variant != MCF_LIGHT && variant != MCF_PLUS) return MCF_ERR_VARIANT;
+  if (!known_variant(variant)) return MCF_ERR_VARIANT;
   for (uint32_t i = 0; i < count; ++i) {
     const int rc = check_tensor(tensors[i], variant);
     if (rc != MCF_OK) return rc;
@@ -771,7 +815,7 @@ int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, i
   if (p->n_chunks) {
     bool ok = hipMalloc((void **)&p->d_descs, descs.size() * sizeof(TensorDesc)) == hipSuccess &&
               hipMalloc((void **)&p->d_chunks, chunks.size() * sizeof(Chunk)) == hipSuccess &&
-              hipMalloc((void **)&p->d_partials, (2ull * p->n_chunks + 2ull * kStage1Blocks) * sizeof(double)) == hipSuccess &&
+              hipMalloc((void **)&p->d_partials, (uint64_t)kEdqVals * ((uint64_t)p->n_chunks + kStage1Blocks) * sizeof(double)) == hipSuccess &&
               hipMemcpy(p->d_descs, descs.data(), descs.size() * sizeof(TensorDesc), hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(p->d_chunks, chunks.data(), chunks.size() * sizeof(Chunk), hipMemcpyHostToDevice) == hipSuccess;
     if (!ok) {
@@ -806,15 +850,13 @@ int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *
   hipStream_t st = (hipStream_t)stream;
   const TensorDesc none = {};
   if (plan->n_chunks) {
-    if (plan->variant == MCF_PLUS)
-      launch_step<1, true>(fast, edq_dev != nullptr, plan->n_chunks, st, plan->d_descs, plan->d_chunks, none, sc, plan->d_partials);
-    else
-      launch_step<0, true>(fast, edq_dev != nullptr, plan->n_chunks, st, plan->d_descs, plan->d_chunks, none, sc, plan->d_partials);
+    launch_variant<true>(plan->variant, fast, edq_dev != nullptr, plan->n_chunks, st, plan->d_descs, plan->d_chunks, none, sc,
+                         plan->d_partials);
     MCF_HIP(hipGetLastError());
   }
   if (edq_dev) {
     // with no chunks the tail sums nothing and writes zeros
-    return launch_edq_tail(plan->d_partials, plan->n_chunks, plan->d_partials + 2ull * plan->n_chunks, edq_dev, st);
+    return launch_edq_tail(plan->d_partials, plan->n_chunks, plan->d_partials + (uint64_t)kEdqVals * plan->n_chunks, edq_dev, st);
   }
   return MCF_OK;
 }
@@ -822,7 +864,7 @@ int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *
 int mcf_adamw_step_flat(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t *v, uint16_t *dv,
                         const uint16_t *grad, uint64_t n, int variant, const mcf_hyper *hyper,
                         uint64_t step, void *stream) {
-  if (variant != MCF_LIGHT && variant != MCF_PLUS) return MCF_ERR_VARIANT;
+  if (!known_variant(variant)) return MCF_ERR_VARIANT;
   const mcf_tensor t = {theta, dtheta, m, v, dv, grad, n};
   int rc = check_tensor(t, variant);
   if (rc != MCF_OK) return rc;
@@ -834,8 +876,7 @@ int mcf_adamw_step_flat(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t
   const uint64_t nch = (slots_of(d.n, d.phase) + kSlotsPerChunk - 1) / kSlotsPerChunk;
   StepScalars sc;
   const bool fast = mcfh::derive_scalars(*hyper, step, sc) && !force_exact();
-  if (variant == MCF_PLUS) launch_step<1, false>(fast, false, (uint32_t)nch, (hipStream_t)stream, nullptr, nullptr, d, sc, nullptr);
-  else launch_step<0, false>(fast, false, (uint32_t)nch, (hipStream_t)stream, nullptr, nullptr, d, sc, nullptr);
+  launch_variant<false>(variant, fast, false, (uint32_t)nch, (hipStream_t)stream, nullptr, nullptr, d, sc, nullptr);
   MCF_HIP(hipGetLastError());
   return MCF_OK;
 }
@@ -928,7 +969,7 @@ int mcf_stream_copy(void *dst, const void *src, uint64_t bytes, void *stream) {
 
 uint64_t mcf_edq_scratch_bytes(uint64_t n) {
   const uint64_t blocks = (slots_of(n, 7) + kBlock - 1) / kBlock + 1;
-  return (2 * blocks + 2ull * kStage1Blocks) * sizeof(double);
+  return (uint64_t)kEdqVals * (blocks + kStage1Blocks) * sizeof(double);
 }
 
 int mcf_edq(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
@@ -957,7 +998,7 @@ int mcf_edq(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, co
   hipLaunchKernelGGL(prim_kernel<P_EDQ>, dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, a,
                      dth0 ? 1u : 0u, dth1 ? 1u : 0u, partials);
   MCF_HIP(hipGetLastError());
-  return launch_edq_tail(partials, blocks, partials + 2 * blocks, edq_dev, (hipStream_t)stream);
+  return launch_edq_tail(partials, blocks, partials + kEdqVals * blocks, edq_dev, (hipStream_t)stream);
 }
 
 int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tensors, uint32_t count) {

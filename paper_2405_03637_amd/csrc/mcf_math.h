@@ -131,9 +131,14 @@ struct ElemIO {          // one pair of elements of every stream
   P2 th, dth, m, v, dv, g;
 };
 
-// Alg. 2 lines 8-13 on one pair.  VARIANT 0 = light, 1 = plus.  On return io holds the new
-// theta, dtheta, m, v (and dv); delta receives line 12's update.  redo is raised (Fast mode)
-// when this pair must be recomputed in Exact mode.
+// Variants of the step.  Light and plus are Collage (Sec. 4.2); the other two are the paper's
+// comparison strategies built on the same chain: plain bf16 (option A: line 13 is Eq. 1,
+// theta <- F(theta + delta)) and Kahan-compensated bf16 (App. B; dtheta holds the Kahan variable).
+enum : int { V_LIGHT = 0, V_PLUS = 1, V_BF16 = 2, V_KAHAN = 3 };
+
+// Alg. 2 lines 8-13 on one pair.  On return io holds the new theta, dtheta, m, v (and dv);
+// delta receives line 12's update.  redo is raised (Fast mode) when this pair must be
+// recomputed in Exact mode.
 template <class M, int VARIANT>
 __device__ __forceinline__ void adamw_pair(ElemIO &io, const StepScalars &s, P2 &delta, bool &redo) {
   using O = Ops<M>;
@@ -142,7 +147,7 @@ __device__ __forceinline__ void adamw_pair(ElemIO &io, const StepScalars &s, P2 
   // line 9
   P2 inc = O::muls(s.c2, O::mul(io.g, io.g));
   P2 v1, dv1 = {0.f, 0.f};
-  if (VARIANT == 0) {
+  if (VARIANT != V_PLUS) {
     v1 = O::add(O::muls(s.b2, io.v), inc);
   } else {
     // Mul((b2, b2l), (v, dv)), Alg. 8 with TwoProdFMA (Alg. 6)
@@ -163,13 +168,20 @@ __device__ __forceinline__ void adamw_pair(ElemIO &io, const StepScalars &s, P2 
   P2 w = O::muls(s.lam, io.th);
   delta = O::muls(s.na, O::add(q, w));
   // line 13
-  P2 th1, dth1;
-  O::grow(io.th, io.dth, delta, th1, dth1);
+  P2 th1, dth1 = {0.f, 0.f};
+  if (VARIANT == V_BF16) {
+    th1 = O::add(io.th, delta);                       // Eq. 1
+  } else if (VARIANT == V_KAHAN) {
+    const P2 u = O::add(delta, io.dth);               // compensate the update with the Kahan variable
+    O::fast2sum(io.th, u, th1, dth1);                 // c <- F(u - F(theta' - theta))
+  } else {
+    O::grow(io.th, io.dth, delta, th1, dth1);
+  }
   if (M::kFast) {
     // Any NaN produced or consumed above reaches theta' or dtheta' (or dv'): m' and v' feed
     // the quotient, the quotient feeds delta, delta feeds theta'.
     redo |= is_nan(th1.lo) | is_nan(dth1.lo) | is_nan(th1.hi) | is_nan(dth1.hi);
-    if (VARIANT == 1) redo |= is_nan(dv1.lo) | is_nan(dv1.hi);
+    if (VARIANT == V_PLUS) redo |= is_nan(dv1.lo) | is_nan(dv1.hi);
   }
   io.th = th1;
   io.dth = dth1;

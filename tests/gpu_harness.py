@@ -41,13 +41,14 @@ class Workload:
         self.name = name
         self.shapes = shape_list if shape_list is not None else W.shapes(name)
         vname = variant or W.WORKLOADS[name][1]
-        self.variant = mcf.PLUS if vname == "plus" else mcf.LIGHT
+        self.variant = {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN}[vname]
         self.hyper = hyper or W.WORKLOADS[name][2]
         self.offs, self.total = W.layout(self.shapes, misalign_tiny=misalign_tiny, align=align)
         self.seed = seed
         self.device = device
         z = lambda: torch.zeros(self.total, dtype=torch.bfloat16, device=device)
-        self.theta, self.dtheta, self.m, self.v = z(), z(), z(), z()
+        self.theta, self.m, self.v = z(), z(), z()
+        self.dtheta = z() if self.variant != mcf.BF16 else None
         self.dv = z() if self.variant == mcf.PLUS else None
         self.grad = z()
         W.init_theta(name, self.shapes, self.offs, self.theta, seed=seed)
@@ -56,14 +57,14 @@ class Workload:
         tensors = []
         for (_, n), o in zip(self.shapes, self.offs):
             sl = slice(o, o + n)
-            tensors.append((self.theta[sl], self.dtheta[sl], self.m[sl], self.v[sl],
+            tensors.append((self.theta[sl], self.dtheta[sl] if self.dtheta is not None else None, self.m[sl], self.v[sl],
                             self.dv[sl] if self.dv is not None else None, self.grad[sl]))
         self.plan = mcf.Plan(tensors, self.variant)
         self.n_params = W.total_params(self.shapes)
         assert self.plan.params == self.n_params
 
     def state_names(self):
-        return ["theta", "dtheta", "m", "v"] + (["dv"] if self.dv is not None else [])
+        return ["theta"] + (["dtheta"] if self.dtheta is not None else []) + ["m", "v"] + (["dv"] if self.dv is not None else [])
 
     def new_grads(self, step):
         W.fill_grads(self.name, self.shapes, self.offs, self.grad, step, seed=self.seed, sigmas=self.sigmas,
@@ -93,7 +94,7 @@ class SampledOracle:
         g = self.wl.gather(self.wl.grad, self.idx_dev)
         s = self.state
         delta = np.empty(g.size, np.uint16) if want_delta else None
-        orc.adamw_step(s["theta"], s["dtheta"], s["m"], s["v"], s.get("dv"), g, self.wl.variant, self.wl.hyper, t,
+        orc.adamw_step(s["theta"], s.get("dtheta"), s["m"], s["v"], s.get("dv"), g, self.wl.variant, self.wl.hyper, t,
                        delta_out=delta)
         return delta
 

@@ -52,7 +52,8 @@ def test_flat_step_argument_errors():
     assert _flat(theta=None) == mcf.MCF_ERR_NULL
     assert _flat(grad=None) == mcf.MCF_ERR_NULL
     assert _flat(variant=1, dv=None) == mcf.MCF_ERR_NULL
-    assert _flat(variant=2) == mcf.MCF_ERR_VARIANT
+    assert _flat(variant=4) == mcf.MCF_ERR_VARIANT
+    assert _flat(variant=3, dtheta=None) == mcf.MCF_ERR_NULL          # Kahan needs its variable
     assert _flat(variant=-1) == mcf.MCF_ERR_VARIANT
     assert _flat(m=FAKE + 1) == mcf.MCF_ERR_ALIGN
     assert _flat(n=(1 << 35) + 1) == mcf.MCF_ERR_SIZE

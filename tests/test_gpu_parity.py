@@ -131,17 +131,17 @@ def _full_oracle_run(wl, steps, edq=False, check_each=True):
     """Whole-state comparison after every step, oracle over every element."""
     names = wl.state_names()
     host = {k: H.torch_to_u16(getattr(wl, k)) for k in names}
-    edq_dev = torch.zeros(3, dtype=torch.float64, device=DEV) if edq else None
+    edq_dev = torch.zeros(4, dtype=torch.float64, device=DEV) if edq else None
     live = np.zeros(wl.total, bool)
     for (_, n), o in zip(wl.shapes, wl.offs):
         live[o:o + n] = True
     for t in range(1, steps + 1):
         wl.new_grads(t)
         g = H.torch_to_u16(wl.grad)
-        before = {k: host[k].copy() for k in ("theta", "dtheta")} if edq else None
+        before = {k: host[k].copy() for k in ("theta", "dtheta") if k in host} if edq else None
         delta = np.zeros(wl.total, np.uint16) if edq else None
         # the oracle steps the whole arena; padding between tensors is stepped too and then ignored
-        orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], host.get("dv"), g, wl.variant, wl.hyper, t,
+        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host["v"], host.get("dv"), g, wl.variant, wl.hyper, t,
                        delta_out=delta)
         wl.plan.step(wl.hyper, t, edq_out=edq_dev)
         torch.cuda.synchronize()
@@ -158,16 +158,18 @@ def _full_oracle_run(wl, steps, edq=False, check_each=True):
             acc = orc.EdqAccumulator()
             for (_, n), o in zip(wl.shapes, wl.offs):
                 sl = slice(o, o + n)
-                acc.add(delta[sl].copy(), before["theta"][sl].copy(), before["dtheta"][sl].copy(),
-                        host["theta"][sl].copy(), host["dtheta"][sl].copy())
+                d0 = before["dtheta"][sl].copy() if "dtheta" in host else None
+                d1 = host["dtheta"][sl].copy() if "dtheta" in host else None
+                acc.add(delta[sl].copy(), before["theta"][sl].copy(), d0, host["theta"][sl].copy(), d1)
             want = acc.value()
             got = edq_dev.cpu().numpy()
             assert abs(got[0] - want) <= 1e-5 * abs(want), (t, got, want)
+            assert int(got[3]) == acc.lost.value, (t, got[3], acc.lost.value)          # exact integer
             assert abs(got[1] - acc.s1.value) <= 1e-5 * abs(acc.s1.value) and abs(got[2] - acc.s2.value) <= 1e-5 * acc.s2.value
             assert want > 0
 
 
-@pytest.mark.parametrize("variant", ["light", "plus"])
+@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan"])
 def test_config1_flat_1m(variant):
     """Config 1: one flat tensor of 2^20, 10 steps, every element after every step; plan and flat entry points."""
     _say(f"config 1 {variant}")
@@ -180,14 +182,14 @@ def test_config1_flat_1m(variant):
     for t in range(1, 4):
         wl.new_grads(t)
         g = H.torch_to_u16(wl.grad)
-        orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], host.get("dv"), g, wl.variant, wl.hyper, t)
+        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host["v"], host.get("dv"), g, wl.variant, wl.hyper, t)
         mcf.adamw_step_flat(wl.theta, wl.dtheta, wl.m, wl.v, wl.dv, wl.grad, wl.variant, wl.hyper, t)
     for k in wl.state_names():
         assert np.array_equal(H.torch_to_u16(getattr(wl, k)), host[k]), k
     wl.close()
 
 
-@pytest.mark.parametrize("variant", ["light", "plus"])
+@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan"])
 def test_many_small_and_ragged_tensors(variant):
     """A few hundred tensors of 1..3000 elements packed back to back at odd offsets, plus three that span
     several chunks with ragged tails: exercises the chunk table, heads, tails and tiny tensors."""
@@ -218,7 +220,7 @@ def test_mutually_misaligned_tensor_goes_elementwise():
     plan.destroy()
 
 
-@pytest.mark.parametrize("variant", ["light", "plus"])
+@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan"])
 def test_special_values_take_the_exact_path(variant):
     """State and gradients drawn from all bit patterns (NaN, infinities, zeros, subnormals, huge and tiny
     values): the guarded fast arithmetic must hand these to the exact path and still match bit for bit."""
@@ -226,7 +228,9 @@ def test_special_values_take_the_exact_path(variant):
     shapes = [("a", n)]
     wl = Workload("flat_1m", variant=variant, shape_list=shapes)
     rnd = lambda s: _dev(_random_bf16(wl.total, s))
-    wl.theta.copy_(rnd(60)); wl.dtheta.copy_(rnd(61)); wl.m.copy_(rnd(62)); wl.v.copy_(rnd(63))
+    wl.theta.copy_(rnd(60)); wl.m.copy_(rnd(62)); wl.v.copy_(rnd(63))
+    if wl.dtheta is not None:
+        wl.dtheta.copy_(rnd(61))
     if wl.dv is not None:
         wl.dv.copy_(rnd(64))
     # v must mostly be non-negative to keep a share of the elements finite
@@ -235,7 +239,7 @@ def test_special_values_take_the_exact_path(variant):
     for t in range(1, 4):
         wl.grad.copy_(rnd(70 + t))
         g = H.torch_to_u16(wl.grad)
-        orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], host.get("dv"), g, wl.variant, wl.hyper, t)
+        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host["v"], host.get("dv"), g, wl.variant, wl.hyper, t)
         wl.plan.step(wl.hyper, t)
         for k in wl.state_names():
             dev = H.torch_to_u16(getattr(wl, k))
@@ -296,7 +300,7 @@ def test_edq_standalone():
     dth0 = np.zeros(n, np.uint16)
     th1, dth1 = orc.grow(th0, dth0, delta)
     plain = orc.binop(orc.ADD, th0, delta)
-    out = torch.zeros(3, dtype=torch.float64, device=DEV)
+    out = torch.zeros(4, dtype=torch.float64, device=DEV)
     scratch = torch.empty(mcf.edq_scratch_bytes(n) // 8, dtype=torch.float64, device=DEV)
     mcf.edq(_dev(delta), _dev(th0), _dev(dth0), _dev(th1), _dev(dth1), scratch, out)
     want = orc.edq(delta, th0, dth0, th1, dth1)
@@ -346,7 +350,7 @@ def _sampled_run(name, steps, check_at, full_first_step=False, misalign_tiny=Fal
     full = None
     if full_first_step:
         full = {k: H.torch_to_u16(getattr(wl, k)) for k in wl.state_names()}
-    edq_dev = torch.zeros(3, dtype=torch.float64, device=DEV) if edq_first else None
+    edq_dev = torch.zeros(4, dtype=torch.float64, device=DEV) if edq_first else None
     for t in range(1, steps + 1):
         wl.new_grads(t)
         delta = so.step(t, want_delta=drift)
