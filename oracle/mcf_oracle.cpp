@@ -97,6 +97,13 @@ inline Pair grow(Pair xy, uint16_t a) {
   return fast2sum(uv.hi, Fadd(xy.lo, uv.lo));
 }
 
+/* Alg. 1 with TwoSum (Alg. 3) in place of Fast2Sum: the same expansion where |x| >= |a| holds
+ * (App. C), and still exact where it does not. */
+inline Pair grow_two_sum(Pair xy, uint16_t a) {
+  Pair uv = two_sum(xy.hi, a);
+  return two_sum(uv.hi, Fadd(xy.lo, uv.lo));
+}
+
 /* Alg. 6 */
 inline Pair two_prod_fma(uint16_t a, uint16_t b) {
   uint16_t x = Fmul(a, b);
@@ -130,7 +137,9 @@ void derive_scalars(const orc_hyper &h, uint64_t t, orc_scalars &s) {
 
 /* Alg. 2 lines 8-13 for one element. */
 inline void adamw_element(uint16_t &theta, uint16_t &dtheta, uint16_t &m, uint16_t &v, uint16_t *dv,
-                          uint16_t g, int variant, const orc_scalars &s, uint16_t *delta_out) {
+                          uint16_t g, int variant_and_flags, const orc_scalars &s, uint16_t *delta_out) {
+  const int variant = variant_and_flags & 0xff;
+  const bool sorted_free = (variant_and_flags & ORC_GROW_TWOSUM) != 0;   /* Grow built on TwoSum */
   /* line 8: m <- beta1*m + (1-beta1)*g */
   uint16_t m_new = Fadd(Fmul(s.b1, m), Fmul(s.c1, g));
 
@@ -143,7 +152,7 @@ inline void adamw_element(uint16_t &theta, uint16_t &dtheta, uint16_t &m, uint16
   } else {
     /* plus: (v,dv) <- Grow(Mul((b2,b2l),(v,dv)), (1-beta2)*g^2) */
     Pair scaled = mul_expansion(Pair{s.b2, s.b2l}, Pair{v, *dv});
-    Pair vv = grow(scaled, inc);
+    Pair vv = sorted_free ? grow_two_sum(scaled, inc) : grow(scaled, inc);
     v_new = vv.hi;
     *dv = vv.lo;
   }
@@ -172,7 +181,7 @@ inline void adamw_element(uint16_t &theta, uint16_t &dtheta, uint16_t &m, uint16
     theta = theta_new;
   } else {
     /* line 13: (theta,dtheta) <- Grow((theta,dtheta), delta) */
-    Pair th = grow(Pair{theta, dtheta}, delta);
+    Pair th = sorted_free ? grow_two_sum(Pair{theta, dtheta}, delta) : grow(Pair{theta, dtheta}, delta);
     theta = th.hi;
     dtheta = th.lo;
   }
@@ -285,6 +294,12 @@ void orc_grow(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n) {
   });
 }
 
+void orc_grow_two_sum(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n) {
+  parallel_ranges(n, 1, [=](uint64_t lo, uint64_t hi) {
+    for (uint64_t i = lo; i < hi; ++i) { Pair p = grow_two_sum(Pair{x[i], y[i]}, a[i]); x[i] = p.hi; y[i] = p.lo; }
+  });
+}
+
 void orc_two_prod_fma(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *e, uint64_t n) {
   parallel_ranges(n, 1, [=](uint64_t lo, uint64_t hi) {
     for (uint64_t i = lo; i < hi; ++i) { Pair p = two_prod_fma(a[i], b[i]); x[i] = p.hi; e[i] = p.lo; }
@@ -310,8 +325,9 @@ void orc_adamw_step(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t *v,
   derive_scalars(*h, t, s);
   parallel_ranges(n, nthreads, [=](uint64_t lo, uint64_t hi) {
     uint16_t unused = 0;
+    const int base = variant & 0xff;
     for (uint64_t i = lo; i < hi; ++i)
-      adamw_element(theta[i], variant == 2 ? unused : dtheta[i], m[i], v[i], variant == 1 ? &dv[i] : nullptr,
+      adamw_element(theta[i], base == 2 ? unused : dtheta[i], m[i], v[i], base == 1 ? &dv[i] : nullptr,
                     grad[i], variant, s, delta_out ? &delta_out[i] : nullptr);
   });
 }

@@ -51,6 +51,8 @@ void orc_fast2sum(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *y
 void orc_two_sum(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *y, uint64_t n);
 /* Alg. 1 (Grow): (x,y) <- Grow((x,y), a), in place. */
 void orc_grow(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n);
+/* Alg. 1 with TwoSum in place of Fast2Sum (App. C: the same expansion without the ordering), in place. */
+void orc_grow_two_sum(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n);
 /* Alg. 6 (TwoProdFMA): x = F(a*b), e = F(fma(a,b,-x)). */
 void orc_two_prod_fma(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *e, uint64_t n);
 /* Alg. 8 (Mul): (x,e) = (a1,a2)*(b1,b2), all arrays of length n. */
@@ -59,6 +61,7 @@ void orc_mul_expansion(const uint16_t *a1, const uint16_t *a2, const uint16_t *b
 
 /* ---- AdamW scalars (Alg. 2 line 1, Table 2, App. D "Scalar and Bias Correction") ---- */
 typedef struct { double lr, beta1, beta2, eps, weight_decay; } orc_hyper;
+#define ORC_GROW_TWOSUM 0x100
 typedef struct {
   uint16_t b1;   /* B(beta1)            */
   uint16_t c1;   /* B(1-beta1)          */
@@ -77,6 +80,8 @@ void orc_scalars_derive(const orc_hyper *h, uint64_t t, orc_scalars *out);
  * variant 0 = Collage-light (option B), 1 = Collage-plus (option C; dv required),
  *         2 = plain bf16 (option A: line 13 is theta <- F(theta + delta), Eq. 1; dtheta unused, may be NULL),
  *         3 = Kahan-compensated bf16 (App. B; dtheta holds the Kahan variable c).
+ * ORC_GROW_TWOSUM may be OR-ed onto variants 0 and 1: every Grow then uses TwoSum (Alg. 3)
+ * instead of Fast2Sum, which drops the |x| >= |a| precondition of Alg. 1.
  * All state is updated in place.  delta_out, if not NULL, receives the bf16
  * update Delta-theta of line 12 for every element.  nthreads >= 1 splits the
  * elements evenly over that many host threads (elements are independent). */

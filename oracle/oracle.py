@@ -18,6 +18,7 @@ _LIB = os.path.join(_HERE, "libmcf_oracle.so")
 
 ADD, SUB, MUL, DIV, SQRT = 0, 1, 2, 3, 4
 LIGHT, PLUS, BF16, KAHAN = 0, 1, 2, 3
+GROW_TWOSUM = 0x100          # OR onto LIGHT or PLUS: Grow built on TwoSum
 
 
 def build(force=False):
@@ -64,6 +65,7 @@ def _load():
     for name in ("orc_fast2sum", "orc_two_sum", "orc_two_prod_fma"):
         getattr(lib, name).argtypes = [_u16p, _u16p, _u16p, _u16p, ctypes.c_uint64]
     lib.orc_grow.argtypes = [_u16p, _u16p, _u16p, ctypes.c_uint64]
+    lib.orc_grow_two_sum.argtypes = [_u16p, _u16p, _u16p, ctypes.c_uint64]
     lib.orc_mul_expansion.argtypes = [_u16p] * 6 + [ctypes.c_uint64]
     lib.orc_scalars_derive.argtypes = [ctypes.POINTER(Hyper), ctypes.c_uint64, ctypes.POINTER(Scalars)]
     lib.orc_adamw_step.argtypes = [_u16p] * 6 + [ctypes.c_uint64, ctypes.c_int, ctypes.POINTER(Hyper),
@@ -166,6 +168,16 @@ def grow(x, y, a):
     return x, y
 
 
+def grow_two_sum(x, y, a):
+    """Grow built on TwoSum.  Returns new (x, y); inputs are not modified."""
+    x = np.array(x, dtype=np.uint16, copy=True)
+    y = np.array(y, dtype=np.uint16, copy=True)
+    a = np.ascontiguousarray(a, dtype=np.uint16)
+    assert x.shape == y.shape == a.shape
+    _load().orc_grow_two_sum(_u16(x), _u16(y), _u16(a), x.size)
+    return x, y
+
+
 def mul_expansion(a1, a2, b1, b2):
     arrs = [np.ascontiguousarray(t, dtype=np.uint16) for t in (a1, a2, b1, b2)]
     x = np.empty_like(arrs[0])
@@ -184,15 +196,16 @@ def scalars(lr, beta1, beta2, eps, weight_decay, t):
 def adamw_step(theta, dtheta, m, v, dv, grad, variant, hyper, t, delta_out=None, nthreads=None):
     """In-place Collage step over uint16 arrays.  hyper = (lr, beta1, beta2, eps, weight_decay)."""
     n = theta.size
-    for arr in (m, v, grad) + (() if variant == BF16 else (dtheta,)):
+    base = variant & 0xFF
+    for arr in (m, v, grad) + (() if base == BF16 else (dtheta,)):
         assert arr.size == n
-    if variant == PLUS:
+    if base == PLUS:
         assert dv is not None and dv.size == n
     if delta_out is not None:
         assert delta_out.size == n
     h = Hyper(*hyper)
-    _load().orc_adamw_step(_u16(theta, True), None if variant == BF16 else _u16(dtheta, True), _u16(m, True), _u16(v, True),
-                           _u16(dv, True) if variant == PLUS else None, _u16(grad), n, int(variant),
+    _load().orc_adamw_step(_u16(theta, True), None if base == BF16 else _u16(dtheta, True), _u16(m, True), _u16(v, True),
+                           _u16(dv, True) if base == PLUS else None, _u16(grad), n, int(variant),
                            ctypes.byref(h), int(t), _u16(delta_out, True),
                            int(nthreads or default_threads()))
 

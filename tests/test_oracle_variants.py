@@ -125,3 +125,62 @@ def test_lost_update_counter(orc):
     acc.add(de, th, None, nw, None)
     assert acc.lost.value == want and 0 < want < n
     assert Fraction(want, n) > Fraction(1, 10)
+
+
+def _ulp_arr(x):
+    a = np.abs(x)
+    _, e = np.frexp(a)
+    e = e.astype(np.int64) - 1
+    return np.where(a == 0, 2.0 ** -133, np.ldexp(1.0, (np.maximum(e, -126) - 7).astype(np.int32)))
+
+
+def test_grow_on_two_sum_needs_no_ordering(orc):
+    """App. C: TwoSum gives Fast2Sum's expansion without |a| >= |b|.  Grow built on it is therefore the same
+    bits where Alg. 1's precondition |x| >= |a| holds, and keeps the Grow identity (the only loss is the
+    rounding of y + v) where it does not -- e.g. parameters near zero, or v = 0 at the first step."""
+    rng = np.random.default_rng(21)
+    n = 1_000_000
+    x = rng.choice(H.bf16_window(-8, 4), n)
+    fx = H.u16_to_f64(x)
+    y = H.np_round_f64_to_bf16(_ulp_arr(fx) * rng.uniform(-0.5, 0.5, n) * 0.99)
+    # addends from 2^-20 of x up to 2^12 times x: half of them violate the precondition
+    a = H.np_round_f64_to_bf16(fx * 2.0 ** rng.uniform(-20, 12, n) * rng.choice([-1.0, 1.0], n))
+    fa, fy = H.u16_to_f64(a), H.u16_to_f64(y)
+    x2, y2 = orc.grow_two_sum(x, y, a)
+    xf, yf = orc.grow(x, y, a)
+    pre = np.abs(fx) >= np.abs(fa)
+    assert 0.3 < pre.mean() < 0.8
+    nz = H.u16_to_f64(yf) != 0
+    assert np.array_equal(x2[pre], xf[pre]) and np.array_equal(y2[pre & nz], yf[pre & nz])
+    assert np.all(H.u16_to_f64(y2)[pre & ~nz] == 0)
+    # identity for every ordering: u = RN(x+a), v = x+a-u exactly, t = RN(y+v); result = u + t exactly
+    u = H.u16_to_f64(H.np_round_f64_to_bf16(fx + fa))
+    v = (fx + fa) - u
+    t_exact = fy + v
+    t = H.u16_to_f64(H.np_round_f64_to_bf16(np.where(t_exact == 0, 0.0, t_exact)))
+    got = H.u16_to_f64(x2) + H.u16_to_f64(y2)
+    assert np.array_equal(got - (fx + fy + fa), t - t_exact)
+    assert np.all(np.abs(H.u16_to_f64(y2)) <= _ulp_arr(H.u16_to_f64(x2)) / 2)
+    # with Fast2Sum the identity does fail somewhere outside the precondition
+    gotf = H.u16_to_f64(xf) + H.u16_to_f64(yf)
+    assert np.any((gotf - (fx + fy + fa))[~pre] != (t - t_exact)[~pre])
+
+
+def test_step_with_two_sum_grow(orc):
+    """The flagged step equals the plain one while the preconditions hold, and differs only through Grow."""
+    n = 20_000
+    hyper = (1e-3, 0.9, 0.999, 1e-8, 0.1)
+    a = dict(_state(n, 8, theta_std=1.0), dv=np.zeros(n, np.uint16))
+    b = {k: v.copy() for k, v in a.items()}
+    same_theta = True
+    for t in range(1, 30):
+        g = _grads(n, 8, t)
+        orc.adamw_step(a["theta"], a["dtheta"], a["m"], a["v"], a["dv"], g, orc.PLUS, hyper, t)
+        orc.adamw_step(b["theta"], b["dtheta"], b["m"], b["v"], b["dv"], g, orc.PLUS | orc.GROW_TWOSUM, hyper, t)
+        assert np.array_equal(a["m"], b["m"])
+        same_theta = same_theta and np.array_equal(a["theta"], b["theta"])
+    # |theta| ~ 1 >> |delta| ~ 1e-3 except for the few elements near zero: nearly all trajectories coincide
+    assert np.mean(a["theta"] == b["theta"]) > 0.99
+    va = H.u16_to_f64(a["v"]) + H.u16_to_f64(a["dv"])
+    vb = H.u16_to_f64(b["v"]) + H.u16_to_f64(b["dv"])
+    assert np.all(np.abs(va - vb) <= 2.0 ** -10 * vb) and np.median(np.abs(va - vb) / vb) < 2.0 ** -14
