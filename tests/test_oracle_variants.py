@@ -172,15 +172,18 @@ def test_step_with_two_sum_grow(orc):
     hyper = (1e-3, 0.9, 0.999, 1e-8, 0.1)
     a = dict(_state(n, 8, theta_std=1.0), dv=np.zeros(n, np.uint16))
     b = {k: v.copy() for k, v in a.items()}
-    same_theta = True
+    ema = np.zeros(n)
     for t in range(1, 30):
         g = _grads(n, 8, t)
         orc.adamw_step(a["theta"], a["dtheta"], a["m"], a["v"], a["dv"], g, orc.PLUS, hyper, t)
         orc.adamw_step(b["theta"], b["dtheta"], b["m"], b["v"], b["dv"], g, orc.PLUS | orc.GROW_TWOSUM, hyper, t)
         assert np.array_equal(a["m"], b["m"])
-        same_theta = same_theta and np.array_equal(a["theta"], b["theta"])
+        ema = 0.999 * ema + 0.001 * H.u16_to_f64(g) ** 2
     # |theta| ~ 1 >> |delta| ~ 1e-3 except for the few elements near zero: nearly all trajectories coincide
     assert np.mean(a["theta"] == b["theta"]) > 0.99
-    va = H.u16_to_f64(a["v"]) + H.u16_to_f64(a["dv"])
-    vb = H.u16_to_f64(b["v"]) + H.u16_to_f64(b["dv"])
-    assert np.all(np.abs(va - vb) <= 2.0 ** -10 * vb) and np.median(np.abs(va - vb) / vb) < 2.0 ** -14
+    # v is young here (v ~ t * 0.001 g^2), so a large gradient often exceeds it and breaks Fast2Sum's ordering;
+    # the TwoSum flavour follows the true average at least as well
+    ea = np.abs(H.u16_to_f64(a["v"]) + H.u16_to_f64(a["dv"]) - ema) / ema
+    eb = np.abs(H.u16_to_f64(b["v"]) + H.u16_to_f64(b["dv"]) - ema) / ema
+    assert eb.max() < 2.0 ** -7 and np.median(eb) < 2.0 ** -9
+    assert eb.mean() <= ea.mean() * 1.001
