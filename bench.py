@@ -54,17 +54,21 @@ def build_light_or_plus(name, variant, dev):
     shapes = W.shapes(name)
     offs, total = W.layout(shapes, misalign_tiny=(name == "stress_64m"))
     z = lambda: torch.zeros(total, dtype=torch.bfloat16, device=dev)
+    base = variant.split("+")[0]
     st = {"theta": z(), "m": z(), "v": z(), "grad": z()}
-    if variant != "bf16":
+    if base != "bf16":
         st["dtheta"] = z()
-    if variant == "plus":
+    if base == "plus":
         st["dv"] = z()
     W.init_theta(name, shapes, offs, st["theta"])
     drift = W.stress_drift(shapes, offs, total, dev) if name == "stress_64m" else None
     W.fill_grads(name, shapes, offs, st["grad"], 1, drift=drift)
-    tensors = [(st["theta"][o:o + n], st["dtheta"][o:o + n] if variant != "bf16" else None, st["m"][o:o + n], st["v"][o:o + n],
-                st["dv"][o:o + n] if variant == "plus" else None, st["grad"][o:o + n]) for (_, n), o in zip(shapes, offs)]
-    plan = mcf.Plan(tensors, {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN}[variant])
+    tensors = [(st["theta"][o:o + n], st["dtheta"][o:o + n] if base != "bf16" else None, st["m"][o:o + n], st["v"][o:o + n],
+                st["dv"][o:o + n] if base == "plus" else None, st["grad"][o:o + n]) for (_, n), o in zip(shapes, offs)]
+    code = {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN}[base]
+    if variant.endswith("+twosum"):
+        code |= mcf.GROW_TWOSUM
+    plan = mcf.Plan(tensors, code)
     return st, plan, W.total_params(shapes), len(shapes)
 
 
@@ -120,7 +124,7 @@ def main():
     log(f"bench: building {name} ({variant})")
     st, plan, n_params, n_tensors = build_light_or_plus(name, variant, dev)
     wall, gpu_s = time_steps(lambda t: plan.step(hyper, t), args.steps, args.warmup)
-    bpp = W.bytes_per_param(variant)
+    bpp = W.bytes_per_param(variant.split("+")[0])
     kern_s = gpu_s / args.steps
     achieved = bpp * n_params / kern_s / 1e9
     traffic = MEASURED_TRAFFIC_BYTES_PER_PARAM.get(variant)
@@ -152,15 +156,16 @@ def main():
             extras["copy_GBps"] = 4 * nb * 10 / s / 1e9
             del src, dst
             st = None
-            for other in ("plus", "light", "kahan", "bf16"):      # the other strategies on the same shapes
+            # the other strategies on the same shapes
+            for other in ("plus", "light", "kahan", "bf16", "light+twosum", "plus+twosum"):
                 if other == variant:
                     continue
                 st2 = None
                 torch.cuda.empty_cache()
                 st2, plan2, _, _ = build_light_or_plus(name, other, dev)
-                h2 = W.HYPER_PLUS_1P3B if other == "plus" else W.HYPER_LIGHT
+                h2 = W.HYPER_PLUS_1P3B if other.startswith("plus") else W.HYPER_LIGHT
                 _, s = time_steps(lambda t: plan2.step(h2, t), args.steps, args.warmup)
-                extras[f"{other}_GBps"] = W.bytes_per_param(other) * n_params * args.steps / s / 1e9
+                extras[f"{other}_GBps"] = W.bytes_per_param(other.split("+")[0]) * n_params * args.steps / s / 1e9
                 extras[f"{other}_ms"] = s / args.steps * 1e3
                 plan2.destroy()
             # option D on the same shapes

@@ -67,6 +67,11 @@ typedef struct { double lr, beta1, beta2, eps, weight_decay; } mcf_hyper;
  * MCF_KAHAN = Kahan-compensated bf16 (App. B): u = F(delta + c), theta' = F(theta + u),
  * c <- F(u - F(theta' - theta)), with c kept in dtheta. */
 typedef enum { MCF_LIGHT = 0, MCF_PLUS = 1, MCF_BF16 = 2, MCF_KAHAN = 3 } mcf_variant;
+/* May be OR-ed onto MCF_LIGHT or MCF_PLUS: every Grow (Alg. 1) is built on TwoSum (Alg. 3, six
+ * operations) instead of Fast2Sum (three), which removes Alg. 1's precondition |x| >= |a| -- it can
+ * fail for parameters near zero, for v = 0 at the first step, and when a gradient spike exceeds v
+ * (App. C: the same expansion without the ordering).  Any other combination is MCF_ERR_VARIANT. */
+#define MCF_GROW_TWOSUM 0x100
 
 /* One parameter tensor: flat, contiguous, n elements per buffer, all device memory.
  * theta, dtheta: the parameter expansion (Alg. 2 lines 2-3; MCF_KAHAN: the Kahan variable;

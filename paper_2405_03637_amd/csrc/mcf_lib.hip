@@ -246,9 +246,14 @@ __device__ __forceinline__ void edq_store_partial(const EdqAcc &a, double *__res
 }
 
 // ---------------------------------------------------------------- the step kernel
+// VARIANT template arguments below carry the variant in the low byte and kGrow2Bit when every Grow
+// is to be built on TwoSum (Alg. 3) instead of Fast2Sum.
+constexpr int kGrow2Bit = 0x100;
 template <int VARIANT> struct StepStreams {
-  static constexpr bool kDth = VARIANT != mcfd::V_BF16;      // second component of theta / Kahan variable
-  static constexpr bool kDv = VARIANT == mcfd::V_PLUS;       // second component of v
+  static constexpr int kBase = VARIANT & 0xff;
+  static constexpr bool kGrow2 = (VARIANT & kGrow2Bit) != 0;
+  static constexpr bool kDth = kBase != mcfd::V_BF16;      // second component of theta / Kahan variable
+  static constexpr bool kDv = kBase == mcfd::V_PLUS;       // second component of v
 };
 
 // Hot path: one full slot, 8 elements of every stream held as 4 dwords each.  Returns true
@@ -269,7 +274,7 @@ __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], u
     if (SS::kDv) io.dv = mcfd::widen2(in[S_DV][k]); else io.dv = {0.f, 0.f};
     const P2 th0 = io.th, dth0 = io.dth;
     P2 delta;
-    mcfd::adamw_pair<M, VARIANT>(io, sc, delta, redo);
+    mcfd::adamw_pair<M, SS::kBase, SS::kGrow2>(io, sc, delta, redo);
     out[S_TH][k] = mcfd::pack2(io.th);
     if (SS::kDth) out[S_DTH][k] = mcfd::pack2(io.dth);
     out[S_M][k] = mcfd::pack2(io.m);
@@ -312,7 +317,7 @@ __device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, cons
     const float th0 = io.th.lo, dth0 = io.dth.lo;
     P2 delta;
     bool unused = false;
-    mcfd::adamw_pair<mcfd::Exact, VARIANT>(io, sc, delta, unused);
+    mcfd::adamw_pair<mcfd::Exact, SS::kBase, SS::kGrow2>(io, sc, delta, unused);
     th[e] = (uint16_t)(mcfd::fbits(io.th.lo) >> 16);
     if (SS::kDth) dth[e] = (uint16_t)(mcfd::fbits(io.dth.lo) >> 16);
     m[e] = (uint16_t)(mcfd::fbits(io.m.lo) >> 16);
@@ -673,9 +678,14 @@ inline void phase_of(const uint64_t *ptrs, int count, uint32_t &phase, uint32_t 
 
 inline uint64_t slots_of(uint64_t n, uint32_t phase) { return (n + phase + 7) / 8; }
 
-inline bool known_variant(int v) { return v == MCF_LIGHT || v == MCF_PLUS || v == MCF_BF16 || v == MCF_KAHAN; }
+inline bool known_variant(int v) {
+  const int base = v & ~MCF_GROW_TWOSUM;
+  if (v & MCF_GROW_TWOSUM) return base == MCF_LIGHT || base == MCF_PLUS;
+  return base == MCF_LIGHT || base == MCF_PLUS || base == MCF_BF16 || base == MCF_KAHAN;
+}
 
 int check_tensor(const mcf_tensor &t, int variant) {
+  variant &= ~MCF_GROW_TWOSUM;
   if (t.n == 0) return MCF_OK;
   const bool need_dth = variant != MCF_BF16, need_dv = variant == MCF_PLUS;
   if (!t.theta || !t.m || !t.v || !t.grad) return MCF_ERR_NULL;
@@ -690,6 +700,7 @@ int check_tensor(const mcf_tensor &t, int variant) {
 // Streams a variant does not use point at theta (v for dv): they are never accessed and do
 // not disturb the alignment class.
 void fill_desc(const mcf_tensor &t, int variant, TensorDesc &d) {
+  variant &= ~MCF_GROW_TWOSUM;
   d.p[S_TH] = (uint64_t)(uintptr_t)t.theta;
   d.p[S_DTH] = variant != MCF_BF16 ? (uint64_t)(uintptr_t)t.dtheta : d.p[S_TH];
   d.p[S_M] = (uint64_t)(uintptr_t)t.m;
@@ -721,6 +732,10 @@ template <bool TABLE>
 void launch_variant(int variant, bool fast, bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs,
                     const Chunk *chunks, const TensorDesc &flat, const StepScalars &sc, double *partials) {
   switch (variant) {
+    case MCF_LIGHT | MCF_GROW_TWOSUM:
+      launch_step<mcfd::V_LIGHT | kGrow2Bit, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
+    case MCF_PLUS | MCF_GROW_TWOSUM:
+      launch_step<mcfd::V_PLUS | kGrow2Bit, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
     case MCF_PLUS: launch_step<mcfd::V_PLUS, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
     case MCF_BF16: launch_step<mcfd::V_BF16, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
     case MCF_KAHAN: launch_step<mcfd::V_KAHAN, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;

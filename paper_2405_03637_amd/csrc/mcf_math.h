@@ -30,8 +30,9 @@ __device__ __forceinline__ float bitsf(uint32_t u) { return __builtin_bit_cast(f
 
 // A dword holds two bf16, element 2k in the low half.
 __device__ __forceinline__ P2 widen2(uint32_t w) { return {bitsf(w << 16), bitsf(w & 0xffff0000u)}; }
-// Pack two fp32 values that already are bf16 values (low halves zero).
-__device__ __forceinline__ uint32_t pack2(P2 x) { return (fbits(x.lo) >> 16) | (fbits(x.hi) & 0xffff0000u); }
+// Pack two fp32 values that already are bf16 values (low halves zero): one v_perm_b32 taking
+// the upper halves of both.
+__device__ __forceinline__ uint32_t pack2(P2 x) { return __builtin_amdgcn_perm(fbits(x.hi), fbits(x.lo), 0x07060302u); }
 
 // fp32 -> bf16 round-to-nearest-even on the bit pattern, result left widened; NaN -> 0x7FC0.
 __device__ __forceinline__ float round_bits(float f) {
@@ -53,11 +54,14 @@ struct Exact {
 
 struct Fast {
   static constexpr bool kFast = true;
-  static __device__ __forceinline__ P2 rnd(P2 x) {
-    f32x2_t v = {x.lo, x.hi};
-    bf16x2_t r = __builtin_convertvector(v, bf16x2_t);      // v_cvt_pk_bf16_f32
-    return widen2(__builtin_bit_cast(uint32_t, r));
+  // v_cvt_pk_bf16_f32 with 0 as its first source leaves bf16(x) in the upper half of the result and
+  // bf16(0) = 0 in the lower half: that IS the rounded value widened back to fp32, in one instruction.
+  static __device__ __forceinline__ float rnd1(float x) {
+    const f32x2_t v = {0.0f, x};
+    const bf16x2_t r = __builtin_convertvector(v, bf16x2_t);      // v_cvt_pk_bf16_f32 dst, 0, x
+    return __builtin_bit_cast(float, r);
   }
+  static __device__ __forceinline__ P2 rnd(P2 x) { return {rnd1(x.lo), rnd1(x.hi)}; }
   // a / b where b is a positive normal scalar with known fp32 reciprocal rb (|rel err| <= 2^-24)
   static __device__ __forceinline__ float div1(float a, float, float rb, bool &redo) {
     float p = a * rb;
@@ -119,6 +123,12 @@ template <class M> struct Ops {
     fast2sum(x, a, u, w);
     fast2sum(u, add(y, w), xo, yo);
   }
+  // Alg. 1 on TwoSum (Alg. 3): no |x| >= |a| precondition
+  static __device__ __forceinline__ void grow2(P2 x, P2 y, P2 a, P2 &xo, P2 &yo) {
+    P2 u, w;
+    two_sum(x, a, u, w);
+    two_sum(u, add(y, w), xo, yo);
+  }
 };
 
 // bf16 scalars of one step, widened to fp32 (exact), plus fp32 reciprocals of the two
@@ -136,10 +146,10 @@ struct ElemIO {          // one pair of elements of every stream
 // theta <- F(theta + delta)) and Kahan-compensated bf16 (App. B; dtheta holds the Kahan variable).
 enum : int { V_LIGHT = 0, V_PLUS = 1, V_BF16 = 2, V_KAHAN = 3 };
 
-// Alg. 2 lines 8-13 on one pair.  On return io holds the new theta, dtheta, m, v (and dv);
+// Alg. 2 lines 8-13 on one pair.  GROW2 builds every Grow on TwoSum.  On return io holds the new theta, dtheta, m, v (and dv);
 // delta receives line 12's update.  redo is raised (Fast mode) when this pair must be
 // recomputed in Exact mode.
-template <class M, int VARIANT>
+template <class M, int VARIANT, bool GROW2 = false>
 __device__ __forceinline__ void adamw_pair(ElemIO &io, const StepScalars &s, P2 &delta, bool &redo) {
   using O = Ops<M>;
   // line 8
@@ -157,7 +167,7 @@ __device__ __forceinline__ void adamw_pair(ElemIO &io, const StepScalars &s, P2 
     P2 e2 = O::add(ex, cross);
     P2 X, E;
     O::fast2sum(x, e2, X, E);
-    O::grow(X, E, inc, v1, dv1);
+    if (GROW2) O::grow2(X, E, inc, v1, dv1); else O::grow(X, E, inc, v1, dv1);
   }
   // lines 10-11
   P2 mh = O::divs(m1, s.bc1, s.rbc1, redo);
@@ -174,6 +184,8 @@ __device__ __forceinline__ void adamw_pair(ElemIO &io, const StepScalars &s, P2 
   } else if (VARIANT == V_KAHAN) {
     const P2 u = O::add(delta, io.dth);               // compensate the update with the Kahan variable
     O::fast2sum(io.th, u, th1, dth1);                 // c <- F(u - F(theta' - theta))
+  } else if (GROW2) {
+    O::grow2(io.th, io.dth, delta, th1, dth1);
   } else {
     O::grow(io.th, io.dth, delta, th1, dth1);
   }

@@ -41,15 +41,17 @@ class Workload:
         self.name = name
         self.shapes = shape_list if shape_list is not None else W.shapes(name)
         vname = variant or W.WORKLOADS[name][1]
-        self.variant = {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN}[vname]
+        self.variant = {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN,
+                        "light+twosum": mcf.LIGHT | mcf.GROW_TWOSUM, "plus+twosum": mcf.PLUS | mcf.GROW_TWOSUM}[vname]
+        base = self.variant & 0xFF
         self.hyper = hyper or W.WORKLOADS[name][2]
         self.offs, self.total = W.layout(self.shapes, misalign_tiny=misalign_tiny, align=align)
         self.seed = seed
         self.device = device
         z = lambda: torch.zeros(self.total, dtype=torch.bfloat16, device=device)
         self.theta, self.m, self.v = z(), z(), z()
-        self.dtheta = z() if self.variant != mcf.BF16 else None
-        self.dv = z() if self.variant == mcf.PLUS else None
+        self.dtheta = z() if base != mcf.BF16 else None
+        self.dv = z() if base == mcf.PLUS else None
         self.grad = z()
         W.init_theta(name, self.shapes, self.offs, self.theta, seed=seed)
         self.drift = W.stress_drift(self.shapes, self.offs, self.total, device, seed) if name == "stress_64m" else None

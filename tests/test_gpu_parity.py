@@ -169,7 +169,7 @@ def _full_oracle_run(wl, steps, edq=False, check_each=True):
             assert want > 0
 
 
-@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan"])
+@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan", "light+twosum", "plus+twosum"])
 def test_config1_flat_1m(variant):
     """Config 1: one flat tensor of 2^20, 10 steps, every element after every step; plan and flat entry points."""
     _say(f"config 1 {variant}")
@@ -189,7 +189,7 @@ def test_config1_flat_1m(variant):
     wl.close()
 
 
-@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan"])
+@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan", "plus+twosum"])
 def test_many_small_and_ragged_tensors(variant):
     """A few hundred tensors of 1..3000 elements packed back to back at odd offsets, plus three that span
     several chunks with ragged tails: exercises the chunk table, heads, tails and tiny tensors."""
@@ -199,7 +199,7 @@ def test_many_small_and_ragged_tensors(variant):
     shapes = [(f"t{i}", n) for i, n in enumerate(sizes)]
     for align in (1, 8):          # 1: every tensor starts wherever the previous one ended
         wl = Workload("flat_1m", variant=variant, shape_list=shapes, misalign_tiny=True, align=align,
-                      hyper=W.HYPER_PLUS_1P3B if variant == "plus" else W.HYPER_LIGHT)
+                      hyper=W.HYPER_PLUS_1P3B if variant.startswith("plus") else W.HYPER_LIGHT)
         _full_oracle_run(wl, 5, edq=True)
         wl.close()
 
@@ -220,7 +220,7 @@ def test_mutually_misaligned_tensor_goes_elementwise():
     plan.destroy()
 
 
-@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan"])
+@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan", "light+twosum", "plus+twosum"])
 def test_special_values_take_the_exact_path(variant):
     """State and gradients drawn from all bit patterns (NaN, infinities, zeros, subnormals, huge and tiny
     values): the guarded fast arithmetic must hand these to the exact path and still match bit for bit."""
