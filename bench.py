@@ -99,8 +99,8 @@ def cpu_baseline(name, variant, hyper, sample=32 * 1024 * 1024, min_seconds=1.5)
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama_7b")
     ap.add_argument("--variant", default=None, help="light or plus (default: the workload's own)")
     ap.add_argument("--no-extras", action="store_true", help="skip the plus / fp32-master / copy legs")

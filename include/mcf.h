@@ -117,6 +117,15 @@ int mcf_fast2sum(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *y,
 int mcf_two_sum(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *y, uint64_t n, void *stream);
 /* Alg. 1 (Grow): (x,y) <- Grow((x,y), a), in place. */
 int mcf_grow(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n, void *stream);
+/* Alg. 1 built on TwoSum instead of Fast2Sum (no |x| >= |a| precondition), in place. */
+int mcf_grow_two_sum(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n, void *stream);
+/* Alg. 6 (TwoProdFMA): x = F(a*b), e = F(fma(a, b, -x)); x + e = a*b exactly. */
+int mcf_two_prod_fma(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *e, uint64_t n, void *stream);
+/* Alg. 7 (Scaling): (x,e) = v * (a1,a2): TwoProdFMA(a1,v); e = F(F(a2*v) + e); Fast2Sum(x,e). */
+int mcf_scaling(const uint16_t *v, const uint16_t *a1, const uint16_t *a2, uint16_t *x, uint16_t *e, uint64_t n, void *stream);
+/* Alg. 8 (Mul): (x,e) = (a1,a2) * (b1,b2): TwoProdFMA(a1,b1); e = F(e + F(F(a1*b2) + F(a2*b1))); Fast2Sum(x,e). */
+int mcf_mul(const uint16_t *a1, const uint16_t *a2, const uint16_t *b1, const uint16_t *b2, uint16_t *x, uint16_t *e,
+            uint64_t n, void *stream);
 /* Sec. 3.1: out = F(a op b) with op 0 add, 1 sub, 2 mul, 3 div, 4 sqrt(a) (b unused, may be NULL). */
 int mcf_bf16_op(int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n, void *stream);
 /* The rounding inside F: out = bf16(in), round-to-nearest-even, in = fp32 device buffer. */

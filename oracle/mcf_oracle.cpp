@@ -111,6 +111,13 @@ inline Pair two_prod_fma(uint16_t a, uint16_t b) {
   return {x, e};
 }
 
+/* Alg. 7: float v times the expansion (a1, a2). */
+inline Pair scaling(uint16_t v, Pair a) {
+  Pair xe = two_prod_fma(a.hi, v);
+  uint16_t e = Fadd(Fmul(a.lo, v), xe.lo);
+  return fast2sum(xe.hi, e);
+}
+
 /* Alg. 8: product of two length-2 expansions. */
 inline Pair mul_expansion(Pair a, Pair b) {
   Pair xe = two_prod_fma(a.hi, b.hi);
@@ -303,6 +310,12 @@ void orc_grow_two_sum(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n) {
 void orc_two_prod_fma(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *e, uint64_t n) {
   parallel_ranges(n, 1, [=](uint64_t lo, uint64_t hi) {
     for (uint64_t i = lo; i < hi; ++i) { Pair p = two_prod_fma(a[i], b[i]); x[i] = p.hi; e[i] = p.lo; }
+  });
+}
+
+void orc_scaling(const uint16_t *v, const uint16_t *a1, const uint16_t *a2, uint16_t *x, uint16_t *e, uint64_t n) {
+  parallel_ranges(n, 1, [=](uint64_t lo, uint64_t hi) {
+    for (uint64_t i = lo; i < hi; ++i) { Pair p = scaling(v[i], Pair{a1[i], a2[i]}); x[i] = p.hi; e[i] = p.lo; }
   });
 }
 

@@ -55,6 +55,8 @@ void orc_grow(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n);
 void orc_grow_two_sum(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n);
 /* Alg. 6 (TwoProdFMA): x = F(a*b), e = F(fma(a,b,-x)). */
 void orc_two_prod_fma(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *e, uint64_t n);
+/* Alg. 7 (Scaling): (x,e) = v * (a1,a2). */
+void orc_scaling(const uint16_t *v, const uint16_t *a1, const uint16_t *a2, uint16_t *x, uint16_t *e, uint64_t n);
 /* Alg. 8 (Mul): (x,e) = (a1,a2)*(b1,b2), all arrays of length n. */
 void orc_mul_expansion(const uint16_t *a1, const uint16_t *a2, const uint16_t *b1, const uint16_t *b2,
                        uint16_t *x, uint16_t *e, uint64_t n);

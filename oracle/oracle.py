@@ -67,6 +67,7 @@ def _load():
     lib.orc_grow.argtypes = [_u16p, _u16p, _u16p, ctypes.c_uint64]
     lib.orc_grow_two_sum.argtypes = [_u16p, _u16p, _u16p, ctypes.c_uint64]
     lib.orc_mul_expansion.argtypes = [_u16p] * 6 + [ctypes.c_uint64]
+    lib.orc_scaling.argtypes = [_u16p] * 5 + [ctypes.c_uint64]
     lib.orc_scalars_derive.argtypes = [ctypes.POINTER(Hyper), ctypes.c_uint64, ctypes.POINTER(Scalars)]
     lib.orc_adamw_step.argtypes = [_u16p] * 6 + [ctypes.c_uint64, ctypes.c_int, ctypes.POINTER(Hyper),
                                                 ctypes.c_uint64, _u16p, ctypes.c_int]
@@ -183,6 +184,14 @@ def mul_expansion(a1, a2, b1, b2):
     x = np.empty_like(arrs[0])
     e = np.empty_like(arrs[0])
     _load().orc_mul_expansion(*[_u16(t) for t in arrs], _u16(x), _u16(e), x.size)
+    return x, e
+
+
+def scaling(v, a1, a2):
+    arrs = [np.ascontiguousarray(t, dtype=np.uint16) for t in (v, a1, a2)]
+    x = np.empty_like(arrs[0])
+    e = np.empty_like(arrs[0])
+    _load().orc_scaling(*[_u16(t) for t in arrs], _u16(x), _u16(e), x.size)
     return x, e
 
 

@@ -69,6 +69,10 @@ def lib():
     L.mcf_fast2sum.argtypes = [_vp] * 4 + [_u64, _vp]
     L.mcf_two_sum.argtypes = [_vp] * 4 + [_u64, _vp]
     L.mcf_grow.argtypes = [_vp] * 3 + [_u64, _vp]
+    L.mcf_grow_two_sum.argtypes = [_vp] * 3 + [_u64, _vp]
+    L.mcf_two_prod_fma.argtypes = [_vp] * 4 + [_u64, _vp]
+    L.mcf_scaling.argtypes = [_vp] * 5 + [_u64, _vp]
+    L.mcf_mul.argtypes = [_vp] * 6 + [_u64, _vp]
     L.mcf_bf16_op.argtypes = [_int] + [_vp] * 3 + [_u64, _vp]
     L.mcf_round_f32.argtypes = [_vp, _vp, _u64, _vp]
     L.mcf_edq_scratch_bytes.restype = _u64
@@ -207,6 +211,22 @@ def two_sum(a, b, x, y, stream=None):
 
 def grow(x, y, a, stream=None):
     _check(lib().mcf_grow(_ptr(x), _ptr(y), _ptr(a), x.numel(), _stream(stream)), "mcf_grow")
+
+
+def grow_two_sum(x, y, a, stream=None):
+    _check(lib().mcf_grow_two_sum(_ptr(x), _ptr(y), _ptr(a), x.numel(), _stream(stream)), "mcf_grow_two_sum")
+
+
+def two_prod_fma(a, b, x, e, stream=None):
+    _check(lib().mcf_two_prod_fma(_ptr(a), _ptr(b), _ptr(x), _ptr(e), a.numel(), _stream(stream)), "mcf_two_prod_fma")
+
+
+def scaling(v, a1, a2, x, e, stream=None):
+    _check(lib().mcf_scaling(_ptr(v), _ptr(a1), _ptr(a2), _ptr(x), _ptr(e), v.numel(), _stream(stream)), "mcf_scaling")
+
+
+def mul(a1, a2, b1, b2, x, e, stream=None):
+    _check(lib().mcf_mul(_ptr(a1), _ptr(a2), _ptr(b1), _ptr(b2), _ptr(x), _ptr(e), a1.numel(), _stream(stream)), "mcf_mul")
 
 
 def bf16_op(op, a, b, out, stream=None):

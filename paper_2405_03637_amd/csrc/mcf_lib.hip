@@ -438,7 +438,7 @@ edq_stage2(const double *__restrict__ mid, uint32_t nmid, double *__restrict__ o
 }
 
 // ---------------------------------------------------------------- element-wise primitives
-enum PrimOp { P_FAST2SUM, P_TWOSUM, P_GROW, P_ADD, P_SUB, P_MUL, P_DIV, P_SQRT, P_EDQ };
+enum PrimOp { P_FAST2SUM, P_TWOSUM, P_GROW, P_ADD, P_SUB, P_MUL, P_DIV, P_SQRT, P_EDQ, P_GROW2, P_TWOPROD, P_SCALING, P_MULX };
 
 struct PrimArgs {
   uint64_t p[kMaxStreams];
@@ -457,6 +457,21 @@ __device__ __forceinline__ void prim_words(const uint32_t (&in)[kMaxStreams][4],
     if (OP == P_FAST2SUM) O::fast2sum(a, b, x, y);
     if (OP == P_TWOSUM) O::two_sum(a, b, x, y);
     if (OP == P_GROW) O::grow(a, b, mcfd::widen2(in[2][k]), x, y);          // streams: x, y, a
+    if (OP == P_GROW2) O::grow2(a, b, mcfd::widen2(in[2][k]), x, y);
+    if (OP == P_TWOPROD) { x = O::mul(a, b); y = O::fms(a, b, x); }         // Alg. 6
+    if (OP == P_SCALING) {                                                  // Alg. 7; streams: v, a1, a2
+      const P2 a2 = mcfd::widen2(in[2][k]);
+      const P2 x0 = O::mul(b, a);
+      const P2 e = O::add(O::mul(a2, a), O::fms(b, a, x0));
+      O::fast2sum(x0, e, x, y);
+    }
+    if (OP == P_MULX) {                                                     // Alg. 8; streams: a1, a2, b1, b2
+      const P2 b1 = mcfd::widen2(in[2][k]), b2 = mcfd::widen2(in[3][k]);
+      const P2 x0 = O::mul(a, b1);
+      const P2 ex = O::fms(a, b1, x0);
+      const P2 cross = O::add(O::mul(a, b2), O::mul(b, b1));
+      O::fast2sum(x0, O::add(ex, cross), x, y);
+    }
     if (OP == P_ADD) x = O::add(a, b);
     if (OP == P_SUB) x = O::sub(a, b);
     if (OP == P_MUL) x = O::mul(a, b);
@@ -488,7 +503,10 @@ __device__ __forceinline__ void prim_words(const uint32_t (&in)[kMaxStreams][4],
 
 // Stream layout per op (inputs first):   reads            writes
 //  FAST2SUM/TWOSUM: p0=a p1=b p2=x p3=y   0,1              out0->p2, out1->p3
-//  GROW:            p0=x p1=y p2=a        0,1,2            out0->p0, out1->p1
+//  GROW, GROW2:     p0=x p1=y p2=a        0,1,2            out0->p0, out1->p1
+//  TWOPROD:         p0=a p1=b p2=x p3=e   0,1              out0->p2, out1->p3
+//  SCALING:         p0=v p1=a1 p2=a2 p3=x p4=e   0,1,2     out0->p3, out1->p4
+//  MULX:            p0=a1 p1=a2 p2=b1 p3=b2 p4=x p5=e  0..3  out0->p4, out1->p5
 //  ADD..SQRT:       p0=a p1=b p2=out      0,1 (sqrt: 0)    out0->p2
 //  EDQ:             p0=delta p1=th0 p2=th1 p3=dth0 p4=dth1  (reads only; partial sums out)
 template <int OP>
@@ -502,7 +520,7 @@ __global__ void __launch_bounds__(kBlock) prim_kernel(PrimArgs a, uint32_t has_d
   if (s.any) {
     uint32_t in[kMaxStreams][4] = {};
     uint32_t out[kMaxStreams][4];
-    constexpr int nin = (OP == P_GROW) ? 3 : (OP == P_SQRT) ? 1 : 2;
+    constexpr int nin = (OP == P_GROW || OP == P_GROW2 || OP == P_SCALING) ? 3 : (OP == P_MULX) ? 4 : (OP == P_SQRT) ? 1 : 2;
     uint32_t valid = 0xffu;              // which of the slot's 8 elements belong to the tensor
     if (OP == P_EDQ) {
       load_slot(d.p[0], d, s, in[0]);
@@ -523,8 +541,10 @@ __global__ void __launch_bounds__(kBlock) prim_kernel(PrimArgs a, uint32_t has_d
       bool unused = false;
       prim_words<mcfd::Exact, OP>(in, out, unused, acc, valid);
     }
-    if (OP == P_FAST2SUM || OP == P_TWOSUM) { store_slot(d.p[2], d, s, out[0]); store_slot(d.p[3], d, s, out[1]); }
-    if (OP == P_GROW) { store_slot(d.p[0], d, s, out[0]); store_slot(d.p[1], d, s, out[1]); }
+    if (OP == P_FAST2SUM || OP == P_TWOSUM || OP == P_TWOPROD) { store_slot(d.p[2], d, s, out[0]); store_slot(d.p[3], d, s, out[1]); }
+    if (OP == P_GROW || OP == P_GROW2) { store_slot(d.p[0], d, s, out[0]); store_slot(d.p[1], d, s, out[1]); }
+    if (OP == P_SCALING) { store_slot(d.p[3], d, s, out[0]); store_slot(d.p[4], d, s, out[1]); }
+    if (OP == P_MULX) { store_slot(d.p[4], d, s, out[0]); store_slot(d.p[5], d, s, out[1]); }
     if (OP == P_ADD || OP == P_SUB || OP == P_MUL || OP == P_DIV || OP == P_SQRT) store_slot(d.p[2], d, s, out[0]);
   }
   if (OP == P_EDQ) edq_store_partial<kBlock>(acc, partials, blockIdx.x);
@@ -897,10 +917,10 @@ int mcf_adamw_step_flat(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t
 }
 
 static int prim_launch(int op, const void *p0, const void *p1, const void *p2, const void *p3, const void *p4,
-                       int nptr, uint64_t n, void *stream) {
-  const void *ps[5] = {p0, p1, p2, p3, p4};
+                       int nptr, uint64_t n, void *stream, const void *p5 = nullptr) {
+  const void *ps[6] = {p0, p1, p2, p3, p4, p5};
   PrimArgs a = {};
-  uint64_t al[5];
+  uint64_t al[6];
   int na = 0;
   for (int i = 0; i < nptr; ++i) {
     a.p[i] = (uint64_t)(uintptr_t)ps[i];
@@ -924,6 +944,10 @@ static int prim_launch(int op, const void *p0, const void *p1, const void *p2, c
     case P_MUL: hipLaunchKernelGGL(prim_kernel<P_MUL>, g, b, 0, st, a, 0u, 0u, nullptr); break;
     case P_DIV: hipLaunchKernelGGL(prim_kernel<P_DIV>, g, b, 0, st, a, 0u, 0u, nullptr); break;
     case P_SQRT: hipLaunchKernelGGL(prim_kernel<P_SQRT>, g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_GROW2: hipLaunchKernelGGL(prim_kernel<P_GROW2>, g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_TWOPROD: hipLaunchKernelGGL(prim_kernel<P_TWOPROD>, g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_SCALING: hipLaunchKernelGGL(prim_kernel<P_SCALING>, g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_MULX: hipLaunchKernelGGL(prim_kernel<P_MULX>, g, b, 0, st, a, 0u, 0u, nullptr); break;
     default: return MCF_ERR_VARIANT;
   }
   MCF_HIP(hipGetLastError());
@@ -946,6 +970,31 @@ int mcf_grow(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n, void *stre
   if (n == 0) return MCF_OK;
   if (!x || !y || !a) return MCF_ERR_NULL;
   return prim_launch(P_GROW, x, y, a, nullptr, nullptr, 3, n, stream);
+}
+
+int mcf_grow_two_sum(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n, void *stream) {
+  if (n == 0) return MCF_OK;
+  if (!x || !y || !a) return MCF_ERR_NULL;
+  return prim_launch(P_GROW2, x, y, a, nullptr, nullptr, 3, n, stream);
+}
+
+int mcf_two_prod_fma(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *e, uint64_t n, void *stream) {
+  if (n == 0) return MCF_OK;
+  if (!a || !b || !x || !e) return MCF_ERR_NULL;
+  return prim_launch(P_TWOPROD, a, b, x, e, nullptr, 4, n, stream);
+}
+
+int mcf_scaling(const uint16_t *v, const uint16_t *a1, const uint16_t *a2, uint16_t *x, uint16_t *e, uint64_t n, void *stream) {
+  if (n == 0) return MCF_OK;
+  if (!v || !a1 || !a2 || !x || !e) return MCF_ERR_NULL;
+  return prim_launch(P_SCALING, v, a1, a2, x, e, 5, n, stream);
+}
+
+int mcf_mul(const uint16_t *a1, const uint16_t *a2, const uint16_t *b1, const uint16_t *b2, uint16_t *x, uint16_t *e,
+            uint64_t n, void *stream) {
+  if (n == 0) return MCF_OK;
+  if (!a1 || !a2 || !b1 || !b2 || !x || !e) return MCF_ERR_NULL;
+  return prim_launch(P_MULX, a1, a2, b1, b2, x, 6, n, stream, e);
 }
 
 int mcf_bf16_op(int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n, void *stream) {

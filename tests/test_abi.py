@@ -117,6 +117,12 @@ def test_primitive_argument_errors():
     assert lib.mcf_fast2sum(FAKE + 1, FAKE, FAKE, FAKE, 4, None) == mcf.MCF_ERR_ALIGN
     assert lib.mcf_grow(FAKE, FAKE, FAKE, (1 << 35) + 1, None) == mcf.MCF_ERR_SIZE
     assert lib.mcf_fast2sum(None, None, None, None, 0, None) == mcf.MCF_OK
+    assert lib.mcf_grow_two_sum(FAKE, FAKE, None, 4, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_two_prod_fma(FAKE, FAKE, FAKE, None, 4, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_scaling(FAKE, FAKE, None, FAKE, FAKE, 4, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_mul(FAKE, FAKE, FAKE, FAKE, FAKE, None, 4, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_mul(FAKE, FAKE, FAKE, FAKE + 1, FAKE, FAKE, 4, None) == mcf.MCF_ERR_ALIGN
+    assert lib.mcf_mul(None, None, None, None, None, None, 0, None) == mcf.MCF_OK
     assert lib.mcf_bf16_op(5, FAKE, FAKE, FAKE, 4, None) == mcf.MCF_ERR_VARIANT
     assert lib.mcf_bf16_op(0, FAKE, None, FAKE, 4, None) == mcf.MCF_ERR_NULL
     assert lib.mcf_round_f32(FAKE + 2, FAKE, 4, None) == mcf.MCF_ERR_ALIGN

@@ -114,6 +114,28 @@ def test_primitives(n, shift):
     assert np.array_equal(H.torch_to_u16(C[sl]), c)
 
 
+@pytest.mark.parametrize("n,shift", [(5, 1), (100_003, 0), (100_003, 3)])
+def test_product_primitives_and_grow_on_two_sum(n, shift):
+    """TwoProdFMA (Alg. 6), Scaling (Alg. 7), Mul (Alg. 8) and the TwoSum-based Grow on random bit patterns."""
+    arrs = [_random_bf16(n, 45 + k) for k in range(4)]
+    pad = lambda u: _dev(np.concatenate([np.zeros(shift, np.uint16), u, np.zeros(8, np.uint16)]))[shift:shift + n]
+    A, Bt, C, D = (pad(u) for u in arrs)
+    a, b, c, d = arrs
+    X, Y = pad(np.zeros(n, np.uint16)), pad(np.zeros(n, np.uint16))
+    mcf.two_prod_fma(A, Bt, X, Y)
+    wx, wy = orc.two_prod_fma(a, b)
+    assert np.array_equal(H.torch_to_u16(X), wx) and np.array_equal(H.torch_to_u16(Y), wy)
+    mcf.scaling(A, Bt, C, X, Y)
+    wx, wy = orc.scaling(a, b, c)
+    assert np.array_equal(H.torch_to_u16(X), wx) and np.array_equal(H.torch_to_u16(Y), wy)
+    mcf.mul(A, Bt, C, D, X, Y)
+    wx, wy = orc.mul_expansion(a, b, c, d)
+    assert np.array_equal(H.torch_to_u16(X), wx) and np.array_equal(H.torch_to_u16(Y), wy)
+    mcf.grow_two_sum(A, Bt, C)
+    wx, wy = orc.grow_two_sum(a, b, c)
+    assert np.array_equal(H.torch_to_u16(A), wx) and np.array_equal(H.torch_to_u16(Bt), wy)
+
+
 def test_primitives_mutually_misaligned_buffers():
     n = 5000
     a, b = _random_bf16(n, 43), _random_bf16(n, 44)
@@ -453,3 +475,34 @@ def test_flat_tensor_longer_than_2_pow_32():
         assert np.array_equal(H.torch_to_u16(v[idx_dev]), host[k]), k
     # and the step really ran everywhere: m is non-zero wherever the gradient is
     assert int(torch.count_nonzero(st["m"]).item()) > 0.99 * n
+
+
+def test_step_replays_in_a_hip_graph():
+    """The step allocates nothing and clears nothing with memsets, so it can be captured; every replay
+    (with eager work and synchronisation in between) must reproduce the eager result bit for bit."""
+    wl = Workload("flat_1m", variant="plus", shape_list=[("a", 300_001), ("b", 77), ("c", 4096)], misalign_tiny=True,
+                  hyper=W.HYPER_PLUS_1P3B)
+    wl.new_grads(1)
+    snap = {k: getattr(wl, k).clone() for k in wl.state_names()}
+    e_eager = torch.zeros(4, dtype=torch.float64, device=DEV)
+    wl.plan.step(wl.hyper, 1, edq_out=e_eager)
+    torch.cuda.synchronize()
+    want = {k: getattr(wl, k).clone() for k in wl.state_names()}
+    for k, v in snap.items():
+        getattr(wl, k).copy_(v)
+    e_graph = torch.zeros(4, dtype=torch.float64, device=DEV)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        wl.plan.step(wl.hyper, 1, edq_out=e_graph)
+    for rep in range(3):
+        for k, v in snap.items():
+            getattr(wl, k).copy_(v)
+        e_graph.zero_()
+        _ = (wl.grad.float() * 2).sum().item()          # unrelated eager work and a synchronisation
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in wl.state_names():
+            assert torch.equal(getattr(wl, k), want[k]), (rep, k)
+        assert torch.equal(e_graph, e_eager), rep
+    wl.close()

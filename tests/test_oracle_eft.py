@@ -184,3 +184,22 @@ def test_mcf_accumulation_against_fp64_sum(orc):
     assert np.all(np.abs(got - exact) <= steps * 2.0 ** -8)
     assert rel.max() < 2.0 ** -10 and np.median(rel) < 2.0 ** -12, (rel.max(), np.median(rel))
     assert np.all(np.abs(H.u16_to_f64(y)) <= _ulp_arr(H.u16_to_f64(x)) / 2)
+
+
+def test_scaling_is_mul_by_a_one_component_number(orc):
+    """Alg. 7 is Alg. 8 with b = (v, 0): the same bits wherever no signed zero is involved, and accurate to the
+    resolution of a two-component number."""
+    rng = np.random.default_rng(12)
+    n = 400_000
+    a1 = rng.choice(H.bf16_window(-6, 6), n)
+    f1 = H.u16_to_f64(a1)
+    a2 = H.np_round_f64_to_bf16(_ulp_arr(f1) * rng.uniform(-0.5, 0.5, n) * 0.99)
+    v = rng.choice(H.bf16_window(-6, 6), n)
+    x, e = orc.scaling(v, a1, a2)
+    xm, em = orc.mul_expansion(a1, a2, v, np.zeros(n, np.uint16))
+    nz = (H.u16_to_f64(e) != 0) & (H.u16_to_f64(a2) != 0)
+    assert np.array_equal(x, xm) and np.array_equal(e[nz], em[nz])
+    exact = (f1 + H.u16_to_f64(a2)) * H.u16_to_f64(v)
+    rel = np.abs(H.u16_to_f64(x) + H.u16_to_f64(e) - exact) / np.abs(exact)
+    assert rel.max() < 2.0 ** -14
+    assert np.all(np.abs(H.u16_to_f64(e)) <= _ulp_arr(H.u16_to_f64(x)) / 2)
