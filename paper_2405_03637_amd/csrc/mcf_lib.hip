@@ -11,11 +11,14 @@
 // tensors of any size is one launch.
 //
 // Launch shape, from sweeps on MI355X at the 7B-parameter set (9 to 11 concurrent streams
-// of 13.5 GB each): one-wave workgroups with one slot per lane, at most 3 waves per SIMD,
-// and non-temporal loads and stores.  Short-lived single-wave groups keep the set of
+// of 13.5 GB each): one-wave workgroups with one slot per lane, at most 11 of them resident
+// per CU, and non-temporal loads and stores.  Short-lived single-wave groups keep the set of
 // addresses in flight compact, and capping the waves in flight keeps the HBM channels
 // from thrashing between too many open rows: 256-thread groups with two slots per lane at
-// full occupancy reached 5.5 TB/s, this shape 6.4 TB/s on the same device in the same run.
+// full occupancy reached 5.5 TB/s, this shape 6.5-6.6 TB/s on the same device in the same run.
+// The cap is set by giving every workgroup 14.5 KiB of dynamic LDS it never touches
+// (160 KiB per CU / 14.5 KiB = 11 groups): unlike a waves-per-SIMD bound it counts per CU and
+// can sit between multiples of four (10/CU: 18.7 ms, 11: 18.4, 12: 18.6, 14: 18.8 for light).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -51,7 +54,19 @@ using mcfd::StepScalars;
 #define MCF_REMAP 0                  // 1: give each XCD (blocks are dealt round-robin to the 8 XCDs) a contiguous run of chunks
 #endif
 #ifndef MCF_STEP_ATTR
-#define MCF_STEP_ATTR __attribute__((amdgpu_waves_per_eu(1, 3)))     // occupancy cap of the step kernels
+#define MCF_STEP_ATTR                // optional extra attribute of the step kernels (e.g. amdgpu_waves_per_eu)
+#endif
+#ifndef MCF_STEP_LDS
+#define MCF_STEP_LDS 14848           // bytes of untouched dynamic LDS per workgroup = the occupancy cap (11 groups per CU)
+#endif
+#ifndef MCF_STEP_LDS_EDQ
+#define MCF_STEP_LDS_EDQ 10752       // with the fused EDQ sums (fp64 arithmetic to hide) 15 groups per CU measure best
+#endif
+#ifndef MCF_FP32MW_LDS
+#define MCF_FP32MW_LDS MCF_STEP_LDS  // the same cap for the fp32-master baseline kernel
+#endif
+#ifndef MCF_COPY_LDS
+#define MCF_COPY_LDS 0               // the plain copy (2 streams) is fastest uncapped: 6.66 TB/s against 4.4 TB/s with the cap
 #endif
 constexpr int kStepBlock = MCF_BLOCK;
 constexpr int kUnroll = MCF_UNROLL;
@@ -740,11 +755,11 @@ void launch_step(bool fast, bool edq, uint32_t blocks, hipStream_t st, const Ten
   const dim3 g(blocks), b(kStepBlock);
 #endif
   if (fast) {
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, 0, st, descs, chunks, flat, sc, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, 0, st, descs, chunks, flat, sc, partials, blocks);
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, sc, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, MCF_STEP_LDS, st, descs, chunks, flat, sc, partials, blocks);
   } else {
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, 0, st, descs, chunks, flat, sc, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, 0, st, descs, chunks, flat, sc, partials, blocks);
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, sc, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, MCF_STEP_LDS, st, descs, chunks, flat, sc, partials, blocks);
   }
 }
 
@@ -1025,7 +1040,7 @@ int mcf_stream_copy(void *dst, const void *src, uint64_t bytes, void *stream) {
   const uint64_t nvec = bytes / 16;
   const uint64_t blocks = (nvec + kStepBlock - 1) / kStepBlock;
   if (blocks > 0x7fffffffull) return MCF_ERR_SIZE;
-  hipLaunchKernelGGL(copy_kernel, dim3((uint32_t)blocks), dim3(kStepBlock), 0, (hipStream_t)stream,
+  hipLaunchKernelGGL(copy_kernel, dim3((uint32_t)blocks), dim3(kStepBlock), MCF_COPY_LDS, (hipStream_t)stream,
                      (uint64_t)(uintptr_t)dst, (uint64_t)(uintptr_t)src, nvec);
   MCF_HIP(hipGetLastError());
   return MCF_OK;
@@ -1148,7 +1163,7 @@ int mcf_fp32mw_step(mcf_fp32mw_plan *plan, const mcf_hyper *hyper, uint64_t step
   s.e = (float)hyper->eps;
   s.lam = (float)hyper->weight_decay;
   s.na = (float)(-hyper->lr);
-  hipLaunchKernelGGL(fp32mw_kernel, dim3(plan->n_chunks), dim3(kStepBlock), 0, (hipStream_t)stream, plan->d_descs, plan->d_chunks, s);
+  hipLaunchKernelGGL(fp32mw_kernel, dim3(plan->n_chunks), dim3(kStepBlock), MCF_FP32MW_LDS, (hipStream_t)stream, plan->d_descs, plan->d_chunks, s);
   MCF_HIP(hipGetLastError());
   return MCF_OK;
 }
