@@ -23,7 +23,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor peak
 # HBM traffic per parameter per step measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
 # what the same counters read for a plain copy of known size (FETCH_SIZE x2.0000, WRITE_SIZE x1.0000);
 # the figures and commands are in profiles/*_llama_7b.md.  None = not measured.
-MEASURED_TRAFFIC_BYTES_PER_PARAM = {"light": 18.250, "plus": 22.250, "fp32mw": 29.389}
+MEASURED_TRAFFIC_BYTES_PER_PARAM = {"light": 18.250, "plus": 22.250, "kahan": 18.250, "bf16": 14.250, "fp32mw": 28.250}
 
 
 def log(msg):
@@ -136,7 +136,7 @@ def main():
     bpp = W.bytes_per_param(variant.split("+")[0])
     kern_s = gpu_s / args.steps
     achieved = bpp * n_params / kern_s / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES_PER_PARAM.get(variant)
+    traffic = MEASURED_TRAFFIC_BYTES_PER_PARAM.get(variant.split("+")[0])
     result = {
         "metric": "MCF-AdamW params updated/sec and % of HBM roofline (GB/s) at 7B, 1 GPU",
         "value": n_params * args.steps / wall,
