@@ -147,6 +147,20 @@ inline void adamw_element(uint16_t &theta, uint16_t &dtheta, uint16_t &m, uint16
                           uint16_t g, int variant_and_flags, const orc_scalars &s, uint16_t *delta_out) {
   const int variant = variant_and_flags & 0xff;
   const bool sorted_free = (variant_and_flags & ORC_GROW_TWOSUM) != 0;   /* Grow built on TwoSum */
+  if (variant == 4) {
+    /* MCF-SGD with momentum (Sec. 1 calls the extension to SGD straightforward and prints no
+     * algorithm; this is SGD with the same two changes as Alg. 2: the decay term inside the summed
+     * update, App. D, and Grow for the parameter).  s.b1 holds the momentum coefficient mu:
+     *   m <- mu*m + g ;  delta <- -alpha*(m + lambda*theta) ;  (theta,dtheta) <- Grow(., delta) */
+    uint16_t m_new = Fadd(Fmul(s.b1, m), g);
+    uint16_t delta = Fmul(s.na, Fadd(m_new, Fmul(s.lam, theta)));
+    Pair th = grow(Pair{theta, dtheta}, delta);
+    theta = th.hi;
+    dtheta = th.lo;
+    m = m_new;
+    if (delta_out) *delta_out = delta;
+    return;
+  }
   /* line 8: m <- beta1*m + (1-beta1)*g */
   uint16_t m_new = Fadd(Fmul(s.b1, m), Fmul(s.c1, g));
 
@@ -339,8 +353,9 @@ void orc_adamw_step(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t *v,
   parallel_ranges(n, nthreads, [=](uint64_t lo, uint64_t hi) {
     uint16_t unused = 0;
     const int base = variant & 0xff;
+    uint16_t no_v = 0;
     for (uint64_t i = lo; i < hi; ++i)
-      adamw_element(theta[i], base == 2 ? unused : dtheta[i], m[i], v[i], base == 1 ? &dv[i] : nullptr,
+      adamw_element(theta[i], base == 2 ? unused : dtheta[i], m[i], base == 4 ? no_v : v[i], base == 1 ? &dv[i] : nullptr,
                     grad[i], variant, s, delta_out ? &delta_out[i] : nullptr);
   });
 }

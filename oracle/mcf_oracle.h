@@ -81,7 +81,9 @@ void orc_scalars_derive(const orc_hyper *h, uint64_t t, orc_scalars *out);
 /* ---- the step (Alg. 2 lines 8-13) ----
  * variant 0 = Collage-light (option B), 1 = Collage-plus (option C; dv required),
  *         2 = plain bf16 (option A: line 13 is theta <- F(theta + delta), Eq. 1; dtheta unused, may be NULL),
- *         3 = Kahan-compensated bf16 (App. B; dtheta holds the Kahan variable c).
+ *         3 = Kahan-compensated bf16 (App. B; dtheta holds the Kahan variable c),
+ *         4 = MCF-SGD with momentum (Sec. 1): m <- beta1*m + g, delta <- -lr*(m + wd*theta), Grow;
+ *             beta1 is the momentum coefficient, beta2 and eps are ignored, v is unused (may be NULL).
  * ORC_GROW_TWOSUM may be OR-ed onto variants 0 and 1: every Grow then uses TwoSum (Alg. 3)
  * instead of Fast2Sum, which drops the |x| >= |a| precondition of Alg. 1.
  * All state is updated in place.  delta_out, if not NULL, receives the bf16

@@ -17,7 +17,7 @@ _SRC = os.path.join(_HERE, "mcf_oracle.cpp")
 _LIB = os.path.join(_HERE, "libmcf_oracle.so")
 
 ADD, SUB, MUL, DIV, SQRT = 0, 1, 2, 3, 4
-LIGHT, PLUS, BF16, KAHAN = 0, 1, 2, 3
+LIGHT, PLUS, BF16, KAHAN, SGD = 0, 1, 2, 3, 4
 GROW_TWOSUM = 0x100          # OR onto LIGHT or PLUS: Grow built on TwoSum
 
 
@@ -206,15 +206,15 @@ def adamw_step(theta, dtheta, m, v, dv, grad, variant, hyper, t, delta_out=None,
     """In-place Collage step over uint16 arrays.  hyper = (lr, beta1, beta2, eps, weight_decay)."""
     n = theta.size
     base = variant & 0xFF
-    for arr in (m, v, grad) + (() if base == BF16 else (dtheta,)):
+    for arr in (m, grad) + (() if base == BF16 else (dtheta,)) + (() if base == SGD else (v,)):
         assert arr.size == n
     if base == PLUS:
         assert dv is not None and dv.size == n
     if delta_out is not None:
         assert delta_out.size == n
     h = Hyper(*hyper)
-    _load().orc_adamw_step(_u16(theta, True), None if base == BF16 else _u16(dtheta, True), _u16(m, True), _u16(v, True),
-                           _u16(dv, True) if base == PLUS else None, _u16(grad), n, int(variant),
+    _load().orc_adamw_step(_u16(theta, True), None if base == BF16 else _u16(dtheta, True), _u16(m, True),
+                           None if base == SGD else _u16(v, True), _u16(dv, True) if base == PLUS else None, _u16(grad), n, int(variant),
                            ctypes.byref(h), int(t), _u16(delta_out, True),
                            int(nthreads or default_threads()))
 

@@ -187,3 +187,48 @@ def test_step_with_two_sum_grow(orc):
     eb = np.abs(H.u16_to_f64(b["v"]) + H.u16_to_f64(b["dv"]) - ema) / ema
     assert eb.max() < 2.0 ** -7 and np.median(eb) < 2.0 ** -9
     assert eb.mean() <= ea.mean() * 1.001
+
+
+def test_mcf_sgd(orc):
+    """MCF-SGD with momentum (Sec. 1: "extensions to SGD are straight-forward"): checked as a composition of
+    pinned primitives, against torch's fp64 SGD (momentum, no decay) and against the closed form of pure decay."""
+    import torch
+    n, steps = 10_000, 80
+    lr, mu = 2.0 ** -14, 0.9
+    st = _state(n, 9, theta_std=1.0)
+    th0 = H.u16_to_f64(st["theta"])
+    p = torch.nn.Parameter(torch.tensor(th0, dtype=torch.float64))
+    opt = torch.optim.SGD([p], lr=lr, momentum=mu)
+    b1 = np.full(n, orc.B(mu), np.uint16)
+    plain = st["theta"].copy()
+    for t in range(1, steps + 1):
+        g = _grads(n, 9, t, std=1.0, mean=0.5)
+        d = np.empty(n, np.uint16)
+        th_b, dth_b, m_b = st["theta"].copy(), st["dtheta"].copy(), st["m"].copy()
+        orc.adamw_step(st["theta"], st["dtheta"], st["m"], None, None, g, orc.SGD, (lr, mu, 0.0, 0.0, 0.0), t, delta_out=d)
+        # composition of single operations and Grow
+        assert np.array_equal(st["m"], orc.binop(orc.ADD, orc.binop(orc.MUL, b1, m_b), g))
+        gx, gy = orc.grow(th_b, dth_b, d)
+        assert np.array_equal(st["theta"], gx) and np.array_equal(st["dtheta"], gy)
+        plain = orc.binop(orc.ADD, plain, d)
+        p.grad = torch.tensor(H.u16_to_f64(g), dtype=torch.float64)
+        opt.step()
+    ref = p.detach().numpy()
+    got = H.u16_to_f64(st["theta"]) + H.u16_to_f64(st["dtheta"])
+    moved = np.abs(ref - th0)
+    big = np.abs(th0) > 0.3
+    assert np.median(moved) > 0.01
+    # the momentum buffer carries 8 bits: a few 2^-8 of the distance travelled, plus the expansion's resolution
+    assert np.all(np.abs(got - ref)[big] <= 0.03 * moved[big] + steps * 2.0 ** -16 * np.abs(th0)[big])
+    # every single update is below half an ulp of theta there, so plain bf16 accumulation is far worse
+    assert np.median(np.abs(H.u16_to_f64(plain) - ref)[big]) > 10 * np.median(np.abs(got - ref)[big])
+    # pure decay: zero gradients
+    st = _state(n, 10, theta_std=1.0)
+    th0 = H.u16_to_f64(st["theta"])
+    z = np.zeros(n, np.uint16)
+    for t in range(1, 101):
+        orc.adamw_step(st["theta"], st["dtheta"], st["m"], None, None, z, orc.SGD, (1e-3, 0.9, 0.0, 0.0, 0.1), t)
+    got = H.u16_to_f64(st["theta"]) + H.u16_to_f64(st["dtheta"])
+    want = th0 * (1 - 1e-3 * 0.1) ** 100
+    assert np.all(np.abs(got - want) <= 0.012 * np.abs(th0 - want) + 100 * 2.0 ** -17 * np.abs(th0))
+    assert not st["m"].any()
