@@ -55,7 +55,8 @@ def build_light_or_plus(name, variant, dev):
     offs, total = W.layout(shapes, misalign_tiny=(name == "stress_64m"))
     z = lambda: torch.zeros(total, dtype=torch.bfloat16, device=dev)
     base = variant.split("+")[0]
-    st = {"theta": z(), "m": z(), "v": z(), "grad": z()}
+    st = {"theta": z(), "m": z(), "grad": z()}
+    st["v"] = z() if base != "sgd" else st["m"]          # SGD keeps no second moment (the pre-warm copies m onto itself)
     if base != "bf16":
         st["dtheta"] = z()
     if base == "plus":
@@ -63,9 +64,10 @@ def build_light_or_plus(name, variant, dev):
     W.init_theta(name, shapes, offs, st["theta"])
     drift = W.stress_drift(shapes, offs, total, dev) if name == "stress_64m" else None
     W.fill_grads(name, shapes, offs, st["grad"], 1, drift=drift)
-    tensors = [(st["theta"][o:o + n], st["dtheta"][o:o + n] if base != "bf16" else None, st["m"][o:o + n], st["v"][o:o + n],
+    tensors = [(st["theta"][o:o + n], st["dtheta"][o:o + n] if base != "bf16" else None, st["m"][o:o + n],
+                st["v"][o:o + n] if base != "sgd" else None,
                 st["dv"][o:o + n] if base == "plus" else None, st["grad"][o:o + n]) for (_, n), o in zip(shapes, offs)]
-    code = {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN}[base]
+    code = {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN, "sgd": mcf.SGD}[base]
     if variant.endswith("+twosum"):
         code |= mcf.GROW_TWOSUM
     plan = mcf.Plan(tensors, code)
@@ -174,7 +176,7 @@ def main():
             del src, dst
             st = None
             # the other strategies on the same shapes
-            for other in ("plus", "light", "kahan", "bf16", "light+twosum", "plus+twosum"):
+            for other in ("plus", "light", "kahan", "bf16", "sgd", "light+twosum", "plus+twosum"):
                 if other == variant:
                     continue
                 st2 = None

@@ -65,8 +65,13 @@ typedef struct { double lr, beta1, beta2, eps, weight_decay; } mcf_hyper;
  * The other two are the paper's comparison strategies on the same chain (lines 8-12
  * unchanged): MCF_BF16 = plain bf16, option A, line 13 is Eq. 1 theta <- F(theta + delta);
  * MCF_KAHAN = Kahan-compensated bf16 (App. B): u = F(delta + c), theta' = F(theta + u),
- * c <- F(u - F(theta' - theta)), with c kept in dtheta. */
-typedef enum { MCF_LIGHT = 0, MCF_PLUS = 1, MCF_BF16 = 2, MCF_KAHAN = 3 } mcf_variant;
+ * c <- F(u - F(theta' - theta)), with c kept in dtheta.
+ * MCF_SGD = SGD with momentum on the parameter expansion (Sec. 1 calls the extension
+ * straightforward and prints no algorithm; the reading here keeps Alg. 2's two changes: the decay
+ * term inside the summed update and Grow): m <- F(F(mu*m) + g), delta <- F(-lr * F(m + F(wd*theta))),
+ * (theta,dtheta) <- Grow((theta,dtheta), delta); mu = hyper.beta1, hyper.beta2 and hyper.eps are
+ * ignored, v and dv are unused and may be NULL. */
+typedef enum { MCF_LIGHT = 0, MCF_PLUS = 1, MCF_BF16 = 2, MCF_KAHAN = 3, MCF_SGD = 4 } mcf_variant;
 /* May be OR-ed onto MCF_LIGHT or MCF_PLUS: every Grow (Alg. 1) is built on TwoSum (Alg. 3, six
  * operations) instead of Fast2Sum (three), which removes Alg. 1's precondition |x| >= |a| -- it can
  * fail for parameters near zero, for v = 0 at the first step, and when a gradient spike exceeds v

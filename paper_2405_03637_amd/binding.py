@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 MCF_OK = 0
 MCF_ERR_NULL, MCF_ERR_SIZE, MCF_ERR_ALIGN, MCF_ERR_VARIANT, MCF_ERR_STEP, MCF_ERR_HYPER, MCF_ERR_HIP = \
     -1, -2, -3, -4, -5, -6, -7
-LIGHT, PLUS, BF16, KAHAN = 0, 1, 2, 3
+LIGHT, PLUS, BF16, KAHAN, SGD = 0, 1, 2, 3, 4
 GROW_TWOSUM = 0x100
 OP_ADD, OP_SUB, OP_MUL, OP_DIV, OP_SQRT = 0, 1, 2, 3, 4
 

@@ -269,6 +269,7 @@ template <int VARIANT> struct StepStreams {
   static constexpr bool kGrow2 = (VARIANT & kGrow2Bit) != 0;
   static constexpr bool kDth = kBase != mcfd::V_BF16;      // second component of theta / Kahan variable
   static constexpr bool kDv = kBase == mcfd::V_PLUS;       // second component of v
+  static constexpr bool kV = kBase != mcfd::V_SGD;         // second moment
 };
 
 // Hot path: one full slot, 8 elements of every stream held as 4 dwords each.  Returns true
@@ -284,7 +285,7 @@ __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], u
     io.th = mcfd::widen2(in[S_TH][k]);
     if (SS::kDth) io.dth = mcfd::widen2(in[S_DTH][k]); else io.dth = {0.f, 0.f};
     io.m = mcfd::widen2(in[S_M][k]);
-    io.v = mcfd::widen2(in[S_V][k]);
+    if (SS::kV) io.v = mcfd::widen2(in[S_V][k]); else io.v = {0.f, 0.f};
     io.g = mcfd::widen2(in[S_G][k]);
     if (SS::kDv) io.dv = mcfd::widen2(in[S_DV][k]); else io.dv = {0.f, 0.f};
     const P2 th0 = io.th, dth0 = io.dth;
@@ -293,7 +294,7 @@ __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], u
     out[S_TH][k] = mcfd::pack2(io.th);
     if (SS::kDth) out[S_DTH][k] = mcfd::pack2(io.dth);
     out[S_M][k] = mcfd::pack2(io.m);
-    out[S_V][k] = mcfd::pack2(io.v);
+    if (SS::kV) out[S_V][k] = mcfd::pack2(io.v);
     if (SS::kDv) out[S_DV][k] = mcfd::pack2(io.dv);
     if (EDQ) {
       edq_add(acc, delta.lo, th0.lo, dth0.lo, io.th.lo, io.dth.lo);
@@ -326,7 +327,7 @@ __device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, cons
     io.th = mcfd::widen2(th[e]);
     if (SS::kDth) io.dth = mcfd::widen2(dth[e]); else io.dth = {0.f, 0.f};
     io.m = mcfd::widen2(m[e]);
-    io.v = mcfd::widen2(v[e]);
+    if (SS::kV) io.v = mcfd::widen2(v[e]); else io.v = {0.f, 0.f};
     io.g = mcfd::widen2(g[e]);
     if (SS::kDv) io.dv = mcfd::widen2(dv[e]); else io.dv = {0.f, 0.f};
     const float th0 = io.th.lo, dth0 = io.dth.lo;
@@ -336,7 +337,7 @@ __device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, cons
     th[e] = (uint16_t)(mcfd::fbits(io.th.lo) >> 16);
     if (SS::kDth) dth[e] = (uint16_t)(mcfd::fbits(io.dth.lo) >> 16);
     m[e] = (uint16_t)(mcfd::fbits(io.m.lo) >> 16);
-    v[e] = (uint16_t)(mcfd::fbits(io.v.lo) >> 16);
+    if (SS::kV) v[e] = (uint16_t)(mcfd::fbits(io.v.lo) >> 16);
     if (SS::kDv) dv[e] = (uint16_t)(mcfd::fbits(io.dv.lo) >> 16);
     if (EDQ) edq_add(acc, delta.lo, th0, dth0, io.th.lo, io.dth.lo);
   }
@@ -379,7 +380,7 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
       load_vec(d.p[S_TH], e0, in[j][S_TH]);
       if (SS::kDth) load_vec(d.p[S_DTH], e0, in[j][S_DTH]);
       load_vec(d.p[S_M], e0, in[j][S_M]);
-      load_vec(d.p[S_V], e0, in[j][S_V]);
+      if (SS::kV) load_vec(d.p[S_V], e0, in[j][S_V]);
       load_vec(d.p[S_G], e0, in[j][S_G]);
       if (SS::kDv) load_vec(d.p[S_DV], e0, in[j][S_DV]);
     }
@@ -399,7 +400,7 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
         store_vec(d.p[S_TH], e0, out[S_TH]);
         if (SS::kDth) store_vec(d.p[S_DTH], e0, out[S_DTH]);
         store_vec(d.p[S_M], e0, out[S_M]);
-        store_vec(d.p[S_V], e0, out[S_V]);
+        if (SS::kV) store_vec(d.p[S_V], e0, out[S_V]);
         if (SS::kDv) store_vec(d.p[S_DV], e0, out[S_DV]);
         if (EDQ) { acc.s1 += local.s1; acc.s2 += local.s2; acc.lost += local.lost; }
       }
@@ -716,17 +717,17 @@ inline uint64_t slots_of(uint64_t n, uint32_t phase) { return (n + phase + 7) / 
 inline bool known_variant(int v) {
   const int base = v & ~MCF_GROW_TWOSUM;
   if (v & MCF_GROW_TWOSUM) return base == MCF_LIGHT || base == MCF_PLUS;
-  return base == MCF_LIGHT || base == MCF_PLUS || base == MCF_BF16 || base == MCF_KAHAN;
+  return base == MCF_LIGHT || base == MCF_PLUS || base == MCF_BF16 || base == MCF_KAHAN || base == MCF_SGD;
 }
 
 int check_tensor(const mcf_tensor &t, int variant) {
   variant &= ~MCF_GROW_TWOSUM;
   if (t.n == 0) return MCF_OK;
-  const bool need_dth = variant != MCF_BF16, need_dv = variant == MCF_PLUS;
-  if (!t.theta || !t.m || !t.v || !t.grad) return MCF_ERR_NULL;
-  if ((need_dth && !t.dtheta) || (need_dv && !t.dv)) return MCF_ERR_NULL;
+  const bool need_dth = variant != MCF_BF16, need_dv = variant == MCF_PLUS, need_v = variant != MCF_SGD;
+  if (!t.theta || !t.m || !t.grad) return MCF_ERR_NULL;
+  if ((need_dth && !t.dtheta) || (need_dv && !t.dv) || (need_v && !t.v)) return MCF_ERR_NULL;
   if (t.n > kMaxTensorElems) return MCF_ERR_SIZE;
-  if (misaligned(t.theta, 2) || misaligned(t.m, 2) || misaligned(t.v, 2) || misaligned(t.grad, 2) ||
+  if (misaligned(t.theta, 2) || misaligned(t.m, 2) || misaligned(t.grad, 2) || (need_v && misaligned(t.v, 2)) ||
       (need_dth && misaligned(t.dtheta, 2)) || (need_dv && misaligned(t.dv, 2)))
     return MCF_ERR_ALIGN;
   return MCF_OK;
@@ -739,7 +740,7 @@ void fill_desc(const mcf_tensor &t, int variant, TensorDesc &d) {
   d.p[S_TH] = (uint64_t)(uintptr_t)t.theta;
   d.p[S_DTH] = variant != MCF_BF16 ? (uint64_t)(uintptr_t)t.dtheta : d.p[S_TH];
   d.p[S_M] = (uint64_t)(uintptr_t)t.m;
-  d.p[S_V] = (uint64_t)(uintptr_t)t.v;
+  d.p[S_V] = variant != MCF_SGD ? (uint64_t)(uintptr_t)t.v : d.p[S_TH];
   d.p[S_G] = (uint64_t)(uintptr_t)t.grad;
   d.p[S_DV] = variant == MCF_PLUS ? (uint64_t)(uintptr_t)t.dv : d.p[S_V];
   d.n = t.n;
@@ -774,6 +775,7 @@ void launch_variant(int variant, bool fast, bool edq, uint32_t blocks, hipStream
     case MCF_PLUS: launch_step<mcfd::V_PLUS, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
     case MCF_BF16: launch_step<mcfd::V_BF16, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
     case MCF_KAHAN: launch_step<mcfd::V_KAHAN, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
+    case MCF_SGD: launch_step<mcfd::V_SGD, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
     default: launch_step<mcfd::V_LIGHT, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
   }
 }

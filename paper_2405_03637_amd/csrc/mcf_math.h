@@ -144,7 +144,8 @@ struct ElemIO {          // one pair of elements of every stream
 // Variants of the step.  Light and plus are Collage (Sec. 4.2); the other two are the paper's
 // comparison strategies built on the same chain: plain bf16 (option A: line 13 is Eq. 1,
 // theta <- F(theta + delta)) and Kahan-compensated bf16 (App. B; dtheta holds the Kahan variable).
-enum : int { V_LIGHT = 0, V_PLUS = 1, V_BF16 = 2, V_KAHAN = 3 };
+// V_SGD is MCF-SGD with momentum (Sec. 1): m <- mu*m + g, delta <- -alpha*(m + lambda*theta), Grow.
+enum : int { V_LIGHT = 0, V_PLUS = 1, V_BF16 = 2, V_KAHAN = 3, V_SGD = 4 };
 
 // Alg. 2 lines 8-13 on one pair.  GROW2 builds every Grow on TwoSum.  On return io holds the new theta, dtheta, m, v (and dv);
 // delta receives line 12's update.  redo is raised (Fast mode) when this pair must be
@@ -152,6 +153,17 @@ enum : int { V_LIGHT = 0, V_PLUS = 1, V_BF16 = 2, V_KAHAN = 3 };
 template <class M, int VARIANT, bool GROW2 = false>
 __device__ __forceinline__ void adamw_pair(ElemIO &io, const StepScalars &s, P2 &delta, bool &redo) {
   using O = Ops<M>;
+  if (VARIANT == V_SGD) {
+    const P2 m1 = O::add(O::muls(s.b1, io.m), io.g);            // s.b1 = momentum coefficient
+    delta = O::muls(s.na, O::add(m1, O::muls(s.lam, io.th)));
+    P2 th1, dth1;
+    O::grow(io.th, io.dth, delta, th1, dth1);
+    if (M::kFast) redo |= is_nan(th1.lo) | is_nan(dth1.lo) | is_nan(th1.hi) | is_nan(dth1.hi);
+    io.th = th1;
+    io.dth = dth1;
+    io.m = m1;
+    return;
+  }
   // line 8
   P2 m1 = O::add(O::muls(s.b1, io.m), O::muls(s.c1, io.g));
   // line 9

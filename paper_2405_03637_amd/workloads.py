@@ -206,5 +206,5 @@ def expected_totals():
 
 def bytes_per_param(kind):
     """Algorithmic HBM bytes moved per parameter per step (state read + written, Table 1 turned into traffic)."""
-    return {"light": 18, "plus": 22, "kahan": 18, "bf16": 14, "fp32mw": 28}[kind]
+    return {"light": 18, "plus": 22, "kahan": 18, "bf16": 14, "sgd": 14, "fp32mw": 28}[kind]
 

@@ -42,14 +42,16 @@ class Workload:
         self.shapes = shape_list if shape_list is not None else W.shapes(name)
         vname = variant or W.WORKLOADS[name][1]
         self.variant = {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN,
-                        "light+twosum": mcf.LIGHT | mcf.GROW_TWOSUM, "plus+twosum": mcf.PLUS | mcf.GROW_TWOSUM}[vname]
+                        "sgd": mcf.SGD, "light+twosum": mcf.LIGHT | mcf.GROW_TWOSUM, "plus+twosum": mcf.PLUS | mcf.GROW_TWOSUM}[vname]
         base = self.variant & 0xFF
         self.hyper = hyper or W.WORKLOADS[name][2]
         self.offs, self.total = W.layout(self.shapes, misalign_tiny=misalign_tiny, align=align)
         self.seed = seed
         self.device = device
         z = lambda: torch.zeros(self.total, dtype=torch.bfloat16, device=device)
-        self.theta, self.m, self.v = z(), z(), z()
+        base = self.variant & 0xFF
+        self.theta, self.m = z(), z()
+        self.v = z() if base != mcf.SGD else None
         self.dtheta = z() if base != mcf.BF16 else None
         self.dv = z() if base == mcf.PLUS else None
         self.grad = z()
@@ -59,14 +61,16 @@ class Workload:
         tensors = []
         for (_, n), o in zip(self.shapes, self.offs):
             sl = slice(o, o + n)
-            tensors.append((self.theta[sl], self.dtheta[sl] if self.dtheta is not None else None, self.m[sl], self.v[sl],
+            tensors.append((self.theta[sl], self.dtheta[sl] if self.dtheta is not None else None, self.m[sl],
+                            self.v[sl] if self.v is not None else None,
                             self.dv[sl] if self.dv is not None else None, self.grad[sl]))
         self.plan = mcf.Plan(tensors, self.variant)
         self.n_params = W.total_params(self.shapes)
         assert self.plan.params == self.n_params
 
     def state_names(self):
-        return ["theta"] + (["dtheta"] if self.dtheta is not None else []) + ["m", "v"] + (["dv"] if self.dv is not None else [])
+        return ["theta"] + (["dtheta"] if self.dtheta is not None else []) + ["m"] + (["v"] if self.v is not None else []) + \
+            (["dv"] if self.dv is not None else [])
 
     def new_grads(self, step):
         W.fill_grads(self.name, self.shapes, self.offs, self.grad, step, seed=self.seed, sigmas=self.sigmas,
@@ -96,7 +100,7 @@ class SampledOracle:
         g = self.wl.gather(self.wl.grad, self.idx_dev)
         s = self.state
         delta = np.empty(g.size, np.uint16) if want_delta else None
-        orc.adamw_step(s["theta"], s.get("dtheta"), s["m"], s["v"], s.get("dv"), g, self.wl.variant, self.wl.hyper, t,
+        orc.adamw_step(s["theta"], s.get("dtheta"), s["m"], s.get("v"), s.get("dv"), g, self.wl.variant, self.wl.hyper, t,
                        delta_out=delta)
         return delta
 

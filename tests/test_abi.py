@@ -52,7 +52,8 @@ def test_flat_step_argument_errors():
     assert _flat(theta=None) == mcf.MCF_ERR_NULL
     assert _flat(grad=None) == mcf.MCF_ERR_NULL
     assert _flat(variant=1, dv=None) == mcf.MCF_ERR_NULL
-    assert _flat(variant=4) == mcf.MCF_ERR_VARIANT
+    assert _flat(variant=99) == mcf.MCF_ERR_VARIANT
+    assert _flat(variant=mcf.SGD | mcf.GROW_TWOSUM) == mcf.MCF_ERR_VARIANT
     assert _flat(variant=mcf.BF16 | mcf.GROW_TWOSUM) == mcf.MCF_ERR_VARIANT     # the flag applies to Collage only
     assert _flat(variant=mcf.LIGHT | 0x200) == mcf.MCF_ERR_VARIANT
     assert _flat(variant=3, dtheta=None) == mcf.MCF_ERR_NULL          # Kahan needs its variable

@@ -163,7 +163,7 @@ def _full_oracle_run(wl, steps, edq=False, check_each=True):
         before = {k: host[k].copy() for k in ("theta", "dtheta") if k in host} if edq else None
         delta = np.zeros(wl.total, np.uint16) if edq else None
         # the oracle steps the whole arena; padding between tensors is stepped too and then ignored
-        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host["v"], host.get("dv"), g, wl.variant, wl.hyper, t,
+        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host.get("v"), host.get("dv"), g, wl.variant, wl.hyper, t,
                        delta_out=delta)
         wl.plan.step(wl.hyper, t, edq_out=edq_dev)
         torch.cuda.synchronize()
@@ -191,7 +191,7 @@ def _full_oracle_run(wl, steps, edq=False, check_each=True):
             assert want > 0
 
 
-@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan", "light+twosum", "plus+twosum"])
+@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan", "sgd", "light+twosum", "plus+twosum"])
 def test_config1_flat_1m(variant):
     """Config 1: one flat tensor of 2^20, 10 steps, every element after every step; plan and flat entry points."""
     _say(f"config 1 {variant}")
@@ -204,14 +204,14 @@ def test_config1_flat_1m(variant):
     for t in range(1, 4):
         wl.new_grads(t)
         g = H.torch_to_u16(wl.grad)
-        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host["v"], host.get("dv"), g, wl.variant, wl.hyper, t)
+        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host.get("v"), host.get("dv"), g, wl.variant, wl.hyper, t)
         mcf.adamw_step_flat(wl.theta, wl.dtheta, wl.m, wl.v, wl.dv, wl.grad, wl.variant, wl.hyper, t)
     for k in wl.state_names():
         assert np.array_equal(H.torch_to_u16(getattr(wl, k)), host[k]), k
     wl.close()
 
 
-@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan", "plus+twosum"])
+@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan", "sgd", "plus+twosum"])
 def test_many_small_and_ragged_tensors(variant):
     """A few hundred tensors of 1..3000 elements packed back to back at odd offsets, plus three that span
     several chunks with ragged tails: exercises the chunk table, heads, tails and tiny tensors."""
@@ -242,7 +242,7 @@ def test_mutually_misaligned_tensor_goes_elementwise():
     plan.destroy()
 
 
-@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan", "light+twosum", "plus+twosum"])
+@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan", "sgd", "light+twosum", "plus+twosum"])
 def test_special_values_take_the_exact_path(variant):
     """State and gradients drawn from all bit patterns (NaN, infinities, zeros, subnormals, huge and tiny
     values): the guarded fast arithmetic must hand these to the exact path and still match bit for bit."""
@@ -250,25 +250,28 @@ def test_special_values_take_the_exact_path(variant):
     shapes = [("a", n)]
     wl = Workload("flat_1m", variant=variant, shape_list=shapes)
     rnd = lambda s: _dev(_random_bf16(wl.total, s))
-    wl.theta.copy_(rnd(60)); wl.m.copy_(rnd(62)); wl.v.copy_(rnd(63))
+    wl.theta.copy_(rnd(60)); wl.m.copy_(rnd(62))
+    if wl.v is not None:
+        wl.v.copy_(rnd(63))
     if wl.dtheta is not None:
         wl.dtheta.copy_(rnd(61))
     if wl.dv is not None:
         wl.dv.copy_(rnd(64))
     # v must mostly be non-negative to keep a share of the elements finite
-    wl.v[: n // 2].abs_()
+    if wl.v is not None:
+        wl.v[: n // 2].abs_()
     host = {k: H.torch_to_u16(getattr(wl, k)) for k in wl.state_names()}
     for t in range(1, 4):
         wl.grad.copy_(rnd(70 + t))
         g = H.torch_to_u16(wl.grad)
-        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host["v"], host.get("dv"), g, wl.variant, wl.hyper, t)
+        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host.get("v"), host.get("dv"), g, wl.variant, wl.hyper, t)
         wl.plan.step(wl.hyper, t)
         for k in wl.state_names():
             dev = H.torch_to_u16(getattr(wl, k))
             bad = np.flatnonzero(dev != host[k])
             assert bad.size == 0, f"step {t} {k}: {bad.size} mismatches, first {int(bad[0])}: got {dev[bad[0]]:#06x} want {host[k][bad[0]]:#06x}"
     frac_nan = np.mean((host["theta"] & 0x7FFF) > 0x7F80)
-    assert 0.05 < frac_nan < 0.9999
+    assert 0.005 < frac_nan < 0.9999
     wl.close()
 
 
