@@ -249,3 +249,48 @@ def edq(delta, th0, dth0, th1, dth1, scratch, out, stream=None):
 def stream_copy(dst, src, stream=None):
     nbytes = src.numel() * src.element_size()
     _check(lib().mcf_stream_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "mcf_stream_copy")
+
+
+# ---- the C names, one to one (each returns nothing and raises McfError on a non-zero status) ----
+def mcf_plan_create(tensors, variant):
+    return Plan(tensors, variant)
+
+
+def mcf_plan_destroy(plan):
+    plan.destroy()
+
+
+def mcf_plan_params(plan):
+    return plan.params
+
+
+def mcf_adamw_step(plan, hyper, step, stream=None, edq_dev=None):
+    plan.step(hyper, step, stream=stream, edq_out=edq_dev)
+
+
+mcf_adamw_step_flat = adamw_step_flat
+mcf_fast2sum = fast2sum
+mcf_two_sum = two_sum
+mcf_grow = grow
+mcf_grow_two_sum = grow_two_sum
+mcf_two_prod_fma = two_prod_fma
+mcf_scaling = scaling
+mcf_mul = mul
+mcf_bf16_op = bf16_op
+mcf_round_f32 = round_f32
+mcf_edq_scratch_bytes = edq_scratch_bytes
+mcf_edq = edq
+mcf_stream_copy = stream_copy
+mcf_status_string = status_string
+
+
+def mcf_fp32mw_plan_create(tensors):
+    return Fp32MwPlan(tensors)
+
+
+def mcf_fp32mw_plan_destroy(plan):
+    plan.destroy()
+
+
+def mcf_fp32mw_step(plan, hyper, step, stream=None):
+    plan.step(hyper, step, stream=stream)

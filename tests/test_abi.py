@@ -148,3 +148,15 @@ def test_fp32mw_argument_errors():
     assert lib.mcf_fp32mw_step(h, ctypes.byref(hy), 0, None) == mcf.MCF_ERR_STEP
     assert lib.mcf_fp32mw_step(h, ctypes.byref(hy), 3, None) == mcf.MCF_OK
     assert lib.mcf_fp32mw_plan_destroy(h) == mcf.MCF_OK
+
+
+def test_binding_has_every_c_name():
+    for n in _declared():
+        assert hasattr(mcf, n), n
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr

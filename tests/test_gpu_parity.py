@@ -509,3 +509,43 @@ def test_step_replays_in_a_hip_graph():
             assert torch.equal(getattr(wl, k), want[k]), (rep, k)
         assert torch.equal(e_graph, e_eager), rep
     wl.close()
+
+
+_EXACT_SCRIPT = r"""
+import sys
+sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[1] + "/tests")
+import numpy as np, torch
+import helpers as H
+from gpu_harness import Workload
+from oracle import oracle as orc
+from paper_2405_03637_amd import workloads as W
+for variant in ("light", "plus", "kahan", "bf16", "sgd", "plus+twosum"):
+    shapes = [("a", 100_003), ("b", 5), ("c", 8192), ("d", 333)]
+    wl = Workload("flat_1m", variant=variant, shape_list=shapes, misalign_tiny=True,
+                  hyper=W.HYPER_PLUS_1P3B if variant.startswith("plus") else W.HYPER_LIGHT)
+    host = {k: H.torch_to_u16(getattr(wl, k)) for k in wl.state_names()}
+    edq = torch.zeros(4, dtype=torch.float64, device="cuda")
+    for t in range(1, 4):
+        wl.new_grads(t)
+        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host.get("v"), host.get("dv"),
+                       H.torch_to_u16(wl.grad), wl.variant, wl.hyper, t)
+        wl.plan.step(wl.hyper, t, edq_out=edq if t == 2 else None)
+    torch.cuda.synchronize()
+    for (_, n), o in zip(wl.shapes, wl.offs):
+        for k in wl.state_names():
+            assert np.array_equal(H.torch_to_u16(getattr(wl, k)[o:o + n]), host[k][o:o + n]), (variant, k)
+    wl.close()
+print("exact mode ok")
+"""
+
+
+def test_forced_exact_arithmetic_mode():
+    """MCF_FORCE_EXACT=1 routes every step through the IEEE divide/sqrt, bit-pattern-rounding kernels (the
+    ones the host falls back to for out-of-range hyper-parameters); they must match the oracle as well.
+    The switch is read once per process, hence the child process."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, MCF_FORCE_EXACT="1")
+    r = subprocess.run([sys.executable, "-c", _EXACT_SCRIPT, root], capture_output=True, text=True, env=env, timeout=300)
+    assert r.returncode == 0 and "exact mode ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
