@@ -14,6 +14,11 @@
  *               rounded once to bf16 with round-to-nearest-even.
  *   R(f)      : fp32 -> bf16, round-to-nearest-even, NaN -> 0x7FC0.
  *   B(x)      : fp64 -> bf16 in ONE rounding (not through float).
+ *   format    : the paper states its algorithms for any low-precision component format and names
+ *               fp16 beside bf16 (Sec. 1, App. A Table 7).  Functions ending in _fmt take a format
+ *               id (ORC_BF16 = 0, ORC_FP16 = 1: IEEE binary16 in a uint16_t) and do the same
+ *               steps with W, R and B of that format; the step takes ORC_FMT_FP16 OR-ed onto its
+ *               variant.  The names without _fmt are the bf16 ones.
  *
  * Parity status: every function below is pinned by tests/test_oracle_*.py to
  * values the paper prints, to exact rational arithmetic, to closed forms or to
@@ -21,7 +26,8 @@
  * Algorithm 2 (one rounding per elementary operation, bf16 scalars, epsilon
  * outside the square root) is a reading of the paper, which prints no worked
  * AdamW step; that reading is the definition and is listed with the repository's
- * design notes.
+ * design notes.  For fp16 the chain code is the same template; its decode and its two roundings
+ * are pinned by tests/test_oracle_fp16.py to exact rational arithmetic and to numpy's binary16.
  */
 #ifndef MCF_ORACLE_H
 #define MCF_ORACLE_H
@@ -37,12 +43,20 @@ uint16_t orc_R(float f);          /* fp32 -> bf16 RNE */
 uint16_t orc_B(double x);         /* fp64 -> bf16 RNE, single rounding */
 float    orc_widen(uint16_t h);   /* bf16 -> fp32, exact */
 void     orc_R_array(const float *f, uint16_t *out, uint64_t n);   /* R over an array */
+#define ORC_BF16 0
+#define ORC_FP16 1
+uint16_t orc_R_fmt(int fmt, float f);
+uint16_t orc_B_fmt(int fmt, double x);
+float    orc_widen_fmt(int fmt, uint16_t h);
+void     orc_R_array_fmt(int fmt, const float *f, uint16_t *out, uint64_t n);
+void     orc_widen_array_fmt(int fmt, const uint16_t *h, float *out, uint64_t n);
 /* 1 if fp32 subnormals are neither flushed on input nor on output here. */
 int      orc_fp_env_ok(void);
 
 /* ---- one bf16 operation over arrays: out[i] = F(a[i] op b[i]) ----
  * op: 0 add, 1 sub, 2 mul, 3 div, 4 sqrt (b ignored, may be NULL). */
 void orc_binop(int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n);
+void orc_binop_fmt(int fmt, int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n);
 
 /* ---- error-free transformations ---- */
 /* Thm 4.1: x = F(a+b), y = F(b - F(x-a)). */
@@ -61,9 +75,16 @@ void orc_scaling(const uint16_t *v, const uint16_t *a1, const uint16_t *a2, uint
 void orc_mul_expansion(const uint16_t *a1, const uint16_t *a2, const uint16_t *b1, const uint16_t *b2,
                        uint16_t *x, uint16_t *e, uint64_t n);
 
+/* Any of the seven above in either format.  which: 0 Fast2Sum(p0,p1), 1 TwoSum(p0,p1),
+ * 2 Grow((p0,p1),p2), 3 Grow on TwoSum, 4 TwoProdFMA(p0,p1), 5 Scaling(v=p0,(p1,p2)),
+ * 6 Mul((p0,p1),(p2,p3)); the two results go to o0 and o1 (which may alias inputs). */
+void orc_prim_fmt(int fmt, int which, const uint16_t *p0, const uint16_t *p1, const uint16_t *p2, const uint16_t *p3,
+                  uint16_t *o0, uint16_t *o1, uint64_t n);
+
 /* ---- AdamW scalars (Alg. 2 line 1, Table 2, App. D "Scalar and Bias Correction") ---- */
 typedef struct { double lr, beta1, beta2, eps, weight_decay; } orc_hyper;
 #define ORC_GROW_TWOSUM 0x100
+#define ORC_FMT_FP16 0x1000    /* OR-ed onto the step's variant: every array and scalar is fp16 */
 typedef struct {
   uint16_t b1;   /* B(beta1)            */
   uint16_t c1;   /* B(1-beta1)          */
@@ -77,6 +98,7 @@ typedef struct {
   uint16_t na;   /* B(-lr)              */
 } orc_scalars;
 void orc_scalars_derive(const orc_hyper *h, uint64_t t, orc_scalars *out);
+void orc_scalars_derive_fmt(int fmt, const orc_hyper *h, uint64_t t, orc_scalars *out);
 
 /* ---- the step (Alg. 2 lines 8-13) ----
  * variant 0 = Collage-light (option B), 1 = Collage-plus (option C; dv required),
@@ -86,6 +108,7 @@ void orc_scalars_derive(const orc_hyper *h, uint64_t t, orc_scalars *out);
  *             beta1 is the momentum coefficient, beta2 and eps are ignored, v is unused (may be NULL).
  * ORC_GROW_TWOSUM may be OR-ed onto variants 0 and 1: every Grow then uses TwoSum (Alg. 3)
  * instead of Fast2Sum, which drops the |x| >= |a| precondition of Alg. 1.
+ * ORC_FMT_FP16 may be OR-ed onto any variant: the same steps on fp16 arrays with fp16 scalars.
  * All state is updated in place.  delta_out, if not NULL, receives the bf16
  * update Delta-theta of line 12 for every element.  nthreads >= 1 splits the
  * elements evenly over that many host threads (elements are independent). */
@@ -109,6 +132,9 @@ void orc_fp32mw_step(uint16_t *theta, float *master, float *m, float *v, const u
 void   orc_edq_accumulate(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0,
                           const uint16_t *th1, const uint16_t *dth1, uint64_t n,
                           double *s1, double *s2, uint64_t *lost /* may be NULL */);
+void   orc_edq_accumulate_fmt(int fmt, const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0,
+                              const uint16_t *th1, const uint16_t *dth1, uint64_t n,
+                              double *s1, double *s2, uint64_t *lost /* may be NULL */);
 double orc_edq_finish(double s1, double s2);
 
 #ifdef __cplusplus

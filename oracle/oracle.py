@@ -4,7 +4,8 @@ TEST INFRASTRUCTURE, NOT THE PRODUCT: only tests/, the smoke check and the
 benchmark's cpu_baseline leg may import this module.  The GPU library never
 does, and this module never imports the GPU package.
 
-bf16 arrays are numpy uint16 arrays (the upper half of an fp32 bit pattern).
+bf16 arrays are numpy uint16 arrays (the upper half of an fp32 bit pattern); with fmt=FMT_FP16
+the same uint16 arrays hold IEEE binary16 patterns and every step is done in that format.
 """
 import ctypes
 import os
@@ -19,6 +20,8 @@ _LIB = os.path.join(_HERE, "libmcf_oracle.so")
 ADD, SUB, MUL, DIV, SQRT = 0, 1, 2, 3, 4
 LIGHT, PLUS, BF16, KAHAN, SGD = 0, 1, 2, 3, 4
 GROW_TWOSUM = 0x100          # OR onto LIGHT or PLUS: Grow built on TwoSum
+FMT_BF16, FMT_FP16 = 0, 1    # component format ids (fmt= arguments)
+STEP_FP16 = 0x1000           # OR onto the step's variant: fp16 arrays and scalars
 
 
 def build(force=False):
@@ -74,6 +77,19 @@ def _load():
     lib.orc_fp32mw_step.argtypes = [_u16p, _f32p, _f32p, _f32p, _u16p, ctypes.c_uint64,
                                     ctypes.POINTER(Hyper), ctypes.c_uint64, ctypes.c_int]
     lib.orc_edq_accumulate.argtypes = [_u16p] * 5 + [ctypes.c_uint64, _f64p, _f64p, ctypes.POINTER(ctypes.c_uint64)]
+    lib.orc_R_fmt.restype = ctypes.c_uint16
+    lib.orc_R_fmt.argtypes = [ctypes.c_int, ctypes.c_float]
+    lib.orc_B_fmt.restype = ctypes.c_uint16
+    lib.orc_B_fmt.argtypes = [ctypes.c_int, ctypes.c_double]
+    lib.orc_widen_fmt.restype = ctypes.c_float
+    lib.orc_widen_fmt.argtypes = [ctypes.c_int, ctypes.c_uint16]
+    lib.orc_R_array_fmt.argtypes = [ctypes.c_int, _f32p, _u16p, ctypes.c_uint64]
+    lib.orc_widen_array_fmt.argtypes = [ctypes.c_int, _u16p, _f32p, ctypes.c_uint64]
+    lib.orc_binop_fmt.argtypes = [ctypes.c_int, ctypes.c_int, _u16p, _u16p, _u16p, ctypes.c_uint64]
+    lib.orc_prim_fmt.argtypes = [ctypes.c_int, ctypes.c_int] + [_u16p] * 6 + [ctypes.c_uint64]
+    lib.orc_scalars_derive_fmt.argtypes = [ctypes.c_int, ctypes.POINTER(Hyper), ctypes.c_uint64, ctypes.POINTER(Scalars)]
+    lib.orc_edq_accumulate_fmt.argtypes = [ctypes.c_int] + [_u16p] * 5 + [ctypes.c_uint64, _f64p, _f64p,
+                                                                          ctypes.POINTER(ctypes.c_uint64)]
     lib.orc_edq_finish.restype = ctypes.c_double
     lib.orc_edq_finish.argtypes = [ctypes.c_double, ctypes.c_double]
     _lib = lib
@@ -99,26 +115,33 @@ def default_threads():
 
 
 # ---- scalar helpers -------------------------------------------------------
-def R(f):
-    """fp32 -> bf16 bits (RNE)."""
-    return int(_load().orc_R(float(np.float32(f))))
+def R(f, fmt=FMT_BF16):
+    """fp32 -> 16-bit pattern (RNE)."""
+    return int(_load().orc_R_fmt(fmt, float(np.float32(f))))
 
 
-def R_array(f):
-    """fp32 array -> bf16 bits (RNE)."""
+def R_array(f, fmt=FMT_BF16):
+    """fp32 array -> 16-bit patterns (RNE)."""
     f = np.ascontiguousarray(f, dtype=np.float32)
     out = np.empty(f.shape, np.uint16)
-    _load().orc_R_array(f.ctypes.data_as(_f32p), _u16(out), f.size)
+    _load().orc_R_array_fmt(fmt, f.ctypes.data_as(_f32p), _u16(out), f.size)
     return out
 
 
-def B(x):
-    """fp64 -> bf16 bits in one rounding."""
-    return int(_load().orc_B(float(x)))
+def B(x, fmt=FMT_BF16):
+    """fp64 -> 16-bit pattern in one rounding."""
+    return int(_load().orc_B_fmt(fmt, float(x)))
 
 
-def widen(h):
-    return float(_load().orc_widen(int(h)))
+def widen(h, fmt=FMT_BF16):
+    return float(_load().orc_widen_fmt(fmt, int(h)))
+
+
+def widen_array(h, fmt=FMT_BF16):
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    out = np.empty(h.shape, np.float32)
+    _load().orc_widen_array_fmt(fmt, _u16(h), out.ctypes.data_as(_f32p), h.size)
+    return out
 
 
 def fp_env_ok():
@@ -126,84 +149,73 @@ def fp_env_ok():
 
 
 # ---- array operations -----------------------------------------------------
-def binop(op, a, b=None):
+def binop(op, a, b=None, fmt=FMT_BF16):
     a = np.ascontiguousarray(a, dtype=np.uint16)
     if b is None:
         b = a
     b = np.ascontiguousarray(b, dtype=np.uint16)
     assert a.shape == b.shape
     out = np.empty_like(a)
-    _load().orc_binop(op, _u16(a), _u16(b), _u16(out), a.size)
+    _load().orc_binop_fmt(fmt, op, _u16(a), _u16(b), _u16(out), a.size)
     return out
 
 
-def _pair_op(name, a, b):
-    a = np.ascontiguousarray(a, dtype=np.uint16)
-    b = np.ascontiguousarray(b, dtype=np.uint16)
-    assert a.shape == b.shape
-    x = np.empty_like(a)
-    y = np.empty_like(a)
-    getattr(_load(), name)(_u16(a), _u16(b), _u16(x), _u16(y), a.size)
+F2S, TWOSUM, GROW, GROW2, TWOPROD, SCALING, MULX = range(7)
+_PRIM_INPUTS = {F2S: 2, TWOSUM: 2, GROW: 3, GROW2: 3, TWOPROD: 2, SCALING: 3, MULX: 4}
+
+
+def prim(which, *inputs, fmt=FMT_BF16):
+    """One of the seven expansion primitives over arrays; returns the two result arrays."""
+    assert len(inputs) == _PRIM_INPUTS[which]
+    arrs = [np.ascontiguousarray(t, dtype=np.uint16) for t in inputs]
+    assert all(t.shape == arrs[0].shape for t in arrs)
+    x = np.empty_like(arrs[0])
+    y = np.empty_like(arrs[0])
+    ptrs = [_u16(t) for t in arrs] + [None] * (4 - len(arrs))
+    _load().orc_prim_fmt(fmt, which, *ptrs, _u16(x), _u16(y), x.size)
     return x, y
 
 
-def fast2sum(a, b):
-    return _pair_op("orc_fast2sum", a, b)
+def fast2sum(a, b, fmt=FMT_BF16):
+    return prim(F2S, a, b, fmt=fmt)
 
 
-def two_sum(a, b):
-    return _pair_op("orc_two_sum", a, b)
+def two_sum(a, b, fmt=FMT_BF16):
+    return prim(TWOSUM, a, b, fmt=fmt)
 
 
-def two_prod_fma(a, b):
-    return _pair_op("orc_two_prod_fma", a, b)
+def two_prod_fma(a, b, fmt=FMT_BF16):
+    return prim(TWOPROD, a, b, fmt=fmt)
 
 
-def grow(x, y, a):
+def grow(x, y, a, fmt=FMT_BF16):
     """Returns new (x, y); inputs are not modified."""
-    x = np.array(x, dtype=np.uint16, copy=True)
-    y = np.array(y, dtype=np.uint16, copy=True)
-    a = np.ascontiguousarray(a, dtype=np.uint16)
-    assert x.shape == y.shape == a.shape
-    _load().orc_grow(_u16(x), _u16(y), _u16(a), x.size)
-    return x, y
+    return prim(GROW, x, y, a, fmt=fmt)
 
 
-def grow_two_sum(x, y, a):
+def grow_two_sum(x, y, a, fmt=FMT_BF16):
     """Grow built on TwoSum.  Returns new (x, y); inputs are not modified."""
-    x = np.array(x, dtype=np.uint16, copy=True)
-    y = np.array(y, dtype=np.uint16, copy=True)
-    a = np.ascontiguousarray(a, dtype=np.uint16)
-    assert x.shape == y.shape == a.shape
-    _load().orc_grow_two_sum(_u16(x), _u16(y), _u16(a), x.size)
-    return x, y
+    return prim(GROW2, x, y, a, fmt=fmt)
 
 
-def mul_expansion(a1, a2, b1, b2):
-    arrs = [np.ascontiguousarray(t, dtype=np.uint16) for t in (a1, a2, b1, b2)]
-    x = np.empty_like(arrs[0])
-    e = np.empty_like(arrs[0])
-    _load().orc_mul_expansion(*[_u16(t) for t in arrs], _u16(x), _u16(e), x.size)
-    return x, e
+def mul_expansion(a1, a2, b1, b2, fmt=FMT_BF16):
+    return prim(MULX, a1, a2, b1, b2, fmt=fmt)
 
 
-def scaling(v, a1, a2):
-    arrs = [np.ascontiguousarray(t, dtype=np.uint16) for t in (v, a1, a2)]
-    x = np.empty_like(arrs[0])
-    e = np.empty_like(arrs[0])
-    _load().orc_scaling(*[_u16(t) for t in arrs], _u16(x), _u16(e), x.size)
-    return x, e
+def scaling(v, a1, a2, fmt=FMT_BF16):
+    return prim(SCALING, v, a1, a2, fmt=fmt)
 
 
-def scalars(lr, beta1, beta2, eps, weight_decay, t):
+def scalars(lr, beta1, beta2, eps, weight_decay, t, fmt=FMT_BF16):
     h = Hyper(lr, beta1, beta2, eps, weight_decay)
     s = Scalars()
-    _load().orc_scalars_derive(ctypes.byref(h), int(t), ctypes.byref(s))
+    _load().orc_scalars_derive_fmt(fmt, ctypes.byref(h), int(t), ctypes.byref(s))
     return {k: getattr(s, k) for k, _ in Scalars._fields_}
 
 
 def adamw_step(theta, dtheta, m, v, dv, grad, variant, hyper, t, delta_out=None, nthreads=None):
-    """In-place Collage step over uint16 arrays.  hyper = (lr, beta1, beta2, eps, weight_decay)."""
+    """In-place Collage step over uint16 arrays.  hyper = (lr, beta1, beta2, eps, weight_decay).
+    variant may carry GROW_TWOSUM and STEP_FP16."""
     n = theta.size
     base = variant & 0xFF
     for arr in (m, grad) + (() if base == BF16 else (dtheta,)) + (() if base == SGD else (v,)):
@@ -230,21 +242,22 @@ def fp32mw_step(theta, master, m, v, grad, hyper, t, nthreads=None):
 class EdqAccumulator:
     """Sums the two EDQ totals over any number of slices, then finishes."""
 
-    def __init__(self):
+    def __init__(self, fmt=FMT_BF16):
+        self.fmt = fmt
         self.s1 = ctypes.c_double(0.0)
         self.s2 = ctypes.c_double(0.0)
         self.lost = ctypes.c_uint64(0)
 
     def add(self, delta, th0, dth0, th1, dth1):
         n = delta.size
-        _load().orc_edq_accumulate(_u16(delta), _u16(th0), _u16(dth0), _u16(th1), _u16(dth1), n,
-                                   ctypes.byref(self.s1), ctypes.byref(self.s2), ctypes.byref(self.lost))
+        _load().orc_edq_accumulate_fmt(self.fmt, _u16(delta), _u16(th0), _u16(dth0), _u16(th1), _u16(dth1), n,
+                                       ctypes.byref(self.s1), ctypes.byref(self.s2), ctypes.byref(self.lost))
 
     def value(self):
         return float(_load().orc_edq_finish(self.s1.value, self.s2.value))
 
 
-def edq(delta, th0, dth0, th1, dth1):
-    acc = EdqAccumulator()
+def edq(delta, th0, dth0, th1, dth1, fmt=FMT_BF16):
+    acc = EdqAccumulator(fmt)
     acc.add(delta, th0, dth0, th1, dth1)
     return acc.value()
