@@ -48,12 +48,14 @@ def time_steps(fn, steps, warmup):
 
 
 def build_light_or_plus(name, variant, dev):
+    """variant: light | plus | bf16 | kahan | sgd, optionally followed by +twosum and/or +fp16."""
     import torch
     from paper_2405_03637_amd import binding as mcf
     from paper_2405_03637_amd import workloads as W
     shapes = W.shapes(name)
     offs, total = W.layout(shapes, misalign_tiny=(name == "stress_64m"))
-    z = lambda: torch.zeros(total, dtype=torch.bfloat16, device=dev)
+    fp16 = "+fp16" in variant
+    z = lambda: torch.zeros(total, dtype=torch.float16 if fp16 else torch.bfloat16, device=dev)
     base = variant.split("+")[0]
     st = {"theta": z(), "m": z(), "grad": z()}
     st["v"] = z() if base != "sgd" else st["m"]          # SGD keeps no second moment (the pre-warm copies m onto itself)
@@ -63,13 +65,15 @@ def build_light_or_plus(name, variant, dev):
         st["dv"] = z()
     W.init_theta(name, shapes, offs, st["theta"])
     drift = W.stress_drift(shapes, offs, total, dev) if name == "stress_64m" else None
-    W.fill_grads(name, shapes, offs, st["grad"], 1, drift=drift)
+    W.fill_grads(name, shapes, offs, st["grad"], 1, drift=drift, grad_scale=W.FP16_LOSS_SCALE if fp16 else 1.0)
     tensors = [(st["theta"][o:o + n], st["dtheta"][o:o + n] if base != "bf16" else None, st["m"][o:o + n],
                 st["v"][o:o + n] if base != "sgd" else None,
                 st["dv"][o:o + n] if base == "plus" else None, st["grad"][o:o + n]) for (_, n), o in zip(shapes, offs)]
     code = {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN, "sgd": mcf.SGD}[base]
-    if variant.endswith("+twosum"):
+    if "+twosum" in variant:
         code |= mcf.GROW_TWOSUM
+    if fp16:
+        code |= mcf.FMT_FP16
     plan = mcf.Plan(tensors, code)
     return st, plan, W.total_params(shapes), len(shapes)
 
@@ -85,13 +89,18 @@ def cpu_baseline(name, variant, hyper, sample=32 * 1024 * 1024, min_seconds=1.5)
     n = min(sample, W.total_params(W.shapes(name)))
     theta = H.torch_to_u16(W.normal_bf16(n, 0.02, (0, 0, 0)))
     z = lambda: np.zeros(n, np.uint16)
-    dth, m, v, dv = z(), z(), z(), (z() if variant == "plus" else None)
+    dth, m, v, dv = z(), z(), z(), (z() if variant.startswith("plus") else None)
     threads = orc.default_threads()
     grads = [H.torch_to_u16(W.normal_bf16(n, 1e-3, (0, 1, t))) for t in (1, 2)]
-    orc.adamw_step(theta, dth, m, v, dv, grads[0], 1 if variant == "plus" else 0, hyper, 1, nthreads=threads)   # warm-up
+    code = {"light": orc.LIGHT, "plus": orc.PLUS, "bf16": orc.BF16, "kahan": orc.KAHAN, "sgd": orc.SGD}[variant.split("+")[0]]
+    if "+twosum" in variant:
+        code |= orc.GROW_TWOSUM
+    if "+fp16" in variant:                 # the same bit patterns read as fp16: the oracle's cost does not depend on the values
+        code |= orc.STEP_FP16
+    orc.adamw_step(theta, dth, m, v, dv, grads[0], code, hyper, 1, nthreads=threads)   # warm-up
     steps, t0 = 0, time.perf_counter()
     while steps < 2 or time.perf_counter() - t0 < min_seconds:
-        orc.adamw_step(theta, dth, m, v, dv, grads[steps & 1], 1 if variant == "plus" else 0, hyper, steps + 2, nthreads=threads)
+        orc.adamw_step(theta, dth, m, v, dv, grads[steps & 1], code, hyper, steps + 2, nthreads=threads)
         steps += 1
     el = time.perf_counter() - t0
     return {"value": n * steps / el, "unit": "params/s", "cores": threads, "kind": "oracle",
@@ -122,6 +131,8 @@ def main():
     name = args.workload
     variant = args.variant or W.WORKLOADS[name][1]
     hyper = W.WORKLOADS[name][2]
+    if "+fp16" in variant:
+        hyper = W.fp16_hyper(hyper)
 
     log(f"bench: building {name} ({variant})")
     st, plan, n_params, n_tensors = build_light_or_plus(name, variant, dev)
@@ -146,7 +157,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "fp16" if "+fp16" in variant else "bf16",
         "data": "synthetic: theta~N(0,0.02), grad~N(0,1e-3) drawn on the GPU before the timed region; zero-initialised m, v, dtheta",
         "config": {"workload": f"{name} Collage-{variant}: {n_tensors} tensors, {n_params} bf16 params, one launch per step",
                    "params": n_params, "tensors": n_tensors, "variant": variant, "bytes_per_param": bpp},
@@ -176,13 +187,15 @@ def main():
             del src, dst
             st = None
             # the other strategies on the same shapes
-            for other in ("plus", "light", "kahan", "bf16", "sgd", "light+twosum", "plus+twosum"):
+            for other in ("plus", "light", "kahan", "bf16", "sgd", "light+twosum", "plus+twosum", "light+fp16", "plus+fp16"):
                 if other == variant:
                     continue
                 st2 = None
                 torch.cuda.empty_cache()
                 st2, plan2, _, _ = build_light_or_plus(name, other, dev)
                 h2 = W.HYPER_PLUS_1P3B if other.startswith("plus") else W.HYPER_LIGHT
+                if "+fp16" in other:
+                    h2 = W.fp16_hyper(h2)
                 _, s = time_steps(lambda t: plan2.step(h2, t), args.steps, args.warmup)
                 extras[f"{other}_GBps"] = W.bytes_per_param(other.split("+")[0]) * n_params * args.steps / s / 1e9
                 extras[f"{other}_ms"] = s / args.steps * 1e3

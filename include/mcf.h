@@ -9,6 +9,14 @@
  *   F(a o b) (Sec. 3.1): operands widened exactly to fp32, one fp32 operation,
  *   one round-to-nearest-even to bf16.  Subnormals are kept, infinities and
  *   NaN follow IEEE 754; every NaN result is stored as 0x7FC0.
+ *   The paper states its algorithms for any low-precision component and names
+ *   fp16 beside bf16 (Sec. 1; App. A Table 7: 5 exponent bits, 10 stored
+ *   significand bits).  With the fp16 component the same uint16_t buffers hold
+ *   IEEE binary16 patterns, F rounds to fp16, the scalars are cast to fp16, and
+ *   every NaN result is stored as 0x7E00.  fp16's range is the caller's
+ *   business: an epsilon below 2^-25 becomes 0 and squared gradients below
+ *   2^-24 are lost or subnormal, so gradients normally need a loss scale the
+ *   paper does not specify; none is applied here.
  *
  * Conventions for every entry point
  *   - Returns MCF_OK (0) or a negative mcf_status.  No exceptions, no errno,
@@ -77,6 +85,11 @@ typedef enum { MCF_LIGHT = 0, MCF_PLUS = 1, MCF_BF16 = 2, MCF_KAHAN = 3, MCF_SGD
  * fail for parameters near zero, for v = 0 at the first step, and when a gradient spike exceeds v
  * (App. C: the same expansion without the ordering).  Any other combination is MCF_ERR_VARIANT. */
 #define MCF_GROW_TWOSUM 0x100
+/* May be OR-ed onto any variant (and combined with MCF_GROW_TWOSUM where that is allowed): the
+ * tensors and the derived scalars are fp16 instead of bf16. */
+#define MCF_FMT_FP16 0x1000
+/* Component format argument of the primitives below. */
+typedef enum { MCF_COMPONENT_BF16 = 0, MCF_COMPONENT_FP16 = 1 } mcf_component;
 
 /* One parameter tensor: flat, contiguous, n elements per buffer, all device memory.
  * theta, dtheta: the parameter expansion (Alg. 2 lines 2-3; MCF_KAHAN: the Kahan variable;
@@ -136,6 +149,27 @@ int mcf_bf16_op(int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uin
 /* The rounding inside F: out = bf16(in), round-to-nearest-even, in = fp32 device buffer. */
 int mcf_round_f32(const float *in, uint16_t *out, uint64_t n, void *stream);
 
+/* The primitives above for either component format (Sec. 1, App. A Table 7); the bf16 names are
+ * these with MCF_COMPONENT_BF16.  An unknown component or code is MCF_ERR_VARIANT.
+ * mcf_primitive: `which` selects the algorithm and fixes the inputs; the two results go to
+ * (o0, o1), which may be the same buffers as (p0, p1) (Grow in place) but must not otherwise
+ * overlap an input; unused inputs may be NULL. */
+typedef enum {
+  MCF_PRIM_FAST2SUM = 0,     /* Thm 4.1: (o0,o1) = Fast2Sum(p0, p1)               */
+  MCF_PRIM_TWOSUM = 1,       /* Alg. 3:  (o0,o1) = TwoSum(p0, p1)                 */
+  MCF_PRIM_GROW = 2,         /* Alg. 1:  (o0,o1) = Grow((p0,p1), p2)              */
+  MCF_PRIM_GROW_TWOSUM = 3,  /* Alg. 1 on Alg. 3                                  */
+  MCF_PRIM_TWOPROD = 4,      /* Alg. 6:  (o0,o1) = TwoProdFMA(p0, p1)             */
+  MCF_PRIM_SCALING = 5,      /* Alg. 7:  (o0,o1) = p0 * (p1,p2)                   */
+  MCF_PRIM_MUL = 6           /* Alg. 8:  (o0,o1) = (p0,p1) * (p2,p3)              */
+} mcf_primitive_code;
+int mcf_primitive(int component, int which, const uint16_t *p0, const uint16_t *p1, const uint16_t *p2, const uint16_t *p3,
+                  uint16_t *o0, uint16_t *o1, uint64_t n, void *stream);
+/* Sec. 3.1: out = F(a op b) in the given component format, op as in mcf_bf16_op. */
+int mcf_component_op(int component, int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n, void *stream);
+/* The rounding inside F for the given component format: fp32 device buffer -> 16-bit patterns. */
+int mcf_round_f32_to(int component, const float *in, uint16_t *out, uint64_t n, void *stream);
+
 /* Def. 3.3 as a stand-alone reduction: delta = intended update, (th0,dth0) the parameter
  * before and (th1,dth1) after the step; dth0/dth1 may be NULL (plain bf16 parameters,
  * Eq. 2 as printed).  edq_dev as in mcf_adamw_step.  scratch_dev: device buffer of at
@@ -143,6 +177,9 @@ int mcf_round_f32(const float *in, uint16_t *out, uint64_t n, void *stream);
 uint64_t mcf_edq_scratch_bytes(uint64_t n);
 int mcf_edq(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
             const uint16_t *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev);
+/* The same reduction over buffers of the given component format. */
+int mcf_edq_component(int component, const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
+                      const uint16_t *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev);
 
 /* ---- option D, the mixed-precision baseline the paper compares against (Sec. 2.1, Table 1):
  * bf16 parameter and gradient, fp32 moments and fp32 master weight; plain fp32 AdamW with the

@@ -315,6 +315,9 @@ void parallel_ranges(uint64_t n, int nthreads, Fn fn) {
   for (auto &th : pool) th.join();
 }
 
+/* Host threads the array functions below split their elements over (results do not depend on it). */
+int g_array_threads = 1;
+
 }  // namespace
 
 /* Run `body` with Chain<Bf16> or Chain<Fp16> bound to the name C. */
@@ -326,11 +329,16 @@ void parallel_ranges(uint64_t n, int nthreads, Fn fn) {
 
 extern "C" {
 
+void orc_set_array_threads(int n) { g_array_threads = n < 1 ? 1 : n; }
+
 uint16_t orc_R_fmt(int fmt, float f) { ORC_WITH_FORMAT(fmt, { (void)sizeof(C); return Fm::R(f); }); return 0; }
 uint16_t orc_B_fmt(int fmt, double x) { ORC_WITH_FORMAT(fmt, { (void)sizeof(C); return Fm::B(x); }); return 0; }
 float orc_widen_fmt(int fmt, uint16_t h) { ORC_WITH_FORMAT(fmt, { (void)sizeof(C); return Fm::W(h); }); return 0; }
 void orc_R_array_fmt(int fmt, const float *f, uint16_t *out, uint64_t n) {
-  ORC_WITH_FORMAT(fmt, { (void)sizeof(C); for (uint64_t i = 0; i < n; ++i) out[i] = Fm::R(f[i]); });
+  ORC_WITH_FORMAT(fmt, {
+    (void)sizeof(C);
+    parallel_ranges(n, g_array_threads, [=](uint64_t lo, uint64_t hi) { for (uint64_t i = lo; i < hi; ++i) out[i] = Fm::R(f[i]); });
+  });
 }
 void orc_widen_array_fmt(int fmt, const uint16_t *h, float *out, uint64_t n) {
   ORC_WITH_FORMAT(fmt, { (void)sizeof(C); for (uint64_t i = 0; i < n; ++i) out[i] = Fm::W(h[i]); });
@@ -350,7 +358,7 @@ int orc_fp_env_ok(void) {
 void orc_binop_fmt(int fmt, int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n) {
   ORC_WITH_FORMAT(fmt, {
     (void)sizeof(Fm);
-    parallel_ranges(n, 1, [=](uint64_t lo, uint64_t hi) {
+    parallel_ranges(n, g_array_threads, [=](uint64_t lo, uint64_t hi) {
       for (uint64_t i = lo; i < hi; ++i) {
         switch (op) {
           case 0: out[i] = C::add(a[i], b[i]); break;
@@ -371,7 +379,7 @@ void orc_prim_fmt(int fmt, int which, const uint16_t *p0, const uint16_t *p1, co
                   uint16_t *o0, uint16_t *o1, uint64_t n) {
   ORC_WITH_FORMAT(fmt, {
     (void)sizeof(Fm);
-    parallel_ranges(n, 1, [=](uint64_t lo, uint64_t hi) {
+    parallel_ranges(n, g_array_threads, [=](uint64_t lo, uint64_t hi) {
       for (uint64_t i = lo; i < hi; ++i) {
         Pair r;
         switch (which) {

@@ -50,6 +50,9 @@ uint16_t orc_B_fmt(int fmt, double x);
 float    orc_widen_fmt(int fmt, uint16_t h);
 void     orc_R_array_fmt(int fmt, const float *f, uint16_t *out, uint64_t n);
 void     orc_widen_array_fmt(int fmt, const uint16_t *h, float *out, uint64_t n);
+/* Host threads the array functions (R over arrays, binop, prim) split their elements over; 1 at
+ * start.  Elements are independent, so the results do not depend on it. */
+void     orc_set_array_threads(int n);
 /* 1 if fp32 subnormals are neither flushed on input nor on output here. */
 int      orc_fp_env_ok(void);
 

@@ -92,6 +92,8 @@ def _load():
                                                                           ctypes.POINTER(ctypes.c_uint64)]
     lib.orc_edq_finish.restype = ctypes.c_double
     lib.orc_edq_finish.argtypes = [ctypes.c_double, ctypes.c_double]
+    lib.orc_set_array_threads.argtypes = [ctypes.c_int]
+    lib.orc_set_array_threads(max(1, len(os.sched_getaffinity(0))))
     _lib = lib
     return lib
 

@@ -1,7 +1,7 @@
 """Thin ctypes binding of libmcf_adamw.so: argument marshalling only.
 
 Every step of the optimizer path runs in the library's HIP kernels; torch is used by callers
-for device memory and streams.  Tensors are passed as torch tensors (bf16 viewed through
+for device memory and streams.  Tensors are passed as torch tensors (bf16 or fp16, viewed through
 their data_ptr) or as raw integer device addresses.  There is no CPU fallback: if the
 library cannot be loaded, importing symbols from it raises.
 """
@@ -17,6 +17,9 @@ MCF_ERR_NULL, MCF_ERR_SIZE, MCF_ERR_ALIGN, MCF_ERR_VARIANT, MCF_ERR_STEP, MCF_ER
     -1, -2, -3, -4, -5, -6, -7
 LIGHT, PLUS, BF16, KAHAN, SGD = 0, 1, 2, 3, 4
 GROW_TWOSUM = 0x100
+FMT_FP16 = 0x1000                              # OR onto a variant: fp16 tensors and scalars
+COMPONENT_BF16, COMPONENT_FP16 = 0, 1          # component format of the primitives
+PRIM_FAST2SUM, PRIM_TWOSUM, PRIM_GROW, PRIM_GROW_TWOSUM, PRIM_TWOPROD, PRIM_SCALING, PRIM_MUL = range(7)
 OP_ADD, OP_SUB, OP_MUL, OP_DIV, OP_SQRT = 0, 1, 2, 3, 4
 
 
@@ -75,6 +78,10 @@ def lib():
     L.mcf_mul.argtypes = [_vp] * 6 + [_u64, _vp]
     L.mcf_bf16_op.argtypes = [_int] + [_vp] * 3 + [_u64, _vp]
     L.mcf_round_f32.argtypes = [_vp, _vp, _u64, _vp]
+    L.mcf_primitive.argtypes = [_int, _int] + [_vp] * 6 + [_u64, _vp]
+    L.mcf_component_op.argtypes = [_int, _int] + [_vp] * 3 + [_u64, _vp]
+    L.mcf_round_f32_to.argtypes = [_int, _vp, _vp, _u64, _vp]
+    L.mcf_edq_component.argtypes = [_int] + [_vp] * 5 + [_u64, _vp, _vp, _vp]
     L.mcf_edq_scratch_bytes.restype = _u64
     L.mcf_edq_scratch_bytes.argtypes = [_u64]
     L.mcf_edq.argtypes = [_vp] * 5 + [_u64, _vp, _vp, _vp]
@@ -237,6 +244,27 @@ def round_f32(src, out, stream=None):
     _check(lib().mcf_round_f32(_ptr(src), _ptr(out), src.numel(), _stream(stream)), "mcf_round_f32")
 
 
+def primitive(component, which, inputs, o0, o1, stream=None):
+    """inputs: the 2 to 4 input tensors of the algorithm `which`; results go to (o0, o1)."""
+    ps = [_ptr(t) for t in inputs] + [None] * (4 - len(inputs))
+    _check(lib().mcf_primitive(int(component), int(which), *ps, _ptr(o0), _ptr(o1), inputs[0].numel(), _stream(stream)),
+           "mcf_primitive")
+
+
+def component_op(component, op, a, b, out, stream=None):
+    _check(lib().mcf_component_op(int(component), int(op), _ptr(a), _ptr(b), _ptr(out), a.numel(), _stream(stream)),
+           "mcf_component_op")
+
+
+def round_f32_to(component, src, out, stream=None):
+    _check(lib().mcf_round_f32_to(int(component), _ptr(src), _ptr(out), src.numel(), _stream(stream)), "mcf_round_f32_to")
+
+
+def edq_component(component, delta, th0, dth0, th1, dth1, scratch, out, stream=None):
+    _check(lib().mcf_edq_component(int(component), _ptr(delta), _ptr(th0), _ptr(dth0), _ptr(th1), _ptr(dth1), delta.numel(),
+                                   _ptr(scratch), _stream(stream), _ptr(out)), "mcf_edq_component")
+
+
 def edq_scratch_bytes(n):
     return int(lib().mcf_edq_scratch_bytes(int(n)))
 
@@ -280,6 +308,10 @@ mcf_bf16_op = bf16_op
 mcf_round_f32 = round_f32
 mcf_edq_scratch_bytes = edq_scratch_bytes
 mcf_edq = edq
+mcf_primitive = primitive
+mcf_component_op = component_op
+mcf_round_f32_to = round_f32_to
+mcf_edq_component = edq_component
 mcf_stream_copy = stream_copy
 mcf_status_string = status_string
 

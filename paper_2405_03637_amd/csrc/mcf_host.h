@@ -1,4 +1,4 @@
-// Host-side preparation for the Collage step: argument checks and the bf16 scalars of
+// Host-side preparation for the Collage step: argument checks and the bf16 (or fp16) scalars of
 // Alg. 2 (computed in fp64 and cast once, App. D "Scalar and Bias Correction").
 #pragma once
 #include <stdint.h>
@@ -48,6 +48,42 @@ inline float bf16_to_f32(uint16_t h) {
   return f;
 }
 
+// fp64 -> fp16 (IEEE binary16) with a single round-to-nearest-even, the same way: 11 of the 53
+// bits remain (fewer in the subnormal range, fixed spacing 2^-24); every NaN becomes 0x7E00.
+inline uint16_t f64_to_f16(double x) {
+  uint64_t u;
+  std::memcpy(&u, &x, 8);
+  const uint16_t sign = (uint16_t)((u >> 48) & 0x8000u);
+  const int ef = (int)((u >> 52) & 0x7ff);
+  const uint64_t frac = u & ((1ull << 52) - 1);
+  if (ef == 0x7ff) return frac ? (uint16_t)0x7e00 : (uint16_t)(sign | 0x7c00);
+  if (ef == 0) return sign;
+  const int e = ef - 1023;
+  const uint64_t sig = frac | (1ull << 52);
+  int shift = 42;                                  // normal: keep 11 of the 53 bits
+  if (e < -14) shift += -14 - e;
+  if (shift > 54) return sign;                     // less than a quarter of the least subnormal
+  const uint64_t q = sig >> shift;
+  const uint64_t rem = sig & ((1ull << shift) - 1);
+  const uint64_t half = 1ull << (shift - 1);
+  const uint64_t up = (rem > half || (rem == half && (q & 1))) ? 1 : 0;
+  uint32_t bits;
+  if (e >= -14) {
+    bits = (uint32_t)((e + 15) << 10) + (uint32_t)(q + up - 1024);   // a carry moves into the exponent
+    if (bits >= 0x7c00u) bits = 0x7c00u;
+  } else {
+    bits = (uint32_t)(q + up);
+  }
+  return (uint16_t)(sign | bits);
+}
+
+// Exact value of a finite fp16 pattern as a double.
+inline double f16_to_f64(uint16_t h) {
+  const int e = (h >> 10) & 0x1f, m = h & 0x3ff;
+  const double mag = e == 0 ? std::ldexp((double)m, -24) : std::ldexp((double)(1024 + m), e - 25);
+  return (h & 0x8000) ? -mag : mag;
+}
+
 inline int check_hyper(const mcf_hyper *h, uint64_t step) {
   if (!h) return MCF_ERR_NULL;
   if (step < 1) return MCF_ERR_STEP;
@@ -86,6 +122,26 @@ inline bool derive_scalars(const mcf_hyper &h, uint64_t step, mcfd::StepScalars 
   auto sane_bc = [](float x) { return x >= 0x1p-60f && x <= 1.0f; };
   const bool eps_ok = (s.e == 0.0f) || (s.e >= 0x1p-100f && s.e <= 0x1p60f);
   return sane_bc(s.bc1) && sane_bc(s.bc2) && eps_ok;
+}
+
+// The same scalars as fp16 patterns, each copied into both halves of a packed register.  The fp16
+// arithmetic has no restricted mode, so there is nothing to report.
+inline void derive_scalars_fp16(const mcf_hyper &h, uint64_t step, mcfd::StepScalarsH &s) {
+  const double t = (double)step;
+  auto splat = [](uint16_t b) { return __builtin_bit_cast(mcfd::h2_t, (uint32_t)b * 0x00010001u); };
+  const uint16_t b2 = f64_to_f16(h.beta2);
+  s.b1 = splat(f64_to_f16(h.beta1));
+  s.c1 = splat(f64_to_f16(1.0 - h.beta1));
+  s.b2 = splat(b2);
+  s.b2l = splat(f64_to_f16(h.beta2 - f16_to_f64(b2)));
+  s.c2 = splat(f64_to_f16(1.0 - h.beta2));
+  s.bc1 = splat(f64_to_f16(1.0 - std::pow(h.beta1, t)));
+  s.bc2 = splat(f64_to_f16(1.0 - std::pow(h.beta2, t)));
+  s.rbc1 = s.bc1;            // unused by the fp16 arithmetic
+  s.rbc2 = s.bc2;
+  s.e = splat(f64_to_f16(h.eps));
+  s.lam = splat(f64_to_f16(h.weight_decay));
+  s.na = splat(f64_to_f16(-h.lr));
 }
 
 }  // namespace mcfh

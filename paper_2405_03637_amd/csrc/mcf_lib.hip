@@ -33,9 +33,11 @@
 
 namespace {
 
-using mcfd::ElemIO;
+using mcfd::ElemIOT;
 using mcfd::P2;
 using mcfd::StepScalars;
+using mcfd::StepScalarsH;
+using mcfd::StepScalarsT;
 
 // Compile-time tuning knobs of the step kernels (defaults = the measured best, see above).
 #ifndef MCF_BLOCK
@@ -261,12 +263,19 @@ __device__ __forceinline__ void edq_store_partial(const EdqAcc &a, double *__res
 }
 
 // ---------------------------------------------------------------- the step kernel
-// VARIANT template arguments below carry the variant in the low byte and kGrow2Bit when every Grow
-// is to be built on TwoSum (Alg. 3) instead of Fast2Sum.
+// VARIANT template arguments below carry the variant in the low byte, kGrow2Bit when every Grow
+// is to be built on TwoSum (Alg. 3) instead of Fast2Sum, and kHalfBit when the components are fp16.
 constexpr int kGrow2Bit = 0x100;
+constexpr int kHalfBit = 0x1000;
 template <int VARIANT> struct StepStreams {
   static constexpr int kBase = VARIANT & 0xff;
   static constexpr bool kGrow2 = (VARIANT & kGrow2Bit) != 0;
+  static constexpr bool kHalf = (VARIANT & kHalfBit) != 0;
+  // arithmetic of the vector path (FAST selects between the two bf16 modes) and of the element path
+  template <bool FAST> using Hot = typename std::conditional<kHalf, mcfd::HalfHot,
+                                       typename std::conditional<FAST, mcfd::Fast, mcfd::Exact>::type>::type;
+  using Cold = typename std::conditional<kHalf, mcfd::HalfCold, mcfd::Exact>::type;
+  using Scalars = StepScalarsT<typename Cold::S>;
   static constexpr bool kDth = kBase != mcfd::V_BF16;      // second component of theta / Kahan variable
   static constexpr bool kDv = kBase == mcfd::V_PLUS;       // second component of v
   static constexpr bool kV = kBase != mcfd::V_SGD;         // second moment
@@ -276,41 +285,45 @@ template <int VARIANT> struct StepStreams {
 // when the Fast arithmetic mode asks for the slot to be recomputed in Exact mode.
 template <class M, int VARIANT, bool EDQ>
 __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], uint32_t (&out)[kMaxStreams][4],
-                                         const StepScalars &sc, EdqAcc &acc) {
+                                         const StepScalarsT<typename M::S> &sc, EdqAcc &acc) {
   using SS = StepStreams<VARIANT>;
+  using T = typename M::T;
   bool redo = false;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
-    ElemIO io;
-    io.th = mcfd::widen2(in[S_TH][k]);
-    if (SS::kDth) io.dth = mcfd::widen2(in[S_DTH][k]); else io.dth = {0.f, 0.f};
-    io.m = mcfd::widen2(in[S_M][k]);
-    if (SS::kV) io.v = mcfd::widen2(in[S_V][k]); else io.v = {0.f, 0.f};
-    io.g = mcfd::widen2(in[S_G][k]);
-    if (SS::kDv) io.dv = mcfd::widen2(in[S_DV][k]); else io.dv = {0.f, 0.f};
-    const P2 th0 = io.th, dth0 = io.dth;
-    P2 delta;
+    ElemIOT<T> io;
+    io.th = M::unpack(in[S_TH][k]);
+    if (SS::kDth) io.dth = M::unpack(in[S_DTH][k]); else io.dth = M::zero();
+    io.m = M::unpack(in[S_M][k]);
+    if (SS::kV) io.v = M::unpack(in[S_V][k]); else io.v = M::zero();
+    io.g = M::unpack(in[S_G][k]);
+    if (SS::kDv) io.dv = M::unpack(in[S_DV][k]); else io.dv = M::zero();
+    const T th0 = io.th, dth0 = io.dth;
+    T delta;
     mcfd::adamw_pair<M, SS::kBase, SS::kGrow2>(io, sc, delta, redo);
-    out[S_TH][k] = mcfd::pack2(io.th);
-    if (SS::kDth) out[S_DTH][k] = mcfd::pack2(io.dth);
-    out[S_M][k] = mcfd::pack2(io.m);
-    if (SS::kV) out[S_V][k] = mcfd::pack2(io.v);
-    if (SS::kDv) out[S_DV][k] = mcfd::pack2(io.dv);
+    out[S_TH][k] = M::pack(io.th);
+    if (SS::kDth) out[S_DTH][k] = M::pack(io.dth);
+    out[S_M][k] = M::pack(io.m);
+    if (SS::kV) out[S_V][k] = M::pack(io.v);
+    if (SS::kDv) out[S_DV][k] = M::pack(io.dv);
     if (EDQ) {
-      edq_add(acc, delta.lo, th0.lo, dth0.lo, io.th.lo, io.dth.lo);
-      edq_add(acc, delta.hi, th0.hi, dth0.hi, io.th.hi, io.dth.hi);
+      edq_add(acc, M::lo(delta), M::lo(th0), M::lo(dth0), M::lo(io.th), M::lo(io.dth));
+      edq_add(acc, M::hi(delta), M::hi(th0), M::hi(dth0), M::hi(io.th), M::hi(io.dth));
     }
   }
   return redo;
 }
 
-// Cold path: one slot element by element in Exact mode, as a rolled loop so that it costs code
+// Cold path: one slot element by element in the variant's element mode (bf16: Exact), as a rolled loop so that it costs code
 // size once.  Serves the slots that straddle a tensor's ends, tensors whose buffers are not
 // mutually aligned, and slots the hot path asked to redo (their inputs are still in memory:
 // nothing of the slot has been stored yet).
 template <int VARIANT, bool EDQ>
-__device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, const StepScalars &sc, EdqAcc &acc) {
+__device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, const typename StepStreams<VARIANT>::Scalars &sc,
+                                          EdqAcc &acc) {
   using SS = StepStreams<VARIANT>;
+  using M = typename SS::Cold;
+  using T = typename M::T;
   const uint64_t lo = d.phase, hi = d.phase + d.n;
   MCF_GLOBAL uint16_t *th = gptr<uint16_t>(d.p[S_TH]);
   MCF_GLOBAL uint16_t *dth = gptr<uint16_t>(d.p[S_DTH]);
@@ -323,32 +336,33 @@ __device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, cons
     const uint64_t c = c0 + k;
     if (c < lo || c >= hi) continue;
     const uint64_t e = c - lo;
-    ElemIO io;                       // the element rides in the low half of a pair
-    io.th = mcfd::widen2(th[e]);
-    if (SS::kDth) io.dth = mcfd::widen2(dth[e]); else io.dth = {0.f, 0.f};
-    io.m = mcfd::widen2(m[e]);
-    if (SS::kV) io.v = mcfd::widen2(v[e]); else io.v = {0.f, 0.f};
-    io.g = mcfd::widen2(g[e]);
-    if (SS::kDv) io.dv = mcfd::widen2(dv[e]); else io.dv = {0.f, 0.f};
-    const float th0 = io.th.lo, dth0 = io.dth.lo;
-    P2 delta;
+    ElemIOT<T> io;                   // the element rides in the low half of a pair
+    io.th = M::unpack(th[e]);
+    if (SS::kDth) io.dth = M::unpack(dth[e]); else io.dth = M::zero();
+    io.m = M::unpack(m[e]);
+    if (SS::kV) io.v = M::unpack(v[e]); else io.v = M::zero();
+    io.g = M::unpack(g[e]);
+    if (SS::kDv) io.dv = M::unpack(dv[e]); else io.dv = M::zero();
+    const float th0 = M::lo(io.th), dth0 = M::lo(io.dth);
+    T delta;
     bool unused = false;
-    mcfd::adamw_pair<mcfd::Exact, SS::kBase, SS::kGrow2>(io, sc, delta, unused);
-    th[e] = (uint16_t)(mcfd::fbits(io.th.lo) >> 16);
-    if (SS::kDth) dth[e] = (uint16_t)(mcfd::fbits(io.dth.lo) >> 16);
-    m[e] = (uint16_t)(mcfd::fbits(io.m.lo) >> 16);
-    if (SS::kV) v[e] = (uint16_t)(mcfd::fbits(io.v.lo) >> 16);
-    if (SS::kDv) dv[e] = (uint16_t)(mcfd::fbits(io.dv.lo) >> 16);
-    if (EDQ) edq_add(acc, delta.lo, th0, dth0, io.th.lo, io.dth.lo);
+    mcfd::adamw_pair<M, SS::kBase, SS::kGrow2>(io, sc, delta, unused);
+    // EDQ is taken on the stored values (a NaN stays a NaN whatever its payload)
+    if (EDQ) edq_add(acc, M::lo(delta), th0, dth0, M::lo(io.th), M::lo(io.dth));
+    th[e] = M::bits_lo(io.th);
+    if (SS::kDth) dth[e] = M::bits_lo(io.dth);
+    m[e] = M::bits_lo(io.m);
+    if (SS::kV) v[e] = M::bits_lo(io.v);
+    if (SS::kDv) dv[e] = M::bits_lo(io.dv);
   }
 }
 
 template <int VARIANT, bool FAST, bool EDQ, bool TABLE>
 __global__ void __launch_bounds__(kStepBlock) MCF_STEP_ATTR
 adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, TensorDesc flat,
-             StepScalars sc, double *__restrict__ partials, uint32_t n_chunks) {
+             typename StepStreams<VARIANT>::Scalars sc, double *__restrict__ partials, uint32_t n_chunks) {
   using SS = StepStreams<VARIANT>;
-  using Mode = typename std::conditional<FAST, mcfd::Fast, mcfd::Exact>::type;
+  using Mode = typename SS::template Hot<FAST>;
   TensorDesc d;
   uint64_t slot0;
   uint32_t chunk_id = blockIdx.x;
@@ -466,33 +480,34 @@ template <class M, int OP>
 __device__ __forceinline__ void prim_words(const uint32_t (&in)[kMaxStreams][4], uint32_t (&out)[kMaxStreams][4],
                                            bool &redo, EdqAcc &acc, uint32_t valid) {
   using O = mcfd::Ops<M>;
+  using T = typename M::T;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
-    P2 a = mcfd::widen2(in[0][k]), b = mcfd::widen2(in[1][k]);
-    P2 x = {0.f, 0.f}, y = {0.f, 0.f};
+    T a = M::unpack(in[0][k]), b = M::unpack(in[1][k]);
+    T x = M::zero(), y = M::zero();
     if (OP == P_FAST2SUM) O::fast2sum(a, b, x, y);
     if (OP == P_TWOSUM) O::two_sum(a, b, x, y);
-    if (OP == P_GROW) O::grow(a, b, mcfd::widen2(in[2][k]), x, y);          // streams: x, y, a
-    if (OP == P_GROW2) O::grow2(a, b, mcfd::widen2(in[2][k]), x, y);
+    if (OP == P_GROW) O::grow(a, b, M::unpack(in[2][k]), x, y);             // streams: x, y, a
+    if (OP == P_GROW2) O::grow2(a, b, M::unpack(in[2][k]), x, y);
     if (OP == P_TWOPROD) { x = O::mul(a, b); y = O::fms(a, b, x); }         // Alg. 6
     if (OP == P_SCALING) {                                                  // Alg. 7; streams: v, a1, a2
-      const P2 a2 = mcfd::widen2(in[2][k]);
-      const P2 x0 = O::mul(b, a);
-      const P2 e = O::add(O::mul(a2, a), O::fms(b, a, x0));
+      const T a2 = M::unpack(in[2][k]);
+      const T x0 = O::mul(b, a);
+      const T e = O::add(O::mul(a2, a), O::fms(b, a, x0));
       O::fast2sum(x0, e, x, y);
     }
     if (OP == P_MULX) {                                                     // Alg. 8; streams: a1, a2, b1, b2
-      const P2 b1 = mcfd::widen2(in[2][k]), b2 = mcfd::widen2(in[3][k]);
-      const P2 x0 = O::mul(a, b1);
-      const P2 ex = O::fms(a, b1, x0);
-      const P2 cross = O::add(O::mul(a, b2), O::mul(b, b1));
+      const T b1 = M::unpack(in[2][k]), b2 = M::unpack(in[3][k]);
+      const T x0 = O::mul(a, b1);
+      const T ex = O::fms(a, b1, x0);
+      const T cross = O::add(O::mul(a, b2), O::mul(b, b1));
       O::fast2sum(x0, O::add(ex, cross), x, y);
     }
     if (OP == P_ADD) x = O::add(a, b);
     if (OP == P_SUB) x = O::sub(a, b);
     if (OP == P_MUL) x = O::mul(a, b);
     if (OP == P_DIV) {
-      if (M::kFast) {
+      if constexpr (M::kFast && !M::kHalf) {
         // the reciprocal route needs |b| zero, infinite, NaN or within [2^-126, 2^126]
         const float alo = __builtin_fabsf(b.lo), ahi = __builtin_fabsf(b.hi);
         redo |= mcfd::is_subnormal(b.lo) | mcfd::is_subnormal(b.hi) | (alo > 0x1p126f && alo < __builtin_inff()) |
@@ -501,32 +516,39 @@ __device__ __forceinline__ void prim_words(const uint32_t (&in)[kMaxStreams][4],
       x = O::divg(a, b, redo);
     }
     if (OP == P_SQRT) {
-      if (M::kFast) redo |= mcfd::is_subnormal(a.lo) | mcfd::is_subnormal(a.hi);
+      if constexpr (M::kFast && !M::kHalf) redo |= mcfd::is_subnormal(a.lo) | mcfd::is_subnormal(a.hi);
       x = O::sqrt(a, redo);
     }
     if (OP == P_EDQ) {
       // streams: delta, th0, th1, dth0, dth1 (absent second components were loaded as zeros);
       // elements outside the tensor are skipped so that they cannot count as lost updates
-      const P2 th1 = mcfd::widen2(in[2][k]), d0 = mcfd::widen2(in[3][k]), d1 = mcfd::widen2(in[4][k]);
-      if (valid & (1u << (2 * k))) edq_add(acc, a.lo, b.lo, d0.lo, th1.lo, d1.lo);
-      if (valid & (1u << (2 * k + 1))) edq_add(acc, a.hi, b.hi, d0.hi, th1.hi, d1.hi);
+      const T th1 = M::unpack(in[2][k]), d0 = M::unpack(in[3][k]), d1 = M::unpack(in[4][k]);
+      if (valid & (1u << (2 * k))) edq_add(acc, M::lo(a), M::lo(b), M::lo(d0), M::lo(th1), M::lo(d1));
+      if (valid & (1u << (2 * k + 1))) edq_add(acc, M::hi(a), M::hi(b), M::hi(d0), M::hi(th1), M::hi(d1));
     }
-    if (M::kFast && OP != P_EDQ) redo |= mcfd::is_nan(x.lo) | mcfd::is_nan(x.hi) | mcfd::is_nan(y.lo) | mcfd::is_nan(y.hi);
-    out[0][k] = mcfd::pack2(x);
-    out[1][k] = mcfd::pack2(y);
+    if (M::kFast && OP != P_EDQ) redo |= M::any_nan(x) | M::any_nan(y);
+    if constexpr (M::kHalf && !M::kFast) {      // the element mode of fp16 stores the format's one NaN
+      out[0][k] = (uint32_t)M::bits_lo(x) | ((uint32_t)M::bits_hi(x) << 16);
+      out[1][k] = (uint32_t)M::bits_lo(y) | ((uint32_t)M::bits_hi(y) << 16);
+    } else {
+      out[0][k] = M::pack(x);
+      out[1][k] = M::pack(y);
+    }
   }
 }
 
 // Stream layout per op (inputs first):   reads            writes
 //  FAST2SUM/TWOSUM: p0=a p1=b p2=x p3=y   0,1              out0->p2, out1->p3
-//  GROW, GROW2:     p0=x p1=y p2=a        0,1,2            out0->p0, out1->p1
+//  GROW, GROW2:     p0=x p1=y p2=a p3=x' p4=y'  0,1,2       out0->p3, out1->p4 (may be p0, p1: a lane reads its slot before it writes)
 //  TWOPROD:         p0=a p1=b p2=x p3=e   0,1              out0->p2, out1->p3
 //  SCALING:         p0=v p1=a1 p2=a2 p3=x p4=e   0,1,2     out0->p3, out1->p4
 //  MULX:            p0=a1 p1=a2 p2=b1 p3=b2 p4=x p5=e  0..3  out0->p4, out1->p5
 //  ADD..SQRT:       p0=a p1=b p2=out      0,1 (sqrt: 0)    out0->p2
 //  EDQ:             p0=delta p1=th0 p2=th1 p3=dth0 p4=dth1  (reads only; partial sums out)
-template <int OP>
+template <int OP, bool HALF>
 __global__ void __launch_bounds__(kBlock) prim_kernel(PrimArgs a, uint32_t has_d0, uint32_t has_d1, double *__restrict__ partials) {
+  using Hot = typename std::conditional<HALF, mcfd::HalfHot, mcfd::Fast>::type;
+  using Cold = typename std::conditional<HALF, mcfd::HalfCold, mcfd::Exact>::type;
   TensorDesc d;
 #pragma unroll
   for (int s = 0; s < kMaxStreams; ++s) d.p[s] = a.p[s];
@@ -552,13 +574,13 @@ __global__ void __launch_bounds__(kBlock) prim_kernel(PrimArgs a, uint32_t has_d
       for (int k = 0; k < nin; ++k) load_slot(d.p[k], d, s, in[k]);
     }
     bool redo = false;
-    prim_words<mcfd::Fast, OP>(in, out, redo, acc, valid);
+    prim_words<Hot, OP>(in, out, redo, acc, valid);
     if (redo) {
       bool unused = false;
-      prim_words<mcfd::Exact, OP>(in, out, unused, acc, valid);
+      prim_words<Cold, OP>(in, out, unused, acc, valid);
     }
     if (OP == P_FAST2SUM || OP == P_TWOSUM || OP == P_TWOPROD) { store_slot(d.p[2], d, s, out[0]); store_slot(d.p[3], d, s, out[1]); }
-    if (OP == P_GROW || OP == P_GROW2) { store_slot(d.p[0], d, s, out[0]); store_slot(d.p[1], d, s, out[1]); }
+    if (OP == P_GROW || OP == P_GROW2) { store_slot(d.p[3], d, s, out[0]); store_slot(d.p[4], d, s, out[1]); }
     if (OP == P_SCALING) { store_slot(d.p[3], d, s, out[0]); store_slot(d.p[4], d, s, out[1]); }
     if (OP == P_MULX) { store_slot(d.p[4], d, s, out[0]); store_slot(d.p[5], d, s, out[1]); }
     if (OP == P_ADD || OP == P_SUB || OP == P_MUL || OP == P_DIV || OP == P_SQRT) store_slot(d.p[2], d, s, out[0]);
@@ -566,16 +588,25 @@ __global__ void __launch_bounds__(kBlock) prim_kernel(PrimArgs a, uint32_t has_d
   if (OP == P_EDQ) edq_store_partial<kBlock>(acc, partials, blockIdx.x);
 }
 
-// fp32 -> bf16 over an array (the rounding inside F).  Two elements per lane.
+// fp32 -> bf16 or fp16 over an array (the rounding inside F).  Two elements per lane.
+template <bool HALF>
 __global__ void __launch_bounds__(kBlock) round_kernel(const float *__restrict__ in, uint16_t *__restrict__ out, uint64_t n) {
+  using Hot = typename std::conditional<HALF, mcfd::HalfHot, mcfd::Fast>::type;
+  using Cold = typename std::conditional<HALF, mcfd::HalfCold, mcfd::Exact>::type;
   const uint64_t i = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 2;
   if (i >= n) return;
   const float a = in[i];
   const float b = (i + 1 < n) ? in[i + 1] : 0.f;
-  P2 r = mcfd::Fast::rnd({a, b});
-  if (mcfd::is_nan(a) | mcfd::is_nan(b)) r = mcfd::Exact::rnd({a, b});
-  out[i] = (uint16_t)(mcfd::fbits(r.lo) >> 16);
-  if (i + 1 < n) out[i + 1] = (uint16_t)(mcfd::fbits(r.hi) >> 16);
+  uint16_t lo, hi;
+  if (mcfd::is_nan(a) | mcfd::is_nan(b)) {
+    const typename Cold::T r = Cold::round_f32(a, b);
+    lo = Cold::bits_lo(r); hi = Cold::bits_hi(r);
+  } else {
+    const typename Hot::T r = Hot::round_f32(a, b);
+    lo = (uint16_t)(Hot::pack(r) & 0xffffu); hi = (uint16_t)(Hot::pack(r) >> 16);
+  }
+  out[i] = lo;
+  if (i + 1 < n) out[i + 1] = hi;
 }
 
 // Plain 128-bit copy in the step kernel's launch shape: the streaming ceiling the step is
@@ -666,7 +697,7 @@ fp32mw_kernel(const Fp32Desc *__restrict__ descs, const Chunk *__restrict__ chun
       store_f4(mp + e0, f32x4_t{m[0], m[1], m[2], m[3]});
       store_f4(vp + e0, f32x4_t{v[0], v[1], v[2], v[3]});
       store_f4(master + e0, f32x4_t{w[0], w[1], w[2], w[3]});
-      const u32x2_t tw = {mcfd::pack2(mcfd::Exact::rnd({w[0], w[1]})), mcfd::pack2(mcfd::Exact::rnd({w[2], w[3]}))};
+      const u32x2_t tw = {mcfd::pack2(mcfd::Exact::round_f32(w[0], w[1])), mcfd::pack2(mcfd::Exact::round_f32(w[2], w[3]))};
 #if MCF_NT_STORE
       __builtin_nontemporal_store(tw, (MCF_GLOBAL u32x2_t *)(theta + e0));
 #else
@@ -714,14 +745,16 @@ inline void phase_of(const uint64_t *ptrs, int count, uint32_t &phase, uint32_t 
 
 inline uint64_t slots_of(uint64_t n, uint32_t phase) { return (n + phase + 7) / 8; }
 
+constexpr int kFlagMask = MCF_GROW_TWOSUM | MCF_FMT_FP16;
+
 inline bool known_variant(int v) {
-  const int base = v & ~MCF_GROW_TWOSUM;
+  const int base = v & ~kFlagMask;
   if (v & MCF_GROW_TWOSUM) return base == MCF_LIGHT || base == MCF_PLUS;
   return base == MCF_LIGHT || base == MCF_PLUS || base == MCF_BF16 || base == MCF_KAHAN || base == MCF_SGD;
 }
 
 int check_tensor(const mcf_tensor &t, int variant) {
-  variant &= ~MCF_GROW_TWOSUM;
+  variant &= ~kFlagMask;
   if (t.n == 0) return MCF_OK;
   const bool need_dth = variant != MCF_BF16, need_dv = variant == MCF_PLUS, need_v = variant != MCF_SGD;
   if (!t.theta || !t.m || !t.grad) return MCF_ERR_NULL;
@@ -736,7 +769,7 @@ int check_tensor(const mcf_tensor &t, int variant) {
 // Streams a variant does not use point at theta (v for dv): they are never accessed and do
 // not disturb the alignment class.
 void fill_desc(const mcf_tensor &t, int variant, TensorDesc &d) {
-  variant &= ~MCF_GROW_TWOSUM;
+  variant &= ~kFlagMask;
   d.p[S_TH] = (uint64_t)(uintptr_t)t.theta;
   d.p[S_DTH] = variant != MCF_BF16 ? (uint64_t)(uintptr_t)t.dtheta : d.p[S_TH];
   d.p[S_M] = (uint64_t)(uintptr_t)t.m;
@@ -747,37 +780,54 @@ void fill_desc(const mcf_tensor &t, int variant, TensorDesc &d) {
   phase_of(d.p, 6, d.phase, d.scalar_only);
 }
 
+// Scalars of one step for both formats; fast = the bf16 Fast mode may be used with them.
+struct HostScalars {
+  StepScalars bf;
+  StepScalarsH hf;
+  bool fast;
+};
+
 template <int VARIANT, bool TABLE>
-void launch_step(bool fast, bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs, const Chunk *chunks,
-                 const TensorDesc &flat, const StepScalars &sc, double *partials) {
+void launch_step(bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs, const Chunk *chunks,
+                 const TensorDesc &flat, const HostScalars &hs, double *partials) {
 #if MCF_REMAP
   const dim3 g((blocks + 7) / 8 * 8), b(kStepBlock);
 #else
   const dim3 g(blocks), b(kStepBlock);
 #endif
-  if (fast) {
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, sc, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, MCF_STEP_LDS, st, descs, chunks, flat, sc, partials, blocks);
+  if constexpr ((VARIANT & kHalfBit) != 0) {
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, hs.hf, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, MCF_STEP_LDS, st, descs, chunks, flat, hs.hf, partials, blocks);
+  } else if (hs.fast) {
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, hs.bf, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, MCF_STEP_LDS, st, descs, chunks, flat, hs.bf, partials, blocks);
   } else {
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, sc, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, MCF_STEP_LDS, st, descs, chunks, flat, sc, partials, blocks);
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, hs.bf, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, MCF_STEP_LDS, st, descs, chunks, flat, hs.bf, partials, blocks);
+  }
+}
+
+template <bool TABLE, int FMT>
+void launch_format(int variant, bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs,
+                   const Chunk *chunks, const TensorDesc &flat, const HostScalars &hs, double *partials) {
+  switch (variant & ~MCF_FMT_FP16) {
+    case MCF_LIGHT | MCF_GROW_TWOSUM:
+      launch_step<mcfd::V_LIGHT | kGrow2Bit | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    case MCF_PLUS | MCF_GROW_TWOSUM:
+      launch_step<mcfd::V_PLUS | kGrow2Bit | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    case MCF_PLUS: launch_step<mcfd::V_PLUS | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    case MCF_BF16: launch_step<mcfd::V_BF16 | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    case MCF_KAHAN: launch_step<mcfd::V_KAHAN | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    case MCF_SGD: launch_step<mcfd::V_SGD | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    default: launch_step<mcfd::V_LIGHT | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
   }
 }
 
 template <bool TABLE>
-void launch_variant(int variant, bool fast, bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs,
-                    const Chunk *chunks, const TensorDesc &flat, const StepScalars &sc, double *partials) {
-  switch (variant) {
-    case MCF_LIGHT | MCF_GROW_TWOSUM:
-      launch_step<mcfd::V_LIGHT | kGrow2Bit, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
-    case MCF_PLUS | MCF_GROW_TWOSUM:
-      launch_step<mcfd::V_PLUS | kGrow2Bit, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
-    case MCF_PLUS: launch_step<mcfd::V_PLUS, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
-    case MCF_BF16: launch_step<mcfd::V_BF16, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
-    case MCF_KAHAN: launch_step<mcfd::V_KAHAN, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
-    case MCF_SGD: launch_step<mcfd::V_SGD, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
-    default: launch_step<mcfd::V_LIGHT, TABLE>(fast, edq, blocks, st, descs, chunks, flat, sc, partials); break;
-  }
+void launch_variant(int variant, bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs,
+                    const Chunk *chunks, const TensorDesc &flat, const HostScalars &hs, double *partials) {
+  if (variant & MCF_FMT_FP16) launch_format<TABLE, kHalfBit>(variant, edq, blocks, st, descs, chunks, flat, hs, partials);
+  else launch_format<TABLE, 0>(variant, edq, blocks, st, descs, chunks, flat, hs, partials);
 }
 
 // Reduce `count` partials (kEdqVals doubles each) to {EDQ, S1, S2, lost}; mid holds kEdqVals*kStage1Blocks doubles.
@@ -796,6 +846,64 @@ bool force_exact() {
   static const bool v = [] { const char *e = getenv("MCF_FORCE_EXACT"); return e && e[0] == '1'; }();
   return v;
 }
+
+HostScalars host_scalars(const mcf_hyper &h, uint64_t step, int variant) {
+  HostScalars hs = {};
+  if (variant & MCF_FMT_FP16) {
+    mcfh::derive_scalars_fp16(h, step, hs.hf);
+    hs.fast = true;
+  } else {
+    hs.fast = mcfh::derive_scalars(h, step, hs.bf) && !force_exact();
+  }
+  return hs;
+}
+
+template <bool HALF>
+int prim_dispatch(int op, const dim3 &g, const dim3 &b, hipStream_t st, const PrimArgs &a) {
+  switch (op) {
+    case P_FAST2SUM: hipLaunchKernelGGL((prim_kernel<P_FAST2SUM, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_TWOSUM: hipLaunchKernelGGL((prim_kernel<P_TWOSUM, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_GROW: hipLaunchKernelGGL((prim_kernel<P_GROW, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_ADD: hipLaunchKernelGGL((prim_kernel<P_ADD, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_SUB: hipLaunchKernelGGL((prim_kernel<P_SUB, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_MUL: hipLaunchKernelGGL((prim_kernel<P_MUL, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_DIV: hipLaunchKernelGGL((prim_kernel<P_DIV, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_SQRT: hipLaunchKernelGGL((prim_kernel<P_SQRT, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_GROW2: hipLaunchKernelGGL((prim_kernel<P_GROW2, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_TWOPROD: hipLaunchKernelGGL((prim_kernel<P_TWOPROD, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_SCALING: hipLaunchKernelGGL((prim_kernel<P_SCALING, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_MULX: hipLaunchKernelGGL((prim_kernel<P_MULX, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    default: return MCF_ERR_VARIANT;
+  }
+  return MCF_OK;
+}
+
+int prim_launch(int format, int op, const void *p0, const void *p1, const void *p2, const void *p3, const void *p4,
+                       int nptr, uint64_t n, void *stream, const void *p5 = nullptr) {
+  const void *ps[6] = {p0, p1, p2, p3, p4, p5};
+  PrimArgs a = {};
+  uint64_t al[6];
+  int na = 0;
+  for (int i = 0; i < nptr; ++i) {
+    a.p[i] = (uint64_t)(uintptr_t)ps[i];
+    if (ps[i]) {
+      if (misaligned(ps[i], 2)) return MCF_ERR_ALIGN;
+      al[na++] = a.p[i];
+    }
+  }
+  if (n > kMaxTensorElems) return MCF_ERR_SIZE;
+  a.n = n;
+  phase_of(al, na, a.phase, a.scalar_only);
+  const uint64_t slots = slots_of(n, a.phase);
+  const dim3 g((uint32_t)((slots + kBlock - 1) / kBlock)), b(kBlock);
+  hipStream_t st = (hipStream_t)stream;
+  const int rc = format == MCF_COMPONENT_FP16 ? prim_dispatch<true>(op, g, b, st, a) : prim_dispatch<false>(op, g, b, st, a);
+  if (rc != MCF_OK) return rc;
+  MCF_HIP(hipGetLastError());
+  return MCF_OK;
+}
+
+inline bool known_component(int c) { return c == MCF_COMPONENT_BF16 || c == MCF_COMPONENT_FP16; }
 
 }  // namespace
 
@@ -897,12 +1005,11 @@ int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *
   const int rc = mcfh::check_hyper(hyper, step);
   if (rc != MCF_OK) return rc;
   if (edq_dev && misaligned(edq_dev, 8)) return MCF_ERR_ALIGN;
-  StepScalars sc;
-  const bool fast = mcfh::derive_scalars(*hyper, step, sc) && !force_exact();
+  const HostScalars hs = host_scalars(*hyper, step, plan->variant);
   hipStream_t st = (hipStream_t)stream;
   const TensorDesc none = {};
   if (plan->n_chunks) {
-    launch_variant<true>(plan->variant, fast, edq_dev != nullptr, plan->n_chunks, st, plan->d_descs, plan->d_chunks, none, sc,
+    launch_variant<true>(plan->variant, edq_dev != nullptr, plan->n_chunks, st, plan->d_descs, plan->d_chunks, none, hs,
                          plan->d_partials);
     MCF_HIP(hipGetLastError());
   }
@@ -926,113 +1033,87 @@ int mcf_adamw_step_flat(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t
   TensorDesc d;
   fill_desc(t, variant, d);
   const uint64_t nch = (slots_of(d.n, d.phase) + kSlotsPerChunk - 1) / kSlotsPerChunk;
-  StepScalars sc;
-  const bool fast = mcfh::derive_scalars(*hyper, step, sc) && !force_exact();
-  launch_variant<false>(variant, fast, false, (uint32_t)nch, (hipStream_t)stream, nullptr, nullptr, d, sc, nullptr);
+  const HostScalars hs = host_scalars(*hyper, step, variant);
+  launch_variant<false>(variant, false, (uint32_t)nch, (hipStream_t)stream, nullptr, nullptr, d, hs, nullptr);
   MCF_HIP(hipGetLastError());
   return MCF_OK;
 }
 
-static int prim_launch(int op, const void *p0, const void *p1, const void *p2, const void *p3, const void *p4,
-                       int nptr, uint64_t n, void *stream, const void *p5 = nullptr) {
-  const void *ps[6] = {p0, p1, p2, p3, p4, p5};
-  PrimArgs a = {};
-  uint64_t al[6];
-  int na = 0;
-  for (int i = 0; i < nptr; ++i) {
-    a.p[i] = (uint64_t)(uintptr_t)ps[i];
-    if (ps[i]) {
-      if (misaligned(ps[i], 2)) return MCF_ERR_ALIGN;
-      al[na++] = a.p[i];
-    }
-  }
-  if (n > kMaxTensorElems) return MCF_ERR_SIZE;
-  a.n = n;
-  phase_of(al, na, a.phase, a.scalar_only);
-  const uint64_t slots = slots_of(n, a.phase);
-  const dim3 g((uint32_t)((slots + kBlock - 1) / kBlock)), b(kBlock);
-  hipStream_t st = (hipStream_t)stream;
-  switch (op) {
-    case P_FAST2SUM: hipLaunchKernelGGL(prim_kernel<P_FAST2SUM>, g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_TWOSUM: hipLaunchKernelGGL(prim_kernel<P_TWOSUM>, g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_GROW: hipLaunchKernelGGL(prim_kernel<P_GROW>, g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_ADD: hipLaunchKernelGGL(prim_kernel<P_ADD>, g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_SUB: hipLaunchKernelGGL(prim_kernel<P_SUB>, g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_MUL: hipLaunchKernelGGL(prim_kernel<P_MUL>, g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_DIV: hipLaunchKernelGGL(prim_kernel<P_DIV>, g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_SQRT: hipLaunchKernelGGL(prim_kernel<P_SQRT>, g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_GROW2: hipLaunchKernelGGL(prim_kernel<P_GROW2>, g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_TWOPROD: hipLaunchKernelGGL(prim_kernel<P_TWOPROD>, g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_SCALING: hipLaunchKernelGGL(prim_kernel<P_SCALING>, g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_MULX: hipLaunchKernelGGL(prim_kernel<P_MULX>, g, b, 0, st, a, 0u, 0u, nullptr); break;
-    default: return MCF_ERR_VARIANT;
-  }
-  MCF_HIP(hipGetLastError());
-  return MCF_OK;
+int mcf_primitive(int component, int which, const uint16_t *p0, const uint16_t *p1, const uint16_t *p2, const uint16_t *p3,
+                  uint16_t *o0, uint16_t *o1, uint64_t n, void *stream) {
+  static const int ops[7] = {P_FAST2SUM, P_TWOSUM, P_GROW, P_GROW2, P_TWOPROD, P_SCALING, P_MULX};
+  static const int nin[7] = {2, 2, 3, 3, 2, 3, 4};
+  if (!known_component(component) || which < 0 || which > 6) return MCF_ERR_VARIANT;
+  if (n == 0) return MCF_OK;
+  const void *ps[6] = {p0, p1, p2, p3, nullptr, nullptr};
+  for (int i = 0; i < nin[which]; ++i)
+    if (!ps[i]) return MCF_ERR_NULL;
+  if (!o0 || !o1) return MCF_ERR_NULL;
+  ps[nin[which]] = o0;
+  ps[nin[which] + 1] = o1;
+  return prim_launch(component, ops[which], ps[0], ps[1], ps[2], ps[3], ps[4], nin[which] + 2, n, stream, ps[5]);
 }
 
 int mcf_fast2sum(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *y, uint64_t n, void *stream) {
-  if (n == 0) return MCF_OK;
-  if (!a || !b || !x || !y) return MCF_ERR_NULL;
-  return prim_launch(P_FAST2SUM, a, b, x, y, nullptr, 4, n, stream);
+  return mcf_primitive(MCF_COMPONENT_BF16, MCF_PRIM_FAST2SUM, a, b, nullptr, nullptr, x, y, n, stream);
 }
 
 int mcf_two_sum(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *y, uint64_t n, void *stream) {
-  if (n == 0) return MCF_OK;
-  if (!a || !b || !x || !y) return MCF_ERR_NULL;
-  return prim_launch(P_TWOSUM, a, b, x, y, nullptr, 4, n, stream);
+  return mcf_primitive(MCF_COMPONENT_BF16, MCF_PRIM_TWOSUM, a, b, nullptr, nullptr, x, y, n, stream);
 }
 
 int mcf_grow(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n, void *stream) {
-  if (n == 0) return MCF_OK;
-  if (!x || !y || !a) return MCF_ERR_NULL;
-  return prim_launch(P_GROW, x, y, a, nullptr, nullptr, 3, n, stream);
+  return mcf_primitive(MCF_COMPONENT_BF16, MCF_PRIM_GROW, x, y, a, nullptr, x, y, n, stream);
 }
 
 int mcf_grow_two_sum(uint16_t *x, uint16_t *y, const uint16_t *a, uint64_t n, void *stream) {
-  if (n == 0) return MCF_OK;
-  if (!x || !y || !a) return MCF_ERR_NULL;
-  return prim_launch(P_GROW2, x, y, a, nullptr, nullptr, 3, n, stream);
+  return mcf_primitive(MCF_COMPONENT_BF16, MCF_PRIM_GROW_TWOSUM, x, y, a, nullptr, x, y, n, stream);
 }
 
 int mcf_two_prod_fma(const uint16_t *a, const uint16_t *b, uint16_t *x, uint16_t *e, uint64_t n, void *stream) {
-  if (n == 0) return MCF_OK;
-  if (!a || !b || !x || !e) return MCF_ERR_NULL;
-  return prim_launch(P_TWOPROD, a, b, x, e, nullptr, 4, n, stream);
+  return mcf_primitive(MCF_COMPONENT_BF16, MCF_PRIM_TWOPROD, a, b, nullptr, nullptr, x, e, n, stream);
 }
 
 int mcf_scaling(const uint16_t *v, const uint16_t *a1, const uint16_t *a2, uint16_t *x, uint16_t *e, uint64_t n, void *stream) {
-  if (n == 0) return MCF_OK;
-  if (!v || !a1 || !a2 || !x || !e) return MCF_ERR_NULL;
-  return prim_launch(P_SCALING, v, a1, a2, x, e, 5, n, stream);
+  return mcf_primitive(MCF_COMPONENT_BF16, MCF_PRIM_SCALING, v, a1, a2, nullptr, x, e, n, stream);
 }
 
 int mcf_mul(const uint16_t *a1, const uint16_t *a2, const uint16_t *b1, const uint16_t *b2, uint16_t *x, uint16_t *e,
             uint64_t n, void *stream) {
-  if (n == 0) return MCF_OK;
-  if (!a1 || !a2 || !b1 || !b2 || !x || !e) return MCF_ERR_NULL;
-  return prim_launch(P_MULX, a1, a2, b1, b2, x, 6, n, stream, e);
+  return mcf_primitive(MCF_COMPONENT_BF16, MCF_PRIM_MUL, a1, a2, b1, b2, x, e, n, stream);
 }
 
-int mcf_bf16_op(int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n, void *stream) {
-  if (op < 0 || op > 4) return MCF_ERR_VARIANT;
+int mcf_component_op(int component, int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n, void *stream) {
+  if (!known_component(component) || op < 0 || op > 4) return MCF_ERR_VARIANT;
   if (n == 0) return MCF_OK;
   if (!a || !out || (op != 4 && !b)) return MCF_ERR_NULL;
   if (op == 4) b = a;
   static const int map[5] = {P_ADD, P_SUB, P_MUL, P_DIV, P_SQRT};
-  return prim_launch(map[op], a, b, out, nullptr, nullptr, 3, n, stream);
+  return prim_launch(component, map[op], a, b, out, nullptr, nullptr, 3, n, stream);
 }
 
-int mcf_round_f32(const float *in, uint16_t *out, uint64_t n, void *stream) {
+int mcf_bf16_op(int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n, void *stream) {
+  return mcf_component_op(MCF_COMPONENT_BF16, op, a, b, out, n, stream);
+}
+
+int mcf_round_f32_to(int component, const float *in, uint16_t *out, uint64_t n, void *stream) {
+  if (!known_component(component)) return MCF_ERR_VARIANT;
   if (n == 0) return MCF_OK;
   if (!in || !out) return MCF_ERR_NULL;
   if (misaligned(in, 4) || misaligned(out, 2)) return MCF_ERR_ALIGN;
   const uint64_t lanes = (n + 1) / 2;
   const uint64_t blocks = (lanes + kBlock - 1) / kBlock;
   if (blocks > 0x7fffffffull) return MCF_ERR_SIZE;
-  hipLaunchKernelGGL(round_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, in, out, n);
+  if (component == MCF_COMPONENT_FP16)
+    hipLaunchKernelGGL(round_kernel<true>, dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, in, out, n);
+  else
+    hipLaunchKernelGGL(round_kernel<false>, dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, in, out, n);
   MCF_HIP(hipGetLastError());
   return MCF_OK;
+}
+
+int mcf_round_f32(const float *in, uint16_t *out, uint64_t n, void *stream) {
+  return mcf_round_f32_to(MCF_COMPONENT_BF16, in, out, n, stream);
 }
 
 int mcf_stream_copy(void *dst, const void *src, uint64_t bytes, void *stream) {
@@ -1053,8 +1134,9 @@ uint64_t mcf_edq_scratch_bytes(uint64_t n) {
   return (uint64_t)kEdqVals * (blocks + kStage1Blocks) * sizeof(double);
 }
 
-int mcf_edq(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
-            const uint16_t *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev) {
+int mcf_edq_component(int component, const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
+                      const uint16_t *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev) {
+  if (!known_component(component)) return MCF_ERR_VARIANT;
   if (!edq_dev) return MCF_ERR_NULL;
   if (misaligned(edq_dev, 8)) return MCF_ERR_ALIGN;
   if (n == 0) return launch_edq_tail(nullptr, 0, nullptr, edq_dev, (hipStream_t)stream);
@@ -1076,10 +1158,19 @@ int mcf_edq(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, co
   a.n = n;
   phase_of(al, na, a.phase, a.scalar_only);
   const uint64_t blocks = (slots_of(n, a.phase) + kBlock - 1) / kBlock;
-  hipLaunchKernelGGL(prim_kernel<P_EDQ>, dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, a,
-                     dth0 ? 1u : 0u, dth1 ? 1u : 0u, partials);
+  if (component == MCF_COMPONENT_FP16)
+    hipLaunchKernelGGL((prim_kernel<P_EDQ, true>), dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, a,
+                       dth0 ? 1u : 0u, dth1 ? 1u : 0u, partials);
+  else
+    hipLaunchKernelGGL((prim_kernel<P_EDQ, false>), dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, a,
+                       dth0 ? 1u : 0u, dth1 ? 1u : 0u, partials);
   MCF_HIP(hipGetLastError());
   return launch_edq_tail(partials, blocks, partials + kEdqVals * blocks, edq_dev, (hipStream_t)stream);
+}
+
+int mcf_edq(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
+            const uint16_t *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev) {
+  return mcf_edq_component(MCF_COMPONENT_BF16, delta, th0, dth0, th1, dth1, n, scratch_dev, stream, edq_dev);
 }
 
 int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tensors, uint32_t count) {

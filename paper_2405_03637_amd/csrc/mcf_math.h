@@ -44,7 +44,9 @@ __device__ __forceinline__ float round_bits(float f) {
 __device__ __forceinline__ bool is_subnormal(float x) { return __builtin_amdgcn_classf(x, 0x90); }
 __device__ __forceinline__ bool is_nan(float x) { return x != x; }
 
-struct Exact {
+// ---- bf16 -------------------------------------------------------------------------------
+// Rounders: how one fp32 result becomes a bf16 value (left widened in an fp32 register).
+struct ExactR {
   static constexpr bool kFast = false;
   static __device__ __forceinline__ P2 rnd(P2 x) { return {round_bits(x.lo), round_bits(x.hi)}; }
   static __device__ __forceinline__ float div1(float a, float b, float, bool &) { return a / b; }
@@ -52,7 +54,7 @@ struct Exact {
   static __device__ __forceinline__ float sqrt1(float a, bool &) { return __builtin_sqrtf(a); }
 };
 
-struct Fast {
+struct FastR {
   static constexpr bool kFast = true;
   // v_cvt_pk_bf16_f32 with 0 as its first source leaves bf16(x) in the upper half of the result and
   // bf16(0) = 0 in the lower half: that IS the rounded value widened back to fp32, in one instruction.
@@ -78,67 +80,143 @@ struct Fast {
   static __device__ __forceinline__ float sqrt1(float a, bool &) { return __builtin_amdgcn_sqrtf(a); }
 };
 
-// The bf16 operations on pairs.  Every function is one F(.): one fp32 operation per
-// element, then one rounding.
-template <class M> struct Ops {
-  static __device__ __forceinline__ P2 add(P2 a, P2 b) { return M::rnd({a.lo + b.lo, a.hi + b.hi}); }
-  static __device__ __forceinline__ P2 sub(P2 a, P2 b) { return M::rnd({a.lo - b.lo, a.hi - b.hi}); }
-  static __device__ __forceinline__ P2 mul(P2 a, P2 b) { return M::rnd({a.lo * b.lo, a.hi * b.hi}); }
-  static __device__ __forceinline__ P2 adds(P2 a, float s) { return M::rnd({a.lo + s, a.hi + s}); }
-  static __device__ __forceinline__ P2 muls(float s, P2 a) { return M::rnd({s * a.lo, s * a.hi}); }
-  // F(s*a - x), product unrounded (the FMA of Alg. 6)
-  static __device__ __forceinline__ P2 fmss(float s, P2 a, P2 x) {
-    return M::rnd({__builtin_fmaf(s, a.lo, -x.lo), __builtin_fmaf(s, a.hi, -x.hi)});
-  }
-  static __device__ __forceinline__ P2 fms(P2 a, P2 b, P2 x) {
-    return M::rnd({__builtin_fmaf(a.lo, b.lo, -x.lo), __builtin_fmaf(a.hi, b.hi, -x.hi)});
-  }
-  static __device__ __forceinline__ P2 divs(P2 a, float b, float rb, bool &redo) {
-    return M::rnd({M::div1(a.lo, b, rb, redo), M::div1(a.hi, b, rb, redo)});
-  }
-  static __device__ __forceinline__ P2 divg(P2 a, P2 b, bool &redo) {
-    return M::rnd({M::divg1(a.lo, b.lo, redo), M::divg1(a.hi, b.hi, redo)});
-  }
-  static __device__ __forceinline__ P2 sqrt(P2 a, bool &redo) {
-    return M::rnd({M::sqrt1(a.lo, redo), M::sqrt1(a.hi, redo)});
-  }
+// The bf16 operations on pairs, held widened.  Every function is one F(.): one fp32 operation
+// per element, then one rounding.
+template <class R> struct Bf {
+  using T = P2;        // a pair of elements
+  using S = float;     // a wave-uniform scalar
+  static constexpr bool kFast = R::kFast;      // may raise redo
+  static constexpr bool kHalf = false;
+  static __device__ __forceinline__ T unpack(uint32_t w) { return widen2(w); }
+  static __device__ __forceinline__ uint32_t pack(T x) { return pack2(x); }
+  static __device__ __forceinline__ T zero() { return {0.f, 0.f}; }
+  static __device__ __forceinline__ float lo(T x) { return x.lo; }
+  static __device__ __forceinline__ float hi(T x) { return x.hi; }
+  static __device__ __forceinline__ uint16_t bits_lo(T x) { return (uint16_t)(fbits(x.lo) >> 16); }
+  static __device__ __forceinline__ uint16_t bits_hi(T x) { return (uint16_t)(fbits(x.hi) >> 16); }
+  static __device__ __forceinline__ bool any_nan(T x) { return is_nan(x.lo) | is_nan(x.hi); }
+  static __device__ __forceinline__ T round_f32(float a, float b) { return R::rnd({a, b}); }
 
+  static __device__ __forceinline__ T add(T a, T b) { return R::rnd({a.lo + b.lo, a.hi + b.hi}); }
+  static __device__ __forceinline__ T sub(T a, T b) { return R::rnd({a.lo - b.lo, a.hi - b.hi}); }
+  static __device__ __forceinline__ T mul(T a, T b) { return R::rnd({a.lo * b.lo, a.hi * b.hi}); }
+  static __device__ __forceinline__ T adds(T a, S s) { return R::rnd({a.lo + s, a.hi + s}); }
+  static __device__ __forceinline__ T muls(S s, T a) { return R::rnd({s * a.lo, s * a.hi}); }
+  // F(s*a - x), product unrounded (the FMA of Alg. 6)
+  static __device__ __forceinline__ T fmss(S s, T a, T x) {
+    return R::rnd({__builtin_fmaf(s, a.lo, -x.lo), __builtin_fmaf(s, a.hi, -x.hi)});
+  }
+  static __device__ __forceinline__ T fms(T a, T b, T x) {
+    return R::rnd({__builtin_fmaf(a.lo, b.lo, -x.lo), __builtin_fmaf(a.hi, b.hi, -x.hi)});
+  }
+  static __device__ __forceinline__ T divs(T a, S b, S rb, bool &redo) {
+    return R::rnd({R::div1(a.lo, b, rb, redo), R::div1(a.hi, b, rb, redo)});
+  }
+  static __device__ __forceinline__ T divg(T a, T b, bool &redo) {
+    return R::rnd({R::divg1(a.lo, b.lo, redo), R::divg1(a.hi, b.hi, redo)});
+  }
+  static __device__ __forceinline__ T sqrt(T a, bool &redo) {
+    return R::rnd({R::sqrt1(a.lo, redo), R::sqrt1(a.hi, redo)});
+  }
+};
+using Exact = Bf<ExactR>;
+using Fast = Bf<FastR>;
+
+// ---- fp16 -------------------------------------------------------------------------------
+// The same operation F(a o b) for IEEE binary16 components (App. A Table 7).  The pair stays packed
+// in one register.  For +, -, * the hardware's packed fp16 instructions round the exact result
+// once to fp16, which equals rounding it first to fp32 and then to fp16 (fp32's 24 bits are at least
+// 2*11+2, so the first rounding can never create or destroy a tie of the second).  The fused
+// multiply-subtract is only ever used as F(a*b - F(a*b)) (Alg. 6): that difference is exactly
+// representable in fp32, so again both routes round the same exact number.  Division and square
+// root have no correctly rounded fp16 instruction: they are done per element as the definition
+// says, widen, one correctly rounded fp32 operation, narrow.
+// NaN: the hardware propagates payloads, the stored format has one NaN (0x7E00).  NaN-ness itself
+// propagates the same way in both, so only stored values need fixing: the vector path (kFast) just
+// detects a NaN in its results and hands the slot to the element path, which stores the one NaN.
+typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
+
+// Keeps the optimizer from folding widen / fp32 op / narrow into an fp16 operation of its own choice.
+__device__ __forceinline__ float opaque(float f) { asm("" : "+v"(f)); return f; }
+
+template <bool HOT> struct Hf {
+  using T = h2_t;
+  using S = h2_t;      // a scalar is the same value in both halves
+  static constexpr bool kFast = HOT;
+  static constexpr bool kHalf = true;
+  static __device__ __forceinline__ T unpack(uint32_t w) { return __builtin_bit_cast(h2_t, w); }
+  static __device__ __forceinline__ uint32_t pack(T x) { return __builtin_bit_cast(uint32_t, x); }
+  static __device__ __forceinline__ T zero() { return h2_t{(_Float16)0, (_Float16)0}; }
+  static __device__ __forceinline__ float lo(T x) { return (float)x.x; }
+  static __device__ __forceinline__ float hi(T x) { return (float)x.y; }
+  static __device__ __forceinline__ uint16_t canon(uint32_t h) { return (h & 0x7fffu) > 0x7c00u ? (uint16_t)0x7e00 : (uint16_t)h; }
+  static __device__ __forceinline__ uint16_t bits_lo(T x) { return canon(pack(x) & 0xffffu); }
+  static __device__ __forceinline__ uint16_t bits_hi(T x) { return canon(pack(x) >> 16); }
+  // a half is NaN iff its magnitude bits exceed 0x7C00; +0x03FF carries exactly those into bit 15
+  static __device__ __forceinline__ bool any_nan(T x) { return (((pack(x) & 0x7fff7fffu) + 0x03ff03ffu) & 0x80008000u) != 0; }
+  static __device__ __forceinline__ T round_f32(float a, float b) { return h2_t{(_Float16)a, (_Float16)b}; }
+
+  static __device__ __forceinline__ T add(T a, T b) { return a + b; }
+  static __device__ __forceinline__ T sub(T a, T b) { return a - b; }
+  static __device__ __forceinline__ T mul(T a, T b) { return a * b; }
+  static __device__ __forceinline__ T adds(T a, S s) { return a + s; }
+  static __device__ __forceinline__ T muls(S s, T a) { return s * a; }
+  static __device__ __forceinline__ T fmss(S s, T a, T x) { return __builtin_elementwise_fma(s, a, -x); }
+  static __device__ __forceinline__ T fms(T a, T b, T x) { return __builtin_elementwise_fma(a, b, -x); }
+  static __device__ __forceinline__ _Float16 div1(_Float16 a, _Float16 b) { return (_Float16)(opaque((float)a) / (float)b); }
+  static __device__ __forceinline__ T divs(T a, S b, S, bool &) { return h2_t{div1(a.x, b.x), div1(a.y, b.y)}; }
+  static __device__ __forceinline__ T divg(T a, T b, bool &) { return h2_t{div1(a.x, b.x), div1(a.y, b.y)}; }
+  static __device__ __forceinline__ T sqrt(T a, bool &) {
+    return h2_t{(_Float16)__builtin_sqrtf(opaque((float)a.x)), (_Float16)__builtin_sqrtf(opaque((float)a.y))};
+  }
+};
+using HalfHot = Hf<true>;
+using HalfCold = Hf<false>;
+
+// The expansion algorithms over any of the modes above.
+template <class M> struct Ops : M {
+  using T = typename M::T;
+  using M::add;
+  using M::sub;
   // Thm 4.1: (x, y) = Fast2Sum(a, b)
-  static __device__ __forceinline__ void fast2sum(P2 a, P2 b, P2 &x, P2 &y) {
+  static __device__ __forceinline__ void fast2sum(T a, T b, T &x, T &y) {
     x = add(a, b);
     y = sub(b, sub(x, a));
   }
   // Alg. 3
-  static __device__ __forceinline__ void two_sum(P2 a, P2 b, P2 &x, P2 &y) {
+  static __device__ __forceinline__ void two_sum(T a, T b, T &x, T &y) {
     x = add(a, b);
-    P2 bv = sub(x, a);
-    P2 av = sub(x, bv);
-    P2 br = sub(b, bv);
-    P2 ar = sub(a, av);
+    T bv = sub(x, a);
+    T av = sub(x, bv);
+    T br = sub(b, bv);
+    T ar = sub(a, av);
     y = add(ar, br);
   }
   // Alg. 1: (x, y) <- Grow((x, y), a)
-  static __device__ __forceinline__ void grow(P2 x, P2 y, P2 a, P2 &xo, P2 &yo) {
-    P2 u, w;
+  static __device__ __forceinline__ void grow(T x, T y, T a, T &xo, T &yo) {
+    T u, w;
     fast2sum(x, a, u, w);
     fast2sum(u, add(y, w), xo, yo);
   }
   // Alg. 1 on TwoSum (Alg. 3): no |x| >= |a| precondition
-  static __device__ __forceinline__ void grow2(P2 x, P2 y, P2 a, P2 &xo, P2 &yo) {
-    P2 u, w;
+  static __device__ __forceinline__ void grow2(T x, T y, T a, T &xo, T &yo) {
+    T u, w;
     two_sum(x, a, u, w);
     two_sum(u, add(y, w), xo, yo);
   }
 };
 
-// bf16 scalars of one step, widened to fp32 (exact), plus fp32 reciprocals of the two
-// bias corrections for the Fast mode.
-struct StepScalars {
-  float b1, c1, b2, b2l, c2, bc1, bc2, rbc1, rbc2, e, lam, na;
+// Scalars of one step in the mode's scalar type (bf16 values widened to fp32, or fp16 values in both
+// halves of a packed register), plus, for the bf16 Fast mode, fp32 reciprocals of the two bias
+// corrections.
+template <class S> struct StepScalarsT {
+  S b1, c1, b2, b2l, c2, bc1, bc2, rbc1, rbc2, e, lam, na;
 };
+using StepScalars = StepScalarsT<float>;
+using StepScalarsH = StepScalarsT<h2_t>;
 
-struct ElemIO {          // one pair of elements of every stream
-  P2 th, dth, m, v, dv, g;
+template <class T> struct ElemIOT {          // one pair of elements of every stream
+  T th, dth, m, v, dv, g;
 };
 
 // Variants of the step.  Light and plus are Collage (Sec. 4.2); the other two are the paper's
@@ -148,53 +226,55 @@ struct ElemIO {          // one pair of elements of every stream
 enum : int { V_LIGHT = 0, V_PLUS = 1, V_BF16 = 2, V_KAHAN = 3, V_SGD = 4 };
 
 // Alg. 2 lines 8-13 on one pair.  GROW2 builds every Grow on TwoSum.  On return io holds the new theta, dtheta, m, v (and dv);
-// delta receives line 12's update.  redo is raised (Fast mode) when this pair must be
-// recomputed in Exact mode.
+// delta receives line 12's update.  redo is raised (modes with kFast) when this pair must be
+// recomputed element by element.
 template <class M, int VARIANT, bool GROW2 = false>
-__device__ __forceinline__ void adamw_pair(ElemIO &io, const StepScalars &s, P2 &delta, bool &redo) {
+__device__ __forceinline__ void adamw_pair(ElemIOT<typename M::T> &io, const StepScalarsT<typename M::S> &s,
+                                           typename M::T &delta, bool &redo) {
   using O = Ops<M>;
+  using T = typename M::T;
   if (VARIANT == V_SGD) {
-    const P2 m1 = O::add(O::muls(s.b1, io.m), io.g);            // s.b1 = momentum coefficient
+    const T m1 = O::add(O::muls(s.b1, io.m), io.g);            // s.b1 = momentum coefficient
     delta = O::muls(s.na, O::add(m1, O::muls(s.lam, io.th)));
-    P2 th1, dth1;
+    T th1, dth1;
     O::grow(io.th, io.dth, delta, th1, dth1);
-    if (M::kFast) redo |= is_nan(th1.lo) | is_nan(dth1.lo) | is_nan(th1.hi) | is_nan(dth1.hi);
+    if (M::kFast) redo |= M::any_nan(th1) | M::any_nan(dth1);
     io.th = th1;
     io.dth = dth1;
     io.m = m1;
     return;
   }
   // line 8
-  P2 m1 = O::add(O::muls(s.b1, io.m), O::muls(s.c1, io.g));
+  T m1 = O::add(O::muls(s.b1, io.m), O::muls(s.c1, io.g));
   // line 9
-  P2 inc = O::muls(s.c2, O::mul(io.g, io.g));
-  P2 v1, dv1 = {0.f, 0.f};
+  T inc = O::muls(s.c2, O::mul(io.g, io.g));
+  T v1, dv1 = M::zero();
   if (VARIANT != V_PLUS) {
     v1 = O::add(O::muls(s.b2, io.v), inc);
   } else {
     // Mul((b2, b2l), (v, dv)), Alg. 8 with TwoProdFMA (Alg. 6)
-    P2 x = O::muls(s.b2, io.v);
-    P2 ex = O::fmss(s.b2, io.v, x);
-    P2 cross = O::add(O::muls(s.b2, io.dv), O::muls(s.b2l, io.v));
-    P2 e2 = O::add(ex, cross);
-    P2 X, E;
+    T x = O::muls(s.b2, io.v);
+    T ex = O::fmss(s.b2, io.v, x);
+    T cross = O::add(O::muls(s.b2, io.dv), O::muls(s.b2l, io.v));
+    T e2 = O::add(ex, cross);
+    T X, E;
     O::fast2sum(x, e2, X, E);
     if (GROW2) O::grow2(X, E, inc, v1, dv1); else O::grow(X, E, inc, v1, dv1);
   }
   // lines 10-11
-  P2 mh = O::divs(m1, s.bc1, s.rbc1, redo);
-  P2 vh = O::divs(v1, s.bc2, s.rbc2, redo);
+  T mh = O::divs(m1, s.bc1, s.rbc1, redo);
+  T vh = O::divs(v1, s.bc2, s.rbc2, redo);
   // line 12 (epsilon outside the root; weight decay inside the summed update)
-  P2 dn = O::adds(O::sqrt(vh, redo), s.e);
-  P2 q = O::divg(mh, dn, redo);
-  P2 w = O::muls(s.lam, io.th);
+  T dn = O::adds(O::sqrt(vh, redo), s.e);
+  T q = O::divg(mh, dn, redo);
+  T w = O::muls(s.lam, io.th);
   delta = O::muls(s.na, O::add(q, w));
   // line 13
-  P2 th1, dth1 = {0.f, 0.f};
+  T th1, dth1 = M::zero();
   if (VARIANT == V_BF16) {
     th1 = O::add(io.th, delta);                       // Eq. 1
   } else if (VARIANT == V_KAHAN) {
-    const P2 u = O::add(delta, io.dth);               // compensate the update with the Kahan variable
+    const T u = O::add(delta, io.dth);                // compensate the update with the Kahan variable
     O::fast2sum(io.th, u, th1, dth1);                 // c <- F(u - F(theta' - theta))
   } else if (GROW2) {
     O::grow2(io.th, io.dth, delta, th1, dth1);
@@ -204,8 +284,8 @@ __device__ __forceinline__ void adamw_pair(ElemIO &io, const StepScalars &s, P2 
   if (M::kFast) {
     // Any NaN produced or consumed above reaches theta' or dtheta' (or dv'): m' and v' feed
     // the quotient, the quotient feeds delta, delta feeds theta'.
-    redo |= is_nan(th1.lo) | is_nan(dth1.lo) | is_nan(th1.hi) | is_nan(dth1.hi);
-    if (VARIANT == V_PLUS) redo |= is_nan(dv1.lo) | is_nan(dv1.hi);
+    redo |= M::any_nan(th1) | M::any_nan(dth1);
+    if (VARIANT == V_PLUS) redo |= M::any_nan(dv1);
   }
   io.th = th1;
   io.dth = dth1;

@@ -18,6 +18,16 @@ HYPER_LIGHT = (3e-4, 0.9, 0.95, 1e-8, 0.1)
 HYPER_PLUS_1P3B = (1e-4, 0.9, 0.999, 1e-8, 0.1)
 HYPER_STRESS = (2.0 ** -20, 0.9, 0.999, 1e-8, 0.1)
 
+# fp16 components: gradients of size 1e-3 square to 1e-6, below fp16's normal range (2^-14), so the
+# synthetic fp16 workloads carry the gradients times a fixed loss scale and epsilon times the same
+# factor (Adam's ratio m/sqrt(v) does not depend on the gradient's scale; epsilon does).
+FP16_LOSS_SCALE = 1024.0
+
+
+def fp16_hyper(h):
+    lr, b1, b2, eps, wd = h
+    return (lr, b1, b2, eps * FP16_LOSS_SCALE, wd)
+
 
 def gpt_shapes(n_layer, d, ffn, vocab, n_pos):
     """GPT-2 style list: embeddings, per-layer {ln1, qkv, proj, ln2, fc, fc2} with biases, final ln."""
@@ -65,7 +75,7 @@ def _gen(device, *key):
 
 
 def normal_bf16(n, std, key, device="cpu", mean=0.0, out=None):
-    """n draws of N(mean, std^2) in fp32, cast to bf16.  key = tuple of ints."""
+    """n draws of N(mean, std^2) in fp32, cast to bf16 (or to out's dtype).  key = tuple of ints."""
     g = _gen(device, *key)
     x = torch.empty(n, dtype=torch.float32, device=device)
     x.normal_(mean=float(mean), std=float(std), generator=g)
@@ -148,7 +158,7 @@ def layout(shape_list, misalign_tiny=False, align=8):
 
 
 def init_theta(name, shape_list, offs, arena, seed=0):
-    """Fill arena (bf16, flat) with the initial parameters of the workload."""
+    """Fill arena (bf16 or fp16, flat) with the initial parameters of the workload."""
     dev = arena.device
     if name == "stress_64m":
         k = len(shape_list)
@@ -174,8 +184,8 @@ def stress_drift(shape_list, offs, arena_len, device, seed=0, sigma=1e-3):
 _CHUNK = 1 << 27     # elements drawn per call when filling a whole arena (bounds the fp32 temporary)
 
 
-def fill_grads(name, shape_list, offs, arena, step, seed=0, sigmas=None, drift=None):
-    """Fill arena (bf16, flat) with the gradients of optimizer step `step` (1-based).
+def fill_grads(name, shape_list, offs, arena, step, seed=0, sigmas=None, drift=None, grad_scale=1.0):
+    """Fill arena (bf16 or fp16, flat) with the gradients of optimizer step `step` (1-based), times grad_scale.
 
     Sets whose tensors share one sigma are drawn arena-wide (padding between tensors gets values
     too; nobody reads them); the 1.3B set, with a sigma per tensor, is drawn tensor by tensor.
@@ -185,7 +195,7 @@ def fill_grads(name, shape_list, offs, arena, step, seed=0, sigmas=None, drift=N
         if sigmas is None:
             sigmas = grad_sigmas(name, shape_list, seed)
         for i, ((_, n), o) in enumerate(zip(shape_list, offs)):
-            normal_bf16(n, sigmas[i], (seed, 1, step, i), device=dev, out=arena[o:o + n])
+            normal_bf16(n, sigmas[i] * grad_scale, (seed, 1, step, i), device=dev, out=arena[o:o + n])
         return
     g = _gen(dev, seed, 1, step)
     total = arena.numel()
@@ -195,6 +205,8 @@ def fill_grads(name, shape_list, offs, arena, step, seed=0, sigmas=None, drift=N
         x.normal_(mean=0.0, std=1e-3, generator=g)
         if drift is not None:
             x += drift[lo:hi]
+        if grad_scale != 1.0:
+            x *= grad_scale
         arena[lo:hi].copy_(x)
 
 

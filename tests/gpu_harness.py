@@ -37,18 +37,20 @@ class Workload:
     """Device state of one named workload and its plan."""
 
     def __init__(self, name, device="cuda", misalign_tiny=False, seed=0, variant=None, shape_list=None, hyper=None,
-                 align=8):
+                 align=8, fp16=False):
         self.name = name
         self.shapes = shape_list if shape_list is not None else W.shapes(name)
         vname = variant or W.WORKLOADS[name][1]
         self.variant = {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN,
                         "sgd": mcf.SGD, "light+twosum": mcf.LIGHT | mcf.GROW_TWOSUM, "plus+twosum": mcf.PLUS | mcf.GROW_TWOSUM}[vname]
-        base = self.variant & 0xFF
-        self.hyper = hyper or W.WORKLOADS[name][2]
+        self.fp16 = fp16
+        self.hyper = hyper or (W.fp16_hyper(W.WORKLOADS[name][2]) if fp16 else W.WORKLOADS[name][2])
+        if fp16:
+            self.variant |= mcf.FMT_FP16           # the same bit is the oracle's STEP_FP16
         self.offs, self.total = W.layout(self.shapes, misalign_tiny=misalign_tiny, align=align)
         self.seed = seed
         self.device = device
-        z = lambda: torch.zeros(self.total, dtype=torch.bfloat16, device=device)
+        z = lambda: torch.zeros(self.total, dtype=torch.float16 if fp16 else torch.bfloat16, device=device)
         base = self.variant & 0xFF
         self.theta, self.m = z(), z()
         self.v = z() if base != mcf.SGD else None
@@ -74,7 +76,7 @@ class Workload:
 
     def new_grads(self, step):
         W.fill_grads(self.name, self.shapes, self.offs, self.grad, step, seed=self.seed, sigmas=self.sigmas,
-                     drift=self.drift)
+                     drift=self.drift, grad_scale=W.FP16_LOSS_SCALE if self.fp16 else 1.0)
 
     def gather(self, tensor, idx_dev):
         return H.torch_to_u16(tensor[idx_dev])
@@ -115,3 +117,45 @@ class SampledOracle:
 
 def assert_bitwise(mism, where):
     assert all(v == 0 for v in mism.values()), f"{where}: mismatching elements {mism}"
+
+
+def full_oracle_run(wl, steps, edq=False, check_each=True):
+    """Whole-state comparison after every step, oracle over every element."""
+    names = wl.state_names()
+    host = {k: H.torch_to_u16(getattr(wl, k)) for k in names}
+    edq_dev = torch.zeros(4, dtype=torch.float64, device=wl.device) if edq else None
+    live = np.zeros(wl.total, bool)
+    for (_, n), o in zip(wl.shapes, wl.offs):
+        live[o:o + n] = True
+    for t in range(1, steps + 1):
+        wl.new_grads(t)
+        g = H.torch_to_u16(wl.grad)
+        before = {k: host[k].copy() for k in ("theta", "dtheta") if k in host} if edq else None
+        delta = np.zeros(wl.total, np.uint16) if edq else None
+        # the oracle steps the whole arena; padding between tensors is stepped too and then ignored
+        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host.get("v"), host.get("dv"), g, wl.variant, wl.hyper, t,
+                       delta_out=delta)
+        wl.plan.step(wl.hyper, t, edq_out=edq_dev)
+        torch.cuda.synchronize()
+        if check_each or t == steps:
+            for k in names:
+                dev = H.torch_to_u16(getattr(wl, k))
+                bad = np.flatnonzero((dev != host[k]) & live)
+                assert bad.size == 0, f"{wl.name} step {t} {k}: {bad.size} mismatches, first at {int(bad[0])}: " \
+                                      f"got {dev[bad[0]]:#06x} want {host[k][bad[0]]:#06x}"
+                # padding is never written by the library
+                assert not dev[~live].any()
+                host[k][~live] = 0
+        if edq:
+            acc = orc.EdqAccumulator(fmt=orc.FMT_FP16 if wl.fp16 else orc.FMT_BF16)
+            for (_, n), o in zip(wl.shapes, wl.offs):
+                sl = slice(o, o + n)
+                d0 = before["dtheta"][sl].copy() if "dtheta" in host else None
+                d1 = host["dtheta"][sl].copy() if "dtheta" in host else None
+                acc.add(delta[sl].copy(), before["theta"][sl].copy(), d0, host["theta"][sl].copy(), d1)
+            want = acc.value()
+            got = edq_dev.cpu().numpy()
+            assert abs(got[0] - want) <= 1e-5 * abs(want), (t, got, want)
+            assert int(got[3]) == acc.lost.value, (t, got[3], acc.lost.value)          # exact integer
+            assert abs(got[1] - acc.s1.value) <= 1e-5 * abs(acc.s1.value) and abs(got[2] - acc.s2.value) <= 1e-5 * acc.s2.value
+            assert want > 0

@@ -128,13 +128,14 @@ def bf16_window(emin, emax, signs=True):
 
 def torch_to_u16(t):
     import torch
-    assert t.dtype == torch.bfloat16
+    assert t.dtype in (torch.bfloat16, torch.float16)
     return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16).copy()
 
 
-def u16_to_torch(u, device="cpu"):
+def u16_to_torch(u, device="cpu", dtype=None):
+    """16-bit patterns -> a torch tensor of dtype bfloat16 (default) or float16 holding those patterns."""
     import torch
-    return torch.from_numpy(np.ascontiguousarray(u).view(np.int16).copy()).view(torch.bfloat16).to(device)
+    return torch.from_numpy(np.ascontiguousarray(u).view(np.int16).copy()).view(dtype or torch.bfloat16).to(device)
 
 
 def read_golden(path):

@@ -10,7 +10,7 @@ import pytest
 import torch
 
 import helpers as H
-from gpu_harness import SampledOracle, Workload, assert_bitwise, sample_indices
+from gpu_harness import SampledOracle, Workload, assert_bitwise, full_oracle_run, sample_indices
 from oracle import oracle as orc
 from paper_2405_03637_amd import binding as mcf
 from paper_2405_03637_amd import workloads as W
@@ -149,54 +149,12 @@ def test_primitives_mutually_misaligned_buffers():
 
 
 # ------------------------------------------------------------------ the step: small, exhaustive comparisons
-def _full_oracle_run(wl, steps, edq=False, check_each=True):
-    """Whole-state comparison after every step, oracle over every element."""
-    names = wl.state_names()
-    host = {k: H.torch_to_u16(getattr(wl, k)) for k in names}
-    edq_dev = torch.zeros(4, dtype=torch.float64, device=DEV) if edq else None
-    live = np.zeros(wl.total, bool)
-    for (_, n), o in zip(wl.shapes, wl.offs):
-        live[o:o + n] = True
-    for t in range(1, steps + 1):
-        wl.new_grads(t)
-        g = H.torch_to_u16(wl.grad)
-        before = {k: host[k].copy() for k in ("theta", "dtheta") if k in host} if edq else None
-        delta = np.zeros(wl.total, np.uint16) if edq else None
-        # the oracle steps the whole arena; padding between tensors is stepped too and then ignored
-        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host.get("v"), host.get("dv"), g, wl.variant, wl.hyper, t,
-                       delta_out=delta)
-        wl.plan.step(wl.hyper, t, edq_out=edq_dev)
-        torch.cuda.synchronize()
-        if check_each or t == steps:
-            for k in names:
-                dev = H.torch_to_u16(getattr(wl, k))
-                bad = np.flatnonzero((dev != host[k]) & live)
-                assert bad.size == 0, f"{wl.name} step {t} {k}: {bad.size} mismatches, first at {int(bad[0])}: " \
-                                      f"got {dev[bad[0]]:#06x} want {host[k][bad[0]]:#06x}"
-                # padding is never written by the library
-                assert not dev[~live].any()
-                host[k][~live] = 0
-        if edq:
-            acc = orc.EdqAccumulator()
-            for (_, n), o in zip(wl.shapes, wl.offs):
-                sl = slice(o, o + n)
-                d0 = before["dtheta"][sl].copy() if "dtheta" in host else None
-                d1 = host["dtheta"][sl].copy() if "dtheta" in host else None
-                acc.add(delta[sl].copy(), before["theta"][sl].copy(), d0, host["theta"][sl].copy(), d1)
-            want = acc.value()
-            got = edq_dev.cpu().numpy()
-            assert abs(got[0] - want) <= 1e-5 * abs(want), (t, got, want)
-            assert int(got[3]) == acc.lost.value, (t, got[3], acc.lost.value)          # exact integer
-            assert abs(got[1] - acc.s1.value) <= 1e-5 * abs(acc.s1.value) and abs(got[2] - acc.s2.value) <= 1e-5 * acc.s2.value
-            assert want > 0
-
-
 @pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan", "sgd", "light+twosum", "plus+twosum"])
 def test_config1_flat_1m(variant):
     """Config 1: one flat tensor of 2^20, 10 steps, every element after every step; plan and flat entry points."""
     _say(f"config 1 {variant}")
     wl = Workload("flat_1m", variant=variant)
-    _full_oracle_run(wl, 10, edq=True)
+    full_oracle_run(wl, 10, edq=True)
     wl.close()
     # the flat entry point on a fresh copy of the same inputs
     wl = Workload("flat_1m", variant=variant)
@@ -222,7 +180,7 @@ def test_many_small_and_ragged_tensors(variant):
     for align in (1, 8):          # 1: every tensor starts wherever the previous one ended
         wl = Workload("flat_1m", variant=variant, shape_list=shapes, misalign_tiny=True, align=align,
                       hyper=W.HYPER_PLUS_1P3B if variant.startswith("plus") else W.HYPER_LIGHT)
-        _full_oracle_run(wl, 5, edq=True)
+        full_oracle_run(wl, 5, edq=True)
         wl.close()
 
 
