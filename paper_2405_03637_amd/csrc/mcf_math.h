@@ -129,8 +129,16 @@ using Fast = Bf<FastR>;
 // 2*11+2, so the first rounding can never create or destroy a tie of the second).  The fused
 // multiply-subtract is only ever used as F(a*b - F(a*b)) (Alg. 6): that difference is exactly
 // representable in fp32, so again both routes round the same exact number.  Division and square
-// root have no correctly rounded fp16 instruction: they are done per element as the definition
-// says, widen, one correctly rounded fp32 operation, narrow.
+// root have no correctly rounded fp16 instruction: they are done per element, widened.  The square
+// root is the definition itself (correctly rounded fp32 root, then narrow).  The quotient is
+// q' = q + (a - b*q)*r with r = v_rcp_f32(b), q = a*r: the residual a - b*q is exact in one FMA
+// (a and b have 11 significant bits, q agrees with a/b to 2^-22), so q' is the fp32 rounding of a
+// number within 2^-44 of a/b: it equals a/b whenever that is an fp32 number (so exact fp16 results
+// and exact ties survive) and is otherwise within 2^-24(1+2^-20) of it, while a quotient of two
+// 11-bit numbers that is not itself a rounding boundary stays more than 2^-23 (relative) away from
+// every fp16 rounding boundary, subnormal results and the overflow threshold included.  Zero or
+// infinite operands make the residual NaN, and a zero dividend loses its sign in the correction; in
+// both cases q is already the IEEE result and is kept.
 // NaN: the hardware propagates payloads, the stored format has one NaN (0x7E00).  NaN-ness itself
 // propagates the same way in both, so only stored values need fixing: the vector path (kFast) just
 // detects a NaN in its results and hands the slot to the element path, which stores the one NaN.
@@ -163,7 +171,14 @@ template <bool HOT> struct Hf {
   static __device__ __forceinline__ T muls(S s, T a) { return s * a; }
   static __device__ __forceinline__ T fmss(S s, T a, T x) { return __builtin_elementwise_fma(s, a, -x); }
   static __device__ __forceinline__ T fms(T a, T b, T x) { return __builtin_elementwise_fma(a, b, -x); }
-  static __device__ __forceinline__ _Float16 div1(_Float16 a, _Float16 b) { return (_Float16)(opaque((float)a) / (float)b); }
+  static __device__ __forceinline__ _Float16 div1(_Float16 ah, _Float16 bh) {
+    const float a = (float)ah, b = (float)bh;
+    const float r = __builtin_amdgcn_rcpf(b);
+    const float q = a * r;
+    const float res = __builtin_fmaf(-b, q, a);
+    const float q1 = __builtin_fmaf(res, r, q);
+    return (_Float16)(__builtin_fabsf(q1) > 0.0f ? q1 : q);     // NaN or zero: keep q (a zero quotient keeps a's sign there)
+  }
   static __device__ __forceinline__ T divs(T a, S b, S, bool &) { return h2_t{div1(a.x, b.x), div1(a.y, b.y)}; }
   static __device__ __forceinline__ T divg(T a, T b, bool &) { return h2_t{div1(a.x, b.x), div1(a.y, b.y)}; }
   static __device__ __forceinline__ T sqrt(T a, bool &) {
