@@ -23,7 +23,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor peak
 # HBM traffic per parameter per step measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
 # what the same counters read for a plain copy of known size (FETCH_SIZE x2.0000, WRITE_SIZE x1.0000);
 # the figures and commands are in profiles/*_llama_7b.md.  None = not measured.
-MEASURED_TRAFFIC_BYTES_PER_PARAM = {"light": 18.250, "plus": 22.250, "kahan": 18.250, "bf16": 14.250, "fp32mw": 28.250}
+MEASURED_TRAFFIC_BYTES_PER_PARAM = {"light": 18.250, "plus": 22.250, "kahan": 18.250, "bf16": 14.250, "sgd": 14.250,
+                                    "fp32mw": 28.250}      # the same with fp16 components (same bytes, same table)
 
 
 def log(msg):
