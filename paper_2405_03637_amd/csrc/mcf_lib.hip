@@ -58,14 +58,13 @@ using mcfd::StepScalarsT;
 #ifndef MCF_STEP_ATTR
 #define MCF_STEP_ATTR                // optional extra attribute of the step kernels (e.g. amdgpu_waves_per_eu)
 #endif
-#ifndef MCF_STEP_LDS
-#define MCF_STEP_LDS 14848           // bytes of untouched dynamic LDS per workgroup = the occupancy cap (11 groups per CU)
-#endif
+// MCF_STEP_LDS, if defined, is the bytes of untouched dynamic LDS per workgroup (= the occupancy cap) of
+// every step kernel; by default the cap is per variant, see StepStreams::kLds.
 #ifndef MCF_STEP_LDS_EDQ
 #define MCF_STEP_LDS_EDQ 10752       // with the fused EDQ sums (fp64 arithmetic to hide) 15 groups per CU measure best
 #endif
 #ifndef MCF_FP32MW_LDS
-#define MCF_FP32MW_LDS MCF_STEP_LDS  // the same cap for the fp32-master baseline kernel
+#define MCF_FP32MW_LDS 12544         // 13 groups per CU for the fp32-master baseline kernel (11: 28.90 ms, 13: 28.82, 16: 29.64)
 #endif
 #ifndef MCF_COPY_LDS
 #define MCF_COPY_LDS 0               // the plain copy (2 streams) is fastest uncapped: 6.66 TB/s against 4.4 TB/s with the cap
@@ -279,6 +278,15 @@ template <int VARIANT> struct StepStreams {
   static constexpr bool kDth = kBase != mcfd::V_BF16;      // second component of theta / Kahan variable
   static constexpr bool kDv = kBase == mcfd::V_PLUS;       // second component of v
   static constexpr bool kV = kBase != mcfd::V_SGD;         // second moment
+  // Untouched dynamic LDS per workgroup = occupancy cap, from a sweep of 8..32 groups per CU at the
+  // 7B-parameter set: 9-stream kernels (light, Kahan) are fastest at 11 groups per CU, the 11-stream plus
+  // at 12 (23.18 ms against 23.38 at 11), the 7-stream plain variant, whose divide and root have less
+  // memory time to hide behind, at 13 (14.24 ms against 15.09), the 7-stream SGD at 11-12.
+#ifdef MCF_STEP_LDS
+  static constexpr uint32_t kLds = MCF_STEP_LDS;
+#else
+  static constexpr uint32_t kLds = kBase == mcfd::V_BF16 ? 12544 : kBase == mcfd::V_PLUS ? 13568 : 14848;
+#endif
 };
 
 // Hot path: one full slot, 8 elements of every stream held as 4 dwords each.  Returns true
@@ -797,13 +805,13 @@ void launch_step(bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *de
 #endif
   if constexpr ((VARIANT & kHalfBit) != 0) {
     if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, hs.hf, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, MCF_STEP_LDS, st, descs, chunks, flat, hs.hf, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, StepStreams<VARIANT>::kLds, st, descs, chunks, flat, hs.hf, partials, blocks);
   } else if (hs.fast) {
     if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, hs.bf, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, MCF_STEP_LDS, st, descs, chunks, flat, hs.bf, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, StepStreams<VARIANT>::kLds, st, descs, chunks, flat, hs.bf, partials, blocks);
   } else {
     if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, hs.bf, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, MCF_STEP_LDS, st, descs, chunks, flat, hs.bf, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, StepStreams<VARIANT>::kLds, st, descs, chunks, flat, hs.bf, partials, blocks);
   }
 }
 
