@@ -296,6 +296,70 @@ def test_edq_standalone():
     assert abs(out[0].item() - want) <= 1e-5 * abs(want)
 
 
+EDGE_HYPERS = [
+    # (lr, beta1, beta2, eps, weight_decay), step
+    ((0.0, 0.9, 0.95, 1e-8, 0.1), 1),                    # no movement: delta = -0 * (...)
+    ((1e-3, 0.0, 0.0, 0.0, 0.0), 1),                     # no memory, no epsilon: sign descent, 0/0 where g = 0
+    ((1e-3, 0.9, 0.999, 1e-8, 0.0), 10 ** 9),            # bias corrections have reached 1
+    ((1.0, 0.5, 0.5, 1.0, 1.0), 3),                      # everything of order one
+    ((1e-3, 0.9, 0.95, 1e30, 0.1), 2),                   # epsilon dwarfs the root
+    ((1e-3, 0.9, 0.95, 1e-40, 0.1), 2),                  # epsilon is a bf16 subnormal (0 in fp16)
+    ((1e-3, 0.9, 1.0 - 1e-10, 1e-8, 0.1), 1),            # beta2 rounds to 1, 1-beta2 and its bias correction are tiny
+    ((3e-4, 0.999999, 0.95, 1e-8, 0.1), 1),              # 1-beta1 = 1e-6
+    ((1e4, 0.9, 0.95, 1e-8, 100.0), 5),                  # absurdly large step and decay: overflow to infinity and NaN
+]
+
+
+@pytest.mark.parametrize("fp16", [False, True])
+@pytest.mark.parametrize("variant", ["light", "plus", "sgd"])
+def test_hyper_parameter_edge_cases(variant, fp16):
+    """Extreme but valid hyper-parameters: whatever arithmetic mode the host picks for them, and whatever
+    infinities and NaN they produce, every stored element must match the oracle."""
+    shapes = [("a", 20_011), ("b", 3)]
+    for hyper, t0 in EDGE_HYPERS:
+        wl = Workload("flat_1m", variant=variant, shape_list=shapes, hyper=hyper, fp16=fp16, misalign_tiny=True)
+        names = wl.state_names()
+        host = {k: H.torch_to_u16(getattr(wl, k)) for k in names}
+        live = np.zeros(wl.total, bool)                      # the oracle steps the arena's padding too; it is ignored
+        for (_, n), o in zip(wl.shapes, wl.offs):
+            live[o:o + n] = True
+        for t in range(t0, t0 + 3):
+            wl.new_grads(t)
+            wl.grad[::5] = 0                                 # exact zeros among the gradients
+            g = H.torch_to_u16(wl.grad)
+            orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host.get("v"), host.get("dv"), g, wl.variant, hyper, t)
+            wl.plan.step(hyper, t)
+            for k in names:
+                dev = H.torch_to_u16(getattr(wl, k))
+                bad = np.flatnonzero((dev != host[k]) & live)
+                assert not dev[~live].any()
+                assert bad.size == 0, f"{variant} fp16={fp16} hyper {hyper} step {t} {k}: {bad.size} mismatches, first " \
+                                      f"{int(bad[0])}: got {dev[bad[0]]:#06x} want {host[k][bad[0]]:#06x}"
+        wl.close()
+
+
+def test_two_plans_on_two_streams():
+    """Distinct plans are independent: two steps enqueued on two streams at once give the same bits as
+    the oracle gives for each alone."""
+    wls = [Workload("flat_1m", variant=v, shape_list=[("a", 3_000_017)], seed=s) for v, s in (("light", 1), ("plus", 2))]
+    hosts = [{k: H.torch_to_u16(getattr(w, k)) for k in w.state_names()} for w in wls]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for t in range(1, 5):
+        for w in wls:
+            w.new_grads(t)
+        torch.cuda.synchronize()
+        for w, st in zip(wls, streams):
+            w.plan.step(w.hyper, t, stream=st)
+        for w, h in zip(wls, hosts):
+            orc.adamw_step(h["theta"], h.get("dtheta"), h["m"], h.get("v"), h.get("dv"), H.torch_to_u16(w.grad), w.variant, w.hyper, t)
+        torch.cuda.synchronize()
+    for w, h in zip(wls, hosts):
+        for k in w.state_names():
+            n = w.shapes[0][1]                     # the oracle also stepped the arena's padding; compare the tensor
+            assert np.array_equal(H.torch_to_u16(getattr(w, k))[:n], h[k][:n]), (w.variant, k)
+        w.close()
+
+
 # ------------------------------------------------------------------ option D
 def test_fp32_master_baseline():
     shapes = [("a", 100_003), ("b", 77), ("c", 8192 * 3)]
