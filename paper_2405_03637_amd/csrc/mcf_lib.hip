@@ -1,8 +1,10 @@
 // Kernels, launch tables and the C ABI of the Collage optimizer step for gfx950.
 //
 // Work decomposition.  A tensor is cut into SLOTS of 8 consecutive bf16 (16 bytes per
-// stream) counted from the 16-byte boundary at or below its first element, so that a
-// slot is one 128-bit access per stream whatever the tensor's own alignment; the slots
+// stream) counted from the 128-byte boundary at or below its first element, so that a
+// slot is one 128-bit access per stream whatever the tensor's own alignment and every
+// wave's 1 KiB run covers whole cache lines (counting from the 16-byte boundary instead, waves of
+// neighbouring workgroups share lines: a set of tensors at odd offsets ran at 5.2 instead of 5.8 TB/s); the slots
 // that straddle the ends of the tensor are handled element by element.  A CHUNK is
 // kStepBlock*kUnroll consecutive slots of one tensor, done by one workgroup; lane l takes
 // slots l, l+kStepBlock, ... so each wave's access is one contiguous 1 KiB run per stream.
@@ -55,6 +57,9 @@ using mcfd::StepScalarsT;
 #ifndef MCF_REMAP
 #define MCF_REMAP 0                  // 1: give each XCD (blocks are dealt round-robin to the 8 XCDs) a contiguous run of chunks
 #endif
+#ifndef MCF_CHUNK_ALIGN
+#define MCF_CHUNK_ALIGN 128          // bytes: a tensor's slots are counted from this address boundary below its first element
+#endif
 #ifndef MCF_STEP_ATTR
 #define MCF_STEP_ATTR                // optional extra attribute of the step kernels (e.g. amdgpu_waves_per_eu)
 #endif
@@ -82,7 +87,7 @@ enum { S_TH = 0, S_DTH = 1, S_M = 2, S_V = 3, S_G = 4, S_DV = 5 };
 struct TensorDesc {
   uint64_t p[kMaxStreams];   // element pointers (bf16), as integers
   uint64_t n;                // elements
-  uint32_t phase;            // elements between the 16-byte boundary below p[0] and p[0]: 0..7
+  uint32_t phase;            // elements between the MCF_CHUNK_ALIGN-byte boundary below p[0] and p[0]
   uint32_t scalar_only;      // 1: streams are not mutually aligned, every slot goes element by element
 };
 static_assert(sizeof(TensorDesc) == 64, "descriptor is one 64-byte scalar load");
@@ -743,8 +748,8 @@ inline bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<ui
 
 // Alignment class of a set of bf16 pointers: common phase (elements above a 16-byte boundary)
 // or scalar_only when they disagree.
-inline void phase_of(const uint64_t *ptrs, int count, uint32_t &phase, uint32_t &scalar_only) {
-  phase = (uint32_t)((ptrs[0] & 15) >> 1);
+inline void phase_of(const uint64_t *ptrs, int count, uint32_t &phase, uint32_t &scalar_only, uint64_t boundary = 16) {
+  phase = (uint32_t)((ptrs[0] & (boundary - 1)) >> 1);
   scalar_only = 0;
   for (int i = 1; i < count; ++i)
     if ((ptrs[i] & 15) != (ptrs[0] & 15)) scalar_only = 1;
@@ -785,7 +790,7 @@ void fill_desc(const mcf_tensor &t, int variant, TensorDesc &d) {
   d.p[S_G] = (uint64_t)(uintptr_t)t.grad;
   d.p[S_DV] = variant == MCF_PLUS ? (uint64_t)(uintptr_t)t.dv : d.p[S_V];
   d.n = t.n;
-  phase_of(d.p, 6, d.phase, d.scalar_only);
+  phase_of(d.p, 6, d.phase, d.scalar_only, MCF_CHUNK_ALIGN);
 }
 
 // Scalars of one step for both formats; fast = the bf16 Fast mode may be used with them.
@@ -1207,7 +1212,7 @@ int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tenso
     d.n = t.n;
     // 128-bit path: theta and grad share a phase, and each fp32 buffer is 16-byte aligned at the
     // element that sits on theta's 16-byte boundary
-    const uint32_t ph = (uint32_t)((d.theta & 15) >> 1);
+    const uint32_t ph = (uint32_t)((d.theta & (MCF_CHUNK_ALIGN - 1)) >> 1);
     bool ok = (d.grad & 15) == (d.theta & 15);
     const uint64_t f32s[3] = {d.master, d.m, d.v};
     for (uint64_t f : f32s) ok = ok && (((f - 4ull * ph) & 15) == 0);
