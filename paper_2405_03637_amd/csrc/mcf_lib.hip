@@ -13,14 +13,17 @@
 // tensors of any size is one launch.
 //
 // Launch shape, from sweeps on MI355X at the 7B-parameter set (9 to 11 concurrent streams
-// of 13.5 GB each): one-wave workgroups with one slot per lane, at most 11 of them resident
-// per CU, and non-temporal loads and stores.  Short-lived single-wave groups keep the set of
+// of 13.5 GB each): one-wave workgroups with one slot per lane, about 10 of them resident per CU,
+// and non-temporal loads and stores.  Short-lived single-wave groups keep the set of
 // addresses in flight compact, and capping the waves in flight keeps the HBM channels
 // from thrashing between too many open rows: 256-thread groups with two slots per lane at
 // full occupancy reached 5.5 TB/s, this shape 6.5-6.6 TB/s on the same device in the same run.
-// The cap is set by giving every workgroup 14.5 KiB of dynamic LDS it never touches
-// (160 KiB per CU / 14.5 KiB = 11 groups): unlike a waves-per-SIMD bound it counts per CU and
-// can sit between multiples of four (10/CU: 18.7 ms, 11: 18.4, 12: 18.6, 14: 18.8 for light).
+// The cap is set by giving every workgroup dynamic LDS it never touches: unlike a waves-per-SIMD
+// bound it counts per CU and can sit between multiples of four.  Caps that differ by less than
+// 1280 bytes time identically, so the 160 KiB of a CU appear to be handed out in 128 granules of
+// 1280 bytes; lds_for_groups() below asks for the largest whole number of granules that still lets
+// the wanted number of groups fit (light, 7B set: 8 groups 19.85 ms, 9: 18.76, 10: 18.50, 11: 18.80,
+// 12: 18.98, 14: 19.15, 16: 19.52, no cap: 20.32).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -65,11 +68,14 @@ using mcfd::StepScalarsT;
 #endif
 // MCF_STEP_LDS, if defined, is the bytes of untouched dynamic LDS per workgroup (= the occupancy cap) of
 // every step kernel; by default the cap is per variant, see StepStreams::kLds.
+// Dynamic LDS that lets `groups` workgroups share a CU: 128/groups granules, less 256 bytes of room for a
+// kernel's own static LDS (the EDQ kernels keep 24 bytes).
+constexpr uint32_t lds_for_groups(uint32_t groups) { return (128u / groups) * 1280u - 256u; }
 #ifndef MCF_STEP_LDS_EDQ
-#define MCF_STEP_LDS_EDQ 10752       // with the fused EDQ sums (fp64 arithmetic to hide) 15 groups per CU measure best
+#define MCF_STEP_LDS_EDQ 0           // 0: per variant (StepStreams::kLdsEdq); else bytes for every EDQ-fused step kernel
 #endif
 #ifndef MCF_FP32MW_LDS
-#define MCF_FP32MW_LDS 12544         // 13 groups per CU for the fp32-master baseline kernel (11: 28.90 ms, 13: 28.82, 16: 29.64)
+#define MCF_FP32MW_LDS lds_for_groups(12)   // fp32-master baseline kernel: 10 groups 28.90 ms, 11: 28.84, 12: 28.82, 14: 29.31
 #endif
 #ifndef MCF_COPY_LDS
 #define MCF_COPY_LDS 0               // the plain copy (2 streams) is fastest uncapped: 6.66 TB/s against 4.4 TB/s with the cap
@@ -283,15 +289,17 @@ template <int VARIANT> struct StepStreams {
   static constexpr bool kDth = kBase != mcfd::V_BF16;      // second component of theta / Kahan variable
   static constexpr bool kDv = kBase == mcfd::V_PLUS;       // second component of v
   static constexpr bool kV = kBase != mcfd::V_SGD;         // second moment
-  // Untouched dynamic LDS per workgroup = occupancy cap, from a sweep of 8..32 groups per CU at the
-  // 7B-parameter set: 9-stream kernels (light, Kahan) are fastest at 11 groups per CU, the 11-stream plus
-  // at 12 (23.18 ms against 23.38 at 11), the 7-stream plain variant, whose divide and root have less
-  // memory time to hide behind, at 13 (14.24 ms against 15.09), the 7-stream SGD at 11-12.
+  // Occupancy cap in workgroups per CU, from sweeps of 8..32 at the 7B-parameter set: the 9-stream
+  // kernels (light, Kahan) are fastest at 10, the 11-stream plus at 11 (23.18 ms against 23.38 at 10), the
+  // 7-stream plain variant, whose divide and root have less memory time to hide behind, at 12 (14.24 ms
+  // against 15.09 at 10), the 7-stream SGD at 10-11.  With the fp64 EDQ sums fused in there is more
+  // arithmetic to hide: 14 (light 18.62 ms against 20.43 at 10), plain variant 16.
 #ifdef MCF_STEP_LDS
   static constexpr uint32_t kLds = MCF_STEP_LDS;
 #else
-  static constexpr uint32_t kLds = kBase == mcfd::V_BF16 ? 12544 : kBase == mcfd::V_PLUS ? 13568 : 14848;
+  static constexpr uint32_t kLds = lds_for_groups(kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? 11 : 10);
 #endif
+  static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : lds_for_groups(kBase == mcfd::V_BF16 ? 16 : 14);
 };
 
 // Hot path: one full slot, 8 elements of every stream held as 4 dwords each.  Returns true
@@ -809,13 +817,13 @@ void launch_step(bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *de
   const dim3 g(blocks), b(kStepBlock);
 #endif
   if constexpr ((VARIANT & kHalfBit) != 0) {
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, hs.hf, partials, blocks);
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, StepStreams<VARIANT>::kLdsEdq, st, descs, chunks, flat, hs.hf, partials, blocks);
     else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, StepStreams<VARIANT>::kLds, st, descs, chunks, flat, hs.hf, partials, blocks);
   } else if (hs.fast) {
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, hs.bf, partials, blocks);
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, StepStreams<VARIANT>::kLdsEdq, st, descs, chunks, flat, hs.bf, partials, blocks);
     else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, StepStreams<VARIANT>::kLds, st, descs, chunks, flat, hs.bf, partials, blocks);
   } else {
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, MCF_STEP_LDS_EDQ, st, descs, chunks, flat, hs.bf, partials, blocks);
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, StepStreams<VARIANT>::kLdsEdq, st, descs, chunks, flat, hs.bf, partials, blocks);
     else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, StepStreams<VARIANT>::kLds, st, descs, chunks, flat, hs.bf, partials, blocks);
   }
 }
