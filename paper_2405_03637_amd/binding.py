@@ -166,6 +166,7 @@ class Plan:
         if self._h:
             _check(lib().mcf_plan_destroy(self._h), "mcf_plan_destroy")
             self._h = _vp()
+            self._keep = None
 
     def __del__(self):
         try:
@@ -193,6 +194,7 @@ class Fp32MwPlan:
         if self._h:
             _check(lib().mcf_fp32mw_plan_destroy(self._h), "mcf_fp32mw_plan_destroy")
             self._h = _vp()
+            self._keep = None
 
     def __del__(self):
         try:

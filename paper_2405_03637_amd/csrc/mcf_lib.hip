@@ -1,6 +1,6 @@
 // Kernels, launch tables and the C ABI of the Collage optimizer step for gfx950.
 //
-// Work decomposition.  A tensor is cut into SLOTS of 8 consecutive bf16 (16 bytes per
+// Work decomposition.  A tensor is cut into SLOTS of 8 consecutive 16-bit elements (bf16 or fp16; 16 bytes per
 // stream) counted from the 128-byte boundary at or below its first element, so that a
 // slot is one 128-bit access per stream whatever the tensor's own alignment and every
 // wave's 1 KiB run covers whole cache lines (counting from the 16-byte boundary instead, waves of
@@ -91,7 +91,7 @@ constexpr int kMaxStreams = 6;
 enum { S_TH = 0, S_DTH = 1, S_M = 2, S_V = 3, S_G = 4, S_DV = 5 };
 
 struct TensorDesc {
-  uint64_t p[kMaxStreams];   // element pointers (bf16), as integers
+  uint64_t p[kMaxStreams];   // element pointers (16-bit elements), as integers
   uint64_t n;                // elements
   uint32_t phase;            // elements between the MCF_CHUNK_ALIGN-byte boundary below p[0] and p[0]
   uint32_t scalar_only;      // 1: streams are not mutually aligned, every slot goes element by element
@@ -117,7 +117,7 @@ __device__ __forceinline__ Slot classify(const TensorDesc &d, uint64_t slot) {
   return s;
 }
 
-// 128-bit access to elements [e0, e0+8) of the bf16 buffer at p.
+// 128-bit access to elements [e0, e0+8) of the 16-bit buffer at p.
 // The pointers are device-memory addresses, so the accesses are typed as global (address
 // space 1): global_load/global_store instead of the generic flat instructions.
 #define MCF_GLOBAL __attribute__((address_space(1)))
@@ -157,7 +157,7 @@ __device__ __forceinline__ void store_f4(MCF_GLOBAL float *p, f32x4_t q) {
 #endif
 }
 
-// Load the slot of stream `p` as 4 dwords (two bf16 each); elements outside the tensor read as 0.
+// Load the slot of stream `p` as 4 dwords (two elements each); elements outside the tensor read as 0.
 __device__ __forceinline__ void load_slot(uint64_t p, const TensorDesc &d, const Slot &s, uint32_t (&w)[4]) {
   const MCF_GLOBAL uint16_t *base = gptr<const uint16_t>(p);
   if (s.full) {
@@ -754,7 +754,7 @@ fp32mw_kernel(const Fp32Desc *__restrict__ descs, const Chunk *__restrict__ chun
 
 inline bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
-// Alignment class of a set of bf16 pointers: common phase (elements above a 16-byte boundary)
+// Alignment class of a set of 16-bit-element pointers: common phase (elements above the boundary)
 // or scalar_only when they disagree.
 inline void phase_of(const uint64_t *ptrs, int count, uint32_t &phase, uint32_t &scalar_only, uint64_t boundary = 16) {
   phase = (uint32_t)((ptrs[0] & (boundary - 1)) >> 1);
