@@ -337,7 +337,7 @@ __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], u
 
 // Cold path: one slot element by element in the variant's element mode (bf16: Exact), as a rolled loop so that it costs code
 // size once.  Serves the slots that straddle a tensor's ends, tensors whose buffers are not
-// mutually aligned, and slots the hot path asked to redo (their inputs are still in memory:
+// mutually aligned, and (bf16) slots the hot path asked to redo (their inputs are still in memory:
 // nothing of the slot has been stored yet).
 template <int VARIANT, bool EDQ>
 __device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, const typename StepStreams<VARIANT>::Scalars &sc,
@@ -428,7 +428,22 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
     if (slot[j].full) {
       uint32_t out[kMaxStreams][4];
       EdqAcc local = {0.0, 0.0, 0u};
-      if (hot_slot<Mode, VARIANT, EDQ>(in[j], out, sc, local)) {
+      bool redo = hot_slot<Mode, VARIANT, EDQ>(in[j], out, sc, local);
+      if constexpr (SS::kHalf) {
+        // fp16: the first pass found a NaN among its results.  The same slot again, still from registers,
+        // in the mode that stores the format's one NaN: the arithmetic is the same packed code, so a
+        // diverged tensor costs 18% more time, not a serial loop (21.8 against 65.5 ms for an all-NaN 7B set).
+        if (redo) {
+          local = {0.0, 0.0, 0u};
+          (void)hot_slot<typename SS::Cold, VARIANT, EDQ>(in[j], out, sc, local);
+          redo = false;
+        }
+      }
+      // bf16: a slot that met a subnormal intermediate or a NaN in Fast mode goes to the element loop
+      // below.  Redoing it from registers with the vectorised Exact arithmetic was measured: an all-redo
+      // 7B set drops from 59.5 to 46.2 ms, but the Exact chain's registers and code slow the ordinary
+      // path of several variants by 1-5%, so the rare case keeps the loop.
+      if (redo) {
         cold |= 1u << j;
       } else {
         const uint64_t e0 = slot[j].c0 - d.phase;
@@ -548,13 +563,8 @@ __device__ __forceinline__ void prim_words(const uint32_t (&in)[kMaxStreams][4],
       if (valid & (1u << (2 * k + 1))) edq_add(acc, M::hi(a), M::hi(b), M::hi(d0), M::hi(th1), M::hi(d1));
     }
     if (M::kFast && OP != P_EDQ) redo |= M::any_nan(x) | M::any_nan(y);
-    if constexpr (M::kHalf && !M::kFast) {      // the element mode of fp16 stores the format's one NaN
-      out[0][k] = (uint32_t)M::bits_lo(x) | ((uint32_t)M::bits_hi(x) << 16);
-      out[1][k] = (uint32_t)M::bits_lo(y) | ((uint32_t)M::bits_hi(y) << 16);
-    } else {
-      out[0][k] = M::pack(x);
-      out[1][k] = M::pack(y);
-    }
+    out[0][k] = M::pack(x);
+    out[1][k] = M::pack(y);
   }
 }
 

@@ -140,8 +140,9 @@ using Fast = Bf<FastR>;
 // infinite operands make the residual NaN, and a zero dividend loses its sign in the correction; in
 // both cases q is already the IEEE result and is kept.
 // NaN: the hardware propagates payloads, the stored format has one NaN (0x7E00).  NaN-ness itself
-// propagates the same way in both, so only stored values need fixing: the vector path (kFast) just
-// detects a NaN in its results and hands the slot to the element path, which stores the one NaN.
+// propagates the same way in both, so only stored values need fixing: the first pass over a slot
+// (kFast) just detects a NaN in its results; the slot is then redone in the mode that replaces every
+// NaN it stores by the one NaN.
 typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
 
 // Keeps the optimizer from folding widen / fp32 op / narrow into an fp16 operation of its own choice.
@@ -153,15 +154,21 @@ template <bool HOT> struct Hf {
   static constexpr bool kFast = HOT;
   static constexpr bool kHalf = true;
   static __device__ __forceinline__ T unpack(uint32_t w) { return __builtin_bit_cast(h2_t, w); }
-  static __device__ __forceinline__ uint32_t pack(T x) { return __builtin_bit_cast(uint32_t, x); }
+  static __device__ __forceinline__ uint32_t raw(T x) { return __builtin_bit_cast(uint32_t, x); }
+  // What is stored: the raw pair on the vector path (which has checked that it holds no NaN), the pair
+  // with every NaN replaced by the format's one NaN otherwise.
+  static __device__ __forceinline__ uint32_t pack(T x) {
+    if (HOT) return raw(x);
+    return (uint32_t)canon(raw(x) & 0xffffu) | ((uint32_t)canon(raw(x) >> 16) << 16);
+  }
   static __device__ __forceinline__ T zero() { return h2_t{(_Float16)0, (_Float16)0}; }
   static __device__ __forceinline__ float lo(T x) { return (float)x.x; }
   static __device__ __forceinline__ float hi(T x) { return (float)x.y; }
   static __device__ __forceinline__ uint16_t canon(uint32_t h) { return (h & 0x7fffu) > 0x7c00u ? (uint16_t)0x7e00 : (uint16_t)h; }
-  static __device__ __forceinline__ uint16_t bits_lo(T x) { return canon(pack(x) & 0xffffu); }
-  static __device__ __forceinline__ uint16_t bits_hi(T x) { return canon(pack(x) >> 16); }
+  static __device__ __forceinline__ uint16_t bits_lo(T x) { return canon(raw(x) & 0xffffu); }
+  static __device__ __forceinline__ uint16_t bits_hi(T x) { return canon(raw(x) >> 16); }
   // a half is NaN iff its magnitude bits exceed 0x7C00; +0x03FF carries exactly those into bit 15
-  static __device__ __forceinline__ bool any_nan(T x) { return (((pack(x) & 0x7fff7fffu) + 0x03ff03ffu) & 0x80008000u) != 0; }
+  static __device__ __forceinline__ bool any_nan(T x) { return (((raw(x) & 0x7fff7fffu) + 0x03ff03ffu) & 0x80008000u) != 0; }
   static __device__ __forceinline__ T round_f32(float a, float b) { return h2_t{(_Float16)a, (_Float16)b}; }
 
   static __device__ __forceinline__ T add(T a, T b) { return a + b; }
