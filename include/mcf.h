@@ -123,6 +123,16 @@ uint64_t mcf_plan_params(const mcf_plan *plan);
  * not change (lost arithmetic, Def. 3.2; LOST/n is the imprecision percentage of Sec. 5.1). */
 int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *stream, double *edq_dev);
 
+/* The ten scalars a step derives from the hyper-parameters (Alg. 2 line 1, Table 2, App. D
+ * "Scalar and Bias Correction"), as 16-bit patterns of the component format, written to the host
+ * array out[10] in this order: beta1, 1-beta1, beta2 (first component of its expansion), the
+ * second component beta2 - first, 1-beta2, 1-beta1^step, 1-beta2^step, eps, weight_decay, -lr.
+ * Each is computed in fp64 and cast once.  Host-only: no GPU is touched.  restricted_mode_ok (may be
+ * NULL) receives 1 when the step kernels may use their reciprocal-based arithmetic for these scalars
+ * and 0 when they will use the IEEE sequences (bf16 only: bias corrections below 2^-60, or a non-zero
+ * epsilon outside [2^-100, 2^60]); the results are the same bits either way. */
+int mcf_step_scalars(int component, const mcf_hyper *hyper, uint64_t step, uint16_t *out, int *restricted_mode_ok);
+
 /* The same step over a single flat tensor, no plan, no allocation.  n == 0 is a no-op. */
 int mcf_adamw_step_flat(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t *v, uint16_t *dv,
                         const uint16_t *grad, uint64_t n, int variant, const mcf_hyper *hyper,

@@ -68,6 +68,7 @@ def lib():
     L.mcf_plan_params.restype = _u64
     L.mcf_plan_params.argtypes = [_vp]
     L.mcf_adamw_step.argtypes = [_vp, ctypes.POINTER(Hyper), _u64, _vp, _vp]
+    L.mcf_step_scalars.argtypes = [_int, ctypes.POINTER(Hyper), _u64, ctypes.POINTER(ctypes.c_uint16), ctypes.POINTER(_int)]
     L.mcf_adamw_step_flat.argtypes = [_vp] * 6 + [_u64, _int, ctypes.POINTER(Hyper), _u64, _vp]
     L.mcf_fast2sum.argtypes = [_vp] * 4 + [_u64, _vp]
     L.mcf_two_sum.argtypes = [_vp] * 4 + [_u64, _vp]
@@ -203,6 +204,18 @@ class Fp32MwPlan:
             pass
 
 
+SCALAR_NAMES = ("b1", "c1", "b2", "b2l", "c2", "bc1", "bc2", "e", "lam", "na")
+
+
+def step_scalars(component, hyper, t):
+    """The step's ten scalars as 16-bit patterns ({name: int}) and whether the reciprocal-based arithmetic applies."""
+    h = _hyper(hyper)
+    out = (ctypes.c_uint16 * 10)()
+    ok = _int(0)
+    _check(lib().mcf_step_scalars(int(component), ctypes.byref(h), int(t), out, ctypes.byref(ok)), "mcf_step_scalars")
+    return dict(zip(SCALAR_NAMES, (int(x) for x in out))), bool(ok.value)
+
+
 def adamw_step_flat(theta, dtheta, m, v, dv, grad, variant, hyper, t, stream=None, n=None):
     h = _hyper(hyper)
     n = theta.numel() if n is None else n
@@ -299,6 +312,7 @@ def mcf_adamw_step(plan, hyper, step, stream=None, edq_dev=None):
 
 
 mcf_adamw_step_flat = adamw_step_flat
+mcf_step_scalars = step_scalars
 mcf_fast2sum = fast2sum
 mcf_two_sum = two_sum
 mcf_grow = grow

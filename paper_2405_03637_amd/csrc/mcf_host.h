@@ -95,30 +95,51 @@ inline int check_hyper(const mcf_hyper *h, uint64_t step) {
   return MCF_OK;
 }
 
+// The ten scalars of one step as 16-bit patterns of the component format, in the order of
+// mcf_step_scalars(): beta1, 1-beta1, beta2 (first component), beta2's second component, 1-beta2,
+// 1-beta1^t, 1-beta2^t, eps, lambda, -alpha.  Each is computed in fp64 and cast once.
+enum { K_B1, K_C1, K_B2, K_B2L, K_C2, K_BC1, K_BC2, K_EPS, K_LAM, K_NA, K_COUNT };
+struct ScalarBits { uint16_t v[K_COUNT]; };
+
+template <uint16_t (*TO16)(double), double (*TO64)(uint16_t)>
+inline ScalarBits derive_bits(const mcf_hyper &h, uint64_t step) {
+  const double t = (double)step;
+  ScalarBits s;
+  s.v[K_B1] = TO16(h.beta1);
+  s.v[K_C1] = TO16(1.0 - h.beta1);
+  s.v[K_B2] = TO16(h.beta2);
+  s.v[K_B2L] = TO16(h.beta2 - TO64(s.v[K_B2]));
+  s.v[K_C2] = TO16(1.0 - h.beta2);
+  s.v[K_BC1] = TO16(1.0 - std::pow(h.beta1, t));
+  s.v[K_BC2] = TO16(1.0 - std::pow(h.beta2, t));
+  s.v[K_EPS] = TO16(h.eps);
+  s.v[K_LAM] = TO16(h.weight_decay);
+  s.v[K_NA] = TO16(-h.lr);
+  return s;
+}
+
+inline double bf16_to_f64(uint16_t h) { return (double)bf16_to_f32(h); }
+inline ScalarBits scalar_bits_bf16(const mcf_hyper &h, uint64_t step) { return derive_bits<f64_to_bf16, bf16_to_f64>(h, step); }
+inline ScalarBits scalar_bits_fp16(const mcf_hyper &h, uint64_t step) { return derive_bits<f64_to_f16, f16_to_f64>(h, step); }
+
 // Returns the scalars and whether the Fast arithmetic mode may be used with them: the two
 // bias corrections must be normal numbers in (0, 1] (so that dividing by them cannot shrink
 // a normal number into the subnormal range) and epsilon zero or a normal number of sane
 // size (so that sqrt(v)+eps is zero, or normal with a normal reciprocal).
 inline bool derive_scalars(const mcf_hyper &h, uint64_t step, mcfd::StepScalars &s) {
-  const double t = (double)step;
-  const uint16_t b1 = f64_to_bf16(h.beta1), c1 = f64_to_bf16(1.0 - h.beta1);
-  const uint16_t b2 = f64_to_bf16(h.beta2), c2 = f64_to_bf16(1.0 - h.beta2);
-  const uint16_t b2l = f64_to_bf16(h.beta2 - (double)bf16_to_f32(b2));
-  const uint16_t bc1 = f64_to_bf16(1.0 - std::pow(h.beta1, t));
-  const uint16_t bc2 = f64_to_bf16(1.0 - std::pow(h.beta2, t));
-  const uint16_t e = f64_to_bf16(h.eps), lam = f64_to_bf16(h.weight_decay), na = f64_to_bf16(-h.lr);
-  s.b1 = bf16_to_f32(b1);
-  s.c1 = bf16_to_f32(c1);
-  s.b2 = bf16_to_f32(b2);
-  s.b2l = bf16_to_f32(b2l);
-  s.c2 = bf16_to_f32(c2);
-  s.bc1 = bf16_to_f32(bc1);
-  s.bc2 = bf16_to_f32(bc2);
+  const ScalarBits b = scalar_bits_bf16(h, step);
+  s.b1 = bf16_to_f32(b.v[K_B1]);
+  s.c1 = bf16_to_f32(b.v[K_C1]);
+  s.b2 = bf16_to_f32(b.v[K_B2]);
+  s.b2l = bf16_to_f32(b.v[K_B2L]);
+  s.c2 = bf16_to_f32(b.v[K_C2]);
+  s.bc1 = bf16_to_f32(b.v[K_BC1]);
+  s.bc2 = bf16_to_f32(b.v[K_BC2]);
   s.rbc1 = (float)(1.0 / (double)s.bc1);
   s.rbc2 = (float)(1.0 / (double)s.bc2);
-  s.e = bf16_to_f32(e);
-  s.lam = bf16_to_f32(lam);
-  s.na = bf16_to_f32(na);
+  s.e = bf16_to_f32(b.v[K_EPS]);
+  s.lam = bf16_to_f32(b.v[K_LAM]);
+  s.na = bf16_to_f32(b.v[K_NA]);
   auto sane_bc = [](float x) { return x >= 0x1p-60f && x <= 1.0f; };
   const bool eps_ok = (s.e == 0.0f) || (s.e >= 0x1p-100f && s.e <= 0x1p60f);
   return sane_bc(s.bc1) && sane_bc(s.bc2) && eps_ok;
@@ -127,21 +148,20 @@ inline bool derive_scalars(const mcf_hyper &h, uint64_t step, mcfd::StepScalars 
 // The same scalars as fp16 patterns, each copied into both halves of a packed register.  The fp16
 // arithmetic has no restricted mode, so there is nothing to report.
 inline void derive_scalars_fp16(const mcf_hyper &h, uint64_t step, mcfd::StepScalarsH &s) {
-  const double t = (double)step;
-  auto splat = [](uint16_t b) { return __builtin_bit_cast(mcfd::h2_t, (uint32_t)b * 0x00010001u); };
-  const uint16_t b2 = f64_to_f16(h.beta2);
-  s.b1 = splat(f64_to_f16(h.beta1));
-  s.c1 = splat(f64_to_f16(1.0 - h.beta1));
-  s.b2 = splat(b2);
-  s.b2l = splat(f64_to_f16(h.beta2 - f16_to_f64(b2)));
-  s.c2 = splat(f64_to_f16(1.0 - h.beta2));
-  s.bc1 = splat(f64_to_f16(1.0 - std::pow(h.beta1, t)));
-  s.bc2 = splat(f64_to_f16(1.0 - std::pow(h.beta2, t)));
+  const ScalarBits b = scalar_bits_fp16(h, step);
+  auto splat = [](uint16_t x) { return __builtin_bit_cast(mcfd::h2_t, (uint32_t)x * 0x00010001u); };
+  s.b1 = splat(b.v[K_B1]);
+  s.c1 = splat(b.v[K_C1]);
+  s.b2 = splat(b.v[K_B2]);
+  s.b2l = splat(b.v[K_B2L]);
+  s.c2 = splat(b.v[K_C2]);
+  s.bc1 = splat(b.v[K_BC1]);
+  s.bc2 = splat(b.v[K_BC2]);
   s.rbc1 = s.bc1;            // unused by the fp16 arithmetic
   s.rbc2 = s.bc2;
-  s.e = splat(f64_to_f16(h.eps));
-  s.lam = splat(f64_to_f16(h.weight_decay));
-  s.na = splat(f64_to_f16(-h.lr));
+  s.e = splat(b.v[K_EPS]);
+  s.lam = splat(b.v[K_LAM]);
+  s.na = splat(b.v[K_NA]);
 }
 
 }  // namespace mcfh

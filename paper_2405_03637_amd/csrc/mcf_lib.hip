@@ -1051,6 +1051,20 @@ int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *
   return MCF_OK;
 }
 
+int mcf_step_scalars(int component, const mcf_hyper *hyper, uint64_t step, uint16_t *out, int *restricted_mode_ok) {
+  if (!known_component(component)) return MCF_ERR_VARIANT;
+  if (!out) return MCF_ERR_NULL;
+  const int rc = mcfh::check_hyper(hyper, step);
+  if (rc != MCF_OK) return rc;
+  const mcfh::ScalarBits b = component == MCF_COMPONENT_FP16 ? mcfh::scalar_bits_fp16(*hyper, step) : mcfh::scalar_bits_bf16(*hyper, step);
+  for (int i = 0; i < mcfh::K_COUNT; ++i) out[i] = b.v[i];
+  if (restricted_mode_ok) {
+    StepScalars unused;
+    *restricted_mode_ok = component == MCF_COMPONENT_FP16 ? 1 : (mcfh::derive_scalars(*hyper, step, unused) && !force_exact()) ? 1 : 0;
+  }
+  return MCF_OK;
+}
+
 int mcf_adamw_step_flat(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t *v, uint16_t *dv,
                         const uint16_t *grad, uint64_t n, int variant, const mcf_hyper *hyper,
                         uint64_t step, void *stream) {

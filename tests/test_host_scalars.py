@@ -1,0 +1,106 @@
+"""Host logic of the GPU library without a GPU: the scalars the step derives from the hyper-parameters
+(mcf_step_scalars), checked against the paper's printed beta2 expansions (Table 2), against exact
+rational rounding, and against the oracle's scalars for both component formats."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import helpers as H
+from paper_2405_03637_amd import binding as mcf
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_values.txt")
+BF, HF = mcf.COMPONENT_BF16, mcf.COMPONENT_FP16
+
+
+def _scal(component, hyper, t):
+    return mcf.step_scalars(component, hyper, t)[0]
+
+
+def _bf(bits):
+    return float(H.u16_to_f64(np.array([bits], np.uint16))[0])
+
+
+def test_beta2_expansions_printed_in_the_paper():
+    """Table 2: the two-component bf16 expansion of beta2, to the printed digits."""
+    rows = [r for r in H.read_golden(GOLDEN) if r[0] == "expand"]
+    assert len(rows) == 3
+    for _, beta, expected, _where in rows:
+        first, second = (float(x) for x in expected.split())
+        s = _scal(BF, (1e-3, 0.9, float(beta), 1e-8, 0.1), 1)
+        assert abs(_bf(s["b2"]) - first) < 5e-5 + 1e-12, beta
+        assert abs(_bf(s["b2l"]) - second) < 5e-5 + 1e-12, beta
+        assert abs(_bf(s["b2"]) + _bf(s["b2l"]) - float(beta)) < 2.0 ** -14          # two components: about 16 bits
+
+
+def test_rounding_of_the_host_conversions_bf16():
+    """weight_decay passes any finite non-negative double through the fp64 -> bf16 cast, lr its negative."""
+    rng = np.random.default_rng(5)
+    xs = np.abs(rng.standard_normal(3000)) * 10.0 ** rng.integers(-45, 39, 3000)
+    pos = H.all_finite_bf16()[: H.BF16_MAX_BITS + 1]
+    ties = []
+    for h in list(range(0, 300)) + list(rng.integers(300, H.BF16_MAX_BITS, 700)):
+        a, b = H.bf16_bits_to_fraction(int(h)), H.bf16_bits_to_fraction(int(h) + 1)
+        mid = float((a + b) / 2)                       # exact in fp64
+        ties += [mid, np.nextafter(mid, np.inf), np.nextafter(mid, 0.0)]
+    xs = np.concatenate([xs, ties, [0.0, 5e-324, 1e-320, 2.0 ** -134, 2.0 ** -133, 3.3895e38, 3.3961e38, 3.4e38, 1e39, 1e300]])
+    want = H.np_round_f64_to_bf16(xs)
+    for x, w in zip(xs, want):
+        s = _scal(BF, (float(x), 0.9, 0.95, 1e-8, float(x)), 1)
+        assert s["lam"] == int(w), (x, hex(s["lam"]), hex(int(w)))
+        assert s["na"] == (int(w) | 0x8000), x
+    for x in xs[:400]:
+        assert _scal(BF, (0.0, 0.9, 0.95, 1e-8, float(x)), 1)["lam"] == H.nearest_bf16(Fraction(float(x)))
+    assert len(pos) == H.BF16_MAX_BITS + 1
+
+
+def test_rounding_of_the_host_conversions_fp16():
+    rng = np.random.default_rng(6)
+    xs = np.abs(rng.standard_normal(3000)) * 10.0 ** rng.integers(-10, 6, 3000)
+    every = np.arange(0x7C00, dtype=np.uint16).view(np.float16).astype(np.float64)
+    mids = (every[:-1] + every[1:]) / 2
+    pick = np.concatenate([np.arange(0, 200), rng.integers(200, mids.size, 800)])
+    ties = np.concatenate([mids[pick], np.nextafter(mids[pick], np.inf), np.nextafter(mids[pick], 0.0)])
+    xs = np.concatenate([xs, ties, [0.0, 2.0 ** -26, 2.0 ** -25, 2.0 ** -24, 65504.0, 65519.99, 65520.0, 1e9]])
+    with np.errstate(over="ignore"):
+        want = xs.astype(np.float16).view(np.uint16)          # numpy casts fp64 -> fp16 in one rounding
+    for x, w in zip(xs, want):
+        s = _scal(HF, (float(x), 0.9, 0.95, 1e-8, float(x)), 1)
+        assert s["lam"] == int(w), (x, hex(s["lam"]), hex(int(w)))
+        assert s["na"] == (int(w) | 0x8000), x
+
+
+@pytest.mark.parametrize("component", [BF, HF])
+def test_scalars_equal_the_oracles(orc, component):
+    fmt = orc.FMT_FP16 if component == HF else orc.FMT_BF16
+    betas = [0.0, 0.5, 0.9, 0.95, 0.98, 0.99, 0.999, 0.99999, 1.0 - 1e-10]
+    for b1 in betas:
+        for b2 in betas:
+            for t in (1, 2, 7, 100, 12345, 10 ** 9):
+                for lr, eps, wd in ((3e-4, 1e-8, 0.1), (1.2e-4, 1e-6, 0.0), (1.0, 0.0, 1e-3)):
+                    got = _scal(component, (lr, b1, b2, eps, wd), t)
+                    want = orc.scalars(lr, b1, b2, eps, wd, t, fmt=fmt)
+                    assert got == want, (component, lr, b1, b2, eps, wd, t, got, want)
+
+
+def test_restricted_mode_report_and_errors():
+    ok = lambda hyper, t=1, c=BF: mcf.step_scalars(c, hyper, t)[1]
+    assert ok((3e-4, 0.9, 0.95, 1e-8, 0.1))
+    assert ok((3e-4, 0.9, 0.95, 0.0, 0.1))
+    assert not ok((3e-4, 0.9, 0.95, 1e-40, 0.1))                 # epsilon is a bf16 subnormal
+    assert not ok((3e-4, 0.9, 0.95, 1e30, 0.1))                  # epsilon beyond 2^60
+    assert ok((3e-4, 0.0, 0.0, 1e-8, 0.1))                       # beta = 0: bias corrections are 1
+    assert ok((3e-4, 1.0 - 2.0 ** -53, 0.95, 1e-8, 0.1))         # the smallest 1 - beta an fp64 beta < 1 allows is still sane
+    assert ok((3e-4, 0.9, 0.95, 1e-40, 0.1), c=HF)               # fp16 arithmetic has no restricted mode
+    import ctypes
+    lib = mcf.lib()
+    out = (ctypes.c_uint16 * 10)()
+    h = mcf.Hyper(1e-3, 0.9, 0.95, 1e-8, 0.1)
+    assert lib.mcf_step_scalars(2, ctypes.byref(h), 1, out, None) == mcf.MCF_ERR_VARIANT
+    assert lib.mcf_step_scalars(0, None, 1, out, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_step_scalars(0, ctypes.byref(h), 1, None, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_step_scalars(0, ctypes.byref(h), 0, out, None) == mcf.MCF_ERR_STEP
+    bad = mcf.Hyper(1e-3, 1.0, 0.95, 1e-8, 0.1)
+    assert lib.mcf_step_scalars(1, ctypes.byref(bad), 1, out, None) == mcf.MCF_ERR_HYPER
+    assert lib.mcf_step_scalars(0, ctypes.byref(h), 1, out, None) == mcf.MCF_OK
