@@ -168,6 +168,20 @@ def test_fp32mw_argument_errors():
     assert lib.mcf_fp32mw_plan_destroy(h) == mcf.MCF_OK
 
 
+def test_header_is_plain_c(tmp_path):
+    """include/mcf.h must be usable from C (no C++ in the interface)."""
+    import shutil
+    import subprocess
+    if not shutil.which("gcc"):
+        pytest.skip("no gcc")
+    src = tmp_path / "use_mcf.c"
+    src.write_text('#include "mcf.h"\nint main(void) { mcf_hyper h = {1e-3, 0.9, 0.95, 1e-8, 0.1}; (void)h; '
+                   'return mcf_status_string(MCF_OK) == 0 || MCF_FMT_FP16 != 0x1000 || MCF_PRIM_MUL != 6; }\n')
+    r = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", os.path.join(ROOT, "include"), str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_binding_has_every_c_name():
     for n in _declared():
         assert hasattr(mcf, n), n
