@@ -84,6 +84,54 @@ struct Fp16 {
   static uint16_t B(double x) { return round_f64_to_16bit<10, -14>(x); }
 };
 
+/* FP8 E5M2 (App. A Table 7: 5 exponent bits, 2 stored significand bits): an IEEE-style format, the
+ * upper byte of a binary16 pattern, with infinities and NaN.  Patterns travel in the low byte of a
+ * uint16_t.  Overflow rounds to infinity; every NaN is stored as 0x7E. */
+struct Fp8E5M2 {
+  static float W(uint16_t h) { return Fp16::W((uint16_t)((h & 0xff) << 8)); }
+  static uint16_t fold(uint16_t r) { return (uint16_t)((r & 0x7f) | ((r & 0x8000) >> 8)); }   /* sign from bit 15 to bit 7 */
+  static uint16_t R(float f) { return fold(round_f64_to_16bit<2, -14>((double)f)); }
+  static uint16_t B(double x) { return fold(round_f64_to_16bit<2, -14>(x)); }
+};
+
+/* FP8 E4M3 (Table 7: 4 exponent bits, 3 stored significand bits) in the form the 8-bit formats are
+ * deployed in (and the paper's FP8 reference uses): bias 7, NO infinities, the all-ones exponent holds
+ * ordinary numbers up to 448 = 0x7E, and only the pattern with all exponent and significand bits set
+ * (0x7F, 0xFF) is NaN.  The paper gives no overflow rule; the reading here is the format's non-saturating
+ * conversion: whatever rounds beyond 448 (infinities included) becomes NaN.  Every NaN is stored as 0x7F. */
+struct Fp8E4M3 {
+  static float W(uint16_t h) {
+    const int e = (h >> 3) & 0xf, m = h & 7;
+    float mag;
+    if (e == 15 && m == 7) mag = std::numeric_limits<float>::quiet_NaN();
+    else if (e == 0) mag = std::ldexp((float)m, -9);                  /* subnormal: m * 2^-9 */
+    else mag = std::ldexp((float)(8 + m), e - 10);                    /* (1 + m/8) * 2^(e-7) */
+    return (h & 0x80) ? -mag : mag;
+  }
+  static uint16_t B(double x) {
+    if (std::isnan(x)) return 0x7f;
+    const uint16_t sign = std::signbit(x) ? 0x80 : 0;
+    const double a = std::fabs(x);
+    if (a == 0.0) return sign;
+    if (std::isinf(a)) return 0x7f;
+    int e;
+    (void)std::frexp(a, &e);
+    e -= 1;                                    /* 2^e <= a < 2^(e+1) */
+    const int emax = e < -6 ? -6 : e;
+    const int qe = emax - 3;                   /* spacing 2^qe */
+    const double sc = std::ldexp(a, -qe);      /* exact */
+    const double fl = std::floor(sc);
+    const double rem = sc - fl;
+    uint32_t k = (uint32_t)(fl > 64.0 ? 64.0 : fl);      /* anything this large is far out of range anyway */
+    if (fl <= 64.0 && (rem > 0.5 || (rem == 0.5 && (k & 1u)))) k += 1;
+    if (e > 8) return 0x7f;                    /* 512 and above */
+    uint32_t bits = e >= -6 ? ((uint32_t)(e + 7) << 3) + (k - 8) : k;      /* a carry moves into the exponent */
+    if (bits >= 0x7f) return 0x7f;             /* beyond 448: no infinity to round to */
+    return (uint16_t)(sign | bits);
+  }
+  static uint16_t R(float f) { return B((double)f); }
+};
+
 struct Pair { uint16_t hi, lo; };
 
 /* Everything the method computes, for one 16-bit component format Fm. */
@@ -321,10 +369,12 @@ int g_array_threads = 1;
 }  // namespace
 
 /* Run `body` with Chain<Bf16> or Chain<Fp16> bound to the name C. */
-#define ORC_WITH_FORMAT(fmt, ...)                                                         \
-  do {                                                                                    \
-    if ((fmt) == ORC_FP16) { using C = Chain<Fp16>; using Fm = Fp16; __VA_ARGS__; }       \
-    else { using C = Chain<Bf16>; using Fm = Bf16; __VA_ARGS__; }                         \
+#define ORC_WITH_FORMAT(fmt, ...)                                                               \
+  do {                                                                                          \
+    if ((fmt) == ORC_FP16) { using C = Chain<Fp16>; using Fm = Fp16; __VA_ARGS__; }             \
+    else if ((fmt) == ORC_FP8_E5M2) { using C = Chain<Fp8E5M2>; using Fm = Fp8E5M2; __VA_ARGS__; } \
+    else if ((fmt) == ORC_FP8_E4M3) { using C = Chain<Fp8E4M3>; using Fm = Fp8E4M3; __VA_ARGS__; } \
+    else { using C = Chain<Bf16>; using Fm = Bf16; __VA_ARGS__; }                               \
   } while (0)
 
 extern "C" {
@@ -414,7 +464,7 @@ void orc_scalars_derive(const orc_hyper *h, uint64_t t, orc_scalars *out) { orc_
 void orc_adamw_step(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t *v, uint16_t *dv,
                     const uint16_t *grad, uint64_t n, int variant, const orc_hyper *h, uint64_t t,
                     uint16_t *delta_out, int nthreads) {
-  const int fmt = (variant & ORC_FMT_FP16) ? ORC_FP16 : 0;
+  const int fmt = (variant >> 12) & 3;          /* ORC_FMT_* flags carry the format id in bits 12-13 */
   ORC_WITH_FORMAT(fmt, {
     (void)sizeof(Fm);
     orc_scalars s;

@@ -18,7 +18,10 @@
  *               fp16 beside bf16 (Sec. 1, App. A Table 7).  Functions ending in _fmt take a format
  *               id (ORC_BF16 = 0, ORC_FP16 = 1: IEEE binary16 in a uint16_t) and do the same
  *               steps with W, R and B of that format; the step takes ORC_FMT_FP16 OR-ed onto its
- *               variant.  The names without _fmt are the bf16 ones.
+ *               variant.  The names without _fmt are the bf16 ones.  The two FP8 formats of Table 7
+ *               (ids 2 and 3) are the paper's "direct extension to 8-bit" (Sec. 7) read as the
+ *               same chain with W, R, B of those formats; E5M2 is IEEE-style, E4M3 has no
+ *               infinities (see the format structs in mcf_oracle.cpp for the overflow reading).
  *
  * Parity status: every function below is pinned by tests/test_oracle_*.py to
  * values the paper prints, to exact rational arithmetic, to closed forms or to
@@ -45,6 +48,8 @@ float    orc_widen(uint16_t h);   /* bf16 -> fp32, exact */
 void     orc_R_array(const float *f, uint16_t *out, uint64_t n);   /* R over an array */
 #define ORC_BF16 0
 #define ORC_FP16 1
+#define ORC_FP8_E5M2 2       /* 8-bit patterns travel in the low byte of the uint16_t arrays */
+#define ORC_FP8_E4M3 3
 uint16_t orc_R_fmt(int fmt, float f);
 uint16_t orc_B_fmt(int fmt, double x);
 float    orc_widen_fmt(int fmt, uint16_t h);
@@ -88,6 +93,8 @@ void orc_prim_fmt(int fmt, int which, const uint16_t *p0, const uint16_t *p1, co
 typedef struct { double lr, beta1, beta2, eps, weight_decay; } orc_hyper;
 #define ORC_GROW_TWOSUM 0x100
 #define ORC_FMT_FP16 0x1000    /* OR-ed onto the step's variant: every array and scalar is fp16 */
+#define ORC_FMT_FP8_E5M2 0x2000   /* ... FP8 E5M2 (format id << 12) */
+#define ORC_FMT_FP8_E4M3 0x3000   /* ... FP8 E4M3 */
 typedef struct {
   uint16_t b1;   /* B(beta1)            */
   uint16_t c1;   /* B(1-beta1)          */
