@@ -63,31 +63,32 @@ def carve(total, count, dev, itemsize=2):
 
 
 def build_state(name, variant, arenas):
-    """variant: light | plus | bf16 | kahan | sgd, optionally followed by +twosum and/or +fp16.
+    """variant: light | plus | bf16 | kahan | sgd, optionally followed by +twosum and/or one of +fp16, +e5m2, +e4m3.
     arenas: six byte arenas from carve(); they are re-initialised (theta drawn, the rest zero) and viewed
-    as bf16 or fp16."""
+    as bf16, fp16 or (their first half) FP8."""
     import torch
     from paper_2405_03637_amd import binding as mcf
     from paper_2405_03637_amd import workloads as W
     shapes = W.shapes(name)
     offs, total = W.layout(shapes, misalign_tiny=(name == "stress_64m"))
-    fp16 = "+fp16" in variant
+    fmt = 1 if "+fp16" in variant else 2 if "+e5m2" in variant else 3 if "+e4m3" in variant else 0
+    fp16 = fmt == 1
     base = variant.split("+")[0]
-    st = {k: a.view(torch.float16 if fp16 else torch.bfloat16) for k, a in zip(ROLES, arenas)}
+    dtype = (torch.bfloat16, torch.float16, torch.float8_e5m2, torch.float8_e4m3fn)[fmt]
+    st = {k: (a if fmt < 2 else a[:total]).view(dtype) for k, a in zip(ROLES, arenas)}
     dev = st["theta"].device
     for k in ROLES:
         st[k].zero_()
     W.init_theta(name, shapes, offs, st["theta"])
     drift = W.stress_drift(shapes, offs, total, dev) if name == "stress_64m" else None
-    W.fill_grads(name, shapes, offs, st["grad"], 1, drift=drift, grad_scale=W.FP16_LOSS_SCALE if fp16 else 1.0)
+    W.fill_grads(name, shapes, offs, st["grad"], 1, drift=drift, grad_scale=W.FP16_LOSS_SCALE if fmt else 1.0)
     tensors = [(st["theta"][o:o + n], st["dtheta"][o:o + n] if base != "bf16" else None, st["m"][o:o + n],
                 st["v"][o:o + n] if base != "sgd" else None,
                 st["dv"][o:o + n] if base == "plus" else None, st["grad"][o:o + n]) for (_, n), o in zip(shapes, offs)]
     code = {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN, "sgd": mcf.SGD}[base]
     if "+twosum" in variant:
         code |= mcf.GROW_TWOSUM
-    if fp16:
-        code |= mcf.FMT_FP16
+    code |= fmt << 12
     plan = mcf.Plan(tensors, code)
     return st, plan, W.total_params(shapes), len(shapes)
 
@@ -111,6 +112,9 @@ def cpu_baseline(name, variant, hyper, sample=32 * 1024 * 1024, min_seconds=1.5)
         code |= orc.GROW_TWOSUM
     if "+fp16" in variant:                 # the same bit patterns read as fp16: the oracle's cost does not depend on the values
         code |= orc.STEP_FP16
+    if "+e5m2" in variant or "+e4m3" in variant:
+        code |= orc.STEP_E5M2 if "+e5m2" in variant else orc.STEP_E4M3
+        theta &= 0xFF; grads = [g & 0xFF for g in grads]        # one 8-bit pattern per element
     orc.adamw_step(theta, dth, m, v, dv, grads[0], code, hyper, 1, nthreads=threads)   # warm-up
     steps, t0 = 0, time.perf_counter()
     while steps < 2 or time.perf_counter() - t0 < min_seconds:
@@ -147,6 +151,8 @@ def main():
     hyper = W.WORKLOADS[name][2]
     if "+fp16" in variant:
         hyper = W.fp16_hyper(hyper)
+    if "+e5m2" in variant or "+e4m3" in variant:
+        hyper = W.HYPER_FP8
 
     log(f"bench: building {name} ({variant})")
     _, total = W.layout(W.shapes(name), misalign_tiny=(name == "stress_64m"))
@@ -162,7 +168,7 @@ def main():
             mcf.stream_copy(st["v"][:nb], st["m"][:nb])
         torch.cuda.synchronize()
     wall, gpu_s = time_steps(lambda t: plan.step(hyper, t), args.steps, args.warmup)
-    bpp = W.bytes_per_param(variant.split("+")[0])
+    bpp = W.bytes_per_param(variant.split("+")[0]) * (0.5 if ("+e5m2" in variant or "+e4m3" in variant) else 1.0)
     kern_s = gpu_s / args.steps
     achieved = bpp * n_params / kern_s / 1e9
     traffic = MEASURED_TRAFFIC_BYTES_PER_PARAM.get(variant.split("+")[0])
@@ -173,7 +179,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "fp16" if "+fp16" in variant else "bf16",
+        "dtype": "fp16" if "+fp16" in variant else "fp8_e5m2" if "+e5m2" in variant else "fp8_e4m3" if "+e4m3" in variant else "bf16",
         "data": "synthetic: theta~N(0,0.02), grad~N(0,1e-3) drawn on the GPU before the timed region; zero-initialised m, v, dtheta",
         "config": {"workload": f"{name} Collage-{variant}: {n_tensors} tensors, {n_params} bf16 params, one launch per step",
                    "params": n_params, "tensors": n_tensors, "variant": variant, "bytes_per_param": bpp},
@@ -202,15 +208,19 @@ def main():
             extras["copy_GBps"] = 4 * nb * 10 / s / 1e9
             del src, dst
             # the other strategies on the same shapes
-            for other in ("plus", "light", "kahan", "bf16", "sgd", "light+twosum", "plus+twosum", "light+fp16", "plus+fp16"):
+            for other in ("plus", "light", "kahan", "bf16", "sgd", "light+twosum", "plus+twosum", "light+fp16", "plus+fp16",
+                          "light+e5m2", "plus+e5m2", "light+e4m3"):
                 if other == variant:
                     continue
                 st2, plan2, _, _ = build_state(name, other, arenas)
                 h2 = W.HYPER_PLUS_1P3B if other.startswith("plus") else W.HYPER_LIGHT
                 if "+fp16" in other:
                     h2 = W.fp16_hyper(h2)
+                fp8 = "+e5m2" in other or "+e4m3" in other
+                if fp8:
+                    h2 = W.HYPER_FP8
                 _, s = time_steps(lambda t: plan2.step(h2, t), args.steps, args.warmup)
-                extras[f"{other}_GBps"] = W.bytes_per_param(other.split("+")[0]) * n_params * args.steps / s / 1e9
+                extras[f"{other}_GBps"] = W.bytes_per_param(other.split("+")[0]) * (0.5 if fp8 else 1.0) * n_params * args.steps / s / 1e9
                 extras[f"{other}_ms"] = s / args.steps * 1e3
                 plan2.destroy()
             # option D on the same shapes (separate allocations: measured faster for this mix of 2- and

@@ -17,6 +17,16 @@
  *   business: an epsilon below 2^-25 becomes 0 and squared gradients below
  *   2^-24 are lost or subnormal, so gradients normally need a loss scale the
  *   paper does not specify; none is applied here.
+ *   The two FP8 formats of Table 7 are the paper's "direct extension to 8-bit"
+ *   (Sec. 7), read as the same chain once more: buffers of uint8_t, one pattern
+ *   per element, passed through the same void pointers.  E5M2 (5 exponent bits,
+ *   2 stored significand bits, bias 15) is IEEE-style with infinities; every NaN
+ *   result is stored as 0x7E.  E4M3 (4 and 3 bits, bias 7) has no infinities:
+ *   its largest number is 448 (0x7E), only S.1111.111 is NaN, and a result that
+ *   rounds beyond 448 (an infinite one included) is NaN, stored as 0x7F.  With
+ *   3 or 4 significant bits most hyper-parameters are far from their fp64
+ *   values (E4M3 turns a learning rate below 2^-10 into 0): the formats are
+ *   provided for the arithmetic's sake, and scaling is again the caller's.
  *
  * Conventions for every entry point
  *   - Returns MCF_OK (0) or a negative mcf_status.  No exceptions, no errno,
@@ -26,8 +36,8 @@
  *     OWNED BY THE CALLER: the library never allocates, frees or keeps tensor
  *     memory.  "host" pointers are ordinary process memory, read during the
  *     call only.
- *   - bf16 buffers need 2-byte alignment, fp32 buffers 4-byte, double buffers
- *     8-byte (else MCF_ERR_ALIGN).  Any 2-byte alignment is accepted; 128-bit
+ *   - bf16 and fp16 buffers need 2-byte alignment (FP8 buffers none), fp32 buffers 4-byte, double
+ *     buffers 8-byte (else MCF_ERR_ALIGN).  Any such alignment is accepted; 128-bit
  *     accesses are used when all buffers of one tensor share the same offset
  *     modulo 16 bytes, element-wise accesses otherwise.
  *   - Updates are in place.  Buffers of different roles or tensors must not
@@ -85,11 +95,13 @@ typedef enum { MCF_LIGHT = 0, MCF_PLUS = 1, MCF_BF16 = 2, MCF_KAHAN = 3, MCF_SGD
  * fail for parameters near zero, for v = 0 at the first step, and when a gradient spike exceeds v
  * (App. C: the same expansion without the ordering).  Any other combination is MCF_ERR_VARIANT. */
 #define MCF_GROW_TWOSUM 0x100
-/* May be OR-ed onto any variant (and combined with MCF_GROW_TWOSUM where that is allowed): the
- * tensors and the derived scalars are fp16 instead of bf16. */
-#define MCF_FMT_FP16 0x1000
 /* Component format argument of the primitives below. */
-typedef enum { MCF_COMPONENT_BF16 = 0, MCF_COMPONENT_FP16 = 1 } mcf_component;
+typedef enum { MCF_COMPONENT_BF16 = 0, MCF_COMPONENT_FP16 = 1, MCF_COMPONENT_FP8_E5M2 = 2, MCF_COMPONENT_FP8_E4M3 = 3 } mcf_component;
+/* One of these may be OR-ed onto any variant (and combined with MCF_GROW_TWOSUM where that is allowed):
+ * the tensors and the derived scalars are of that component format (mcf_component << 12) instead of bf16. */
+#define MCF_FMT_FP16 0x1000
+#define MCF_FMT_FP8_E5M2 0x2000
+#define MCF_FMT_FP8_E4M3 0x3000
 
 /* One parameter tensor: flat, contiguous, n elements per buffer, all device memory.
  * theta, dtheta: the parameter expansion (Alg. 2 lines 2-3; MCF_KAHAN: the Kahan variable;
@@ -97,8 +109,8 @@ typedef enum { MCF_COMPONENT_BF16 = 0, MCF_COMPONENT_FP16 = 1 } mcf_component;
  * dv: second component of v (MCF_PLUS only, otherwise ignored and may be NULL);
  * grad: this step's gradient, read only. */
 typedef struct {
-  uint16_t *theta, *dtheta, *m, *v, *dv;
-  const uint16_t *grad;
+  void *theta, *dtheta, *m, *v, *dv;     /* uint16_t elements (bf16, fp16) or uint8_t elements (FP8) */
+  const void *grad;
   uint64_t n;
 } mcf_tensor;
 
@@ -126,7 +138,8 @@ int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *
 /* The ten scalars a step derives from the hyper-parameters (Alg. 2 line 1, Table 2, App. D
  * "Scalar and Bias Correction"), as 16-bit patterns of the component format, written to the host
  * array out[10] in this order: beta1, 1-beta1, beta2 (first component of its expansion), the
- * second component beta2 - first, 1-beta2, 1-beta1^step, 1-beta2^step, eps, weight_decay, -lr.
+ * second component beta2 - first, 1-beta2, 1-beta1^step, 1-beta2^step, eps, weight_decay, -lr
+ * (FP8 patterns in the low byte).
  * Each is computed in fp64 and cast once.  Host-only: no GPU is touched.  restricted_mode_ok (may be
  * NULL) receives 1 when the step kernels may use their reciprocal-based arithmetic for these scalars
  * and 0 when they will use the IEEE sequences (bf16 only: bias corrections below 2^-60, or a non-zero
@@ -134,8 +147,8 @@ int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *
 int mcf_step_scalars(int component, const mcf_hyper *hyper, uint64_t step, uint16_t *out, int *restricted_mode_ok);
 
 /* The same step over a single flat tensor, no plan, no allocation.  n == 0 is a no-op. */
-int mcf_adamw_step_flat(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t *v, uint16_t *dv,
-                        const uint16_t *grad, uint64_t n, int variant, const mcf_hyper *hyper,
+int mcf_adamw_step_flat(void *theta, void *dtheta, void *m, void *v, void *dv,
+                        const void *grad, uint64_t n, int variant, const mcf_hyper *hyper,
                         uint64_t step, void *stream);
 
 /* ---- primitives (element-wise over n elements, device buffers) ---- */
@@ -173,12 +186,12 @@ typedef enum {
   MCF_PRIM_SCALING = 5,      /* Alg. 7:  (o0,o1) = p0 * (p1,p2)                   */
   MCF_PRIM_MUL = 6           /* Alg. 8:  (o0,o1) = (p0,p1) * (p2,p3)              */
 } mcf_primitive_code;
-int mcf_primitive(int component, int which, const uint16_t *p0, const uint16_t *p1, const uint16_t *p2, const uint16_t *p3,
-                  uint16_t *o0, uint16_t *o1, uint64_t n, void *stream);
+int mcf_primitive(int component, int which, const void *p0, const void *p1, const void *p2, const void *p3,
+                  void *o0, void *o1, uint64_t n, void *stream);
 /* Sec. 3.1: out = F(a op b) in the given component format, op as in mcf_bf16_op. */
-int mcf_component_op(int component, int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n, void *stream);
-/* The rounding inside F for the given component format: fp32 device buffer -> 16-bit patterns. */
-int mcf_round_f32_to(int component, const float *in, uint16_t *out, uint64_t n, void *stream);
+int mcf_component_op(int component, int op, const void *a, const void *b, void *out, uint64_t n, void *stream);
+/* The rounding inside F for the given component format: fp32 device buffer -> 16- or 8-bit patterns. */
+int mcf_round_f32_to(int component, const float *in, void *out, uint64_t n, void *stream);
 
 /* Def. 3.3 as a stand-alone reduction: delta = intended update, (th0,dth0) the parameter
  * before and (th1,dth1) after the step; dth0/dth1 may be NULL (plain bf16 parameters,
@@ -188,8 +201,8 @@ uint64_t mcf_edq_scratch_bytes(uint64_t n);
 int mcf_edq(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
             const uint16_t *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev);
 /* The same reduction over buffers of the given component format. */
-int mcf_edq_component(int component, const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
-                      const uint16_t *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev);
+int mcf_edq_component(int component, const void *delta, const void *th0, const void *dth0, const void *th1,
+                      const void *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev);
 
 /* ---- option D, the mixed-precision baseline the paper compares against (Sec. 2.1, Table 1):
  * bf16 parameter and gradient, fp32 moments and fp32 master weight; plain fp32 AdamW with the

@@ -84,6 +84,54 @@ inline double f16_to_f64(uint16_t h) {
   return (h & 0x8000) ? -mag : mag;
 }
 
+// fp64 -> FP8 with a single round-to-nearest-even on the double's fields.  E5M2 (bias 15) is
+// IEEE-style: overflow gives infinity, NaN is 0x7E.  E4M3 (bias 7) has no infinities: its largest
+// number is 448 = 0x7E and whatever rounds beyond it, infinities included, becomes NaN = 0x7F.
+template <int MBITS, int EMIN>
+inline bool f64_to_small(double x, uint32_t &magnitude_bits, uint16_t &sign) {      // false: x is NaN
+  uint64_t u;
+  std::memcpy(&u, &x, 8);
+  sign = (uint16_t)((u >> 56) & 0x80u);
+  const int ef = (int)((u >> 52) & 0x7ff);
+  const uint64_t frac = u & ((1ull << 52) - 1);
+  if (ef == 0x7ff) { magnitude_bits = 0xffffffffu; return frac == 0; }     // infinity: "beyond everything"
+  if (ef == 0) { magnitude_bits = 0; return true; }
+  const int e = ef - 1023;
+  if (e > 40) { magnitude_bits = 0xffffffffu; return true; }
+  const uint64_t sig = frac | (1ull << 52);
+  int shift = 52 - MBITS;
+  if (e < EMIN) shift += EMIN - e;
+  if (shift > 54) { magnitude_bits = 0; return true; }
+  const uint64_t q = sig >> shift;
+  const uint64_t rem = sig & ((1ull << shift) - 1);
+  const uint64_t half = 1ull << (shift - 1);
+  const uint64_t up = (rem > half || (rem == half && (q & 1))) ? 1 : 0;
+  if (e >= EMIN) magnitude_bits = (uint32_t)((e - EMIN + 1) << MBITS) + (uint32_t)(q + up - (1u << MBITS));
+  else magnitude_bits = (uint32_t)(q + up);
+  return true;
+}
+
+inline uint16_t f64_to_e5m2(double x) {
+  uint32_t mag; uint16_t sign;
+  if (!f64_to_small<2, -14>(x, mag, sign)) return 0x7e;
+  if (mag >= 0x7c) mag = 0x7c;
+  return (uint16_t)(sign | mag);
+}
+
+inline uint16_t f64_to_e4m3(double x) {
+  uint32_t mag; uint16_t sign;
+  if (!f64_to_small<3, -6>(x, mag, sign)) return 0x7f;
+  if (mag >= 0x7f) return 0x7f;
+  return (uint16_t)(sign | mag);
+}
+
+inline double e5m2_to_f64(uint16_t h) { return f16_to_f64((uint16_t)((h & 0xff) << 8)); }     // finite patterns only
+inline double e4m3_to_f64(uint16_t h) {
+  const int e = (h >> 3) & 0xf, m = h & 7;
+  const double mag = e == 0 ? std::ldexp((double)m, -9) : std::ldexp((double)(8 + m), e - 10);
+  return (h & 0x80) ? -mag : mag;
+}
+
 inline int check_hyper(const mcf_hyper *h, uint64_t step) {
   if (!h) return MCF_ERR_NULL;
   if (step < 1) return MCF_ERR_STEP;
@@ -121,6 +169,8 @@ inline ScalarBits derive_bits(const mcf_hyper &h, uint64_t step) {
 inline double bf16_to_f64(uint16_t h) { return (double)bf16_to_f32(h); }
 inline ScalarBits scalar_bits_bf16(const mcf_hyper &h, uint64_t step) { return derive_bits<f64_to_bf16, bf16_to_f64>(h, step); }
 inline ScalarBits scalar_bits_fp16(const mcf_hyper &h, uint64_t step) { return derive_bits<f64_to_f16, f16_to_f64>(h, step); }
+inline ScalarBits scalar_bits_e5m2(const mcf_hyper &h, uint64_t step) { return derive_bits<f64_to_e5m2, e5m2_to_f64>(h, step); }
+inline ScalarBits scalar_bits_e4m3(const mcf_hyper &h, uint64_t step) { return derive_bits<f64_to_e4m3, e4m3_to_f64>(h, step); }
 
 // Returns the scalars and whether the Fast arithmetic mode may be used with them: the two
 // bias corrections must be normal numbers in (0, 1] (so that dividing by them cannot shrink
@@ -162,6 +212,32 @@ inline void derive_scalars_fp16(const mcf_hyper &h, uint64_t step, mcfd::StepSca
   s.e = splat(b.v[K_EPS]);
   s.lam = splat(b.v[K_LAM]);
   s.na = splat(b.v[K_NA]);
+}
+
+// FP8 scalars widened to fp32 (infinities and NaN included: a scalar that left the format's range
+// poisons the step exactly as it does in the definition), with fp32 reciprocals of the two bias
+// corrections for the corrected quotient.
+inline void derive_scalars_fp8(const mcf_hyper &h, uint64_t step, bool e4m3, mcfd::StepScalars &s) {
+  const ScalarBits b = e4m3 ? scalar_bits_e4m3(h, step) : scalar_bits_e5m2(h, step);
+  auto widen = [e4m3](uint16_t x) -> float {
+    if (e4m3) return (x & 0x7f) == 0x7f ? std::nanf("") : (float)e4m3_to_f64(x);
+    const uint16_t mag = x & 0x7f;
+    if (mag > 0x7c) return std::nanf("");
+    if (mag == 0x7c) return (x & 0x80) ? -INFINITY : INFINITY;
+    return (float)e5m2_to_f64(x);
+  };
+  s.b1 = widen(b.v[K_B1]);
+  s.c1 = widen(b.v[K_C1]);
+  s.b2 = widen(b.v[K_B2]);
+  s.b2l = widen(b.v[K_B2L]);
+  s.c2 = widen(b.v[K_C2]);
+  s.bc1 = widen(b.v[K_BC1]);
+  s.bc2 = widen(b.v[K_BC2]);
+  s.rbc1 = (float)(1.0 / (double)s.bc1);        // 1/0 = inf: the corrected quotient then keeps a*inf, the IEEE result
+  s.rbc2 = (float)(1.0 / (double)s.bc2);
+  s.e = widen(b.v[K_EPS]);
+  s.lam = widen(b.v[K_LAM]);
+  s.na = widen(b.v[K_NA]);
 }
 
 }  // namespace mcfh

@@ -103,41 +103,44 @@ struct Chunk {
   uint32_t slot0;
 };
 
-struct Slot {       // where one lane's 8 elements sit
-  uint64_t c0;      // aligned coordinate of the first element (multiple of 8)
+struct Slot {       // where one lane's 16 bytes of elements sit
+  uint64_t c0;      // aligned coordinate of the first element (multiple of the elements per slot)
   bool any, full;
 };
 
+// EB = bytes per element (2: bf16, fp16; 1: FP8); a slot holds 16/EB elements.
+template <int EB>
 __device__ __forceinline__ Slot classify(const TensorDesc &d, uint64_t slot) {
+  constexpr uint64_t kEps = 16 / EB;
   Slot s;
-  s.c0 = slot * 8;
+  s.c0 = slot * kEps;
   const uint64_t lo = d.phase, hi = d.phase + d.n;
-  s.any = (s.c0 + 8 > lo) && (s.c0 < hi);
-  s.full = (s.c0 >= lo) && (s.c0 + 8 <= hi) && !d.scalar_only;
+  s.any = (s.c0 + kEps > lo) && (s.c0 < hi);
+  s.full = (s.c0 >= lo) && (s.c0 + kEps <= hi) && !d.scalar_only;
   return s;
 }
 
-// 128-bit access to elements [e0, e0+8) of the 16-bit buffer at p.
+// 128-bit access to the 16 bytes at byte offset `off` of the buffer at p.
 // The pointers are device-memory addresses, so the accesses are typed as global (address
 // space 1): global_load/global_store instead of the generic flat instructions.
 #define MCF_GLOBAL __attribute__((address_space(1)))
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 template <class T> __device__ __forceinline__ MCF_GLOBAL T *gptr(uint64_t p) { return (MCF_GLOBAL T *)p; }
 
-__device__ __forceinline__ void load_vec(uint64_t p, uint64_t e0, uint32_t (&w)[4]) {
+__device__ __forceinline__ void load_vec(uint64_t p, uint64_t off, uint32_t (&w)[4]) {
 #if MCF_NT_LOAD
-  const u32x4_t q = __builtin_nontemporal_load(gptr<const u32x4_t>(p + 2 * e0));
+  const u32x4_t q = __builtin_nontemporal_load(gptr<const u32x4_t>(p + off));
 #else
-  const u32x4_t q = *gptr<const u32x4_t>(p + 2 * e0);
+  const u32x4_t q = *gptr<const u32x4_t>(p + off);
 #endif
   w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
 }
-__device__ __forceinline__ void store_vec(uint64_t p, uint64_t e0, const uint32_t (&w)[4]) {
+__device__ __forceinline__ void store_vec(uint64_t p, uint64_t off, const uint32_t (&w)[4]) {
   const u32x4_t q = {w[0], w[1], w[2], w[3]};
 #if MCF_NT_STORE
-  __builtin_nontemporal_store(q, gptr<u32x4_t>(p + 2 * e0));
+  __builtin_nontemporal_store(q, gptr<u32x4_t>(p + off));
 #else
-  *gptr<u32x4_t>(p + 2 * e0) = q;
+  *gptr<u32x4_t>(p + off) = q;
 #endif
 }
 
@@ -157,35 +160,49 @@ __device__ __forceinline__ void store_f4(MCF_GLOBAL float *p, f32x4_t q) {
 #endif
 }
 
-// Load the slot of stream `p` as 4 dwords (two elements each); elements outside the tensor read as 0.
+// One element of EB bytes.
+template <int EB> __device__ __forceinline__ uint32_t load_elem(uint64_t p, uint64_t e) {
+  if constexpr (EB == 1) return gptr<const uint8_t>(p)[e]; else return gptr<const uint16_t>(p)[e];
+}
+template <int EB> __device__ __forceinline__ void store_elem(uint64_t p, uint64_t e, uint32_t bits) {
+  if constexpr (EB == 1) gptr<uint8_t>(p)[e] = (uint8_t)bits; else gptr<uint16_t>(p)[e] = (uint16_t)bits;
+}
+
+// Load the slot of stream `p` as 4 dwords (4/EB elements each); elements outside the tensor read as 0.
+template <int EB>
 __device__ __forceinline__ void load_slot(uint64_t p, const TensorDesc &d, const Slot &s, uint32_t (&w)[4]) {
-  const MCF_GLOBAL uint16_t *base = gptr<const uint16_t>(p);
   if (s.full) {
-    load_vec(p, s.c0 - d.phase, w);
+    load_vec(p, (s.c0 - d.phase) * EB, w);
   } else {
+    constexpr int kPer = 4 / EB;        // elements per dword
     const uint64_t lo = d.phase, hi = d.phase + d.n;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      const uint64_t c = s.c0 + 2 * k;
-      uint32_t a = 0, b = 0;
-      if (c >= lo && c < hi) a = base[c - lo];
-      if (c + 1 >= lo && c + 1 < hi) b = base[c + 1 - lo];
-      w[k] = a | (b << 16);
+      uint32_t word = 0;
+#pragma unroll
+      for (int j = 0; j < kPer; ++j) {
+        const uint64_t c = s.c0 + kPer * k + j;
+        if (c >= lo && c < hi) word |= load_elem<EB>(p, c - lo) << (8 * EB * j);
+      }
+      w[k] = word;
     }
   }
 }
 
+template <int EB>
 __device__ __forceinline__ void store_slot(uint64_t p, const TensorDesc &d, const Slot &s, const uint32_t (&w)[4]) {
-  MCF_GLOBAL uint16_t *base = gptr<uint16_t>(p);
   if (s.full) {
-    store_vec(p, s.c0 - d.phase, w);
+    store_vec(p, (s.c0 - d.phase) * EB, w);
   } else {
+    constexpr int kPer = 4 / EB;
     const uint64_t lo = d.phase, hi = d.phase + d.n;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      const uint64_t c = s.c0 + 2 * k;
-      if (c >= lo && c < hi) base[c - lo] = (uint16_t)(w[k] & 0xffffu);
-      if (c + 1 >= lo && c + 1 < hi) base[c + 1 - lo] = (uint16_t)(w[k] >> 16);
+#pragma unroll
+      for (int j = 0; j < kPer; ++j) {
+        const uint64_t c = s.c0 + kPer * k + j;
+        if (c >= lo && c < hi) store_elem<EB>(p, c - lo, (w[k] >> (8 * EB * j)) & (EB == 1 ? 0xffu : 0xffffu));
+      }
     }
   }
 }
@@ -274,18 +291,32 @@ __device__ __forceinline__ void edq_store_partial(const EdqAcc &a, double *__res
 
 // ---------------------------------------------------------------- the step kernel
 // VARIANT template arguments below carry the variant in the low byte, kGrow2Bit when every Grow
-// is to be built on TwoSum (Alg. 3) instead of Fast2Sum, and kHalfBit when the components are fp16.
+// is to be built on TwoSum (Alg. 3) instead of Fast2Sum, and the component format (mcf_component) in
+// bits 12-13, as in the C ABI's variant argument.
 constexpr int kGrow2Bit = 0x100;
-constexpr int kHalfBit = 0x1000;
+constexpr int kFmtShift = 12;
+constexpr int kHalfBit = MCF_COMPONENT_FP16 << kFmtShift;
+
+// Arithmetic modes of a component format: the first pass over a vector slot (FAST selects between the
+// two bf16 modes) and the mode of the element path and of a redo.
+template <int FMT, bool FAST> struct ModeOf;
+template <bool FAST> struct ModeOf<MCF_COMPONENT_BF16, FAST> {
+  using Hot = typename std::conditional<FAST, mcfd::Fast, mcfd::Exact>::type;
+  using Cold = mcfd::Exact;
+};
+template <bool FAST> struct ModeOf<MCF_COMPONENT_FP16, FAST> { using Hot = mcfd::HalfHot; using Cold = mcfd::HalfCold; };
+template <bool FAST> struct ModeOf<MCF_COMPONENT_FP8_E5M2, FAST> { using Hot = mcfd::F8<false, true>; using Cold = mcfd::F8<false, false>; };
+template <bool FAST> struct ModeOf<MCF_COMPONENT_FP8_E4M3, FAST> { using Hot = mcfd::F8<true, true>; using Cold = mcfd::F8<true, false>; };
 template <int VARIANT> struct StepStreams {
   static constexpr int kBase = VARIANT & 0xff;
   static constexpr bool kGrow2 = (VARIANT & kGrow2Bit) != 0;
-  static constexpr bool kHalf = (VARIANT & kHalfBit) != 0;
-  // arithmetic of the vector path (FAST selects between the two bf16 modes) and of the element path
-  template <bool FAST> using Hot = typename std::conditional<kHalf, mcfd::HalfHot,
-                                       typename std::conditional<FAST, mcfd::Fast, mcfd::Exact>::type>::type;
-  using Cold = typename std::conditional<kHalf, mcfd::HalfCold, mcfd::Exact>::type;
+  static constexpr int kFmt = (VARIANT >> kFmtShift) & 3;
+  static constexpr bool kBf16 = kFmt == MCF_COMPONENT_BF16;
+  template <bool FAST> using Hot = typename ModeOf<kFmt, FAST>::Hot;
+  using Cold = typename ModeOf<kFmt, true>::Cold;
   using Scalars = StepScalarsT<typename Cold::S>;
+  static constexpr int kEB = Cold::kBytes;                 // bytes per element
+  static constexpr int kEps = 16 / kEB;                    // elements per slot
   static constexpr bool kDth = kBase != mcfd::V_BF16;      // second component of theta / Kahan variable
   static constexpr bool kDv = kBase == mcfd::V_PLUS;       // second component of v
   static constexpr bool kV = kBase != mcfd::V_SGD;         // second moment
@@ -302,35 +333,50 @@ template <int VARIANT> struct StepStreams {
   static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : lds_for_groups(kBase == mcfd::V_BF16 ? 16 : 14);
 };
 
-// Hot path: one full slot, 8 elements of every stream held as 4 dwords each.  Returns true
-// when the Fast arithmetic mode asks for the slot to be recomputed in Exact mode.
+// A dword of a stream holds one pair (2-byte elements) or two pairs (1-byte elements).
+template <class M, int PAIR> __device__ __forceinline__ typename M::T unpack_pair(uint32_t w) {
+  if constexpr (M::kBytes == 1) return M::template unpack<PAIR>(w); else return M::unpack(w);
+}
+template <class M, int N> __device__ __forceinline__ uint32_t pack_pairs(const typename M::T (&x)[N]) {
+  if constexpr (M::kBytes == 1) return M::pack(x[0], x[1]); else return M::pack(x[0]);
+}
+
+// Hot path: one full slot, 16 bytes of every stream held as 4 dwords each.  Returns true
+// when the arithmetic mode asks for the slot to be recomputed (bf16 Fast mode: in Exact mode; fp16
+// and FP8: in the mode that stores canonical NaN).
 template <class M, int VARIANT, bool EDQ>
 __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], uint32_t (&out)[kMaxStreams][4],
                                          const StepScalarsT<typename M::S> &sc, EdqAcc &acc) {
   using SS = StepStreams<VARIANT>;
   using T = typename M::T;
+  constexpr int kPairs = M::kBytes == 1 ? 2 : 1;
   bool redo = false;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
-    ElemIOT<T> io;
-    io.th = M::unpack(in[S_TH][k]);
-    if (SS::kDth) io.dth = M::unpack(in[S_DTH][k]); else io.dth = M::zero();
-    io.m = M::unpack(in[S_M][k]);
-    if (SS::kV) io.v = M::unpack(in[S_V][k]); else io.v = M::zero();
-    io.g = M::unpack(in[S_G][k]);
-    if (SS::kDv) io.dv = M::unpack(in[S_DV][k]); else io.dv = M::zero();
-    const T th0 = io.th, dth0 = io.dth;
-    T delta;
-    mcfd::adamw_pair<M, SS::kBase, SS::kGrow2>(io, sc, delta, redo);
-    out[S_TH][k] = M::pack(io.th);
-    if (SS::kDth) out[S_DTH][k] = M::pack(io.dth);
-    out[S_M][k] = M::pack(io.m);
-    if (SS::kV) out[S_V][k] = M::pack(io.v);
-    if (SS::kDv) out[S_DV][k] = M::pack(io.dv);
-    if (EDQ) {
-      edq_add(acc, M::lo(delta), M::lo(th0), M::lo(dth0), M::lo(io.th), M::lo(io.dth));
-      edq_add(acc, M::hi(delta), M::hi(th0), M::hi(dth0), M::hi(io.th), M::hi(io.dth));
-    }
+    T th[kPairs], dth[kPairs], m[kPairs], v[kPairs], dv[kPairs];
+    static_for<0, kPairs>([&](auto pc) {
+      constexpr int P = decltype(pc)::value;
+      ElemIOT<T> io;
+      io.th = unpack_pair<M, P>(in[S_TH][k]);
+      if (SS::kDth) io.dth = unpack_pair<M, P>(in[S_DTH][k]); else io.dth = M::zero();
+      io.m = unpack_pair<M, P>(in[S_M][k]);
+      if (SS::kV) io.v = unpack_pair<M, P>(in[S_V][k]); else io.v = M::zero();
+      io.g = unpack_pair<M, P>(in[S_G][k]);
+      if (SS::kDv) io.dv = unpack_pair<M, P>(in[S_DV][k]); else io.dv = M::zero();
+      const T th0 = io.th, dth0 = io.dth;
+      T delta;
+      mcfd::adamw_pair<M, SS::kBase, SS::kGrow2>(io, sc, delta, redo);
+      th[P] = io.th; dth[P] = io.dth; m[P] = io.m; v[P] = io.v; dv[P] = io.dv;
+      if (EDQ) {
+        edq_add(acc, M::lo(delta), M::lo(th0), M::lo(dth0), M::lo(io.th), M::lo(io.dth));
+        edq_add(acc, M::hi(delta), M::hi(th0), M::hi(dth0), M::hi(io.th), M::hi(io.dth));
+      }
+    });
+    out[S_TH][k] = pack_pairs<M>(th);
+    if (SS::kDth) out[S_DTH][k] = pack_pairs<M>(dth);
+    out[S_M][k] = pack_pairs<M>(m);
+    if (SS::kV) out[S_V][k] = pack_pairs<M>(v);
+    if (SS::kDv) out[S_DV][k] = pack_pairs<M>(dv);
   }
   return redo;
 }
@@ -345,36 +391,31 @@ __device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, cons
   using SS = StepStreams<VARIANT>;
   using M = typename SS::Cold;
   using T = typename M::T;
+  constexpr int EB = SS::kEB;
   const uint64_t lo = d.phase, hi = d.phase + d.n;
-  MCF_GLOBAL uint16_t *th = gptr<uint16_t>(d.p[S_TH]);
-  MCF_GLOBAL uint16_t *dth = gptr<uint16_t>(d.p[S_DTH]);
-  MCF_GLOBAL uint16_t *m = gptr<uint16_t>(d.p[S_M]);
-  MCF_GLOBAL uint16_t *v = gptr<uint16_t>(d.p[S_V]);
-  MCF_GLOBAL uint16_t *dv = gptr<uint16_t>(d.p[S_DV]);
-  const MCF_GLOBAL uint16_t *g = gptr<const uint16_t>(d.p[S_G]);
 #pragma unroll 1
-  for (int k = 0; k < 8; ++k) {
+  for (int k = 0; k < SS::kEps; ++k) {
     const uint64_t c = c0 + k;
     if (c < lo || c >= hi) continue;
     const uint64_t e = c - lo;
     ElemIOT<T> io;                   // the element rides in the low half of a pair
-    io.th = M::unpack(th[e]);
-    if (SS::kDth) io.dth = M::unpack(dth[e]); else io.dth = M::zero();
-    io.m = M::unpack(m[e]);
-    if (SS::kV) io.v = M::unpack(v[e]); else io.v = M::zero();
-    io.g = M::unpack(g[e]);
-    if (SS::kDv) io.dv = M::unpack(dv[e]); else io.dv = M::zero();
+    io.th = M::unpack(load_elem<EB>(d.p[S_TH], e));
+    if (SS::kDth) io.dth = M::unpack(load_elem<EB>(d.p[S_DTH], e)); else io.dth = M::zero();
+    io.m = M::unpack(load_elem<EB>(d.p[S_M], e));
+    if (SS::kV) io.v = M::unpack(load_elem<EB>(d.p[S_V], e)); else io.v = M::zero();
+    io.g = M::unpack(load_elem<EB>(d.p[S_G], e));
+    if (SS::kDv) io.dv = M::unpack(load_elem<EB>(d.p[S_DV], e)); else io.dv = M::zero();
     const float th0 = M::lo(io.th), dth0 = M::lo(io.dth);
     T delta;
     bool unused = false;
     mcfd::adamw_pair<M, SS::kBase, SS::kGrow2>(io, sc, delta, unused);
     // EDQ is taken on the stored values (a NaN stays a NaN whatever its payload)
     if (EDQ) edq_add(acc, M::lo(delta), th0, dth0, M::lo(io.th), M::lo(io.dth));
-    th[e] = M::bits_lo(io.th);
-    if (SS::kDth) dth[e] = M::bits_lo(io.dth);
-    m[e] = M::bits_lo(io.m);
-    if (SS::kV) v[e] = M::bits_lo(io.v);
-    if (SS::kDv) dv[e] = M::bits_lo(io.dv);
+    store_elem<EB>(d.p[S_TH], e, M::bits_lo(io.th));
+    if (SS::kDth) store_elem<EB>(d.p[S_DTH], e, M::bits_lo(io.dth));
+    store_elem<EB>(d.p[S_M], e, M::bits_lo(io.m));
+    if (SS::kV) store_elem<EB>(d.p[S_V], e, M::bits_lo(io.v));
+    if (SS::kDv) store_elem<EB>(d.p[S_DV], e, M::bits_lo(io.dv));
   }
 }
 
@@ -409,9 +450,9 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
   uint32_t in[kUnroll][kMaxStreams][4];
   static_for<0, kUnroll>([&](auto jc) {
     constexpr int j = decltype(jc)::value;
-    slot[j] = classify(d, slot0 + (uint64_t)j * kStepBlock + threadIdx.x);
+    slot[j] = classify<SS::kEB>(d, slot0 + (uint64_t)j * kStepBlock + threadIdx.x);
     if (slot[j].full) {
-      const uint64_t e0 = slot[j].c0 - d.phase;
+      const uint64_t e0 = (slot[j].c0 - d.phase) * SS::kEB;       // byte offset
       load_vec(d.p[S_TH], e0, in[j][S_TH]);
       if (SS::kDth) load_vec(d.p[S_DTH], e0, in[j][S_DTH]);
       load_vec(d.p[S_M], e0, in[j][S_M]);
@@ -429,8 +470,8 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
       uint32_t out[kMaxStreams][4];
       EdqAcc local = {0.0, 0.0, 0u};
       bool redo = hot_slot<Mode, VARIANT, EDQ>(in[j], out, sc, local);
-      if constexpr (SS::kHalf) {
-        // fp16: the first pass found a NaN among its results.  The same slot again, still from registers,
+      if constexpr (!SS::kBf16) {
+        // fp16, FP8: the first pass found a NaN among its results.  The same slot again, still from registers,
         // in the mode that stores the format's one NaN: the arithmetic is the same packed code, so a
         // diverged tensor costs 18% more time, not a serial loop (21.8 against 65.5 ms for an all-NaN 7B set).
         if (redo) {
@@ -446,7 +487,7 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
       if (redo) {
         cold |= 1u << j;
       } else {
-        const uint64_t e0 = slot[j].c0 - d.phase;
+        const uint64_t e0 = (slot[j].c0 - d.phase) * SS::kEB;
         store_vec(d.p[S_TH], e0, out[S_TH]);
         if (SS::kDth) store_vec(d.p[S_DTH], e0, out[S_DTH]);
         store_vec(d.p[S_M], e0, out[S_M]);
@@ -463,7 +504,7 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
     for (int j = 0; j < kUnroll; ++j) {
       if (!((cold >> j) & 1u)) continue;
       EdqAcc local = {0.0, 0.0, 0u};
-      cold_slot<VARIANT, EDQ>(d, (slot0 + (uint64_t)j * kStepBlock + threadIdx.x) * 8, sc, local);
+      cold_slot<VARIANT, EDQ>(d, (slot0 + (uint64_t)j * kStepBlock + threadIdx.x) * SS::kEps, sc, local);
       if (EDQ) { acc.s1 += local.s1; acc.s2 += local.s2; acc.lost += local.lost; }
     }
   }
@@ -512,59 +553,73 @@ struct PrimArgs {
   uint32_t phase, scalar_only;
 };
 
+// One pair of elements of one primitive: inputs i[0..3] (and i[4] for EDQ), results (x, y).
+template <class M, int OP>
+__device__ __forceinline__ void prim_pair(const typename M::T (&i)[5], typename M::T &x, typename M::T &y,
+                                          bool &redo, EdqAcc &acc, uint32_t valid2) {
+  using O = mcfd::Ops<M>;
+  using T = typename M::T;
+  const T a = i[0], b = i[1];
+  x = M::zero(); y = M::zero();
+  if (OP == P_FAST2SUM) O::fast2sum(a, b, x, y);
+  if (OP == P_TWOSUM) O::two_sum(a, b, x, y);
+  if (OP == P_GROW) O::grow(a, b, i[2], x, y);                            // streams: x, y, a
+  if (OP == P_GROW2) O::grow2(a, b, i[2], x, y);
+  if (OP == P_TWOPROD) { x = O::mul(a, b); y = O::fms(a, b, x); }         // Alg. 6
+  if (OP == P_SCALING) {                                                  // Alg. 7; streams: v, a1, a2
+    const T x0 = O::mul(b, a);
+    const T e = O::add(O::mul(i[2], a), O::fms(b, a, x0));
+    O::fast2sum(x0, e, x, y);
+  }
+  if (OP == P_MULX) {                                                     // Alg. 8; streams: a1, a2, b1, b2
+    const T b1 = i[2], b2 = i[3];
+    const T x0 = O::mul(a, b1);
+    const T ex = O::fms(a, b1, x0);
+    const T cross = O::add(O::mul(a, b2), O::mul(b, b1));
+    O::fast2sum(x0, O::add(ex, cross), x, y);
+  }
+  if (OP == P_ADD) x = O::add(a, b);
+  if (OP == P_SUB) x = O::sub(a, b);
+  if (OP == P_MUL) x = O::mul(a, b);
+  if (OP == P_DIV) {
+    if constexpr (M::kGuarded) {
+      // the reciprocal route needs |b| zero, infinite, NaN or within [2^-126, 2^126]
+      const float alo = __builtin_fabsf(b.lo), ahi = __builtin_fabsf(b.hi);
+      redo |= mcfd::is_subnormal(b.lo) | mcfd::is_subnormal(b.hi) | (alo > 0x1p126f && alo < __builtin_inff()) |
+              (ahi > 0x1p126f && ahi < __builtin_inff());
+    }
+    x = O::divg(a, b, redo);
+  }
+  if (OP == P_SQRT) {
+    if constexpr (M::kGuarded) redo |= mcfd::is_subnormal(a.lo) | mcfd::is_subnormal(a.hi);
+    x = O::sqrt(a, redo);
+  }
+  if (OP == P_EDQ) {
+    // streams: delta, th0, th1, dth0, dth1 (absent second components were loaded as zeros);
+    // elements outside the tensor are skipped so that they cannot count as lost updates
+    if (valid2 & 1u) edq_add(acc, M::lo(a), M::lo(b), M::lo(i[3]), M::lo(i[2]), M::lo(i[4]));
+    if (valid2 & 2u) edq_add(acc, M::hi(a), M::hi(b), M::hi(i[3]), M::hi(i[2]), M::hi(i[4]));
+  }
+  if (M::kFast && OP != P_EDQ) redo |= M::any_nan(x) | M::any_nan(y);
+}
+
+// One slot of a primitive: 4 dwords per stream, 4/M::kBytes elements per dword.
 template <class M, int OP>
 __device__ __forceinline__ void prim_words(const uint32_t (&in)[kMaxStreams][4], uint32_t (&out)[kMaxStreams][4],
                                            bool &redo, EdqAcc &acc, uint32_t valid) {
-  using O = mcfd::Ops<M>;
   using T = typename M::T;
+  constexpr int kPairs = M::kBytes == 1 ? 2 : 1;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
-    T a = M::unpack(in[0][k]), b = M::unpack(in[1][k]);
-    T x = M::zero(), y = M::zero();
-    if (OP == P_FAST2SUM) O::fast2sum(a, b, x, y);
-    if (OP == P_TWOSUM) O::two_sum(a, b, x, y);
-    if (OP == P_GROW) O::grow(a, b, M::unpack(in[2][k]), x, y);             // streams: x, y, a
-    if (OP == P_GROW2) O::grow2(a, b, M::unpack(in[2][k]), x, y);
-    if (OP == P_TWOPROD) { x = O::mul(a, b); y = O::fms(a, b, x); }         // Alg. 6
-    if (OP == P_SCALING) {                                                  // Alg. 7; streams: v, a1, a2
-      const T a2 = M::unpack(in[2][k]);
-      const T x0 = O::mul(b, a);
-      const T e = O::add(O::mul(a2, a), O::fms(b, a, x0));
-      O::fast2sum(x0, e, x, y);
-    }
-    if (OP == P_MULX) {                                                     // Alg. 8; streams: a1, a2, b1, b2
-      const T b1 = M::unpack(in[2][k]), b2 = M::unpack(in[3][k]);
-      const T x0 = O::mul(a, b1);
-      const T ex = O::fms(a, b1, x0);
-      const T cross = O::add(O::mul(a, b2), O::mul(b, b1));
-      O::fast2sum(x0, O::add(ex, cross), x, y);
-    }
-    if (OP == P_ADD) x = O::add(a, b);
-    if (OP == P_SUB) x = O::sub(a, b);
-    if (OP == P_MUL) x = O::mul(a, b);
-    if (OP == P_DIV) {
-      if constexpr (M::kFast && !M::kHalf) {
-        // the reciprocal route needs |b| zero, infinite, NaN or within [2^-126, 2^126]
-        const float alo = __builtin_fabsf(b.lo), ahi = __builtin_fabsf(b.hi);
-        redo |= mcfd::is_subnormal(b.lo) | mcfd::is_subnormal(b.hi) | (alo > 0x1p126f && alo < __builtin_inff()) |
-                (ahi > 0x1p126f && ahi < __builtin_inff());
-      }
-      x = O::divg(a, b, redo);
-    }
-    if (OP == P_SQRT) {
-      if constexpr (M::kFast && !M::kHalf) redo |= mcfd::is_subnormal(a.lo) | mcfd::is_subnormal(a.hi);
-      x = O::sqrt(a, redo);
-    }
-    if (OP == P_EDQ) {
-      // streams: delta, th0, th1, dth0, dth1 (absent second components were loaded as zeros);
-      // elements outside the tensor are skipped so that they cannot count as lost updates
-      const T th1 = M::unpack(in[2][k]), d0 = M::unpack(in[3][k]), d1 = M::unpack(in[4][k]);
-      if (valid & (1u << (2 * k))) edq_add(acc, M::lo(a), M::lo(b), M::lo(d0), M::lo(th1), M::lo(d1));
-      if (valid & (1u << (2 * k + 1))) edq_add(acc, M::hi(a), M::hi(b), M::hi(d0), M::hi(th1), M::hi(d1));
-    }
-    if (M::kFast && OP != P_EDQ) redo |= M::any_nan(x) | M::any_nan(y);
-    out[0][k] = M::pack(x);
-    out[1][k] = M::pack(y);
+    T x[kPairs], y[kPairs];
+    static_for<0, kPairs>([&](auto pc) {
+      constexpr int P = decltype(pc)::value;
+      const T i[5] = {unpack_pair<M, P>(in[0][k]), unpack_pair<M, P>(in[1][k]), unpack_pair<M, P>(in[2][k]),
+                      unpack_pair<M, P>(in[3][k]), unpack_pair<M, P>(in[4][k])};
+      prim_pair<M, OP>(i, x[P], y[P], redo, acc, (valid >> (2 * (kPairs * k + P))) & 3u);
+    });
+    out[0][k] = pack_pairs<M>(x);
+    out[1][k] = pack_pairs<M>(y);
   }
 }
 
@@ -576,33 +631,35 @@ __device__ __forceinline__ void prim_words(const uint32_t (&in)[kMaxStreams][4],
 //  MULX:            p0=a1 p1=a2 p2=b1 p3=b2 p4=x p5=e  0..3  out0->p4, out1->p5
 //  ADD..SQRT:       p0=a p1=b p2=out      0,1 (sqrt: 0)    out0->p2
 //  EDQ:             p0=delta p1=th0 p2=th1 p3=dth0 p4=dth1  (reads only; partial sums out)
-template <int OP, bool HALF>
+template <int OP, int FMT>
 __global__ void __launch_bounds__(kBlock) prim_kernel(PrimArgs a, uint32_t has_d0, uint32_t has_d1, double *__restrict__ partials) {
-  using Hot = typename std::conditional<HALF, mcfd::HalfHot, mcfd::Fast>::type;
-  using Cold = typename std::conditional<HALF, mcfd::HalfCold, mcfd::Exact>::type;
+  using Hot = typename ModeOf<FMT, true>::Hot;
+  using Cold = typename ModeOf<FMT, true>::Cold;
+  constexpr int EB = Cold::kBytes;
+  constexpr int kEps = 16 / EB;
   TensorDesc d;
 #pragma unroll
   for (int s = 0; s < kMaxStreams; ++s) d.p[s] = a.p[s];
   d.n = a.n; d.phase = a.phase; d.scalar_only = a.scalar_only;
-  const Slot s = classify(d, (uint64_t)blockIdx.x * kBlock + threadIdx.x);
+  const Slot s = classify<EB>(d, (uint64_t)blockIdx.x * kBlock + threadIdx.x);
   EdqAcc acc = {0.0, 0.0, 0u};
   if (s.any) {
     uint32_t in[kMaxStreams][4] = {};
     uint32_t out[kMaxStreams][4];
     constexpr int nin = (OP == P_GROW || OP == P_GROW2 || OP == P_SCALING) ? 3 : (OP == P_MULX) ? 4 : (OP == P_SQRT) ? 1 : 2;
-    uint32_t valid = 0xffu;              // which of the slot's 8 elements belong to the tensor
+    uint32_t valid = 0xffffu;            // which of the slot's elements belong to the tensor
     if (OP == P_EDQ) {
-      load_slot(d.p[0], d, s, in[0]);
-      load_slot(d.p[1], d, s, in[1]);
-      load_slot(d.p[2], d, s, in[2]);
-      if (has_d0) load_slot(d.p[3], d, s, in[3]);
-      if (has_d1) load_slot(d.p[4], d, s, in[4]);
+      load_slot<EB>(d.p[0], d, s, in[0]);
+      load_slot<EB>(d.p[1], d, s, in[1]);
+      load_slot<EB>(d.p[2], d, s, in[2]);
+      if (has_d0) load_slot<EB>(d.p[3], d, s, in[3]);
+      if (has_d1) load_slot<EB>(d.p[4], d, s, in[4]);
       valid = 0;
-      for (int k = 0; k < 8; ++k)
+      for (int k = 0; k < kEps; ++k)
         if (s.c0 + k >= d.phase && s.c0 + k < d.phase + d.n) valid |= 1u << k;
     } else {
 #pragma unroll
-      for (int k = 0; k < nin; ++k) load_slot(d.p[k], d, s, in[k]);
+      for (int k = 0; k < nin; ++k) load_slot<EB>(d.p[k], d, s, in[k]);
     }
     bool redo = false;
     prim_words<Hot, OP>(in, out, redo, acc, valid);
@@ -610,34 +667,40 @@ __global__ void __launch_bounds__(kBlock) prim_kernel(PrimArgs a, uint32_t has_d
       bool unused = false;
       prim_words<Cold, OP>(in, out, unused, acc, valid);
     }
-    if (OP == P_FAST2SUM || OP == P_TWOSUM || OP == P_TWOPROD) { store_slot(d.p[2], d, s, out[0]); store_slot(d.p[3], d, s, out[1]); }
-    if (OP == P_GROW || OP == P_GROW2) { store_slot(d.p[3], d, s, out[0]); store_slot(d.p[4], d, s, out[1]); }
-    if (OP == P_SCALING) { store_slot(d.p[3], d, s, out[0]); store_slot(d.p[4], d, s, out[1]); }
-    if (OP == P_MULX) { store_slot(d.p[4], d, s, out[0]); store_slot(d.p[5], d, s, out[1]); }
-    if (OP == P_ADD || OP == P_SUB || OP == P_MUL || OP == P_DIV || OP == P_SQRT) store_slot(d.p[2], d, s, out[0]);
+    if (OP == P_FAST2SUM || OP == P_TWOSUM || OP == P_TWOPROD) { store_slot<EB>(d.p[2], d, s, out[0]); store_slot<EB>(d.p[3], d, s, out[1]); }
+    if (OP == P_GROW || OP == P_GROW2) { store_slot<EB>(d.p[3], d, s, out[0]); store_slot<EB>(d.p[4], d, s, out[1]); }
+    if (OP == P_SCALING) { store_slot<EB>(d.p[3], d, s, out[0]); store_slot<EB>(d.p[4], d, s, out[1]); }
+    if (OP == P_MULX) { store_slot<EB>(d.p[4], d, s, out[0]); store_slot<EB>(d.p[5], d, s, out[1]); }
+    if (OP == P_ADD || OP == P_SUB || OP == P_MUL || OP == P_DIV || OP == P_SQRT) store_slot<EB>(d.p[2], d, s, out[0]);
   }
   if (OP == P_EDQ) edq_store_partial<kBlock>(acc, partials, blockIdx.x);
 }
 
-// fp32 -> bf16 or fp16 over an array (the rounding inside F).  Two elements per lane.
-template <bool HALF>
-__global__ void __launch_bounds__(kBlock) round_kernel(const float *__restrict__ in, uint16_t *__restrict__ out, uint64_t n) {
-  using Hot = typename std::conditional<HALF, mcfd::HalfHot, mcfd::Fast>::type;
-  using Cold = typename std::conditional<HALF, mcfd::HalfCold, mcfd::Exact>::type;
+// fp32 -> the component format over an array (the rounding inside F).  Two elements per lane.
+template <int FMT>
+__global__ void __launch_bounds__(kBlock) round_kernel(const float *__restrict__ in, uint64_t out, uint64_t n) {
+  using Hot = typename ModeOf<FMT, true>::Hot;
+  using Cold = typename ModeOf<FMT, true>::Cold;
+  constexpr int EB = Cold::kBytes;
   const uint64_t i = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 2;
   if (i >= n) return;
   const float a = in[i];
   const float b = (i + 1 < n) ? in[i + 1] : 0.f;
-  uint16_t lo, hi;
-  if (mcfd::is_nan(a) | mcfd::is_nan(b)) {
-    const typename Cold::T r = Cold::round_f32(a, b);
-    lo = Cold::bits_lo(r); hi = Cold::bits_hi(r);
+  uint32_t lo, hi;
+  if constexpr (FMT == MCF_COMPONENT_BF16) {
+    if (mcfd::is_nan(a) | mcfd::is_nan(b)) {
+      const typename Cold::T r = Cold::round_f32(a, b);
+      lo = Cold::bits_lo(r); hi = Cold::bits_hi(r);
+    } else {
+      const typename Hot::T r = Hot::round_f32(a, b);             // the hardware conversion
+      lo = Hot::pack(r) & 0xffffu; hi = Hot::pack(r) >> 16;
+    }
   } else {
-    const typename Hot::T r = Hot::round_f32(a, b);
-    lo = (uint16_t)(Hot::pack(r) & 0xffffu); hi = (uint16_t)(Hot::pack(r) >> 16);
+    const typename Cold::T r = Cold::round_f32(a, b);             // stores the format's one NaN
+    lo = Cold::bits_lo(r); hi = Cold::bits_hi(r);
   }
-  out[i] = lo;
-  if (i + 1 < n) out[i + 1] = hi;
+  store_elem<EB>(out, i, lo);
+  if (i + 1 < n) store_elem<EB>(out, i + 1, hi);
 }
 
 // Plain 128-bit copy in the step kernel's launch shape: the streaming ceiling the step is
@@ -647,8 +710,8 @@ copy_kernel(uint64_t dst, uint64_t src, uint64_t nvec) {
   const uint64_t i = (uint64_t)blockIdx.x * kStepBlock + threadIdx.x;
   if (i >= nvec) return;
   uint32_t w[4];
-  load_vec(src, 8 * i, w);
-  store_vec(dst, 8 * i, w);
+  load_vec(src, 16 * i, w);
+  store_vec(dst, 16 * i, w);
 }
 
 // ---------------------------------------------------------------- option D (fp32 master weights)
@@ -743,7 +806,7 @@ fp32mw_kernel(const Fp32Desc *__restrict__ descs, const Chunk *__restrict__ chun
   t.n = d.n; t.phase = d.phase; t.scalar_only = d.scalar_only;
 #pragma unroll 1
   for (int j = 0; j < kUnroll; ++j) {
-    const Slot s = classify(t, (uint64_t)c.slot0 + (uint64_t)j * kStepBlock + threadIdx.x);
+    const Slot s = classify<2>(t, (uint64_t)c.slot0 + (uint64_t)j * kStepBlock + threadIdx.x);
     if (!s.any) continue;
     const uint64_t lo = d.phase, hi = d.phase + d.n;
 #pragma unroll 1
@@ -766,17 +829,24 @@ inline bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<ui
 
 // Alignment class of a set of 16-bit-element pointers: common phase (elements above the boundary)
 // or scalar_only when they disagree.
-inline void phase_of(const uint64_t *ptrs, int count, uint32_t &phase, uint32_t &scalar_only, uint64_t boundary = 16) {
-  phase = (uint32_t)((ptrs[0] & (boundary - 1)) >> 1);
+inline void phase_of(const uint64_t *ptrs, int count, uint32_t &phase, uint32_t &scalar_only, uint64_t boundary = 16,
+                     uint32_t elem_bytes = 2) {
+  phase = (uint32_t)((ptrs[0] & (boundary - 1)) / elem_bytes);
   scalar_only = 0;
   for (int i = 1; i < count; ++i)
     if ((ptrs[i] & 15) != (ptrs[0] & 15)) scalar_only = 1;
   if (scalar_only) phase = 0;
 }
 
-inline uint64_t slots_of(uint64_t n, uint32_t phase) { return (n + phase + 7) / 8; }
+inline uint64_t slots_of(uint64_t n, uint32_t phase, uint32_t elem_bytes = 2) {
+  const uint64_t eps = 16 / elem_bytes;
+  return (n + phase + eps - 1) / eps;
+}
 
-constexpr int kFlagMask = MCF_GROW_TWOSUM | MCF_FMT_FP16;
+constexpr int kFmtMask = 3 << kFmtShift;
+constexpr int kFlagMask = MCF_GROW_TWOSUM | kFmtMask;
+inline int format_of(int variant) { return (variant >> kFmtShift) & 3; }
+inline uint32_t elem_bytes_of(int component) { return component >= MCF_COMPONENT_FP8_E5M2 ? 1u : 2u; }
 
 inline bool known_variant(int v) {
   const int base = v & ~kFlagMask;
@@ -785,14 +855,15 @@ inline bool known_variant(int v) {
 }
 
 int check_tensor(const mcf_tensor &t, int variant) {
+  const uintptr_t eb = elem_bytes_of(format_of(variant));
   variant &= ~kFlagMask;
   if (t.n == 0) return MCF_OK;
   const bool need_dth = variant != MCF_BF16, need_dv = variant == MCF_PLUS, need_v = variant != MCF_SGD;
   if (!t.theta || !t.m || !t.grad) return MCF_ERR_NULL;
   if ((need_dth && !t.dtheta) || (need_dv && !t.dv) || (need_v && !t.v)) return MCF_ERR_NULL;
   if (t.n > kMaxTensorElems) return MCF_ERR_SIZE;
-  if (misaligned(t.theta, 2) || misaligned(t.m, 2) || misaligned(t.grad, 2) || (need_v && misaligned(t.v, 2)) ||
-      (need_dth && misaligned(t.dtheta, 2)) || (need_dv && misaligned(t.dv, 2)))
+  if (misaligned(t.theta, eb) || misaligned(t.m, eb) || misaligned(t.grad, eb) || (need_v && misaligned(t.v, eb)) ||
+      (need_dth && misaligned(t.dtheta, eb)) || (need_dv && misaligned(t.dv, eb)))
     return MCF_ERR_ALIGN;
   return MCF_OK;
 }
@@ -800,6 +871,7 @@ int check_tensor(const mcf_tensor &t, int variant) {
 // Streams a variant does not use point at theta (v for dv): they are never accessed and do
 // not disturb the alignment class.
 void fill_desc(const mcf_tensor &t, int variant, TensorDesc &d) {
+  const uint32_t eb = elem_bytes_of(format_of(variant));
   variant &= ~kFlagMask;
   d.p[S_TH] = (uint64_t)(uintptr_t)t.theta;
   d.p[S_DTH] = variant != MCF_BF16 ? (uint64_t)(uintptr_t)t.dtheta : d.p[S_TH];
@@ -808,7 +880,7 @@ void fill_desc(const mcf_tensor &t, int variant, TensorDesc &d) {
   d.p[S_G] = (uint64_t)(uintptr_t)t.grad;
   d.p[S_DV] = variant == MCF_PLUS ? (uint64_t)(uintptr_t)t.dv : d.p[S_V];
   d.n = t.n;
-  phase_of(d.p, 6, d.phase, d.scalar_only, MCF_CHUNK_ALIGN);
+  phase_of(d.p, 6, d.phase, d.scalar_only, MCF_CHUNK_ALIGN, eb);
 }
 
 // Scalars of one step for both formats; fast = the bf16 Fast mode may be used with them.
@@ -826,39 +898,45 @@ void launch_step(bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *de
 #else
   const dim3 g(blocks), b(kStepBlock);
 #endif
-  if constexpr ((VARIANT & kHalfBit) != 0) {
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, StepStreams<VARIANT>::kLdsEdq, st, descs, chunks, flat, hs.hf, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, StepStreams<VARIANT>::kLds, st, descs, chunks, flat, hs.hf, partials, blocks);
-  } else if (hs.fast) {
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, StepStreams<VARIANT>::kLdsEdq, st, descs, chunks, flat, hs.bf, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, StepStreams<VARIANT>::kLds, st, descs, chunks, flat, hs.bf, partials, blocks);
-  } else {
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, StepStreams<VARIANT>::kLdsEdq, st, descs, chunks, flat, hs.bf, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, StepStreams<VARIANT>::kLds, st, descs, chunks, flat, hs.bf, partials, blocks);
+  using SS = StepStreams<VARIANT>;
+  if constexpr (SS::kFmt == MCF_COMPONENT_FP16) {
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, SS::kLdsEdq, st, descs, chunks, flat, hs.hf, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, SS::kLds, st, descs, chunks, flat, hs.hf, partials, blocks);
+  } else if (hs.fast) {          // always set for FP8: its one mode has no restrictions
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, SS::kLdsEdq, st, descs, chunks, flat, hs.bf, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, SS::kLds, st, descs, chunks, flat, hs.bf, partials, blocks);
+  } else if constexpr (SS::kBf16) {
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, SS::kLdsEdq, st, descs, chunks, flat, hs.bf, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, SS::kLds, st, descs, chunks, flat, hs.bf, partials, blocks);
   }
 }
 
 template <bool TABLE, int FMT>
 void launch_format(int variant, bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs,
                    const Chunk *chunks, const TensorDesc &flat, const HostScalars &hs, double *partials) {
-  switch (variant & ~MCF_FMT_FP16) {
+  constexpr int F = FMT << kFmtShift;
+  switch (variant & ~kFmtMask) {
     case MCF_LIGHT | MCF_GROW_TWOSUM:
-      launch_step<mcfd::V_LIGHT | kGrow2Bit | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+      launch_step<mcfd::V_LIGHT | kGrow2Bit | F, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
     case MCF_PLUS | MCF_GROW_TWOSUM:
-      launch_step<mcfd::V_PLUS | kGrow2Bit | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
-    case MCF_PLUS: launch_step<mcfd::V_PLUS | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
-    case MCF_BF16: launch_step<mcfd::V_BF16 | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
-    case MCF_KAHAN: launch_step<mcfd::V_KAHAN | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
-    case MCF_SGD: launch_step<mcfd::V_SGD | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
-    default: launch_step<mcfd::V_LIGHT | FMT, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+      launch_step<mcfd::V_PLUS | kGrow2Bit | F, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    case MCF_PLUS: launch_step<mcfd::V_PLUS | F, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    case MCF_BF16: launch_step<mcfd::V_BF16 | F, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    case MCF_KAHAN: launch_step<mcfd::V_KAHAN | F, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    case MCF_SGD: launch_step<mcfd::V_SGD | F, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    default: launch_step<mcfd::V_LIGHT | F, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
   }
 }
 
 template <bool TABLE>
 void launch_variant(int variant, bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs,
                     const Chunk *chunks, const TensorDesc &flat, const HostScalars &hs, double *partials) {
-  if (variant & MCF_FMT_FP16) launch_format<TABLE, kHalfBit>(variant, edq, blocks, st, descs, chunks, flat, hs, partials);
-  else launch_format<TABLE, 0>(variant, edq, blocks, st, descs, chunks, flat, hs, partials);
+  switch (format_of(variant)) {
+    case MCF_COMPONENT_FP16: launch_format<TABLE, MCF_COMPONENT_FP16>(variant, edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    case MCF_COMPONENT_FP8_E5M2: launch_format<TABLE, MCF_COMPONENT_FP8_E5M2>(variant, edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    case MCF_COMPONENT_FP8_E4M3: launch_format<TABLE, MCF_COMPONENT_FP8_E4M3>(variant, edq, blocks, st, descs, chunks, flat, hs, partials); break;
+    default: launch_format<TABLE, MCF_COMPONENT_BF16>(variant, edq, blocks, st, descs, chunks, flat, hs, partials); break;
+  }
 }
 
 // Reduce `count` partials (kEdqVals doubles each) to {EDQ, S1, S2, lost}; mid holds kEdqVals*kStage1Blocks doubles.
@@ -880,8 +958,12 @@ bool force_exact() {
 
 HostScalars host_scalars(const mcf_hyper &h, uint64_t step, int variant) {
   HostScalars hs = {};
-  if (variant & MCF_FMT_FP16) {
+  const int fmt = format_of(variant);
+  if (fmt == MCF_COMPONENT_FP16) {
     mcfh::derive_scalars_fp16(h, step, hs.hf);
+    hs.fast = true;
+  } else if (fmt != MCF_COMPONENT_BF16) {
+    mcfh::derive_scalars_fp8(h, step, fmt == MCF_COMPONENT_FP8_E4M3, hs.bf);
     hs.fast = true;
   } else {
     hs.fast = mcfh::derive_scalars(h, step, hs.bf) && !force_exact();
@@ -889,21 +971,21 @@ HostScalars host_scalars(const mcf_hyper &h, uint64_t step, int variant) {
   return hs;
 }
 
-template <bool HALF>
+template <int FMT>
 int prim_dispatch(int op, const dim3 &g, const dim3 &b, hipStream_t st, const PrimArgs &a) {
   switch (op) {
-    case P_FAST2SUM: hipLaunchKernelGGL((prim_kernel<P_FAST2SUM, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_TWOSUM: hipLaunchKernelGGL((prim_kernel<P_TWOSUM, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_GROW: hipLaunchKernelGGL((prim_kernel<P_GROW, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_ADD: hipLaunchKernelGGL((prim_kernel<P_ADD, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_SUB: hipLaunchKernelGGL((prim_kernel<P_SUB, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_MUL: hipLaunchKernelGGL((prim_kernel<P_MUL, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_DIV: hipLaunchKernelGGL((prim_kernel<P_DIV, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_SQRT: hipLaunchKernelGGL((prim_kernel<P_SQRT, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_GROW2: hipLaunchKernelGGL((prim_kernel<P_GROW2, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_TWOPROD: hipLaunchKernelGGL((prim_kernel<P_TWOPROD, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_SCALING: hipLaunchKernelGGL((prim_kernel<P_SCALING, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
-    case P_MULX: hipLaunchKernelGGL((prim_kernel<P_MULX, HALF>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_FAST2SUM: hipLaunchKernelGGL((prim_kernel<P_FAST2SUM, FMT>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_TWOSUM: hipLaunchKernelGGL((prim_kernel<P_TWOSUM, FMT>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_GROW: hipLaunchKernelGGL((prim_kernel<P_GROW, FMT>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_ADD: hipLaunchKernelGGL((prim_kernel<P_ADD, FMT>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_SUB: hipLaunchKernelGGL((prim_kernel<P_SUB, FMT>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_MUL: hipLaunchKernelGGL((prim_kernel<P_MUL, FMT>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_DIV: hipLaunchKernelGGL((prim_kernel<P_DIV, FMT>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_SQRT: hipLaunchKernelGGL((prim_kernel<P_SQRT, FMT>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_GROW2: hipLaunchKernelGGL((prim_kernel<P_GROW2, FMT>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_TWOPROD: hipLaunchKernelGGL((prim_kernel<P_TWOPROD, FMT>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_SCALING: hipLaunchKernelGGL((prim_kernel<P_SCALING, FMT>), g, b, 0, st, a, 0u, 0u, nullptr); break;
+    case P_MULX: hipLaunchKernelGGL((prim_kernel<P_MULX, FMT>), g, b, 0, st, a, 0u, 0u, nullptr); break;
     default: return MCF_ERR_VARIANT;
   }
   return MCF_OK;
@@ -912,29 +994,36 @@ int prim_dispatch(int op, const dim3 &g, const dim3 &b, hipStream_t st, const Pr
 int prim_launch(int format, int op, const void *p0, const void *p1, const void *p2, const void *p3, const void *p4,
                        int nptr, uint64_t n, void *stream, const void *p5 = nullptr) {
   const void *ps[6] = {p0, p1, p2, p3, p4, p5};
+  const uint32_t eb = elem_bytes_of(format);
   PrimArgs a = {};
   uint64_t al[6];
   int na = 0;
   for (int i = 0; i < nptr; ++i) {
     a.p[i] = (uint64_t)(uintptr_t)ps[i];
     if (ps[i]) {
-      if (misaligned(ps[i], 2)) return MCF_ERR_ALIGN;
+      if (misaligned(ps[i], eb)) return MCF_ERR_ALIGN;
       al[na++] = a.p[i];
     }
   }
   if (n > kMaxTensorElems) return MCF_ERR_SIZE;
   a.n = n;
-  phase_of(al, na, a.phase, a.scalar_only);
-  const uint64_t slots = slots_of(n, a.phase);
+  phase_of(al, na, a.phase, a.scalar_only, 16, eb);
+  const uint64_t slots = slots_of(n, a.phase, eb);
   const dim3 g((uint32_t)((slots + kBlock - 1) / kBlock)), b(kBlock);
   hipStream_t st = (hipStream_t)stream;
-  const int rc = format == MCF_COMPONENT_FP16 ? prim_dispatch<true>(op, g, b, st, a) : prim_dispatch<false>(op, g, b, st, a);
+  int rc;
+  switch (format) {
+    case MCF_COMPONENT_FP16: rc = prim_dispatch<MCF_COMPONENT_FP16>(op, g, b, st, a); break;
+    case MCF_COMPONENT_FP8_E5M2: rc = prim_dispatch<MCF_COMPONENT_FP8_E5M2>(op, g, b, st, a); break;
+    case MCF_COMPONENT_FP8_E4M3: rc = prim_dispatch<MCF_COMPONENT_FP8_E4M3>(op, g, b, st, a); break;
+    default: rc = prim_dispatch<MCF_COMPONENT_BF16>(op, g, b, st, a); break;
+  }
   if (rc != MCF_OK) return rc;
   MCF_HIP(hipGetLastError());
   return MCF_OK;
 }
 
-inline bool known_component(int c) { return c == MCF_COMPONENT_BF16 || c == MCF_COMPONENT_FP16; }
+inline bool known_component(int c) { return c >= MCF_COMPONENT_BF16 && c <= MCF_COMPONENT_FP8_E4M3; }
 
 }  // namespace
 
@@ -986,7 +1075,7 @@ int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, i
     if (tensors[i].n == 0) continue;
     TensorDesc d;
     fill_desc(tensors[i], variant, d);
-    const uint64_t slots = slots_of(d.n, d.phase);
+    const uint64_t slots = slots_of(d.n, d.phase, elem_bytes_of(format_of(variant)));
     const uint64_t nch = (slots + kSlotsPerChunk - 1) / kSlotsPerChunk;
     if (chunks.size() + nch > 0x7fffffffull) return MCF_ERR_SIZE;
     const uint32_t id = (uint32_t)descs.size();
@@ -1056,17 +1145,20 @@ int mcf_step_scalars(int component, const mcf_hyper *hyper, uint64_t step, uint1
   if (!out) return MCF_ERR_NULL;
   const int rc = mcfh::check_hyper(hyper, step);
   if (rc != MCF_OK) return rc;
-  const mcfh::ScalarBits b = component == MCF_COMPONENT_FP16 ? mcfh::scalar_bits_fp16(*hyper, step) : mcfh::scalar_bits_bf16(*hyper, step);
+  const mcfh::ScalarBits b = component == MCF_COMPONENT_FP16       ? mcfh::scalar_bits_fp16(*hyper, step)
+                             : component == MCF_COMPONENT_FP8_E5M2 ? mcfh::scalar_bits_e5m2(*hyper, step)
+                             : component == MCF_COMPONENT_FP8_E4M3 ? mcfh::scalar_bits_e4m3(*hyper, step)
+                                                                   : mcfh::scalar_bits_bf16(*hyper, step);
   for (int i = 0; i < mcfh::K_COUNT; ++i) out[i] = b.v[i];
   if (restricted_mode_ok) {
     StepScalars unused;
-    *restricted_mode_ok = component == MCF_COMPONENT_FP16 ? 1 : (mcfh::derive_scalars(*hyper, step, unused) && !force_exact()) ? 1 : 0;
+    *restricted_mode_ok = component != MCF_COMPONENT_BF16 ? 1 : (mcfh::derive_scalars(*hyper, step, unused) && !force_exact()) ? 1 : 0;
   }
   return MCF_OK;
 }
 
-int mcf_adamw_step_flat(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t *v, uint16_t *dv,
-                        const uint16_t *grad, uint64_t n, int variant, const mcf_hyper *hyper,
+int mcf_adamw_step_flat(void *theta, void *dtheta, void *m, void *v, void *dv,
+                        const void *grad, uint64_t n, int variant, const mcf_hyper *hyper,
                         uint64_t step, void *stream) {
   if (!known_variant(variant)) return MCF_ERR_VARIANT;
   const mcf_tensor t = {theta, dtheta, m, v, dv, grad, n};
@@ -1077,15 +1169,15 @@ int mcf_adamw_step_flat(uint16_t *theta, uint16_t *dtheta, uint16_t *m, uint16_t
   if (n == 0) return MCF_OK;
   TensorDesc d;
   fill_desc(t, variant, d);
-  const uint64_t nch = (slots_of(d.n, d.phase) + kSlotsPerChunk - 1) / kSlotsPerChunk;
+  const uint64_t nch = (slots_of(d.n, d.phase, elem_bytes_of(format_of(variant))) + kSlotsPerChunk - 1) / kSlotsPerChunk;
   const HostScalars hs = host_scalars(*hyper, step, variant);
   launch_variant<false>(variant, false, (uint32_t)nch, (hipStream_t)stream, nullptr, nullptr, d, hs, nullptr);
   MCF_HIP(hipGetLastError());
   return MCF_OK;
 }
 
-int mcf_primitive(int component, int which, const uint16_t *p0, const uint16_t *p1, const uint16_t *p2, const uint16_t *p3,
-                  uint16_t *o0, uint16_t *o1, uint64_t n, void *stream) {
+int mcf_primitive(int component, int which, const void *p0, const void *p1, const void *p2, const void *p3,
+                  void *o0, void *o1, uint64_t n, void *stream) {
   static const int ops[7] = {P_FAST2SUM, P_TWOSUM, P_GROW, P_GROW2, P_TWOPROD, P_SCALING, P_MULX};
   static const int nin[7] = {2, 2, 3, 3, 2, 3, 4};
   if (!known_component(component) || which < 0 || which > 6) return MCF_ERR_VARIANT;
@@ -1128,7 +1220,7 @@ int mcf_mul(const uint16_t *a1, const uint16_t *a2, const uint16_t *b1, const ui
   return mcf_primitive(MCF_COMPONENT_BF16, MCF_PRIM_MUL, a1, a2, b1, b2, x, e, n, stream);
 }
 
-int mcf_component_op(int component, int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uint64_t n, void *stream) {
+int mcf_component_op(int component, int op, const void *a, const void *b, void *out, uint64_t n, void *stream) {
   if (!known_component(component) || op < 0 || op > 4) return MCF_ERR_VARIANT;
   if (n == 0) return MCF_OK;
   if (!a || !out || (op != 4 && !b)) return MCF_ERR_NULL;
@@ -1141,18 +1233,23 @@ int mcf_bf16_op(int op, const uint16_t *a, const uint16_t *b, uint16_t *out, uin
   return mcf_component_op(MCF_COMPONENT_BF16, op, a, b, out, n, stream);
 }
 
-int mcf_round_f32_to(int component, const float *in, uint16_t *out, uint64_t n, void *stream) {
+int mcf_round_f32_to(int component, const float *in, void *out, uint64_t n, void *stream) {
   if (!known_component(component)) return MCF_ERR_VARIANT;
   if (n == 0) return MCF_OK;
   if (!in || !out) return MCF_ERR_NULL;
-  if (misaligned(in, 4) || misaligned(out, 2)) return MCF_ERR_ALIGN;
+  if (misaligned(in, 4) || misaligned(out, elem_bytes_of(component))) return MCF_ERR_ALIGN;
   const uint64_t lanes = (n + 1) / 2;
   const uint64_t blocks = (lanes + kBlock - 1) / kBlock;
   if (blocks > 0x7fffffffull) return MCF_ERR_SIZE;
-  if (component == MCF_COMPONENT_FP16)
-    hipLaunchKernelGGL(round_kernel<true>, dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, in, out, n);
-  else
-    hipLaunchKernelGGL(round_kernel<false>, dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, in, out, n);
+  const dim3 g((uint32_t)blocks), b(kBlock);
+  const uint64_t o = (uint64_t)(uintptr_t)out;
+  hipStream_t st = (hipStream_t)stream;
+  switch (component) {
+    case MCF_COMPONENT_FP16: hipLaunchKernelGGL(round_kernel<MCF_COMPONENT_FP16>, g, b, 0, st, in, o, n); break;
+    case MCF_COMPONENT_FP8_E5M2: hipLaunchKernelGGL(round_kernel<MCF_COMPONENT_FP8_E5M2>, g, b, 0, st, in, o, n); break;
+    case MCF_COMPONENT_FP8_E4M3: hipLaunchKernelGGL(round_kernel<MCF_COMPONENT_FP8_E4M3>, g, b, 0, st, in, o, n); break;
+    default: hipLaunchKernelGGL(round_kernel<MCF_COMPONENT_BF16>, g, b, 0, st, in, o, n); break;
+  }
   MCF_HIP(hipGetLastError());
   return MCF_OK;
 }
@@ -1179,8 +1276,8 @@ uint64_t mcf_edq_scratch_bytes(uint64_t n) {
   return (uint64_t)kEdqVals * (blocks + kStage1Blocks) * sizeof(double);
 }
 
-int mcf_edq_component(int component, const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
-                      const uint16_t *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev) {
+int mcf_edq_component(int component, const void *delta, const void *th0, const void *dth0, const void *th1,
+                      const void *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev) {
   if (!known_component(component)) return MCF_ERR_VARIANT;
   if (!edq_dev) return MCF_ERR_NULL;
   if (misaligned(edq_dev, 8)) return MCF_ERR_ALIGN;
@@ -1190,8 +1287,9 @@ int mcf_edq_component(int component, const uint16_t *delta, const uint16_t *th0,
   double *partials = (double *)scratch_dev;
   // stream order: delta, th0, th1, dth0, dth1 (absent second components are not read)
   const void *ps[5] = {delta, th0, th1, dth0, dth1};
+  const uint32_t eb = elem_bytes_of(component);
   for (int i = 0; i < 5; ++i)
-    if (ps[i] && misaligned(ps[i], 2)) return MCF_ERR_ALIGN;
+    if (ps[i] && misaligned(ps[i], eb)) return MCF_ERR_ALIGN;
   PrimArgs a = {};
   uint64_t al[5];
   int na = 0;
@@ -1201,14 +1299,17 @@ int mcf_edq_component(int component, const uint16_t *delta, const uint16_t *th0,
   }
   if (n > kMaxTensorElems) return MCF_ERR_SIZE;
   a.n = n;
-  phase_of(al, na, a.phase, a.scalar_only);
-  const uint64_t blocks = (slots_of(n, a.phase) + kBlock - 1) / kBlock;
-  if (component == MCF_COMPONENT_FP16)
-    hipLaunchKernelGGL((prim_kernel<P_EDQ, true>), dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, a,
-                       dth0 ? 1u : 0u, dth1 ? 1u : 0u, partials);
-  else
-    hipLaunchKernelGGL((prim_kernel<P_EDQ, false>), dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream, a,
-                       dth0 ? 1u : 0u, dth1 ? 1u : 0u, partials);
+  phase_of(al, na, a.phase, a.scalar_only, 16, eb);
+  const uint64_t blocks = (slots_of(n, a.phase, eb) + kBlock - 1) / kBlock;
+  const dim3 g((uint32_t)blocks), b(kBlock);
+  hipStream_t st = (hipStream_t)stream;
+  const uint32_t h0 = dth0 ? 1u : 0u, h1 = dth1 ? 1u : 0u;
+  switch (component) {
+    case MCF_COMPONENT_FP16: hipLaunchKernelGGL((prim_kernel<P_EDQ, MCF_COMPONENT_FP16>), g, b, 0, st, a, h0, h1, partials); break;
+    case MCF_COMPONENT_FP8_E5M2: hipLaunchKernelGGL((prim_kernel<P_EDQ, MCF_COMPONENT_FP8_E5M2>), g, b, 0, st, a, h0, h1, partials); break;
+    case MCF_COMPONENT_FP8_E4M3: hipLaunchKernelGGL((prim_kernel<P_EDQ, MCF_COMPONENT_FP8_E4M3>), g, b, 0, st, a, h0, h1, partials); break;
+    default: hipLaunchKernelGGL((prim_kernel<P_EDQ, MCF_COMPONENT_BF16>), g, b, 0, st, a, h0, h1, partials); break;
+  }
   MCF_HIP(hipGetLastError());
   return launch_edq_tail(partials, blocks, partials + kEdqVals * blocks, edq_dev, (hipStream_t)stream);
 }

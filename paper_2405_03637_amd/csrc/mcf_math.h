@@ -87,6 +87,8 @@ template <class R> struct Bf {
   using S = float;     // a wave-uniform scalar
   static constexpr bool kFast = R::kFast;      // may raise redo
   static constexpr bool kHalf = false;
+  static constexpr bool kGuarded = R::kFast;   // the reciprocal routes need operands checked for range (single operations)
+  static constexpr int kBytes = 2;             // bytes per stored element
   static __device__ __forceinline__ T unpack(uint32_t w) { return widen2(w); }
   static __device__ __forceinline__ uint32_t pack(T x) { return pack2(x); }
   static __device__ __forceinline__ T zero() { return {0.f, 0.f}; }
@@ -153,6 +155,8 @@ template <bool HOT> struct Hf {
   using S = h2_t;      // a scalar is the same value in both halves
   static constexpr bool kFast = HOT;
   static constexpr bool kHalf = true;
+  static constexpr bool kGuarded = false;
+  static constexpr int kBytes = 2;
   static __device__ __forceinline__ T unpack(uint32_t w) { return __builtin_bit_cast(h2_t, w); }
   static __device__ __forceinline__ uint32_t raw(T x) { return __builtin_bit_cast(uint32_t, x); }
   // What is stored: the raw pair on the vector path (which has checked that it holds no NaN), the pair
@@ -194,6 +198,88 @@ template <bool HOT> struct Hf {
 };
 using HalfHot = Hf<true>;
 using HalfCold = Hf<false>;
+
+// ---- FP8 --------------------------------------------------------------------------------
+// The two 8-bit formats of App. A Table 7 (the 8-bit extension named in Sec. 7): E5M2, IEEE-style
+// with infinities, and E4M3 without infinities (largest 448, only S.1111.111 is NaN, whatever rounds
+// beyond 448 becomes NaN).  gfx950 converts both in hardware, round to nearest even, non-saturating,
+// which is exactly that reading (checked against the definition over all 2^32 fp32 inputs by the test
+// suite).  A pair is held widened in two fp32 registers as for bf16; F(a o b) is the fp32 operation,
+// one v_cvt_pk_{bf8,fp8}_f32 for the pair and one v_cvt_f32_{bf8,fp8} per element to widen it back.
+// Division is the corrected quotient of the fp16 mode (exact whenever a/b is an fp32 number, so the
+// exact ties that do occur among subnormal results survive; every other quotient of two 3- or 4-bit
+// numbers is further than 2^-12 from a rounding boundary); the square root is v_sqrt_f32 (1 ulp): the
+// root of an 8-bit number is never a rounding boundary and stays more than 2^-12 away from one.  Both
+// are checked over every operand pair and every input.  Widened operands are normal fp32 numbers or
+// zero, so no range guards are needed.  NaN: as for fp16, the first pass detects, the redo stores the
+// format's one NaN (0x7E, 0x7F).
+template <bool E4M3> struct F8Cvt {
+  // two fp32 -> two 8-bit patterns in the low (HIGH = false) or high half of `old`
+  template <bool HIGH> static __device__ __forceinline__ uint32_t enc(float a, float b, uint32_t old) {
+    if constexpr (E4M3) return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, HIGH);
+    else return (uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(a, b, (int)old, HIGH);
+  }
+  template <int BYTE> static __device__ __forceinline__ float dec(uint32_t w) {
+    if constexpr (E4M3) return __builtin_amdgcn_cvt_f32_fp8((int)w, BYTE);
+    else return __builtin_amdgcn_cvt_f32_bf8((int)w, BYTE);
+  }
+  static __device__ __forceinline__ uint32_t canon(uint32_t b) {      // one 8-bit pattern
+    if constexpr (E4M3) return (b & 0x7fu) == 0x7fu ? 0x7fu : b;
+    else return (b & 0x7fu) > 0x7cu ? 0x7eu : b;
+  }
+};
+
+// a / b from r ~ 1/b: q + (a - b*q)*r, keeping q where the correction is NaN (zero or infinite operand)
+// or zero (sign of a zero dividend).
+__device__ __forceinline__ float div_corrected(float a, float b, float r) {
+  const float q = a * r;
+  const float res = __builtin_fmaf(-b, q, a);
+  const float q1 = __builtin_fmaf(res, r, q);
+  return __builtin_fabsf(q1) > 0.0f ? q1 : q;
+}
+
+template <bool E4M3, bool HOT> struct F8 {
+  using C = F8Cvt<E4M3>;
+  using T = P2;
+  using S = float;
+  static constexpr bool kFast = HOT;       // may raise redo (NaN among the results)
+  static constexpr bool kHalf = false;
+  static constexpr bool kGuarded = false;
+  static constexpr int kBytes = 1;
+  // pair PAIR (0 or 1) of the four elements in a dword
+  template <int PAIR> static __device__ __forceinline__ T unpack(uint32_t w) { return {C::template dec<2 * PAIR>(w), C::template dec<2 * PAIR + 1>(w)}; }
+  static __device__ __forceinline__ T unpack(uint32_t w) { return unpack<0>(w); }
+  static __device__ __forceinline__ uint32_t pack(T a, T b) {          // four elements -> one dword
+    uint32_t w = C::template enc<false>(a.lo, a.hi, 0u);
+    w = C::template enc<true>(b.lo, b.hi, w);
+    if (HOT) return w;
+    return C::canon(w & 0xffu) | (C::canon((w >> 8) & 0xffu) << 8) | (C::canon((w >> 16) & 0xffu) << 16) | (C::canon(w >> 24) << 24);
+  }
+  static __device__ __forceinline__ T zero() { return {0.f, 0.f}; }
+  static __device__ __forceinline__ float lo(T x) { return x.lo; }
+  static __device__ __forceinline__ float hi(T x) { return x.hi; }
+  static __device__ __forceinline__ uint16_t bits_lo(T x) { return (uint16_t)C::canon(C::template enc<false>(x.lo, x.hi, 0u) & 0xffu); }
+  static __device__ __forceinline__ uint16_t bits_hi(T x) { return (uint16_t)C::canon((C::template enc<false>(x.lo, x.hi, 0u) >> 8) & 0xffu); }
+  static __device__ __forceinline__ bool any_nan(T x) { return is_nan(x.lo) | is_nan(x.hi); }
+  static __device__ __forceinline__ T rnd(T x) {
+    const uint32_t w = C::template enc<false>(x.lo, x.hi, 0u);
+    return {C::template dec<0>(w), C::template dec<1>(w)};
+  }
+  static __device__ __forceinline__ T round_f32(float a, float b) { return rnd({a, b}); }
+
+  static __device__ __forceinline__ T add(T a, T b) { return rnd({a.lo + b.lo, a.hi + b.hi}); }
+  static __device__ __forceinline__ T sub(T a, T b) { return rnd({a.lo - b.lo, a.hi - b.hi}); }
+  static __device__ __forceinline__ T mul(T a, T b) { return rnd({a.lo * b.lo, a.hi * b.hi}); }
+  static __device__ __forceinline__ T adds(T a, S s) { return rnd({a.lo + s, a.hi + s}); }
+  static __device__ __forceinline__ T muls(S s, T a) { return rnd({s * a.lo, s * a.hi}); }
+  static __device__ __forceinline__ T fmss(S s, T a, T x) { return rnd({__builtin_fmaf(s, a.lo, -x.lo), __builtin_fmaf(s, a.hi, -x.hi)}); }
+  static __device__ __forceinline__ T fms(T a, T b, T x) { return rnd({__builtin_fmaf(a.lo, b.lo, -x.lo), __builtin_fmaf(a.hi, b.hi, -x.hi)}); }
+  static __device__ __forceinline__ T divs(T a, S b, S rb, bool &) { return rnd({div_corrected(a.lo, b, rb), div_corrected(a.hi, b, rb)}); }
+  static __device__ __forceinline__ T divg(T a, T b, bool &) {
+    return rnd({div_corrected(a.lo, b.lo, __builtin_amdgcn_rcpf(b.lo)), div_corrected(a.hi, b.hi, __builtin_amdgcn_rcpf(b.hi))});
+  }
+  static __device__ __forceinline__ T sqrt(T a, bool &) { return rnd({__builtin_amdgcn_sqrtf(a.lo), __builtin_amdgcn_sqrtf(a.hi)}); }
+};
 
 // The expansion algorithms over any of the modes above.
 template <class M> struct Ops : M {

@@ -29,6 +29,12 @@ def fp16_hyper(h):
     return (lr, b1, b2, eps * FP16_LOSS_SCALE, wd)
 
 
+# FP8 components (3 or 4 significant bits; E4M3 spans 2^-9 .. 448): hyper-parameters that both formats
+# hold, or round to something usable -- E4M3 would turn a learning rate of 3e-4 into 0 -- and the same
+# loss scale on the gradients.  beta2 = 15/16 is an E4M3 number and, in E5M2, the expansion (1, -1/16).
+HYPER_FP8 = (2.0 ** -6, 0.875, 0.9375, 2.0 ** -6, 0.125)
+
+
 def gpt_shapes(n_layer, d, ffn, vocab, n_pos):
     """GPT-2 style list: embeddings, per-layer {ln1, qkv, proj, ln2, fc, fc2} with biases, final ln."""
     out = [("wte", vocab * d), ("wpe", n_pos * d)]

@@ -37,20 +37,21 @@ class Workload:
     """Device state of one named workload and its plan."""
 
     def __init__(self, name, device="cuda", misalign_tiny=False, seed=0, variant=None, shape_list=None, hyper=None,
-                 align=8, fp16=False):
+                 align=8, fp16=False, fmt=None):
         self.name = name
         self.shapes = shape_list if shape_list is not None else W.shapes(name)
         vname = variant or W.WORKLOADS[name][1]
         self.variant = {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN,
                         "sgd": mcf.SGD, "light+twosum": mcf.LIGHT | mcf.GROW_TWOSUM, "plus+twosum": mcf.PLUS | mcf.GROW_TWOSUM}[vname]
-        self.fp16 = fp16
-        self.hyper = hyper or (W.fp16_hyper(W.WORKLOADS[name][2]) if fp16 else W.WORKLOADS[name][2])
-        if fp16:
-            self.variant |= mcf.FMT_FP16           # the same bit is the oracle's STEP_FP16
+        self.fmt = fmt if fmt is not None else (1 if fp16 else 0)        # component format id, the same in the library and the oracle
+        self.fp16 = self.fmt == 1
+        self.hyper = hyper or (W.HYPER_FP8 if self.fmt >= 2 else W.fp16_hyper(W.WORKLOADS[name][2]) if self.fp16 else W.WORKLOADS[name][2])
+        self.variant |= self.fmt << 12             # the flag bits are the same in the library and the oracle
+        self.dtype = (torch.bfloat16, torch.float16, torch.float8_e5m2, torch.float8_e4m3fn)[self.fmt]
         self.offs, self.total = W.layout(self.shapes, misalign_tiny=misalign_tiny, align=align)
         self.seed = seed
         self.device = device
-        z = lambda: torch.zeros(self.total, dtype=torch.float16 if fp16 else torch.bfloat16, device=device)
+        z = lambda: torch.zeros(self.total, dtype=torch.uint8 if self.fmt >= 2 else self.dtype, device=device).view(self.dtype)
         base = self.variant & 0xFF
         self.theta, self.m = z(), z()
         self.v = z() if base != mcf.SGD else None
@@ -76,9 +77,11 @@ class Workload:
 
     def new_grads(self, step):
         W.fill_grads(self.name, self.shapes, self.offs, self.grad, step, seed=self.seed, sigmas=self.sigmas,
-                     drift=self.drift, grad_scale=W.FP16_LOSS_SCALE if self.fp16 else 1.0)
+                     drift=self.drift, grad_scale=W.FP16_LOSS_SCALE if self.fmt else 1.0)
 
     def gather(self, tensor, idx_dev):
+        if tensor.element_size() == 1:
+            tensor = tensor.view(torch.uint8)           # index the patterns, not a float8 tensor
         return H.torch_to_u16(tensor[idx_dev])
 
     def close(self):
@@ -147,7 +150,7 @@ def full_oracle_run(wl, steps, edq=False, check_each=True):
                 assert not dev[~live].any()
                 host[k][~live] = 0
         if edq:
-            acc = orc.EdqAccumulator(fmt=orc.FMT_FP16 if wl.fp16 else orc.FMT_BF16)
+            acc = orc.EdqAccumulator(fmt=wl.fmt)
             for (_, n), o in zip(wl.shapes, wl.offs):
                 sl = slice(o, o + n)
                 d0 = before["dtheta"][sl].copy() if "dtheta" in host else None

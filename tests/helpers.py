@@ -127,15 +127,21 @@ def bf16_window(emin, emax, signs=True):
 
 
 def torch_to_u16(t):
+    """Bit patterns of a bf16/fp16 tensor, or of an FP8/uint8 tensor (one 8-bit pattern per uint16), as numpy uint16."""
     import torch
-    assert t.dtype in (torch.bfloat16, torch.float16)
-    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16).copy()
+    if t.dtype in (torch.bfloat16, torch.float16):
+        return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16).copy()
+    assert t.element_size() == 1
+    return t.detach().cpu().contiguous().view(torch.uint8).numpy().astype(np.uint16)
 
 
 def u16_to_torch(u, device="cpu", dtype=None):
     """16-bit patterns -> a torch tensor of dtype bfloat16 (default) or float16 holding those patterns."""
     import torch
-    return torch.from_numpy(np.ascontiguousarray(u).view(np.int16).copy()).view(dtype or torch.bfloat16).to(device)
+    dtype = dtype or torch.bfloat16
+    if dtype in (torch.bfloat16, torch.float16):
+        return torch.from_numpy(np.ascontiguousarray(u).view(np.int16).copy()).view(dtype).to(device)
+    return torch.from_numpy(np.ascontiguousarray(u).astype(np.uint8)).view(dtype).to(device)      # FP8: low byte of each pattern
 
 
 def read_golden(path):

@@ -56,7 +56,11 @@ def test_flat_step_argument_errors():
     assert _flat(variant=mcf.SGD | mcf.GROW_TWOSUM) == mcf.MCF_ERR_VARIANT
     assert _flat(variant=mcf.BF16 | mcf.GROW_TWOSUM) == mcf.MCF_ERR_VARIANT     # the flag applies to Collage only
     assert _flat(variant=mcf.LIGHT | 0x200) == mcf.MCF_ERR_VARIANT
-    assert _flat(variant=mcf.LIGHT | 0x2000) == mcf.MCF_ERR_VARIANT
+    assert _flat(variant=mcf.LIGHT | 0x4000) == mcf.MCF_ERR_VARIANT
+    assert _flat(variant=mcf.SGD | mcf.GROW_TWOSUM | mcf.FMT_FP8_E4M3) == mcf.MCF_ERR_VARIANT
+    assert _flat(variant=mcf.LIGHT | mcf.FMT_FP8_E5M2, step=0) == mcf.MCF_ERR_STEP
+    assert _flat(variant=mcf.LIGHT | mcf.FMT_FP8_E5M2, m=FAKE + 1, n=0) == mcf.MCF_OK
+    assert _flat(variant=mcf.LIGHT | mcf.FMT_FP16, m=FAKE + 1) == mcf.MCF_ERR_ALIGN      # 2-byte elements need 2-byte alignment
     assert _flat(variant=mcf.SGD | mcf.GROW_TWOSUM | mcf.FMT_FP16) == mcf.MCF_ERR_VARIANT
     assert _flat(variant=mcf.PLUS | mcf.FMT_FP16, dv=None) == mcf.MCF_ERR_NULL       # the format flag changes no requirement
     assert _flat(variant=mcf.LIGHT | mcf.FMT_FP16, step=0) == mcf.MCF_ERR_STEP
@@ -136,13 +140,16 @@ def test_primitive_argument_errors():
     assert lib.mcf_edq(FAKE, FAKE, None, FAKE, None, 4, None, None, FAKE) == mcf.MCF_ERR_NULL
     assert lib.mcf_edq(FAKE, FAKE, None, FAKE + 1, None, 4, FAKE, None, FAKE) == mcf.MCF_ERR_ALIGN
     # the component-aware forms: unknown component or code, then the same pointer checks
-    assert lib.mcf_primitive(2, 0, FAKE, FAKE, None, None, FAKE, FAKE, 4, None) == mcf.MCF_ERR_VARIANT
+    assert lib.mcf_primitive(4, 0, FAKE, FAKE, None, None, FAKE, FAKE, 4, None) == mcf.MCF_ERR_VARIANT
+    assert lib.mcf_primitive(2, mcf.PRIM_GROW, FAKE, FAKE, None, None, FAKE, FAKE, 4, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_primitive(1, mcf.PRIM_FAST2SUM, FAKE + 1, FAKE, None, None, FAKE, FAKE, 4, None) == mcf.MCF_ERR_ALIGN
     assert lib.mcf_primitive(1, 7, FAKE, FAKE, None, None, FAKE, FAKE, 4, None) == mcf.MCF_ERR_VARIANT
     assert lib.mcf_primitive(1, mcf.PRIM_GROW, FAKE, FAKE, None, None, FAKE, FAKE, 4, None) == mcf.MCF_ERR_NULL
     assert lib.mcf_primitive(1, mcf.PRIM_MUL, FAKE, FAKE, FAKE, FAKE, FAKE, None, 4, None) == mcf.MCF_ERR_NULL
     assert lib.mcf_primitive(1, mcf.PRIM_MUL, FAKE, FAKE, FAKE, FAKE + 1, FAKE, FAKE, 4, None) == mcf.MCF_ERR_ALIGN
     assert lib.mcf_primitive(1, mcf.PRIM_FAST2SUM, None, None, None, None, None, None, 0, None) == mcf.MCF_OK
-    assert lib.mcf_component_op(3, 0, FAKE, FAKE, FAKE, 4, None) == mcf.MCF_ERR_VARIANT
+    assert lib.mcf_component_op(4, 0, FAKE, FAKE, FAKE, 4, None) == mcf.MCF_ERR_VARIANT
+    assert lib.mcf_component_op(3, 0, FAKE, None, FAKE, 4, None) == mcf.MCF_ERR_NULL
     assert lib.mcf_component_op(1, 5, FAKE, FAKE, FAKE, 4, None) == mcf.MCF_ERR_VARIANT
     assert lib.mcf_component_op(1, 0, FAKE, None, FAKE, 4, None) == mcf.MCF_ERR_NULL
     assert lib.mcf_round_f32_to(-1, FAKE, FAKE, 4, None) == mcf.MCF_ERR_VARIANT

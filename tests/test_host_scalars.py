@@ -12,6 +12,7 @@ from paper_2405_03637_amd import binding as mcf
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_values.txt")
 BF, HF = mcf.COMPONENT_BF16, mcf.COMPONENT_FP16
+E5, E4 = mcf.COMPONENT_FP8_E5M2, mcf.COMPONENT_FP8_E4M3
 
 
 def _scal(component, hyper, t):
@@ -71,9 +72,33 @@ def test_rounding_of_the_host_conversions_fp16():
         assert s["na"] == (int(w) | 0x8000), x
 
 
-@pytest.mark.parametrize("component", [BF, HF])
+def test_rounding_of_the_host_conversions_fp8():
+    """Against torch's float8 casts where the value stays in range, and the range rules by hand."""
+    import torch
+    rng = np.random.default_rng(7)
+    for comp, dt, top in ((E5, torch.float8_e5m2, 57344.0), (E4, torch.float8_e4m3fn, 448.0)):
+        every = torch.arange(0, 0x7C if comp == E5 else 0x7F, dtype=torch.int32).to(torch.uint8).view(dt).double().numpy()
+        mids = (every[:-1] + every[1:]) / 2
+        m32 = mids.astype(np.float32)                              # exact
+        xs = np.concatenate([(np.abs(rng.standard_normal(2000)) * 10.0 ** rng.integers(-6, 3, 2000)).astype(np.float32),
+                             every.astype(np.float32), m32, np.nextafter(m32, np.float32(np.inf)),
+                             np.nextafter(m32, np.float32(0))]).astype(np.float64)
+        xs = xs[xs <= top]
+        # torch casts through fp32, so the inputs are fp32 numbers: the cast is then one rounding
+        want = torch.from_numpy(xs.astype(np.float32)).to(dt).view(torch.uint8).numpy()
+        for x, w in zip(xs, want):
+            s = _scal(comp, (float(x), 0.9, 0.95, 1e-8, float(x)), 1)
+            assert s["lam"] == int(w), (comp, x, hex(s["lam"]), hex(int(w)))
+            assert s["na"] == (int(w) | 0x80), x
+    lam = lambda comp, x: _scal(comp, (0.0, 0.9, 0.95, 1e-8, x), 1)["lam"]
+    assert lam(E5, 61439.0) == 0x7B and lam(E5, 61440.0) == 0x7C and lam(E5, 1e30) == 0x7C          # tie at the top goes to infinity
+    assert lam(E4, 464.0) == 0x7E and lam(E4, 464.0001) == 0x7F and lam(E4, 1e30) == 0x7F           # tie stays, beyond is NaN
+    assert lam(E5, 2.0 ** -17) == 0 and lam(E5, 2.0 ** -17 * (1 + 2.0 ** -50)) == 1 and lam(E4, 2.0 ** -10) == 0     # one rounding from fp64
+
+
+@pytest.mark.parametrize("component", [BF, HF, E5, E4])
 def test_scalars_equal_the_oracles(orc, component):
-    fmt = orc.FMT_FP16 if component == HF else orc.FMT_BF16
+    fmt = component            # the oracle's format ids are the same numbers
     betas = [0.0, 0.5, 0.9, 0.95, 0.98, 0.99, 0.999, 0.99999, 1.0 - 1e-10]
     for b1 in betas:
         for b2 in betas:
@@ -97,7 +122,7 @@ def test_restricted_mode_report_and_errors():
     lib = mcf.lib()
     out = (ctypes.c_uint16 * 10)()
     h = mcf.Hyper(1e-3, 0.9, 0.95, 1e-8, 0.1)
-    assert lib.mcf_step_scalars(2, ctypes.byref(h), 1, out, None) == mcf.MCF_ERR_VARIANT
+    assert lib.mcf_step_scalars(4, ctypes.byref(h), 1, out, None) == mcf.MCF_ERR_VARIANT
     assert lib.mcf_step_scalars(0, None, 1, out, None) == mcf.MCF_ERR_NULL
     assert lib.mcf_step_scalars(0, ctypes.byref(h), 1, None, None) == mcf.MCF_ERR_NULL
     assert lib.mcf_step_scalars(0, ctypes.byref(h), 0, out, None) == mcf.MCF_ERR_STEP
