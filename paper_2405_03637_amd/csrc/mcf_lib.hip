@@ -325,12 +325,15 @@ template <int VARIANT> struct StepStreams {
   // 7-stream plain variant, whose divide and root have less memory time to hide behind, at 12 (14.24 ms
   // against 15.09 at 10), the 7-stream SGD at 10-11.  With the fp64 EDQ sums fused in there is more
   // arithmetic to hide: 14 (light 18.62 ms against 20.43 at 10), plain variant 16.
+  // The FP8 kernels move half the bytes with about the same arithmetic (a conversion to and from the
+  // 8-bit format around every operation) and are bound by the vector ALU, not by HBM: they run uncapped
+  // (light E5M2, 7B set: 16.7 ms at 10 groups per CU, 15.3 at 16, 15.0 uncapped).
 #ifdef MCF_STEP_LDS
   static constexpr uint32_t kLds = MCF_STEP_LDS;
 #else
-  static constexpr uint32_t kLds = lds_for_groups(kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? 11 : 10);
+  static constexpr uint32_t kLds = kEB == 1 ? 0 : lds_for_groups(kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? 11 : 10);
 #endif
-  static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : lds_for_groups(kBase == mcfd::V_BF16 ? 16 : 14);
+  static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : kEB == 1 ? 0 : lds_for_groups(kBase == mcfd::V_BF16 ? 16 : 14);
 };
 
 // A dword of a stream holds one pair (2-byte elements) or two pairs (1-byte elements).

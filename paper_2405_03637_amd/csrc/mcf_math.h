@@ -204,8 +204,8 @@ using HalfCold = Hf<false>;
 // with infinities, and E4M3 without infinities (largest 448, only S.1111.111 is NaN, whatever rounds
 // beyond 448 becomes NaN).  gfx950 converts both in hardware, round to nearest even, non-saturating,
 // which is exactly that reading (checked against the definition over all 2^32 fp32 inputs by the test
-// suite).  A pair is held widened in two fp32 registers as for bf16; F(a o b) is the fp32 operation,
-// one v_cvt_pk_{bf8,fp8}_f32 for the pair and one v_cvt_f32_{bf8,fp8} per element to widen it back.
+// suite).  A pair is held widened in two fp32 registers as for bf16; F(a o b) is the fp32 operation per
+// element, one v_cvt_pk_{bf8,fp8}_f32 for the pair and one v_cvt_pk_f32_{bf8,fp8} to widen it back.
 // Division is the corrected quotient of the fp16 mode (exact whenever a/b is an fp32 number, so the
 // exact ties that do occur among subnormal results survive; every other quotient of two 3- or 4-bit
 // numbers is further than 2^-12 from a rounding boundary); the square root is v_sqrt_f32 (1 ulp): the
@@ -219,9 +219,12 @@ template <bool E4M3> struct F8Cvt {
     if constexpr (E4M3) return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, HIGH);
     else return (uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(a, b, (int)old, HIGH);
   }
-  template <int BYTE> static __device__ __forceinline__ float dec(uint32_t w) {
-    if constexpr (E4M3) return __builtin_amdgcn_cvt_f32_fp8((int)w, BYTE);
-    else return __builtin_amdgcn_cvt_f32_bf8((int)w, BYTE);
+  // the two 8-bit patterns in the low (HIGH = false) or high half of w -> two fp32, one instruction
+  template <bool HIGH> static __device__ __forceinline__ P2 dec2(uint32_t w) {
+    f32x2_t r;
+    if constexpr (E4M3) r = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, HIGH);
+    else r = __builtin_amdgcn_cvt_pk_f32_bf8((int)w, HIGH);
+    return {r.x, r.y};
   }
   static __device__ __forceinline__ uint32_t canon(uint32_t b) {      // one 8-bit pattern
     if constexpr (E4M3) return (b & 0x7fu) == 0x7fu ? 0x7fu : b;
@@ -247,7 +250,7 @@ template <bool E4M3, bool HOT> struct F8 {
   static constexpr bool kGuarded = false;
   static constexpr int kBytes = 1;
   // pair PAIR (0 or 1) of the four elements in a dword
-  template <int PAIR> static __device__ __forceinline__ T unpack(uint32_t w) { return {C::template dec<2 * PAIR>(w), C::template dec<2 * PAIR + 1>(w)}; }
+  template <int PAIR> static __device__ __forceinline__ T unpack(uint32_t w) { return C::template dec2<PAIR == 1>(w); }
   static __device__ __forceinline__ T unpack(uint32_t w) { return unpack<0>(w); }
   static __device__ __forceinline__ uint32_t pack(T a, T b) {          // four elements -> one dword
     uint32_t w = C::template enc<false>(a.lo, a.hi, 0u);
@@ -261,10 +264,7 @@ template <bool E4M3, bool HOT> struct F8 {
   static __device__ __forceinline__ uint16_t bits_lo(T x) { return (uint16_t)C::canon(C::template enc<false>(x.lo, x.hi, 0u) & 0xffu); }
   static __device__ __forceinline__ uint16_t bits_hi(T x) { return (uint16_t)C::canon((C::template enc<false>(x.lo, x.hi, 0u) >> 8) & 0xffu); }
   static __device__ __forceinline__ bool any_nan(T x) { return is_nan(x.lo) | is_nan(x.hi); }
-  static __device__ __forceinline__ T rnd(T x) {
-    const uint32_t w = C::template enc<false>(x.lo, x.hi, 0u);
-    return {C::template dec<0>(w), C::template dec<1>(w)};
-  }
+  static __device__ __forceinline__ T rnd(T x) { return C::template dec2<false>(C::template enc<false>(x.lo, x.hi, 0u)); }
   static __device__ __forceinline__ T round_f32(float a, float b) { return rnd({a, b}); }
 
   static __device__ __forceinline__ T add(T a, T b) { return rnd({a.lo + b.lo, a.hi + b.hi}); }
