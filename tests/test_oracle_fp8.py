@@ -371,3 +371,19 @@ def test_e4m3_overflow_is_nan_and_e5m2_overflow_is_infinity(orc, fmt):
     else:
         assert s[0] == 0x7F and p[0] == 0x7F
         assert np.isnan(orc.widen(0x7F, fmt=fmt)) and np.isnan(orc.widen(0xFF, fmt=fmt))
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+def test_division_by_a_scalar_through_its_fp32_reciprocal(orc, fmt):
+    """What the GPU kernels rely on for the two bias corrections: with r = fl32(1/b) (b's reciprocal
+    computed in fp64 and rounded to fp32), F(a * r) is the same 8-bit pattern as F(a / b) for every one of
+    the 256 x 256 (a, b) -- exact quotients and the exact ties among subnormal results included, b = 0,
+    infinite or NaN included.  Only IEEE fp32 multiplication is involved, so this holds on any machine."""
+    v = orc.widen_array(ALL, fmt=fmt)
+    a, b = np.repeat(v, 256), np.tile(v, 256)
+    with np.errstate(all="ignore"):
+        r = (1.0 / b.astype(np.float64)).astype(np.float32)
+        via_reciprocal = (a * r).astype(np.float32)
+    got = orc.R_array(via_reciprocal, fmt=fmt)
+    want = orc.binop(3, np.repeat(ALL, 256), np.tile(ALL, 256), fmt=fmt)
+    assert np.array_equal(got, want)
