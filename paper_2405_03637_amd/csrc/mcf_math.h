@@ -14,6 +14,10 @@
 //           one.  That argument needs the fp32 result to be a normal number; a pair that
 //           meets a subnormal intermediate, or produces any NaN, raises `redo` and the
 //           caller recomputes that slot in Exact mode.
+// The same chains run over three more component formats (App. A Table 7), each with a first-pass mode
+// and a mode that stores the format's one NaN: fp16 in packed half arithmetic (Hf), and FP8 E5M2 and
+// E4M3 through the hardware conversions (F8).  Every mode offers the same static interface (T, S,
+// unpack, pack, add ... sqrt), and Ops<M> builds the expansion algorithms on it.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
