@@ -257,7 +257,7 @@ template <bool E4M3, bool HOT> struct F8 {
   template <int PAIR> static __device__ __forceinline__ T unpack(uint32_t w) { return C::template dec2<PAIR == 1>(w); }
   static __device__ __forceinline__ T unpack(uint32_t w) { return unpack<0>(w); }
   static __device__ __forceinline__ uint32_t pack(T a, T b) {          // four elements -> one dword
-    uint32_t w = C::template enc<false>(a.lo, a.hi, 0u);
+    uint32_t w = C::template enc<false>(a.lo, a.hi, fbits(a.lo));       // both halves are overwritten
     w = C::template enc<true>(b.lo, b.hi, w);
     if (HOT) return w;
     return C::canon(w & 0xffu) | (C::canon((w >> 8) & 0xffu) << 8) | (C::canon((w >> 16) & 0xffu) << 16) | (C::canon(w >> 24) << 24);
@@ -268,7 +268,10 @@ template <bool E4M3, bool HOT> struct F8 {
   static __device__ __forceinline__ uint16_t bits_lo(T x) { return (uint16_t)C::canon(C::template enc<false>(x.lo, x.hi, 0u) & 0xffu); }
   static __device__ __forceinline__ uint16_t bits_hi(T x) { return (uint16_t)C::canon((C::template enc<false>(x.lo, x.hi, 0u) >> 8) & 0xffu); }
   static __device__ __forceinline__ bool any_nan(T x) { return is_nan(x.lo) | is_nan(x.hi); }
-  static __device__ __forceinline__ T rnd(T x) { return C::template dec2<false>(C::template enc<false>(x.lo, x.hi, 0u)); }
+  // The conversion writes one half of its destination and keeps the other half from `old`.  Only the
+  // written half is read back, so `old` is given a value that dies here (the unrounded x.lo) and the
+  // destination can take over its register; a constant would cost a move per rounding.
+  static __device__ __forceinline__ T rnd(T x) { return C::template dec2<false>(C::template enc<false>(x.lo, x.hi, fbits(x.lo))); }
   static __device__ __forceinline__ T round_f32(float a, float b) { return rnd({a, b}); }
 
   static __device__ __forceinline__ T add(T a, T b) { return rnd({a.lo + b.lo, a.hi + b.hi}); }
