@@ -95,6 +95,10 @@ typedef enum { MCF_LIGHT = 0, MCF_PLUS = 1, MCF_BF16 = 2, MCF_KAHAN = 3, MCF_SGD
  * fail for parameters near zero, for v = 0 at the first step, and when a gradient spike exceeds v
  * (App. C: the same expansion without the ordering).  Any other combination is MCF_ERR_VARIANT. */
 #define MCF_GROW_TWOSUM 0x100
+/* May be OR-ed onto any variant but MCF_SGD: the denominator of line 12 is F(sqrt(F(v_hat + eps))), epsilon
+ * under the root sign as Alg. 2 prints it, instead of the default F(F(sqrt(v_hat)) + eps) of the AdamW the
+ * paper says it modifies. */
+#define MCF_EPS_INSIDE_SQRT 0x200
 /* Component format argument of the primitives below. */
 typedef enum { MCF_COMPONENT_BF16 = 0, MCF_COMPONENT_FP16 = 1, MCF_COMPONENT_FP8_E5M2 = 2, MCF_COMPONENT_FP8_E4M3 = 3 } mcf_component;
 /* One of these may be OR-ed onto any variant (and combined with MCF_GROW_TWOSUM where that is allowed):

@@ -257,7 +257,10 @@ struct Chain {
 
     /* line 12: delta <- -alpha * ( m_hat/(sqrt(v_hat)+eps) + lambda*theta )
      * (weight decay inside the summed update, App. D "Weight Decay") */
-    uint16_t denom = add(sqrt(v_hat), s.e);
+    /* Alg. 2 prints the epsilon under the root sign; the default reading puts it outside, as in the
+     * AdamW the paper says it modifies.  ORC_EPS_INSIDE_SQRT selects the printed form. */
+    const bool eps_inside = (variant_and_flags & ORC_EPS_INSIDE_SQRT) != 0;
+    uint16_t denom = eps_inside ? sqrt(add(v_hat, s.e)) : add(sqrt(v_hat), s.e);
     uint16_t ratio = div(m_hat, denom);
     uint16_t decay = mul(s.lam, theta);
     uint16_t delta = mul(s.na, add(ratio, decay));

@@ -92,6 +92,7 @@ void orc_prim_fmt(int fmt, int which, const uint16_t *p0, const uint16_t *p1, co
 /* ---- AdamW scalars (Alg. 2 line 1, Table 2, App. D "Scalar and Bias Correction") ---- */
 typedef struct { double lr, beta1, beta2, eps, weight_decay; } orc_hyper;
 #define ORC_GROW_TWOSUM 0x100
+#define ORC_EPS_INSIDE_SQRT 0x200   /* line 12 as printed: m_hat / sqrt(v_hat + eps) instead of m_hat / (sqrt(v_hat) + eps) */
 #define ORC_FMT_FP16 0x1000    /* OR-ed onto the step's variant: every array and scalar is fp16 */
 #define ORC_FMT_FP8_E5M2 0x2000   /* ... FP8 E5M2 (format id << 12) */
 #define ORC_FMT_FP8_E4M3 0x3000   /* ... FP8 E4M3 */
@@ -119,6 +120,8 @@ void orc_scalars_derive_fmt(int fmt, const orc_hyper *h, uint64_t t, orc_scalars
  * ORC_GROW_TWOSUM may be OR-ed onto variants 0 and 1: every Grow then uses TwoSum (Alg. 3)
  * instead of Fast2Sum, which drops the |x| >= |a| precondition of Alg. 1.
  * ORC_FMT_FP16 may be OR-ed onto any variant: the same steps on fp16 arrays with fp16 scalars.
+ * ORC_EPS_INSIDE_SQRT may be OR-ed onto variants 0-3: the denominator of line 12 is F(sqrt(F(v_hat + eps)))
+ * as Alg. 2 prints it, instead of F(F(sqrt(v_hat)) + eps).
  * All state is updated in place.  delta_out, if not NULL, receives the bf16
  * update Delta-theta of line 12 for every element.  nthreads >= 1 splits the
  * elements evenly over that many host threads (elements are independent). */

@@ -20,6 +20,7 @@ _LIB = os.path.join(_HERE, "libmcf_oracle.so")
 ADD, SUB, MUL, DIV, SQRT = 0, 1, 2, 3, 4
 LIGHT, PLUS, BF16, KAHAN, SGD = 0, 1, 2, 3, 4
 GROW_TWOSUM = 0x100          # OR onto LIGHT or PLUS: Grow built on TwoSum
+EPS_INSIDE_SQRT = 0x200      # OR onto any AdamW variant: epsilon under the root sign, as Alg. 2 prints line 12
 FMT_BF16, FMT_FP16, FMT_E5M2, FMT_E4M3 = 0, 1, 2, 3    # component format ids (fmt= arguments)
 STEP_FP16 = 0x1000           # OR onto the step's variant: fp16 arrays and scalars
 STEP_E5M2, STEP_E4M3 = 0x2000, 0x3000      # FP8 arrays (one 8-bit pattern per uint16 element) and scalars

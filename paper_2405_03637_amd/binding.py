@@ -17,6 +17,7 @@ MCF_ERR_NULL, MCF_ERR_SIZE, MCF_ERR_ALIGN, MCF_ERR_VARIANT, MCF_ERR_STEP, MCF_ER
     -1, -2, -3, -4, -5, -6, -7
 LIGHT, PLUS, BF16, KAHAN, SGD = 0, 1, 2, 3, 4
 GROW_TWOSUM = 0x100
+EPS_INSIDE_SQRT = 0x200                        # OR onto any variant but SGD: epsilon under the root sign (Alg. 2 as printed)
 FMT_FP16, FMT_FP8_E5M2, FMT_FP8_E4M3 = 0x1000, 0x2000, 0x3000      # OR onto a variant: tensors and scalars of that format
 COMPONENT_BF16, COMPONENT_FP16, COMPONENT_FP8_E5M2, COMPONENT_FP8_E4M3 = 0, 1, 2, 3      # component format of the primitives
 PRIM_FAST2SUM, PRIM_TWOSUM, PRIM_GROW, PRIM_GROW_TWOSUM, PRIM_TWOPROD, PRIM_SCALING, PRIM_MUL = range(7)

@@ -190,6 +190,7 @@ inline bool derive_scalars(const mcf_hyper &h, uint64_t step, mcfd::StepScalars 
   s.e = bf16_to_f32(b.v[K_EPS]);
   s.lam = bf16_to_f32(b.v[K_LAM]);
   s.na = bf16_to_f32(b.v[K_NA]);
+  s.eps_inside_sqrt = 0;
   auto sane_bc = [](float x) { return x >= 0x1p-60f && x <= 1.0f; };
   const bool eps_ok = (s.e == 0.0f) || (s.e >= 0x1p-100f && s.e <= 0x1p60f);
   return sane_bc(s.bc1) && sane_bc(s.bc2) && eps_ok;
@@ -212,6 +213,7 @@ inline void derive_scalars_fp16(const mcf_hyper &h, uint64_t step, mcfd::StepSca
   s.e = splat(b.v[K_EPS]);
   s.lam = splat(b.v[K_LAM]);
   s.na = splat(b.v[K_NA]);
+  s.eps_inside_sqrt = 0;
 }
 
 // FP8 scalars widened to fp32 (infinities and NaN included: a scalar that left the format's range
@@ -238,6 +240,7 @@ inline void derive_scalars_fp8(const mcf_hyper &h, uint64_t step, bool e4m3, mcf
   s.e = widen(b.v[K_EPS]);
   s.lam = widen(b.v[K_LAM]);
   s.na = widen(b.v[K_NA]);
+  s.eps_inside_sqrt = 0;
 }
 
 }  // namespace mcfh

@@ -386,8 +386,11 @@ __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], u
 
 // Cold path: one slot element by element in the variant's element mode (bf16: Exact), as a rolled loop so that it costs code
 // size once.  Serves the slots that straddle a tensor's ends, tensors whose buffers are not
-// mutually aligned, and (bf16) slots the hot path asked to redo (their inputs are still in memory:
-// nothing of the slot has been stored yet).
+// mutually aligned, (bf16) slots the hot path asked to redo (their inputs are still in memory:
+// nothing of the slot has been stored yet), and every slot of a launch with MCF_EPS_INSIDE_SQRT: that
+// reading of line 12 is kept for reference, and keeping it out of the vector path keeps the vector
+// path's code and registers as they are (a compiled second copy of the chain there cost the default
+// reading 5% at the 7B set).
 template <int VARIANT, bool EDQ>
 __device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, const typename StepStreams<VARIANT>::Scalars &sc,
                                           EdqAcc &acc) {
@@ -411,7 +414,8 @@ __device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, cons
     const float th0 = M::lo(io.th), dth0 = M::lo(io.dth);
     T delta;
     bool unused = false;
-    mcfd::adamw_pair<M, SS::kBase, SS::kGrow2>(io, sc, delta, unused);
+    if (SS::kBase != mcfd::V_SGD && sc.eps_inside_sqrt) mcfd::adamw_pair<M, SS::kBase, SS::kGrow2, true>(io, sc, delta, unused);
+    else mcfd::adamw_pair<M, SS::kBase, SS::kGrow2, false>(io, sc, delta, unused);
     // EDQ is taken on the stored values (a NaN stays a NaN whatever its payload)
     if (EDQ) edq_add(acc, M::lo(delta), th0, dth0, M::lo(io.th), M::lo(io.dth));
     store_elem<EB>(d.p[S_TH], e, M::bits_lo(io.th));
@@ -451,9 +455,11 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
   // the buffers the loads read, so the compiler would not move a later slot's loads above them.
   Slot slot[kUnroll];
   uint32_t in[kUnroll][kMaxStreams][4];
+  const bool elementwise = SS::kBase != mcfd::V_SGD && sc.eps_inside_sqrt != 0;      // uniform over the launch
   static_for<0, kUnroll>([&](auto jc) {
     constexpr int j = decltype(jc)::value;
     slot[j] = classify<SS::kEB>(d, slot0 + (uint64_t)j * kStepBlock + threadIdx.x);
+    if (elementwise) slot[j].full = false;
     if (slot[j].full) {
       const uint64_t e0 = (slot[j].c0 - d.phase) * SS::kEB;       // byte offset
       load_vec(d.p[S_TH], e0, in[j][S_TH]);
@@ -847,12 +853,13 @@ inline uint64_t slots_of(uint64_t n, uint32_t phase, uint32_t elem_bytes = 2) {
 }
 
 constexpr int kFmtMask = 3 << kFmtShift;
-constexpr int kFlagMask = MCF_GROW_TWOSUM | kFmtMask;
+constexpr int kFlagMask = MCF_GROW_TWOSUM | MCF_EPS_INSIDE_SQRT | kFmtMask;
 inline int format_of(int variant) { return (variant >> kFmtShift) & 3; }
 inline uint32_t elem_bytes_of(int component) { return component >= MCF_COMPONENT_FP8_E5M2 ? 1u : 2u; }
 
 inline bool known_variant(int v) {
   const int base = v & ~kFlagMask;
+  if ((v & MCF_EPS_INSIDE_SQRT) && base == MCF_SGD) return false;          // SGD has no epsilon
   if (v & MCF_GROW_TWOSUM) return base == MCF_LIGHT || base == MCF_PLUS;
   return base == MCF_LIGHT || base == MCF_PLUS || base == MCF_BF16 || base == MCF_KAHAN || base == MCF_SGD;
 }
@@ -918,7 +925,7 @@ template <bool TABLE, int FMT>
 void launch_format(int variant, bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs,
                    const Chunk *chunks, const TensorDesc &flat, const HostScalars &hs, double *partials) {
   constexpr int F = FMT << kFmtShift;
-  switch (variant & ~kFmtMask) {
+  switch (variant & ~(kFmtMask | MCF_EPS_INSIDE_SQRT)) {       // the epsilon flag travels in the scalars
     case MCF_LIGHT | MCF_GROW_TWOSUM:
       launch_step<mcfd::V_LIGHT | kGrow2Bit | F, TABLE>(edq, blocks, st, descs, chunks, flat, hs, partials); break;
     case MCF_PLUS | MCF_GROW_TWOSUM:
@@ -971,6 +978,7 @@ HostScalars host_scalars(const mcf_hyper &h, uint64_t step, int variant) {
   } else {
     hs.fast = mcfh::derive_scalars(h, step, hs.bf) && !force_exact();
   }
+  hs.bf.eps_inside_sqrt = hs.hf.eps_inside_sqrt = (variant & MCF_EPS_INSIDE_SQRT) ? 1u : 0u;
   return hs;
 }
 

@@ -102,6 +102,10 @@ template <class R> struct Bf {
   static __device__ __forceinline__ uint16_t bits_hi(T x) { return (uint16_t)(fbits(x.hi) >> 16); }
   static __device__ __forceinline__ bool any_nan(T x) { return is_nan(x.lo) | is_nan(x.hi); }
   static __device__ __forceinline__ T round_f32(float a, float b) { return R::rnd({a, b}); }
+  // Fast mode: a sum about to go under the approximate root must not be a subnormal fp32 number
+  static __device__ __forceinline__ void guard_root_operand(T x, bool &redo) {
+    if (R::kFast) redo |= is_subnormal(x.lo) | is_subnormal(x.hi);
+  }
 
   static __device__ __forceinline__ T add(T a, T b) { return R::rnd({a.lo + b.lo, a.hi + b.hi}); }
   static __device__ __forceinline__ T sub(T a, T b) { return R::rnd({a.lo - b.lo, a.hi - b.hi}); }
@@ -178,6 +182,7 @@ template <bool HOT> struct Hf {
   // a half is NaN iff its magnitude bits exceed 0x7C00; +0x03FF carries exactly those into bit 15
   static __device__ __forceinline__ bool any_nan(T x) { return (((raw(x) & 0x7fff7fffu) + 0x03ff03ffu) & 0x80008000u) != 0; }
   static __device__ __forceinline__ T round_f32(float a, float b) { return h2_t{(_Float16)a, (_Float16)b}; }
+  static __device__ __forceinline__ void guard_root_operand(T, bool &) {}
 
   static __device__ __forceinline__ T add(T a, T b) { return a + b; }
   static __device__ __forceinline__ T sub(T a, T b) { return a - b; }
@@ -273,6 +278,7 @@ template <bool E4M3, bool HOT> struct F8 {
   // destination can take over its register; a constant would cost a move per rounding.
   static __device__ __forceinline__ T rnd(T x) { return C::template dec2<false>(C::template enc<false>(x.lo, x.hi, fbits(x.lo))); }
   static __device__ __forceinline__ T round_f32(float a, float b) { return rnd({a, b}); }
+  static __device__ __forceinline__ void guard_root_operand(T, bool &) {}
 
   static __device__ __forceinline__ T add(T a, T b) { return rnd({a.lo + b.lo, a.hi + b.hi}); }
   static __device__ __forceinline__ T sub(T a, T b) { return rnd({a.lo - b.lo, a.hi - b.hi}); }
@@ -331,6 +337,7 @@ template <class M> struct Ops : M {
 // corrections.
 template <class S> struct StepScalarsT {
   S b1, c1, b2, b2l, c2, bc1, bc2, rbc1, rbc2, e, lam, na;
+  uint32_t eps_inside_sqrt;      // 1: line 12's denominator is F(sqrt(F(v_hat + eps))), as Alg. 2 prints it
 };
 using StepScalars = StepScalarsT<float>;
 using StepScalarsH = StepScalarsT<h2_t>;
@@ -345,10 +352,10 @@ template <class T> struct ElemIOT {          // one pair of elements of every st
 // V_SGD is MCF-SGD with momentum (Sec. 1): m <- mu*m + g, delta <- -alpha*(m + lambda*theta), Grow.
 enum : int { V_LIGHT = 0, V_PLUS = 1, V_BF16 = 2, V_KAHAN = 3, V_SGD = 4 };
 
-// Alg. 2 lines 8-13 on one pair.  GROW2 builds every Grow on TwoSum.  On return io holds the new theta, dtheta, m, v (and dv);
+// Alg. 2 lines 8-13 on one pair.  GROW2 builds every Grow on TwoSum, EPS_INSIDE puts epsilon under the root.  On return io holds the new theta, dtheta, m, v (and dv);
 // delta receives line 12's update.  redo is raised (modes with kFast) when this pair must be
 // recomputed element by element.
-template <class M, int VARIANT, bool GROW2 = false>
+template <class M, int VARIANT, bool GROW2 = false, bool EPS_INSIDE = false>
 __device__ __forceinline__ void adamw_pair(ElemIOT<typename M::T> &io, const StepScalarsT<typename M::S> &s,
                                            typename M::T &delta, bool &redo) {
   using O = Ops<M>;
@@ -384,8 +391,16 @@ __device__ __forceinline__ void adamw_pair(ElemIOT<typename M::T> &io, const Ste
   // lines 10-11
   T mh = O::divs(m1, s.bc1, s.rbc1, redo);
   T vh = O::divs(v1, s.bc2, s.rbc2, redo);
-  // line 12 (epsilon outside the root; weight decay inside the summed update)
-  T dn = O::adds(O::sqrt(vh, redo), s.e);
+  // line 12 (epsilon outside the root unless the caller asked for the printed form; weight decay
+  // inside the summed update)
+  T dn;
+  if (EPS_INSIDE) {
+    const T sum = O::adds(vh, s.e);
+    M::guard_root_operand(sum, redo);
+    dn = O::sqrt(sum, redo);
+  } else {
+    dn = O::adds(O::sqrt(vh, redo), s.e);
+  }
   T q = O::divg(mh, dn, redo);
   T w = O::muls(s.lam, io.th);
   delta = O::muls(s.na, O::add(q, w));

@@ -55,7 +55,9 @@ def test_flat_step_argument_errors():
     assert _flat(variant=99) == mcf.MCF_ERR_VARIANT
     assert _flat(variant=mcf.SGD | mcf.GROW_TWOSUM) == mcf.MCF_ERR_VARIANT
     assert _flat(variant=mcf.BF16 | mcf.GROW_TWOSUM) == mcf.MCF_ERR_VARIANT     # the flag applies to Collage only
-    assert _flat(variant=mcf.LIGHT | 0x200) == mcf.MCF_ERR_VARIANT
+    assert _flat(variant=mcf.LIGHT | 0x400) == mcf.MCF_ERR_VARIANT
+    assert _flat(variant=mcf.SGD | mcf.EPS_INSIDE_SQRT) == mcf.MCF_ERR_VARIANT         # SGD has no epsilon
+    assert _flat(variant=mcf.PLUS | mcf.EPS_INSIDE_SQRT, dv=None) == mcf.MCF_ERR_NULL
     assert _flat(variant=mcf.LIGHT | 0x4000) == mcf.MCF_ERR_VARIANT
     assert _flat(variant=mcf.SGD | mcf.GROW_TWOSUM | mcf.FMT_FP8_E4M3) == mcf.MCF_ERR_VARIANT
     assert _flat(variant=mcf.LIGHT | mcf.FMT_FP8_E5M2, step=0) == mcf.MCF_ERR_STEP

@@ -338,6 +338,47 @@ def test_hyper_parameter_edge_cases(variant, fp16):
         wl.close()
 
 
+@pytest.mark.parametrize("fmt", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan", "plus+twosum"])
+def test_epsilon_under_the_root_flag(variant, fmt):
+    """MCF_EPS_INSIDE_SQRT (line 12 as Alg. 2 prints it) in every component format: ragged tensors, fused EDQ,
+    plan and flat entry points; and it really is a different computation from the default."""
+    shapes = [("a", 100_003), ("b", 5), ("c", 8192), ("d", 333)]
+    eps = {0: 1e-6, 1: 1.0, 2: 2.0 ** -6, 3: 2.0 ** -6}[fmt]              # comparable to v_hat in that format's scaling
+    base_h = W.HYPER_FP8 if fmt >= 2 else W.fp16_hyper(W.HYPER_LIGHT) if fmt == 1 else W.HYPER_LIGHT
+    hyper = (base_h[0], base_h[1], base_h[2], eps, base_h[4])
+    wl = Workload("flat_1m", variant=variant, shape_list=shapes, misalign_tiny=True, hyper=hyper, fmt=fmt)
+    ref = Workload("flat_1m", variant=variant, shape_list=shapes, misalign_tiny=True, hyper=hyper, fmt=fmt)
+    wl.plan.destroy()
+    wl.variant |= mcf.EPS_INSIDE_SQRT                                       # the same bit in the oracle
+    tensors = []
+    for (_, n), o in zip(wl.shapes, wl.offs):
+        sl = slice(o, o + n)
+        tensors.append((wl.theta[sl], wl.dtheta[sl] if wl.dtheta is not None else None, wl.m[sl], wl.v[sl],
+                        wl.dv[sl] if wl.dv is not None else None, wl.grad[sl]))
+    wl.plan = mcf.Plan(tensors, wl.variant)
+    full_oracle_run(wl, 4, edq=True)
+    for t in range(1, 5):
+        ref.new_grads(t)
+        ref.plan.step(ref.hyper, t)
+    torch.cuda.synchronize()
+    assert not np.array_equal(H.torch_to_u16(wl.theta), H.torch_to_u16(ref.theta))       # the flag changes the trajectory
+    assert np.array_equal(H.torch_to_u16(wl.m), H.torch_to_u16(ref.m))                    # but not the moments
+    n = wl.shapes[0][1]
+    flat = Workload("flat_1m", variant=variant, shape_list=[("a", n)], hyper=hyper, fmt=fmt)
+    host = {k: H.torch_to_u16(getattr(flat, k)) for k in flat.state_names()}
+    for t in range(1, 3):
+        flat.new_grads(t)
+        g = H.torch_to_u16(flat.grad)
+        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host.get("v"), host.get("dv"), g,
+                       flat.variant | orc.EPS_INSIDE_SQRT, hyper, t)
+        mcf.adamw_step_flat(flat.theta, flat.dtheta, flat.m, flat.v, flat.dv, flat.grad, flat.variant | mcf.EPS_INSIDE_SQRT, hyper, t)
+    for k in flat.state_names():
+        assert np.array_equal(H.torch_to_u16(getattr(flat, k))[:n], host[k][:n]), k
+    for w in (wl, ref, flat):
+        w.close()
+
+
 def test_two_plans_on_two_streams():
     """Distinct plans are independent: two steps enqueued on two streams at once give the same bits as
     the oracle gives for each alone."""

@@ -98,6 +98,31 @@ def test_first_step_closed_form(orc, variant):
     assert np.all(np.abs(new - (theta0 + got))[pre] <= 2.0 ** -15 * np.abs(theta0)[pre] + 2.0 ** -133)
 
 
+@pytest.mark.parametrize("variant", [0, 1])
+def test_first_step_closed_form_with_epsilon_under_the_root(orc, variant):
+    """The flagged reading of line 12 as Alg. 2 prints it: delta = -lr * ( g / sqrt(g^2 + eps) + wd*theta ) at t = 1;
+    the default reading (eps outside) is far outside the rounding tolerance, and nothing else changes."""
+    n = 4096
+    hyper = (1e-2, 0.9, 0.95, 4e-6, 0.5)          # eps comparable to g^2
+    st = _state(n, 1, theta_std=1.0, plus=bool(variant))
+    st_default = {k: (v.copy() if v is not None else None) for k, v in st.items()}
+    theta0 = H.u16_to_f64(st["theta"])
+    g = _grads(n, 1, 1, std=2e-3)
+    deltas, deltas_default = [], []
+    _run(orc, st, variant | orc.EPS_INSIDE_SQRT, hyper, 1, lambda t: g, deltas)
+    _run(orc, st_default, variant, hyper, 1, lambda t: g, deltas_default)
+    gf = H.u16_to_f64(g)
+    lr, _, _, eps, wd = hyper
+    want = -lr * (gf / np.sqrt(gf * gf + eps) + wd * theta0)
+    got = H.u16_to_f64(deltas[0])
+    tol = 12 * 2.0 ** -9 * lr * (np.abs(gf) / np.sqrt(gf * gf + eps) + wd * np.abs(theta0)) + 1e-30
+    assert np.all(np.abs(got - want) <= tol)
+    outside = -lr * (gf / (np.abs(gf) + eps) + wd * theta0)
+    assert np.mean(np.abs(got - outside) > tol) > 0.9
+    assert np.mean(deltas[0] != deltas_default[0]) > 0.9
+    assert np.array_equal(st["m"], st_default["m"]) and np.array_equal(st["v"], st_default["v"])     # the moments do not see eps
+
+
 # ------------------------------------------------------------------ tracks a textbook fp64 AdamW
 @pytest.mark.parametrize("variant,beta2", [(0, 0.95), (1, 0.95), (1, 0.999)])
 def test_tracks_fp64_adamw(orc, variant, beta2):
