@@ -130,6 +130,15 @@ int mcf_plan_destroy(mcf_plan *plan);      /* NULL is accepted */
 /* Number of parameters the plan covers (0 for NULL). */
 uint64_t mcf_plan_params(const mcf_plan *plan);
 
+/* Point an existing plan at other buffers of the same sizes (for callers whose gradient or parameter
+ * buffers are reallocated between steps) without rebuilding it: no allocation.  `tensors` must
+ * have the `count` of mcf_plan_create, every n unchanged (else MCF_ERR_SIZE), and each tensor's
+ * buffers must sit at the same offset modulo 128 bytes, and be mutually aligned or not, as the buffers
+ * they replace (else MCF_ERR_ALIGN: the plan's work split was cut for that alignment; create a new
+ * plan).  The new table is copied in `stream` order, after the steps already enqueued there, and
+ * the call returns once the copy is done (it waits for that stream).  On an error the plan is unchanged. */
+int mcf_plan_update(mcf_plan *plan, const mcf_tensor *tensors, uint32_t count, void *stream);
+
 /* One optimizer step, Alg. 2 lines 8-13, over every tensor of the plan: one launch.
  * step = t >= 1.  edq_dev: NULL, or a device pointer to 4 doubles that receive, in
  * stream order, {EDQ, S1, S2, LOST} for this step over all parameters of the plan, where

@@ -66,6 +66,7 @@ def lib():
     L.mcf_status_string.argtypes = [_int]
     L.mcf_plan_create.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(Tensor), ctypes.c_uint32, _int]
     L.mcf_plan_destroy.argtypes = [_vp]
+    L.mcf_plan_update.argtypes = [_vp, ctypes.POINTER(Tensor), ctypes.c_uint32, _vp]
     L.mcf_plan_params.restype = _u64
     L.mcf_plan_params.argtypes = [_vp]
     L.mcf_adamw_step.argtypes = [_vp, ctypes.POINTER(Hyper), _u64, _vp, _vp]
@@ -158,6 +159,14 @@ class Plan:
     @property
     def params(self):
         return int(lib().mcf_plan_params(self._h))
+
+    def update(self, tensors, stream=None):
+        """Point the plan at other buffers of the same sizes and alignment (mcf_plan_update)."""
+        arr = (Tensor * max(1, len(tensors)))()
+        for i, (th, dth, m, v, dv, g) in enumerate(tensors):
+            arr[i] = Tensor(_ptr(th), _ptr(dth), _ptr(m), _ptr(v), _ptr(dv), _ptr(g), th.numel())
+        _check(lib().mcf_plan_update(self._h, arr, len(tensors), _stream(stream)), "mcf_plan_update")
+        self._keep = tensors
 
     def step(self, hyper, t, stream=None, edq_out=None):
         """One optimizer step.  edq_out: optional float64 device tensor of 4 elements {EDQ, S1, S2, LOST}."""
@@ -306,6 +315,10 @@ def mcf_plan_destroy(plan):
 
 def mcf_plan_params(plan):
     return plan.params
+
+
+def mcf_plan_update(plan, tensors, stream=None):
+    plan.update(tensors, stream=stream)
 
 
 def mcf_adamw_step(plan, hyper, step, stream=None, edq_dev=None):

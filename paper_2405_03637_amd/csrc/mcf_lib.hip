@@ -1045,7 +1045,9 @@ struct mcf_plan {
   uint64_t n_params;
   TensorDesc *d_descs;
   Chunk *d_chunks;
-  double *d_partials;   // 2*n_chunks doubles, then 2*kStage1Blocks doubles
+  double *d_partials;   // kEdqVals*n_chunks doubles, then kEdqVals*kStage1Blocks doubles
+  std::vector<TensorDesc> h_descs;   // host copy of the descriptor table (for mcf_plan_update)
+  std::vector<uint64_t> in_n;        // n of every tensor given at creation, empty ones included
 };
 
 struct mcf_fp32mw_plan {
@@ -1103,6 +1105,9 @@ int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, i
   p->d_descs = nullptr;
   p->d_chunks = nullptr;
   p->d_partials = nullptr;
+  p->h_descs = descs;
+  p->in_n.resize(count);
+  for (uint32_t i = 0; i < count; ++i) p->in_n[i] = tensors[i].n;
   if (p->n_chunks) {
     bool ok = hipMalloc((void **)&p->d_descs, descs.size() * sizeof(TensorDesc)) == hipSuccess &&
               hipMalloc((void **)&p->d_chunks, chunks.size() * sizeof(Chunk)) == hipSuccess &&
@@ -1130,6 +1135,33 @@ int mcf_plan_destroy(mcf_plan *plan) {
 }
 
 uint64_t mcf_plan_params(const mcf_plan *plan) { return plan ? plan->n_params : 0; }
+
+int mcf_plan_update(mcf_plan *plan, const mcf_tensor *tensors, uint32_t count, void *stream) {
+  if (!plan) return MCF_ERR_NULL;
+  if (count != plan->in_n.size()) return MCF_ERR_SIZE;
+  if (count && !tensors) return MCF_ERR_NULL;
+  std::vector<TensorDesc> descs;
+  descs.reserve(plan->h_descs.size());
+  for (uint32_t i = 0; i < count; ++i) {
+    if (tensors[i].n != plan->in_n[i]) return MCF_ERR_SIZE;
+    const int rc = check_tensor(tensors[i], plan->variant);
+    if (rc != MCF_OK) return rc;
+    if (tensors[i].n == 0) continue;
+    TensorDesc d;
+    fill_desc(tensors[i], plan->variant, d);
+    const TensorDesc &old = plan->h_descs[descs.size()];
+    // the chunk table was cut for the old buffers' alignment class: the new ones must share it
+    if (d.phase != old.phase || d.scalar_only != old.scalar_only) return MCF_ERR_ALIGN;
+    descs.push_back(d);
+  }
+  if (!descs.empty()) {
+    // the descriptor table is read by kernels already enqueued on `stream`; the copy is ordered after them
+    MCF_HIP(hipMemcpyAsync(plan->d_descs, descs.data(), descs.size() * sizeof(TensorDesc), hipMemcpyHostToDevice, (hipStream_t)stream));
+    MCF_HIP(hipStreamSynchronize((hipStream_t)stream));      // descs is a local: the copy must have read it before it goes
+  }
+  plan->h_descs.swap(descs);
+  return MCF_OK;
+}
 
 int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *stream, double *edq_dev) {
   if (!plan) return MCF_ERR_NULL;

@@ -105,6 +105,18 @@ def test_plan_argument_errors():
     assert lib.mcf_adamw_step(h, ctypes.byref(hy), 1, None, FAKE + 4) == mcf.MCF_ERR_ALIGN
     assert lib.mcf_adamw_step(h, ctypes.byref(hy), 1, None, None) == mcf.MCF_OK
     assert lib.mcf_plan_destroy(h) == mcf.MCF_OK
+    # mcf_plan_update: argument errors come before any device work (a plan over nothing has no table to copy)
+    assert lib.mcf_plan_update(None, one, 1, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_plan_create(ctypes.byref(h), None, 0, 0) == mcf.MCF_OK
+    assert lib.mcf_plan_update(h, one, 1, None) == mcf.MCF_ERR_SIZE            # created over 0 tensors
+    assert lib.mcf_plan_update(h, None, 0, None) == mcf.MCF_OK
+    assert lib.mcf_plan_destroy(h) == mcf.MCF_OK
+    empty1 = (mcf.Tensor * 1)(mcf.Tensor(None, None, None, None, None, None, 0))
+    assert lib.mcf_plan_create(ctypes.byref(h), empty1, 1, 0) == mcf.MCF_OK
+    assert lib.mcf_plan_update(h, one, 1, None) == mcf.MCF_ERR_SIZE            # n changed from 0 to 8
+    assert lib.mcf_plan_update(h, None, 1, None) == mcf.MCF_ERR_NULL
+    assert lib.mcf_plan_update(h, empty1, 1, None) == mcf.MCF_OK
+    assert lib.mcf_plan_destroy(h) == mcf.MCF_OK
     empty = (mcf.Tensor * 2)(mcf.Tensor(None, None, None, None, None, None, 0), mcf.Tensor(None, None, None, None, None, None, 0))
     assert lib.mcf_plan_create(ctypes.byref(h), empty, 2, 1) == mcf.MCF_OK
     assert lib.mcf_plan_params(h) == 0

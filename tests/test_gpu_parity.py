@@ -379,6 +379,49 @@ def test_epsilon_under_the_root_flag(variant, fmt):
         w.close()
 
 
+def test_plan_update_repoints_the_plan():
+    """mcf_plan_update: the same plan stepped over a second set of buffers (same sizes and alignment), then back;
+    both trajectories follow the oracle; a set with another alignment is refused and leaves the plan usable."""
+    shapes = [("a", 70_001), ("b", 5), ("c", 8192), ("d", 333)]
+    a = Workload("flat_1m", variant="plus", shape_list=shapes, misalign_tiny=True, hyper=W.HYPER_PLUS_1P3B, seed=3)
+    b = Workload("flat_1m", variant="plus", shape_list=shapes, misalign_tiny=True, hyper=W.HYPER_PLUS_1P3B, seed=4)
+    def tensors(w, shift=0):
+        return [(w.theta[o + shift:o + shift + n], w.dtheta[o + shift:o + shift + n], w.m[o + shift:o + shift + n],
+                 w.v[o + shift:o + shift + n], w.dv[o + shift:o + shift + n], w.grad[o + shift:o + shift + n])
+                for (_, n), o in zip(w.shapes, w.offs)]
+    hosts = [{k: H.torch_to_u16(getattr(w, k)) for k in w.state_names()} for w in (a, b)]
+    plan = a.plan
+    t = 0
+    for which in (0, 1, 0, 1):
+        w, host = (a, b)[which], hosts[which]
+        plan.update(tensors(w))
+        for _ in range(2):
+            t += 1
+            w.new_grads(t)
+            orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], host["dv"], H.torch_to_u16(w.grad), w.variant, w.hyper, t)
+            plan.step(w.hyper, t)
+        torch.cuda.synchronize()
+        live = np.zeros(w.total, bool)
+        for (_, n), o in zip(w.shapes, w.offs):
+            live[o:o + n] = True
+        for k in w.state_names():
+            assert np.array_equal(H.torch_to_u16(getattr(w, k))[live], host[k][live]), (which, k)
+    with pytest.raises(mcf.McfError) as e:                       # every tensor one element further: another alignment class
+        plan.update([tuple(x[1:] for x in tt) for tt in tensors(b)][:1] + tensors(b)[1:])
+    assert e.value.status in (mcf.MCF_ERR_SIZE, mcf.MCF_ERR_ALIGN)
+    with pytest.raises(mcf.McfError):
+        plan.update(tensors(b)[:-1])                             # a tensor short
+    plan.update(tensors(a))                                      # still usable
+    a.new_grads(99)
+    orc.adamw_step(hosts[0]["theta"], hosts[0]["dtheta"], hosts[0]["m"], hosts[0]["v"], hosts[0]["dv"], H.torch_to_u16(a.grad), a.variant, a.hyper, 99)
+    plan.step(a.hyper, 99)
+    live = np.zeros(a.total, bool)
+    for (_, n), o in zip(a.shapes, a.offs):
+        live[o:o + n] = True
+    assert np.array_equal(H.torch_to_u16(a.theta)[live], hosts[0]["theta"][live])
+    a.close(); b.close()
+
+
 def test_two_plans_on_two_streams():
     """Distinct plans are independent: two steps enqueued on two streams at once give the same bits as
     the oracle gives for each alone."""
