@@ -190,7 +190,7 @@ inline bool derive_scalars(const mcf_hyper &h, uint64_t step, mcfd::StepScalars 
   s.e = bf16_to_f32(b.v[K_EPS]);
   s.lam = bf16_to_f32(b.v[K_LAM]);
   s.na = bf16_to_f32(b.v[K_NA]);
-  s.eps_inside_sqrt = 0;
+  s.eps_inside_sqrt = s.elementwise = 0;
   auto sane_bc = [](float x) { return x >= 0x1p-60f && x <= 1.0f; };
   const bool eps_ok = (s.e == 0.0f) || (s.e >= 0x1p-100f && s.e <= 0x1p60f);
   return sane_bc(s.bc1) && sane_bc(s.bc2) && eps_ok;
@@ -208,39 +208,52 @@ inline void derive_scalars_fp16(const mcf_hyper &h, uint64_t step, mcfd::StepSca
   s.c2 = splat(b.v[K_C2]);
   s.bc1 = splat(b.v[K_BC1]);
   s.bc2 = splat(b.v[K_BC2]);
-  s.rbc1 = s.bc1;            // unused by the fp16 arithmetic
-  s.rbc2 = s.bc2;
+  s.rbc1 = s.rbc2 = 0.0f;    // unused by the fp16 arithmetic
   s.e = splat(b.v[K_EPS]);
   s.lam = splat(b.v[K_LAM]);
   s.na = splat(b.v[K_NA]);
-  s.eps_inside_sqrt = 0;
+  s.eps_inside_sqrt = s.elementwise = 0;
 }
 
-// FP8 scalars widened to fp32 (infinities and NaN included: a scalar that left the format's range
-// poisons the step exactly as it does in the definition), with fp32 reciprocals of the two bias
-// corrections for the corrected quotient.
-inline void derive_scalars_fp8(const mcf_hyper &h, uint64_t step, bool e4m3, mcfd::StepScalars &s) {
+// FP8 scalars as fp16 values (every FP8 number is one; infinities and NaN carry over: a scalar that
+// left the format's range poisons the step exactly as it does in the definition), each copied into both
+// halves of a packed register, with the fp16 roundings of the reciprocals of the two bias corrections.
+// Returns false when one of those reciprocals is not an fp16 number (E5M2's +-2^-16): the first pass
+// multiplies by them, so such a step must take the element path.
+inline bool derive_scalars_fp8(const mcf_hyper &h, uint64_t step, bool e4m3, mcfd::StepScalarsF8 &s) {
   const ScalarBits b = e4m3 ? scalar_bits_e4m3(h, step) : scalar_bits_e5m2(h, step);
-  auto widen = [e4m3](uint16_t x) -> float {
-    if (e4m3) return (x & 0x7f) == 0x7f ? std::nanf("") : (float)e4m3_to_f64(x);
-    const uint16_t mag = x & 0x7f;
-    if (mag > 0x7c) return std::nanf("");
-    if (mag == 0x7c) return (x & 0x80) ? -INFINITY : INFINITY;
-    return (float)e5m2_to_f64(x);
+  auto half_bits = [e4m3](uint16_t x) -> uint16_t {
+    if (!e4m3) return (uint16_t)((x & 0xff) << 8);                        // E5M2 is the upper byte of an fp16
+    if ((x & 0x7f) == 0x7f) return 0x7e00;                                // NaN
+    return f64_to_f16(e4m3_to_f64(x));                                    // exact
   };
-  s.b1 = widen(b.v[K_B1]);
-  s.c1 = widen(b.v[K_C1]);
-  s.b2 = widen(b.v[K_B2]);
-  s.b2l = widen(b.v[K_B2L]);
-  s.c2 = widen(b.v[K_C2]);
-  s.bc1 = widen(b.v[K_BC1]);
-  s.bc2 = widen(b.v[K_BC2]);
-  s.rbc1 = (float)(1.0 / (double)s.bc1);        // 1/0 = inf: the corrected quotient then keeps a*inf, the IEEE result
-  s.rbc2 = (float)(1.0 / (double)s.bc2);
-  s.e = widen(b.v[K_EPS]);
-  s.lam = widen(b.v[K_LAM]);
-  s.na = widen(b.v[K_NA]);
-  s.eps_inside_sqrt = 0;
+  auto splat16 = [](uint16_t hb) { return __builtin_bit_cast(mcfd::h2_t, (uint32_t)hb * 0x00010001u); };
+  auto splat = [&](uint16_t x) { return splat16(half_bits(x)); };
+  bool ok = true;
+  auto reciprocal = [&](uint16_t x) {
+    const uint16_t hb = half_bits(x);
+    const uint16_t sign = hb & 0x8000, mag = hb & 0x7fff;
+    if (mag > 0x7c00) return splat16(0x7e00);                             // NaN
+    if (mag == 0x7c00) return splat16(sign);                              // 1/inf = 0
+    if (mag == 0) return splat16(sign | 0x7c00);                          // a * inf is the IEEE result of a / 0
+    const double r = 1.0 / f16_to_f64(hb);
+    if (std::fabs(r) > 65504.0) ok = false;
+    return splat16(f64_to_f16(r));
+  };
+  s.b1 = splat(b.v[K_B1]);
+  s.c1 = splat(b.v[K_C1]);
+  s.b2 = splat(b.v[K_B2]);
+  s.b2l = splat(b.v[K_B2L]);
+  s.c2 = splat(b.v[K_C2]);
+  s.bc1 = splat(b.v[K_BC1]);
+  s.bc2 = splat(b.v[K_BC2]);
+  s.rbc1 = reciprocal(b.v[K_BC1]);
+  s.rbc2 = reciprocal(b.v[K_BC2]);
+  s.e = splat(b.v[K_EPS]);
+  s.lam = splat(b.v[K_LAM]);
+  s.na = splat(b.v[K_NA]);
+  s.eps_inside_sqrt = s.elementwise = 0;
+  return ok;
 }
 
 }  // namespace mcfh

@@ -42,6 +42,7 @@ using mcfd::ElemIOT;
 using mcfd::P2;
 using mcfd::StepScalars;
 using mcfd::StepScalarsH;
+using mcfd::StepScalarsF8;
 using mcfd::StepScalarsT;
 
 // Compile-time tuning knobs of the step kernels (defaults = the measured best, see above).
@@ -314,7 +315,7 @@ template <int VARIANT> struct StepStreams {
   static constexpr bool kBf16 = kFmt == MCF_COMPONENT_BF16;
   template <bool FAST> using Hot = typename ModeOf<kFmt, FAST>::Hot;
   using Cold = typename ModeOf<kFmt, true>::Cold;
-  using Scalars = StepScalarsT<typename Cold::S>;
+  using Scalars = StepScalarsT<typename Cold::S, typename Cold::Rcp>;
   static constexpr int kEB = Cold::kBytes;                 // bytes per element
   static constexpr int kEps = 16 / kEB;                    // elements per slot
   static constexpr bool kDth = kBase != mcfd::V_BF16;      // second component of theta / Kahan variable
@@ -349,7 +350,7 @@ template <class M, int N> __device__ __forceinline__ uint32_t pack_pairs(const t
 // and FP8: in the mode that stores canonical NaN).
 template <class M, int VARIANT, bool EDQ>
 __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], uint32_t (&out)[kMaxStreams][4],
-                                         const StepScalarsT<typename M::S> &sc, EdqAcc &acc) {
+                                         const StepScalarsT<typename M::S, typename M::Rcp> &sc, EdqAcc &acc) {
   using SS = StepStreams<VARIANT>;
   using T = typename M::T;
   constexpr int kPairs = M::kBytes == 1 ? 2 : 1;
@@ -380,6 +381,12 @@ __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], u
     out[S_M][k] = pack_pairs<M>(m);
     if (SS::kV) out[S_V][k] = pack_pairs<M>(v);
     if (SS::kDv) out[S_DV][k] = pack_pairs<M>(dv);
+    if constexpr (M::kFast && M::kNanOnWords) {
+      // any NaN produced or consumed by the chain reaches theta' or dtheta' (or dv')
+      redo |= M::word_has_nan(out[S_TH][k]);
+      if (SS::kDth) redo |= M::word_has_nan(out[S_DTH][k]);
+      if (SS::kDv) redo |= M::word_has_nan(out[S_DV][k]);
+    }
   }
   return redo;
 }
@@ -455,7 +462,7 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
   // the buffers the loads read, so the compiler would not move a later slot's loads above them.
   Slot slot[kUnroll];
   uint32_t in[kUnroll][kMaxStreams][4];
-  const bool elementwise = SS::kBase != mcfd::V_SGD && sc.eps_inside_sqrt != 0;      // uniform over the launch
+  const bool elementwise = sc.elementwise != 0;      // uniform over the launch
   static_for<0, kUnroll>([&](auto jc) {
     constexpr int j = decltype(jc)::value;
     slot[j] = classify<SS::kEB>(d, slot0 + (uint64_t)j * kStepBlock + threadIdx.x);
@@ -897,6 +904,7 @@ void fill_desc(const mcf_tensor &t, int variant, TensorDesc &d) {
 struct HostScalars {
   StepScalars bf;
   StepScalarsH hf;
+  StepScalarsF8 f8;
   bool fast;
 };
 
@@ -909,13 +917,16 @@ void launch_step(bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *de
   const dim3 g(blocks), b(kStepBlock);
 #endif
   using SS = StepStreams<VARIANT>;
-  if constexpr (SS::kFmt == MCF_COMPONENT_FP16) {
+  if constexpr (SS::kFmt == MCF_COMPONENT_FP16) {          // one first-pass mode
     if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, SS::kLdsEdq, st, descs, chunks, flat, hs.hf, partials, blocks);
     else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, SS::kLds, st, descs, chunks, flat, hs.hf, partials, blocks);
-  } else if (hs.fast) {          // always set for FP8: its one mode has no restrictions
+  } else if constexpr (!SS::kBf16) {                       // FP8, likewise
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, SS::kLdsEdq, st, descs, chunks, flat, hs.f8, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, SS::kLds, st, descs, chunks, flat, hs.f8, partials, blocks);
+  } else if (hs.fast) {
     if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, SS::kLdsEdq, st, descs, chunks, flat, hs.bf, partials, blocks);
     else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, SS::kLds, st, descs, chunks, flat, hs.bf, partials, blocks);
-  } else if constexpr (SS::kBf16) {
+  } else {
     if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, SS::kLdsEdq, st, descs, chunks, flat, hs.bf, partials, blocks);
     else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, SS::kLds, st, descs, chunks, flat, hs.bf, partials, blocks);
   }
@@ -973,12 +984,16 @@ HostScalars host_scalars(const mcf_hyper &h, uint64_t step, int variant) {
     mcfh::derive_scalars_fp16(h, step, hs.hf);
     hs.fast = true;
   } else if (fmt != MCF_COMPONENT_BF16) {
-    mcfh::derive_scalars_fp8(h, step, fmt == MCF_COMPONENT_FP8_E4M3, hs.bf);
     hs.fast = true;
+    if (!mcfh::derive_scalars_fp8(h, step, fmt == MCF_COMPONENT_FP8_E4M3, hs.f8)) hs.f8.elementwise = 1u;
   } else {
     hs.fast = mcfh::derive_scalars(h, step, hs.bf) && !force_exact();
   }
-  hs.bf.eps_inside_sqrt = hs.hf.eps_inside_sqrt = (variant & MCF_EPS_INSIDE_SQRT) ? 1u : 0u;
+  // the printed form of line 12 is compiled into the element path only (SGD has no such line)
+  if ((variant & MCF_EPS_INSIDE_SQRT) && (variant & 0xff) != MCF_SGD) {
+    hs.bf.eps_inside_sqrt = hs.hf.eps_inside_sqrt = hs.f8.eps_inside_sqrt = 1u;
+    hs.bf.elementwise = hs.hf.elementwise = hs.f8.elementwise = 1u;
+  }
   return hs;
 }
 

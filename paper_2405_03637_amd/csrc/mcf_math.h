@@ -92,7 +92,9 @@ template <class R> struct Bf {
   static constexpr bool kFast = R::kFast;      // may raise redo
   static constexpr bool kHalf = false;
   static constexpr bool kGuarded = R::kFast;   // the reciprocal routes need operands checked for range (single operations)
+  static constexpr bool kNanOnWords = false;
   static constexpr int kBytes = 2;             // bytes per stored element
+  using Rcp = float;   // reciprocal of a scalar
   static __device__ __forceinline__ T unpack(uint32_t w) { return widen2(w); }
   static __device__ __forceinline__ uint32_t pack(T x) { return pack2(x); }
   static __device__ __forceinline__ T zero() { return {0.f, 0.f}; }
@@ -164,7 +166,9 @@ template <bool HOT> struct Hf {
   static constexpr bool kFast = HOT;
   static constexpr bool kHalf = true;
   static constexpr bool kGuarded = false;
+  static constexpr bool kNanOnWords = false;
   static constexpr int kBytes = 2;
+  using Rcp = float;   // unused: fp16 divides by the scalar itself
   static __device__ __forceinline__ T unpack(uint32_t w) { return __builtin_bit_cast(h2_t, w); }
   static __device__ __forceinline__ uint32_t raw(T x) { return __builtin_bit_cast(uint32_t, x); }
   // What is stored: the raw pair on the vector path (which has checked that it holds no NaN), the pair
@@ -199,7 +203,7 @@ template <bool HOT> struct Hf {
     const float q1 = __builtin_fmaf(res, r, q);
     return (_Float16)(__builtin_fabsf(q1) > 0.0f ? q1 : q);     // NaN or zero: keep q (a zero quotient keeps a's sign there)
   }
-  static __device__ __forceinline__ T divs(T a, S b, S, bool &) { return h2_t{div1(a.x, b.x), div1(a.y, b.y)}; }
+  static __device__ __forceinline__ T divs(T a, S b, float, bool &) { return h2_t{div1(a.x, b.x), div1(a.y, b.y)}; }
   static __device__ __forceinline__ T divg(T a, T b, bool &) { return h2_t{div1(a.x, b.x), div1(a.y, b.y)}; }
   static __device__ __forceinline__ T sqrt(T a, bool &) {
     return h2_t{(_Float16)__builtin_sqrtf(opaque((float)a.x)), (_Float16)__builtin_sqrtf(opaque((float)a.y))};
@@ -211,92 +215,134 @@ using HalfCold = Hf<false>;
 // ---- FP8 --------------------------------------------------------------------------------
 // The two 8-bit formats of App. A Table 7 (the 8-bit extension named in Sec. 7): E5M2, IEEE-style
 // with infinities, and E4M3 without infinities (largest 448, only S.1111.111 is NaN, whatever rounds
-// beyond 448 becomes NaN).  gfx950 converts both in hardware, round to nearest even, non-saturating,
-// which is exactly that reading (checked against the definition over all 2^32 fp32 inputs by the test
-// suite).  A pair is held widened in two fp32 registers as for bf16; F(a o b) is the fp32 operation per
-// element, one v_cvt_pk_{bf8,fp8}_f32 for the pair and one v_cvt_pk_f32_{bf8,fp8} to widen it back.
-// Division is the corrected quotient of the fp16 mode (exact whenever a/b is an fp32 number, so the
-// exact ties that do occur among subnormal results survive; every other quotient of two 3- or 4-bit
-// numbers is further than 2^-12 from a rounding boundary); the square root is v_sqrt_f32 (1 ulp): the
-// root of an 8-bit number is never a rounding boundary and stays more than 2^-12 away from one.  Both
-// are checked over every operand pair and every input.  Widened operands are normal fp32 numbers or
-// zero, so no range guards are needed.  NaN: as for fp16, the first pass detects, the redo stores the
-// format's one NaN (0x7E, 0x7F).
+// beyond 448 becomes NaN).  gfx950 converts to and from both in hardware, round to nearest even,
+// non-saturating, which is exactly that reading: from fp32 (v_cvt_pk_{bf8,fp8}_f32, checked against the
+// definition over all 2^32 inputs by the test suite) and from fp16 (v_cvt_scalef32_pk_{bf8,fp8}_f16 with
+// scale 1, equal to the definition on all 2^16 fp16 inputs).
+//
+// Every FP8 number is an fp16 number, so a pair is held as packed fp16 and +, -, * and the FMA of Alg. 6
+// are the packed fp16 instructions followed by the conversion to the 8-bit format and back: three
+// instructions per pair.  That is F(a o b): the fp16 instruction rounds the exact result to 11 bits, and
+// rounding that again to 3 or 4 bits gives what rounding the exact result (or its fp32 rounding) once
+// would, since 11 >= 2*4+2; where fp16 itself runs out, the results agree too -- sums and differences
+// of FP8 numbers and products of E4M3 numbers are fp16 numbers exactly; an E5M2 product below fp16's
+// grid (2^-24) is below 2^-19 and rounds to zero either way; whatever overflows fp16 (65520 and up) is
+// beyond both formats' ranges.  For the FMA, a*b - F(a*b) is an fp16 number whenever a*b >= 2^-17, and
+// rounds to zero either way below.
+//
+// A pair also carries the two 8-bit patterns it was decoded from (every rounding produces them on the
+// way): packing a result is then one byte permute, and the fp32 operations below widen from the
+// patterns, one instruction per pair.
+//
+// Quotient: fl32(a * r), r = v_rcp_f32(b), rounded to fp16 and then to the format.  A quotient of two
+// 3- or 4-bit significands that is an exact tie of the 8-bit rounding is an fp16 number, and a*r lies
+// within 2^-22 of it, so the fp16 rounding lands on it and the tie is seen as a tie; every other
+// quotient is further than 2^-9 (relative; 2^-22 absolute among E5M2's subnormal results) from the
+// nearest rounding boundary and cannot cross it.  a * inf, a * 0 and their NaN cases are IEEE's a / 0
+// and a / inf.  Checked on the CPU against the definition for all 256 x 256 operands with r anywhere
+// within two units in the last place of 1/b (tests/test_oracle_fp8.py), and on the GPU for all of them.
+// Quotient by a scalar b: one packed fp16 multiplication by RN16(1/b), then the conversion: right for
+// every a and b (same CPU test) except E5M2's b = +-2^-16, whose reciprocal is not an fp16 number; the
+// host sends such a step to the element path, whose mode divides by b as above.
+// Root: v_sqrt_f32, then one conversion from fp32 (a root of a 3- or 4-bit number is either exact or
+// further than 2^-12 from any boundary; checked on every input).
+// NaN: as for fp16, the first pass detects, the redo stores the format's one NaN (0x7E, 0x7F).
+typedef short s16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
 template <bool E4M3> struct F8Cvt {
-  // two fp32 -> two 8-bit patterns in the low (HIGH = false) or high half of `old`
-  template <bool HIGH> static __device__ __forceinline__ uint32_t enc(float a, float b, uint32_t old) {
-    if constexpr (E4M3) return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, HIGH);
-    else return (uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(a, b, (int)old, HIGH);
+  // two fp32 -> two 8-bit patterns in the low half of the result (the other half comes from `old`)
+  static __device__ __forceinline__ uint32_t enc_f32(float a, float b, uint32_t old) {
+    if constexpr (E4M3) return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, false);
+    else return (uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(a, b, (int)old, false);
   }
-  // the two 8-bit patterns in the low (HIGH = false) or high half of w -> two fp32, one instruction
-  template <bool HIGH> static __device__ __forceinline__ P2 dec2(uint32_t w) {
-    f32x2_t r;
-    if constexpr (E4M3) r = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, HIGH);
-    else r = __builtin_amdgcn_cvt_pk_f32_bf8((int)w, HIGH);
-    return {r.x, r.y};
+  // packed fp16 pair -> two 8-bit patterns in the low half of the result
+  static __device__ __forceinline__ uint32_t enc(h2_t x, uint32_t old) {
+    const s16x2_t o = __builtin_bit_cast(s16x2_t, old);
+    if constexpr (E4M3) return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_fp8_f16(o, x, 1.0f, false));
+    else return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf8_f16(o, x, 1.0f, false));
+  }
+  // the two 8-bit patterns in the low or high half of w -> packed fp16 pair (exact)
+  template <bool HIGH> static __device__ __forceinline__ h2_t dec(uint32_t w) {
+    if constexpr (E4M3) return __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, HIGH);
+    else return __builtin_amdgcn_cvt_scalef32_pk_f16_bf8(w, 1.0f, HIGH);
+  }
+  // the two 8-bit patterns in the low half of w -> two fp32 (exact)
+  static __device__ __forceinline__ f32x2_t dec_f32(uint32_t w) {
+    if constexpr (E4M3) return __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
+    else return __builtin_amdgcn_cvt_pk_f32_bf8((int)w, false);
   }
   static __device__ __forceinline__ uint32_t canon(uint32_t b) {      // one 8-bit pattern
     if constexpr (E4M3) return (b & 0x7fu) == 0x7fu ? 0x7fu : b;
     else return (b & 0x7fu) > 0x7cu ? 0x7eu : b;
   }
+  // Adding this to the magnitude bits of a pattern carries into bit 7 exactly for the NaN patterns.
+  static constexpr uint32_t kNanCarry = E4M3 ? 0x01u : 0x03u;
 };
 
-// a / b from r ~ 1/b: q + (a - b*q)*r, keeping q where the correction is NaN (zero or infinite operand)
-// or zero (sign of a zero dividend).
-__device__ __forceinline__ float div_corrected(float a, float b, float r) {
-  const float q = a * r;
-  const float res = __builtin_fmaf(-b, q, a);
-  const float q1 = __builtin_fmaf(res, r, q);
-  return __builtin_fabsf(q1) > 0.0f ? q1 : q;
-}
+struct F8Pair {
+  h2_t h;         // the two values
+  uint32_t e;     // their 8-bit patterns in bits 0-15; bits 16-31 are not meaningful
+};
 
 template <bool E4M3, bool HOT> struct F8 {
   using C = F8Cvt<E4M3>;
-  using T = P2;
-  using S = float;
+  using T = F8Pair;
+  using S = h2_t;      // a scalar is the same fp16 value in both halves
+  using Rcp = h2_t;    // reciprocal of a scalar, likewise
   static constexpr bool kFast = HOT;       // may raise redo (NaN among the results)
   static constexpr bool kHalf = false;
   static constexpr bool kGuarded = false;
+  static constexpr bool kNanOnWords = true;      // the step looks for NaN in the packed result words instead of per pair
   static constexpr int kBytes = 1;
+  static __device__ __forceinline__ uint32_t raw(h2_t x) { return __builtin_bit_cast(uint32_t, x); }
   // pair PAIR (0 or 1) of the four elements in a dword
-  template <int PAIR> static __device__ __forceinline__ T unpack(uint32_t w) { return C::template dec2<PAIR == 1>(w); }
+  template <int PAIR> static __device__ __forceinline__ T unpack(uint32_t w) { return T{C::template dec<PAIR == 1>(w), PAIR == 1 ? w >> 16 : w}; }
   static __device__ __forceinline__ T unpack(uint32_t w) { return unpack<0>(w); }
   static __device__ __forceinline__ uint32_t pack(T a, T b) {          // four elements -> one dword
-    uint32_t w = C::template enc<false>(a.lo, a.hi, fbits(a.lo));       // both halves are overwritten
-    w = C::template enc<true>(b.lo, b.hi, w);
+    const uint32_t w = __builtin_amdgcn_perm(b.e, a.e, 0x05040100u);   // a's two low bytes, then b's
     if (HOT) return w;
     return C::canon(w & 0xffu) | (C::canon((w >> 8) & 0xffu) << 8) | (C::canon((w >> 16) & 0xffu) << 16) | (C::canon(w >> 24) << 24);
   }
-  static __device__ __forceinline__ T zero() { return {0.f, 0.f}; }
-  static __device__ __forceinline__ float lo(T x) { return x.lo; }
-  static __device__ __forceinline__ float hi(T x) { return x.hi; }
-  static __device__ __forceinline__ uint16_t bits_lo(T x) { return (uint16_t)C::canon(C::template enc<false>(x.lo, x.hi, 0u) & 0xffu); }
-  static __device__ __forceinline__ uint16_t bits_hi(T x) { return (uint16_t)C::canon((C::template enc<false>(x.lo, x.hi, 0u) >> 8) & 0xffu); }
-  static __device__ __forceinline__ bool any_nan(T x) { return is_nan(x.lo) | is_nan(x.hi); }
+  static __device__ __forceinline__ T zero() { return T{h2_t{(_Float16)0, (_Float16)0}, 0u}; }
+  static __device__ __forceinline__ float lo(T x) { return (float)x.h.x; }
+  static __device__ __forceinline__ float hi(T x) { return (float)x.h.y; }
+  static __device__ __forceinline__ uint16_t bits_lo(T x) { return (uint16_t)C::canon(x.e & 0xffu); }
+  static __device__ __forceinline__ uint16_t bits_hi(T x) { return (uint16_t)C::canon((x.e >> 8) & 0xffu); }
+  static __device__ __forceinline__ bool any_nan(T x) { return (((x.e & 0x7f7fu) + C::kNanCarry * 0x0101u) & 0x8080u) != 0; }
+  static __device__ __forceinline__ bool word_has_nan(uint32_t w) { return (((w & 0x7f7f7f7fu) + C::kNanCarry * 0x01010101u) & 0x80808080u) != 0; }
   // The conversion writes one half of its destination and keeps the other half from `old`.  Only the
-  // written half is read back, so `old` is given a value that dies here (the unrounded x.lo) and the
+  // written half is read back, so `old` is given a value that dies here (the unrounded x) and the
   // destination can take over its register; a constant would cost a move per rounding.
-  static __device__ __forceinline__ T rnd(T x) { return C::template dec2<false>(C::template enc<false>(x.lo, x.hi, fbits(x.lo))); }
-  static __device__ __forceinline__ T round_f32(float a, float b) { return rnd({a, b}); }
+  static __device__ __forceinline__ T rnd(h2_t x, uint32_t old) { const uint32_t e = C::enc(x, old); return T{C::template dec<false>(e), e}; }
+  static __device__ __forceinline__ T rnd(h2_t x) { return rnd(x, raw(x)); }
+  static __device__ __forceinline__ T rnd_f32(float a, float b) { const uint32_t e = C::enc_f32(a, b, fbits(a)); return T{C::template dec<false>(e), e}; }
+  static __device__ __forceinline__ T round_f32(float a, float b) { return rnd_f32(a, b); }
   static __device__ __forceinline__ void guard_root_operand(T, bool &) {}
 
-  static __device__ __forceinline__ T add(T a, T b) { return rnd({a.lo + b.lo, a.hi + b.hi}); }
-  static __device__ __forceinline__ T sub(T a, T b) { return rnd({a.lo - b.lo, a.hi - b.hi}); }
-  static __device__ __forceinline__ T mul(T a, T b) { return rnd({a.lo * b.lo, a.hi * b.hi}); }
-  static __device__ __forceinline__ T adds(T a, S s) { return rnd({a.lo + s, a.hi + s}); }
-  static __device__ __forceinline__ T muls(S s, T a) { return rnd({s * a.lo, s * a.hi}); }
-  static __device__ __forceinline__ T fmss(S s, T a, T x) { return rnd({__builtin_fmaf(s, a.lo, -x.lo), __builtin_fmaf(s, a.hi, -x.hi)}); }
-  static __device__ __forceinline__ T fms(T a, T b, T x) { return rnd({__builtin_fmaf(a.lo, b.lo, -x.lo), __builtin_fmaf(a.hi, b.hi, -x.hi)}); }
-  // a / b for a scalar b whose reciprocal rb = fl32(1/b) was rounded correctly on the host: a*rb rounds to
-  // the same 8-bit result as the IEEE quotient for every one of the 256 x 256 (a, b), zero and infinite b
-  // included (checked exhaustively on the CPU, IEEE multiplication only: tests/test_oracle_fp8.py).
-  static __device__ __forceinline__ T divs(T a, S, S rb, bool &) { return rnd({a.lo * rb, a.hi * rb}); }
-  // a / b for any b: v_rcp_f32 is not the correctly rounded reciprocal, and a*v_rcp_f32(b) alone breaks
-  // exact ties (28 of the 65,536 E4M3 pairs come out wrong), hence the correction.
-  static __device__ __forceinline__ T divg(T a, T b, bool &) {
-    return rnd({div_corrected(a.lo, b.lo, __builtin_amdgcn_rcpf(b.lo)), div_corrected(a.hi, b.hi, __builtin_amdgcn_rcpf(b.hi))});
+  static __device__ __forceinline__ T add(T a, T b) { return rnd(a.h + b.h); }
+  static __device__ __forceinline__ T sub(T a, T b) { return rnd(a.h - b.h); }
+  static __device__ __forceinline__ T mul(T a, T b) { return rnd(a.h * b.h); }
+  static __device__ __forceinline__ T adds(T a, S s) { return rnd(a.h + s); }
+  static __device__ __forceinline__ T muls(S s, T a) { return rnd(s * a.h); }
+  static __device__ __forceinline__ T fmss(S s, T a, T x) { return rnd(__builtin_elementwise_fma(s, a.h, -x.h)); }
+  static __device__ __forceinline__ T fms(T a, T b, T x) { return rnd(__builtin_elementwise_fma(a.h, b.h, -x.h)); }
+  static __device__ __forceinline__ T quotient(f32x2_t a, float blo, float bhi) {
+    const float qlo = a.x * __builtin_amdgcn_rcpf(blo), qhi = a.y * __builtin_amdgcn_rcpf(bhi);
+    return rnd(h2_t{(_Float16)qlo, (_Float16)qhi}, fbits(qlo));
   }
-  static __device__ __forceinline__ T sqrt(T a, bool &) { return rnd({__builtin_amdgcn_sqrtf(a.lo), __builtin_amdgcn_sqrtf(a.hi)}); }
+  static __device__ __forceinline__ T divs(T a, S b, Rcp rb, bool &) {
+    if (HOT) return rnd(a.h * rb);
+    return quotient(C::dec_f32(a.e), (float)b.x, (float)b.y);
+  }
+  static __device__ __forceinline__ T divg(T a, T b, bool &) {
+    const f32x2_t fb = C::dec_f32(b.e);
+    return quotient(C::dec_f32(a.e), fb.x, fb.y);
+  }
+  static __device__ __forceinline__ T sqrt(T a, bool &) {
+    const f32x2_t fa = C::dec_f32(a.e);
+    return rnd_f32(__builtin_amdgcn_sqrtf(fa.x), __builtin_amdgcn_sqrtf(fa.y));
+  }
 };
 
 // The expansion algorithms over any of the modes above.
@@ -333,14 +379,17 @@ template <class M> struct Ops : M {
 };
 
 // Scalars of one step in the mode's scalar type (bf16 values widened to fp32, or fp16 values in both
-// halves of a packed register), plus, for the bf16 Fast mode, fp32 reciprocals of the two bias
-// corrections.
-template <class S> struct StepScalarsT {
-  S b1, c1, b2, b2l, c2, bc1, bc2, rbc1, rbc2, e, lam, na;
+// halves of a packed register), plus reciprocals of the two bias corrections for the modes that
+// multiply by them.
+template <class S, class Rcp> struct StepScalarsT {
+  S b1, c1, b2, b2l, c2, bc1, bc2, e, lam, na;
+  Rcp rbc1, rbc2;                // 1/bc1, 1/bc2 rounded to Rcp: the bf16 Fast mode and the FP8 first pass multiply by them
   uint32_t eps_inside_sqrt;      // 1: line 12's denominator is F(sqrt(F(v_hat + eps))), as Alg. 2 prints it
+  uint32_t elementwise;          // 1: every slot of this launch takes the element path
 };
-using StepScalars = StepScalarsT<float>;
-using StepScalarsH = StepScalarsT<h2_t>;
+using StepScalars = StepScalarsT<float, float>;      // bf16
+using StepScalarsH = StepScalarsT<h2_t, float>;      // fp16
+using StepScalarsF8 = StepScalarsT<h2_t, h2_t>;      // FP8
 
 template <class T> struct ElemIOT {          // one pair of elements of every stream
   T th, dth, m, v, dv, g;
@@ -356,7 +405,7 @@ enum : int { V_LIGHT = 0, V_PLUS = 1, V_BF16 = 2, V_KAHAN = 3, V_SGD = 4 };
 // delta receives line 12's update.  redo is raised (modes with kFast) when this pair must be
 // recomputed element by element.
 template <class M, int VARIANT, bool GROW2 = false, bool EPS_INSIDE = false>
-__device__ __forceinline__ void adamw_pair(ElemIOT<typename M::T> &io, const StepScalarsT<typename M::S> &s,
+__device__ __forceinline__ void adamw_pair(ElemIOT<typename M::T> &io, const StepScalarsT<typename M::S, typename M::Rcp> &s,
                                            typename M::T &delta, bool &redo) {
   using O = Ops<M>;
   using T = typename M::T;
@@ -365,7 +414,7 @@ __device__ __forceinline__ void adamw_pair(ElemIOT<typename M::T> &io, const Ste
     delta = O::muls(s.na, O::add(m1, O::muls(s.lam, io.th)));
     T th1, dth1;
     O::grow(io.th, io.dth, delta, th1, dth1);
-    if (M::kFast) redo |= M::any_nan(th1) | M::any_nan(dth1);
+    if (M::kFast && !M::kNanOnWords) redo |= M::any_nan(th1) | M::any_nan(dth1);
     io.th = th1;
     io.dth = dth1;
     io.m = m1;
@@ -416,9 +465,10 @@ __device__ __forceinline__ void adamw_pair(ElemIOT<typename M::T> &io, const Ste
   } else {
     O::grow(io.th, io.dth, delta, th1, dth1);
   }
-  if (M::kFast) {
+  if (M::kFast && !M::kNanOnWords) {
     // Any NaN produced or consumed above reaches theta' or dtheta' (or dv'): m' and v' feed
-    // the quotient, the quotient feeds delta, delta feeds theta'.
+    // the quotient, the quotient feeds delta, delta feeds theta'.  (Modes with kNanOnWords leave this
+    // check to the caller, on the packed words of the same three results.)
     redo |= M::any_nan(th1) | M::any_nan(dth1);
     if (VARIANT == V_PLUS) redo |= M::any_nan(dv1);
   }

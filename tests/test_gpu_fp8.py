@@ -174,6 +174,43 @@ def test_fp8_special_values(fmt, variant):
 
 
 @pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("variant", ["light", "plus"])
+def test_fp8_bias_corrections_of_many_steps_and_betas(fmt, variant):
+    """The vector path multiplies by the fp16 reciprocal of each bias correction instead of dividing: one
+    step from the same all-patterns state for many (beta1, beta2, t), so that the two corrections take
+    most of the values they can, every element against the oracle."""
+    n = 1 << 16
+    code = {"light": mcf.LIGHT, "plus": mcf.PLUS}[variant] | (fmt << 12)
+    state0 = {k: _random_fp8(n, 300 + i) for i, k in enumerate(("theta", "dtheta", "m", "v", "dv", "grad"))}
+    state0["v"] &= 0x7F
+    if variant != "plus":
+        state0["dv"] = None
+    seen = set()
+    tiny = 1.0 - 2.0 ** -16        # first-step correction 2^-16: E5M2's smallest number, whose reciprocal is no fp16 number
+    for b1 in (0.0, 0.25, 0.5, 0.75, 0.875, tiny):
+        for b2 in (0.5, 0.8125, 0.9375, 0.96875, tiny):
+            hyper = (2.0 ** -6, b1, b2, 2.0 ** -6, 0.125)
+            for t in (1, 2, 3, 4, 6, 9, 14, 40):
+                bits = orc.scalars(*hyper, t, fmt=fmt)
+                seen.add((int(bits["bc1"]), int(bits["bc2"])))
+                host = {k: (None if v is None else v.copy()) for k, v in state0.items()}
+                dev = {k: (None if v is None else _dev(v)) for k, v in state0.items()}
+                orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], host["dv"], host["grad"], code, hyper, t)
+                mcf.adamw_step_flat(dev["theta"], dev["dtheta"], dev["m"], dev["v"], dev["dv"], dev["grad"], code, hyper, t)
+                for k in ("theta", "dtheta", "m", "v", "dv"):
+                    if host[k] is None:
+                        continue
+                    got = H.torch_to_u16(dev[k])
+                    bad = np.flatnonzero(got != host[k])
+                    assert bad.size == 0, f"fmt {fmt} {variant} betas ({b1}, {b2}) step {t} {k}: {bad.size} mismatches, " \
+                                          f"first {int(bad[0])}: got {got[bad[0]]:#04x} want {host[k][bad[0]]:#04x}"
+        _say(f"fp8 fmt {fmt} {variant} beta1 {b1}: ok, {len(seen)} distinct correction pairs so far")
+    assert len(seen) >= 12
+    if fmt == 2:
+        assert any(0x01 in pair for pair in seen)          # the corner was met
+
+
+@pytest.mark.parametrize("fmt", FMTS)
 def test_fp8_edq_standalone(fmt):
     n = 300_001
     rng = np.random.default_rng(280 + fmt)

@@ -373,17 +373,46 @@ def test_e4m3_overflow_is_nan_and_e5m2_overflow_is_infinity(orc, fmt):
         assert np.isnan(orc.widen(0x7F, fmt=fmt)) and np.isnan(orc.widen(0xFF, fmt=fmt))
 
 
+def _same_patterns(orc, fmt, got, want):
+    """Equal 8-bit patterns, any NaN matching any NaN."""
+    nan_got, nan_want = np.isnan(orc.widen_array(got, fmt=fmt)), np.isnan(orc.widen_array(want, fmt=fmt))
+    return (got == want) | (nan_got & nan_want)
+
+
 @pytest.mark.parametrize("fmt", FMTS)
-def test_division_by_a_scalar_through_its_fp32_reciprocal(orc, fmt):
-    """What the GPU kernels rely on for the two bias corrections: with r = fl32(1/b) (b's reciprocal
-    computed in fp64 and rounded to fp32), F(a * r) is the same 8-bit pattern as F(a / b) for every one of
-    the 256 x 256 (a, b) -- exact quotients and the exact ties among subnormal results included, b = 0,
-    infinite or NaN included.  Only IEEE fp32 multiplication is involved, so this holds on any machine."""
+@pytest.mark.parametrize("ulps", [0, 1, -1, 2, -2])
+def test_quotient_through_an_fp32_reciprocal_and_an_fp16_rounding(orc, fmt, ulps):
+    """What the GPU kernels rely on for F(a / b): fl32(a * r), rounded to fp16 and then to the format, is
+    F(a / b) for every one of the 256 x 256 (a, b) as long as r is within two units in the last place of
+    1/b -- the exact ties among the quotients are fp16 numbers, so the fp16 rounding restores them and
+    the last rounding sees them as ties; b = 0, infinite or NaN included.  IEEE fp32 and fp16 arithmetic
+    only, so this holds on any machine (the hardware's reciprocal instruction is within one unit)."""
     v = orc.widen_array(ALL, fmt=fmt)
     a, b = np.repeat(v, 256), np.tile(v, 256)
     with np.errstate(all="ignore"):
         r = (1.0 / b.astype(np.float64)).astype(np.float32)
-        via_reciprocal = (a * r).astype(np.float32)
-    got = orc.R_array(via_reciprocal, fmt=fmt)
+        moved = r.copy()
+        for _ in range(abs(ulps)):
+            moved = np.nextafter(moved, np.float32(np.inf if ulps > 0 else -np.inf) * np.sign(r).astype(np.float32))
+        r = np.where(np.isfinite(r) & (r != 0), moved, r)
+        q16 = (a * r).astype(np.float32).astype(np.float16)
+    got = orc.R_array(q16.astype(np.float32), fmt=fmt)
     want = orc.binop(3, np.repeat(ALL, 256), np.tile(ALL, 256), fmt=fmt)
-    assert np.array_equal(got, want)
+    assert _same_patterns(orc, fmt, got, want).all()
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+def test_division_by_a_scalar_through_its_fp16_reciprocal(orc, fmt):
+    """What the GPU kernels rely on for the two bias corrections: with r = RN16(1/b), one fp16
+    multiplication a * r followed by the rounding to the format is F(a / b) for every a and every b whose
+    reciprocal is an fp16 number -- all of E4M3, and all of E5M2 but +-2^-16 (the library sends a step
+    with such a bias correction down its element path, which divides properly)."""
+    v = orc.widen_array(ALL, fmt=fmt)
+    a, b = np.repeat(v, 256), np.tile(v, 256)
+    with np.errstate(all="ignore"):
+        r16 = (1.0 / b.astype(np.float64)).astype(np.float16)
+        prod = (a.astype(np.float64) * r16.astype(np.float64)).astype(np.float16)       # exact product, one rounding
+    got = orc.R_array(prod.astype(np.float32), fmt=fmt)
+    want = orc.binop(3, np.repeat(ALL, 256), np.tile(ALL, 256), fmt=fmt)
+    bad_b = np.unique(np.abs(b[~_same_patterns(orc, fmt, got, want)]))
+    assert list(bad_b) == ([] if fmt == orc.FMT_E4M3 else [2.0 ** -16])
