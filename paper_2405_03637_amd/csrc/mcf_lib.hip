@@ -327,8 +327,8 @@ template <int VARIANT> struct StepStreams {
   // against 15.09 at 10), the 7-stream SGD at 10-11.  With the fp64 EDQ sums fused in there is more
   // arithmetic to hide: 14 (light 18.62 ms against 20.43 at 10), plain variant 16.
   // The FP8 kernels move half the bytes with about the same arithmetic (a conversion to and from the
-  // 8-bit format around every operation) and are bound by the vector ALU, not by HBM: they run uncapped
-  // (light E5M2, 7B set: 16.7 ms at 10 groups per CU, 15.3 at 16, 15.0 uncapped).
+  // 8-bit format around every operation): their vector-ALU time is level with their HBM time and they run
+  // uncapped (light E5M2, 7B set: 10.5 ms uncapped, 10.7-10.9 at 12 to 24 groups per CU).
 #ifdef MCF_STEP_LDS
   static constexpr uint32_t kLds = MCF_STEP_LDS;
 #else
