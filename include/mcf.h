@@ -60,7 +60,7 @@ extern "C" {
 typedef enum {
   MCF_OK = 0,
   MCF_ERR_NULL = -1,     /* a required pointer is NULL */
-  MCF_ERR_SIZE = -2,     /* a size is out of range (tensor longer than 2^35 elements, table too large) */
+  MCF_ERR_SIZE = -2,     /* a size is out of range (tensor longer than 2^35 - 128 elements, table too large) */
   MCF_ERR_ALIGN = -3,    /* a pointer is not aligned to its element size */
   MCF_ERR_VARIANT = -4,  /* variant is not one of mcf_variant, or an operation code is unknown */
   MCF_ERR_STEP = -5,     /* step < 1 (the bias correction 1 - beta^0 would be zero) */

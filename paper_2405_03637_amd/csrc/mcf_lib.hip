@@ -1,7 +1,7 @@
 // Kernels, launch tables and the C ABI of the Collage optimizer step for gfx950.
 //
-// Work decomposition.  A tensor is cut into SLOTS of 8 consecutive 16-bit elements (bf16 or fp16; 16 bytes per
-// stream) counted from the 128-byte boundary at or below its first element, so that a
+// Work decomposition.  A tensor is cut into SLOTS of 16 bytes per stream (8 consecutive bf16 or fp16
+// elements, 16 FP8 elements) counted from the 128-byte boundary at or below its first element, so that a
 // slot is one 128-bit access per stream whatever the tensor's own alignment and every
 // wave's 1 KiB run covers whole cache lines (counting from the 16-byte boundary instead, waves of
 // neighbouring workgroups share lines: a set of tensors at odd offsets ran at 5.2 instead of 5.8 TB/s); the slots
@@ -85,14 +85,14 @@ constexpr int kStepBlock = MCF_BLOCK;
 constexpr int kUnroll = MCF_UNROLL;
 constexpr uint32_t kSlotsPerChunk = kStepBlock * kUnroll;
 constexpr int kBlock = 256;          // threads per workgroup of the primitives and reduction tails
-constexpr uint64_t kMaxTensorElems = 1ull << 35;
+constexpr uint64_t kMaxTensorElems = (1ull << 35) - 128;   // keeps a tensor's slot count, phase included, below 2^32
 constexpr int kMaxStreams = 6;
 
 // Streams of the Collage step, in descriptor order.
 enum { S_TH = 0, S_DTH = 1, S_M = 2, S_V = 3, S_G = 4, S_DV = 5 };
 
 struct TensorDesc {
-  uint64_t p[kMaxStreams];   // element pointers (16-bit elements), as integers
+  uint64_t p[kMaxStreams];   // the streams' device addresses, as integers
   uint64_t n;                // elements
   uint32_t phase;            // elements between the MCF_CHUNK_ALIGN-byte boundary below p[0] and p[0]
   uint32_t scalar_only;      // 1: streams are not mutually aligned, every slot goes element by element
@@ -101,7 +101,7 @@ static_assert(sizeof(TensorDesc) == 64, "descriptor is one 64-byte scalar load")
 
 struct Chunk {
   uint32_t tensor;
-  uint32_t slot0;
+  uint32_t slot0;     // first slot of the chunk within its tensor (plan creation refuses a tensor with 2^32 slots or more)
 };
 
 struct Slot {       // where one lane's 16 bytes of elements sit
@@ -1105,7 +1105,7 @@ int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, i
     fill_desc(tensors[i], variant, d);
     const uint64_t slots = slots_of(d.n, d.phase, elem_bytes_of(format_of(variant)));
     const uint64_t nch = (slots + kSlotsPerChunk - 1) / kSlotsPerChunk;
-    if (chunks.size() + nch > 0x7fffffffull) return MCF_ERR_SIZE;
+    if (slots > 0xffffffffull || chunks.size() + nch > 0x7fffffffull) return MCF_ERR_SIZE;
     const uint32_t id = (uint32_t)descs.size();
     descs.push_back(d);
     for (uint64_t c = 0; c < nch; ++c) chunks.push_back(Chunk{id, (uint32_t)(c * kSlotsPerChunk)});
@@ -1409,8 +1409,9 @@ int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tenso
     for (uint64_t f : f32s) ok = ok && (((f - 4ull * ph) & 15) == 0);
     d.phase = ok ? ph : 0;
     d.scalar_only = ok ? 0 : 1;
-    const uint64_t nch = (slots_of(d.n, d.phase) + kSlotsPerChunk - 1) / kSlotsPerChunk;
-    if (chunks.size() + nch > 0x7fffffffull) return MCF_ERR_SIZE;
+    const uint64_t slots = slots_of(d.n, d.phase);
+    const uint64_t nch = (slots + kSlotsPerChunk - 1) / kSlotsPerChunk;
+    if (slots > 0xffffffffull || chunks.size() + nch > 0x7fffffffull) return MCF_ERR_SIZE;
     const uint32_t id = (uint32_t)descs.size();
     descs.push_back(d);
     for (uint64_t c = 0; c < nch; ++c) chunks.push_back(Chunk{id, (uint32_t)(c * kSlotsPerChunk)});

@@ -69,7 +69,7 @@ def test_flat_step_argument_errors():
     assert _flat(variant=3, dtheta=None) == mcf.MCF_ERR_NULL          # Kahan needs its variable
     assert _flat(variant=-1) == mcf.MCF_ERR_VARIANT
     assert _flat(m=FAKE + 1) == mcf.MCF_ERR_ALIGN
-    assert _flat(n=(1 << 35) + 1) == mcf.MCF_ERR_SIZE
+    assert _flat(n=(1 << 35) - 127) == mcf.MCF_ERR_SIZE
     assert _flat(step=0) == mcf.MCF_ERR_STEP
     assert _flat(hyper=_hyper(beta1=1.0)) == mcf.MCF_ERR_HYPER
     assert _flat(hyper=_hyper(beta2=-0.1)) == mcf.MCF_ERR_HYPER
@@ -91,7 +91,7 @@ def test_plan_argument_errors():
     assert lib.mcf_plan_create(ctypes.byref(h), one, 1, 1) == mcf.MCF_ERR_NULL           # plus needs dv
     bad = (mcf.Tensor * 1)(mcf.Tensor(FAKE, FAKE + 1, FAKE, FAKE, None, FAKE, 8))
     assert lib.mcf_plan_create(ctypes.byref(h), bad, 1, 0) == mcf.MCF_ERR_ALIGN
-    big = (mcf.Tensor * 1)(mcf.Tensor(FAKE, FAKE, FAKE, FAKE, None, FAKE, (1 << 35) + 8))
+    big = (mcf.Tensor * 1)(mcf.Tensor(FAKE, FAKE, FAKE, FAKE, None, FAKE, (1 << 35) - 127))
     assert lib.mcf_plan_create(ctypes.byref(h), big, 1, 0) == mcf.MCF_ERR_SIZE
     assert not h.value
     hy = _hyper()
@@ -138,7 +138,7 @@ def test_primitive_argument_errors():
     assert lib.mcf_two_sum(FAKE, FAKE, FAKE, None, 4, None) == mcf.MCF_ERR_NULL
     assert lib.mcf_grow(FAKE, None, FAKE, 4, None) == mcf.MCF_ERR_NULL
     assert lib.mcf_fast2sum(FAKE + 1, FAKE, FAKE, FAKE, 4, None) == mcf.MCF_ERR_ALIGN
-    assert lib.mcf_grow(FAKE, FAKE, FAKE, (1 << 35) + 1, None) == mcf.MCF_ERR_SIZE
+    assert lib.mcf_grow(FAKE, FAKE, FAKE, (1 << 35) - 127, None) == mcf.MCF_ERR_SIZE
     assert lib.mcf_fast2sum(None, None, None, None, 0, None) == mcf.MCF_OK
     assert lib.mcf_grow_two_sum(FAKE, FAKE, None, 4, None) == mcf.MCF_ERR_NULL
     assert lib.mcf_two_prod_fma(FAKE, FAKE, FAKE, None, 4, None) == mcf.MCF_ERR_NULL
