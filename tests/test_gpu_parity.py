@@ -557,6 +557,24 @@ def test_config4_llama_7b():
     _sampled_run("llama_7b", 10, {1, 2, 5, 10})
 
 
+@pytest.mark.parametrize("variant", ["plus", "kahan", "bf16", "sgd", "light+twosum", "plus+twosum"])
+def test_llama_7b_other_strategies_sampled(variant):
+    """The other strategies the benchmark times on the 7B-shaped set, in that launch configuration: three
+    steps, sampled elements of every tensor against the oracle."""
+    _say(f"llama_7b {variant}: building")
+    wl = Workload("llama_7b", variant=variant)
+    idx = sample_indices(wl.shapes, wl.offs, seed=9)
+    so = SampledOracle(wl, idx)
+    for t in range(1, 4):
+        wl.new_grads(t)
+        so.step(t)
+        wl.plan.step(wl.hyper, t)
+        torch.cuda.synchronize()
+        assert_bitwise(so.mismatches(), f"llama_7b {variant} step {t}")
+        _say(f"llama_7b {variant} step {t}: {idx.size} sampled elements identical")
+    wl.close()
+
+
 def test_config5_stress_64m():
     """Config 5: 64 Mi parameters incl. 4096 tensors of 1..256 elements at odd offsets, plus, lr = 2^-20,
     1000 steps.  Every tiny tensor and windows of the large ones are followed by the oracle."""
