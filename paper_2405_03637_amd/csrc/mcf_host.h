@@ -173,9 +173,9 @@ inline ScalarBits scalar_bits_e5m2(const mcf_hyper &h, uint64_t step) { return d
 inline ScalarBits scalar_bits_e4m3(const mcf_hyper &h, uint64_t step) { return derive_bits<f64_to_e4m3, e4m3_to_f64>(h, step); }
 
 // Returns the scalars and whether the Fast arithmetic mode may be used with them: the two
-// bias corrections must be normal numbers in (0, 1] (so that dividing by them cannot shrink
-// a normal number into the subnormal range) and epsilon zero or a normal number of sane
-// size (so that sqrt(v)+eps is zero, or normal with a normal reciprocal).
+// bias corrections must be numbers in [2^-60, 1] (their fp32 reciprocals are then normal and correctly
+// rounded) and epsilon zero or a normal number of sane size (so that sqrt(v)+eps is zero, or
+// normal with a normal reciprocal).
 inline bool derive_scalars(const mcf_hyper &h, uint64_t step, mcfd::StepScalars &s) {
   const ScalarBits b = scalar_bits_bf16(h, step);
   s.b1 = bf16_to_f32(b.v[K_B1]);

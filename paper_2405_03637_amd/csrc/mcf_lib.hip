@@ -496,10 +496,18 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
           redo = false;
         }
       }
-      // bf16: a slot that met a subnormal intermediate or a NaN in Fast mode goes to the element loop
-      // below.  Redoing it from registers with the vectorised Exact arithmetic was measured: an all-redo
-      // 7B set drops from 59.5 to 46.2 ms, but the Exact chain's registers and code slow the ordinary
-      // path of several variants by 1-5%, so the rare case keeps the loop.
+      if constexpr (SS::kBf16 && FAST) {
+        // bf16 Fast mode: the root met a subnormal operand (or there is a NaN).  The same slot again with
+        // the root that scales such operands; what still asks for a redo after that has a NaN.
+        if (redo) {
+          local = {0.0, 0.0, 0u};
+          redo = hot_slot<mcfd::FastScaled, VARIANT, EDQ>(in[j], out, sc, local);
+        }
+      }
+      // bf16: a slot that produced a NaN in Fast mode goes to the element loop below.  Redoing it from
+      // registers with the vectorised Exact arithmetic was measured: an all-redo 7B set drops from 59.5
+      // to 46.2 ms, but the Exact chain's registers and code slow the ordinary path of several variants
+      // by 1-5%, so the diverged case keeps the loop.
       if (redo) {
         cold |= 1u << j;
       } else {
@@ -606,10 +614,7 @@ __device__ __forceinline__ void prim_pair(const typename M::T (&i)[5], typename 
     }
     x = O::divg(a, b, redo);
   }
-  if (OP == P_SQRT) {
-    if constexpr (M::kGuarded) redo |= mcfd::is_subnormal(a.lo) | mcfd::is_subnormal(a.hi);
-    x = O::sqrt(a, redo);
-  }
+  if (OP == P_SQRT) x = O::sqrt(a, redo);
   if (OP == P_EDQ) {
     // streams: delta, th0, th1, dth0, dth1 (absent second components were loaded as zeros);
     // elements outside the tensor are skipped so that they cannot count as lost updates

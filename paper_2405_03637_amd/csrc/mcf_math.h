@@ -8,12 +8,21 @@
 //           NaN stored as 0x7FC0.  Correct for all inputs.
 //   Fast  : v_cvt_pk_bf16_f32 for the rounding, v_rcp_f32 / v_sqrt_f32 (1 ulp) for divide
 //           and square root.  Because every operand is a bf16 value (8 significant bits),
-//           a/b and sqrt(a) can never fall on a bf16 rounding midpoint and stay at least
-//           2^-17 (divide) or 2^-19 (root) away from one in relative terms, so a result
-//           with relative error 2^-22 rounds to the same bf16 as the correctly rounded
-//           one.  That argument needs the fp32 result to be a normal number; a pair that
-//           meets a subnormal intermediate, or produces any NaN, raises `redo` and the
-//           caller recomputes that slot in Exact mode.
+//           a normal a/b or sqrt(a) can never fall on a bf16 rounding midpoint and stays at
+//           least 2^-17 (divide) or 2^-19 (root) away from one in relative terms, so a result
+//           with relative error 2^-22 rounds to the same bf16 as the correctly rounded one.
+//           Quotients below 2^-126 sit on fp32's fixed grid of 2^-149: one that is not a tie of
+//           the bf16 rounding (spacing 2^-133 there) is at least 2^-142 from the nearest, far more
+//           than the error of a*r; one that is a tie has a divisor whose significand divides
+//           the dividend's, so it is either below 2^-127.5, where the error of a*r is under half
+//           a grid step and the fp32 rounding of the product lands on the tie itself, or has a
+//           power of two as divisor, whose reciprocal is exact.  (All bf16 pairs with such
+//           quotients, r anywhere within one unit of 1/b: tests/test_oracle_rounding.py; all 2^32
+//           pairs on the hardware: the GPU sweep.)  v_sqrt_f32 takes a subnormal operand for
+//           zero: the first pass raises `redo` on one (a second moment that decayed to nothing
+//           under zero gradients), and the caller redoes that slot with a root that scales such
+//           operands by 2^64 first.  What is left for Exact mode: the host finds the step's
+//           scalars outside the ranges above, or a pair produces a NaN, which also raises `redo`.
 // The same chains run over three more component formats (App. A Table 7), each with a first-pass mode
 // and a mode that stores the format's one NaN: fp16 in packed half arithmetic (Hf), and FP8 E5M2 and
 // E4M3 through the hardware conversions (F8).  Every mode offers the same static interface (T, S,
@@ -58,7 +67,10 @@ struct ExactR {
   static __device__ __forceinline__ float sqrt1(float a, bool &) { return __builtin_sqrtf(a); }
 };
 
-struct FastR {
+// SCALED selects how the root treats a subnormal operand, which v_sqrt_f32 takes for zero: false raises
+// `redo` (first pass: such operands are rare and the test is one instruction), true scales it by the
+// exact factor 2^64 first and the root by 2^-32 afterwards (the pass that redoes those slots).
+template <bool SCALED> struct FastRT {
   static constexpr bool kFast = true;
   // v_cvt_pk_bf16_f32 with 0 as its first source leaves bf16(x) in the upper half of the result and
   // bf16(0) = 0 in the lower half: that IS the rounded value widened back to fp32, in one instruction.
@@ -69,19 +81,19 @@ struct FastR {
   }
   static __device__ __forceinline__ P2 rnd(P2 x) { return {rnd1(x.lo), rnd1(x.hi)}; }
   // a / b where b is a positive normal scalar with known fp32 reciprocal rb (|rel err| <= 2^-24)
-  static __device__ __forceinline__ float div1(float a, float, float rb, bool &redo) {
-    float p = a * rb;
-    redo |= is_subnormal(p);
-    return p;
-  }
+  static __device__ __forceinline__ float div1(float a, float, float rb, bool &) { return a * rb; }
   // a / b, b any value whose magnitude is 0, infinite or within [2^-126, 2^126]
-  static __device__ __forceinline__ float divg1(float a, float b, bool &redo) {
-    float p = a * __builtin_amdgcn_rcpf(b);
-    redo |= is_subnormal(p);
-    return p;
+  static __device__ __forceinline__ float divg1(float a, float b, bool &) { return a * __builtin_amdgcn_rcpf(b); }
+  static __device__ __forceinline__ float sqrt1(float a, bool &redo) {
+    if constexpr (SCALED) {
+      const bool tiny = a < 0x1p-96f;          // every subnormal operand, and whatever else is cheap to include
+      const float r = __builtin_amdgcn_sqrtf(a * (tiny ? 0x1p64f : 1.0f));
+      return r * (tiny ? 0x1p-32f : 1.0f);
+    } else {
+      redo |= is_subnormal(a);
+      return __builtin_amdgcn_sqrtf(a);
+    }
   }
-  // sqrt(a), a zero, normal, infinite or NaN
-  static __device__ __forceinline__ float sqrt1(float a, bool &) { return __builtin_amdgcn_sqrtf(a); }
 };
 
 // The bf16 operations on pairs, held widened.  Every function is one F(.): one fp32 operation
@@ -91,7 +103,7 @@ template <class R> struct Bf {
   using S = float;     // a wave-uniform scalar
   static constexpr bool kFast = R::kFast;      // may raise redo
   static constexpr bool kHalf = false;
-  static constexpr bool kGuarded = R::kFast;   // the reciprocal routes need operands checked for range (single operations)
+  static constexpr bool kGuarded = R::kFast;   // the reciprocal route needs its divisor checked for range (single operations)
   static constexpr bool kNanOnWords = false;
   static constexpr int kBytes = 2;             // bytes per stored element
   using Rcp = float;   // reciprocal of a scalar
@@ -104,10 +116,6 @@ template <class R> struct Bf {
   static __device__ __forceinline__ uint16_t bits_hi(T x) { return (uint16_t)(fbits(x.hi) >> 16); }
   static __device__ __forceinline__ bool any_nan(T x) { return is_nan(x.lo) | is_nan(x.hi); }
   static __device__ __forceinline__ T round_f32(float a, float b) { return R::rnd({a, b}); }
-  // Fast mode: a sum about to go under the approximate root must not be a subnormal fp32 number
-  static __device__ __forceinline__ void guard_root_operand(T x, bool &redo) {
-    if (R::kFast) redo |= is_subnormal(x.lo) | is_subnormal(x.hi);
-  }
 
   static __device__ __forceinline__ T add(T a, T b) { return R::rnd({a.lo + b.lo, a.hi + b.hi}); }
   static __device__ __forceinline__ T sub(T a, T b) { return R::rnd({a.lo - b.lo, a.hi - b.hi}); }
@@ -132,7 +140,8 @@ template <class R> struct Bf {
   }
 };
 using Exact = Bf<ExactR>;
-using Fast = Bf<FastR>;
+using Fast = Bf<FastRT<false>>;          // first pass
+using FastScaled = Bf<FastRT<true>>;     // second pass over the slots whose root met a subnormal operand
 
 // ---- fp16 -------------------------------------------------------------------------------
 // The same operation F(a o b) for IEEE binary16 components (App. A Table 7).  The pair stays packed
@@ -186,7 +195,6 @@ template <bool HOT> struct Hf {
   // a half is NaN iff its magnitude bits exceed 0x7C00; +0x03FF carries exactly those into bit 15
   static __device__ __forceinline__ bool any_nan(T x) { return (((raw(x) & 0x7fff7fffu) + 0x03ff03ffu) & 0x80008000u) != 0; }
   static __device__ __forceinline__ T round_f32(float a, float b) { return h2_t{(_Float16)a, (_Float16)b}; }
-  static __device__ __forceinline__ void guard_root_operand(T, bool &) {}
 
   static __device__ __forceinline__ T add(T a, T b) { return a + b; }
   static __device__ __forceinline__ T sub(T a, T b) { return a - b; }
@@ -318,7 +326,6 @@ template <bool E4M3, bool HOT> struct F8 {
   static __device__ __forceinline__ T rnd(h2_t x) { return rnd(x, raw(x)); }
   static __device__ __forceinline__ T rnd_f32(float a, float b) { const uint32_t e = C::enc_f32(a, b, fbits(a)); return T{C::template dec<false>(e), e}; }
   static __device__ __forceinline__ T round_f32(float a, float b) { return rnd_f32(a, b); }
-  static __device__ __forceinline__ void guard_root_operand(T, bool &) {}
 
   static __device__ __forceinline__ T add(T a, T b) { return rnd(a.h + b.h); }
   static __device__ __forceinline__ T sub(T a, T b) { return rnd(a.h - b.h); }
@@ -444,9 +451,7 @@ __device__ __forceinline__ void adamw_pair(ElemIOT<typename M::T> &io, const Ste
   // inside the summed update)
   T dn;
   if (EPS_INSIDE) {
-    const T sum = O::adds(vh, s.e);
-    M::guard_root_operand(sum, redo);
-    dn = O::sqrt(sum, redo);
+    dn = O::sqrt(O::adds(vh, s.e), redo);
   } else {
     dn = O::adds(O::sqrt(vh, redo), s.e);
   }

@@ -259,6 +259,38 @@ def test_tiny_magnitudes_subnormal_intermediates():
         wl.close()
 
 
+@pytest.mark.parametrize("variant", ["light", "plus", "kahan", "bf16", "light+twosum"])
+def test_moments_decaying_into_the_subnormal_range(variant):
+    """Parameters that stop receiving gradients: m and v shrink by beta every step, pass through the
+    subnormal range and stick at the least subnormal numbers, so the bias-corrected moments, the root's
+    operand and the quotient are subnormal step after step (the restricted arithmetic mode's second pass)."""
+    n = 1 << 15
+    hyper = (1e-3, 0.9, 0.95, 1e-8, 0.1)
+    wl = Workload("flat_1m", variant=variant, shape_list=[("a", n - 5)], hyper=hyper)
+    rng = np.random.default_rng(85)
+    small = lambda lo, hi, signed: H.np_round_f64_to_bf16(2.0 ** rng.uniform(lo, hi, wl.total) *
+                                                        (rng.choice([-1.0, 1.0], wl.total) if signed else 1.0))
+    wl.m.copy_(_dev(small(-131, -118, True)))
+    wl.v.copy_(_dev(small(-132, -116, False)))
+    if wl.dv is not None:
+        wl.dv.copy_(_dev(small(-133, -128, True)))
+    host = {k: H.torch_to_u16(getattr(wl, k)) for k in wl.state_names()}
+    zero = np.zeros(wl.total, np.uint16)
+    wl.grad.zero_()
+    for t in range(1, 61):
+        orc.adamw_step(host["theta"], host.get("dtheta"), host["m"], host["v"], host.get("dv"), zero, wl.variant, hyper, t)
+        wl.plan.step(hyper, t)
+        if t in (1, 2, 5, 20, 60):
+            for k in wl.state_names():
+                dev = H.torch_to_u16(getattr(wl, k))[:n - 5]
+                bad = np.flatnonzero(dev != host[k][:n - 5])
+                assert bad.size == 0, f"{variant} step {t} {k}: {bad.size} mismatches, first at {int(bad[0])}"
+    stuck = H.u16_to_f64(host["m"][:n - 5])
+    # the first moments end up on the few least subnormal numbers that F(beta1 * m) maps to themselves
+    assert float(np.mean((np.abs(stuck) > 0) & (np.abs(stuck) <= 2.0 ** -131))) > 0.5
+    wl.close()
+
+
 def test_checkpoint_resume_is_bitwise():
     """State is the tensors plus t: 6 steps equal 3 steps, a new plan, 3 more steps."""
     a = Workload("flat_1m", variant="plus", shape_list=[("x", 50_001), ("y", 333)], misalign_tiny=True)

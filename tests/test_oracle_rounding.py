@@ -287,3 +287,54 @@ def test_fp_environment_and_threads(orc):
     two = np.array([0x4000], np.uint16)
     assert orc.binop(orc.MUL, tiny, two)[0] == 0x0002
     assert orc.binop(orc.ADD, tiny, tiny)[0] == 0x0002
+
+
+# ------------------------------------------------------------------ quotients below the normal range
+def _bf16_as_f32(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+@pytest.mark.parametrize("ulps", [0, 1, -1])
+def test_small_quotients_through_a_reciprocal(orc, ulps):
+    """What the GPU's restricted arithmetic mode relies on below the normal range: for every bf16 a and every
+    bf16 b with 2^-126 <= |b| <= 2^126 whose quotient lies below 2^-125 (subnormal results, and those that
+    round to zero or up to the least normal number), R(fl32(a * r)) = F(a / b) for r anywhere within one unit
+    in the last place of 1/b -- except that a power of two must have its exact reciprocal, which is the
+    only case where a quotient this size can sit on a rounding tie that the product's own rounding does
+    not restore.  IEEE fp32 multiplication with subnormal results only, so this holds on any machine."""
+    bad = checked = 0
+    with np.errstate(all="ignore"):
+        for eb in range(1, 254):                                   # biased exponent of b
+            mant = np.arange(128) if eb < 253 else np.arange(1)    # 2^126 itself is the last divisor allowed
+            b_bits = ((eb << 7) | mant).astype(np.uint16)
+            lo_e, hi_e = max(0, eb - 136), min(254, eb - 124)      # |a/b| within [2^-137, 2^-123)
+            if hi_e < lo_e:
+                continue
+            a_bits = np.array([(e << 7) | m for e in range(lo_e, hi_e + 1) for m in range(128)], np.uint16)
+            a_bits = a_bits[a_bits != 0]
+            a_bits = np.concatenate([a_bits, a_bits | 0x8000])
+            A, B = [x.ravel() for x in np.meshgrid(a_bits, b_bits, indexing="ij")]
+            fa, fb = _bf16_as_f32(A), _bf16_as_f32(B)
+            r = (1.0 / fb.astype(np.float64)).astype(np.float32)
+            if ulps:
+                moved = np.nextafter(r, np.float32(np.inf if ulps > 0 else -np.inf))
+                r = np.where((B & 0x7F) == 0, r, moved)
+            got = orc.R_array((fa * r).astype(np.float32))
+            want = orc.binop(orc.DIV, A, B)
+            bad += int(np.sum(got != want))
+            checked += A.size
+    assert checked > 5e7 and bad == 0
+
+
+def test_small_quotients_by_a_bias_correction(orc):
+    """The same for the two divisions by a bias correction bc in [2^-60, 1], whose reciprocal the host
+    rounds correctly: R(fl32(a * fl32(1/bc))) = F(a / bc) for every bf16 a small enough for the quotient to
+    be subnormal (|a| < 2^-125)."""
+    a_bits = np.arange(1, 3 << 7, dtype=np.uint16)                 # biased exponents 0..2: up to 2^-124
+    a_bits = np.concatenate([a_bits, a_bits | 0x8000])
+    bc_bits = np.arange((127 - 60) << 7, (127 << 7) + 1, dtype=np.uint16)
+    A, B = [x.ravel() for x in np.meshgrid(a_bits, bc_bits, indexing="ij")]
+    with np.errstate(all="ignore"):
+        r = (1.0 / _bf16_as_f32(B).astype(np.float64)).astype(np.float32)
+        got = orc.R_array((_bf16_as_f32(A) * r).astype(np.float32))
+    assert np.array_equal(got, orc.binop(orc.DIV, A, B))
