@@ -325,7 +325,9 @@ template <int VARIANT> struct StepStreams {
   // kernels (light, Kahan) are fastest at 10, the 11-stream plus at 11 (23.18 ms against 23.38 at 10), the
   // 7-stream plain variant, whose divide and root have less memory time to hide behind, at 12 (14.24 ms
   // against 15.09 at 10), the 7-stream SGD at 10-11.  With the fp64 EDQ sums fused in there is more
-  // arithmetic to hide: 14 (light 18.62 ms against 20.43 at 10), plain variant 16.
+  // arithmetic to hide and more registers in use: light, Kahan and plus 12 (light 18.76 ms against 19.13
+  // at 14 and 19.30 at 11; plus 23.3 against 24.2 at 14, in both 16-bit formats), fp16 light, SGD and the
+  // TwoSum flavours 14 (SGD 14.32 against 15.15 at 12), the plain variant 16.
   // The FP8 kernels move half the bytes with about the same arithmetic (a conversion to and from the
   // 8-bit format around every operation): their vector-ALU time is level with their HBM time and they run
   // uncapped (light E5M2, 7B set: 10.5 ms uncapped, 10.7-10.9 at 12 to 24 groups per CU).
@@ -334,7 +336,9 @@ template <int VARIANT> struct StepStreams {
 #else
   static constexpr uint32_t kLds = kEB == 1 ? 0 : lds_for_groups(kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? 11 : 10);
 #endif
-  static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : kEB == 1 ? 0 : lds_for_groups(kBase == mcfd::V_BF16 ? 16 : 14);
+  static constexpr int kEdqGroups = kBase == mcfd::V_BF16 ? 16 : (kGrow2 || kBase == mcfd::V_SGD) ? 14
+                                    : (kBase == mcfd::V_PLUS || kBf16) ? 12 : 14;
+  static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : kEB == 1 ? 0 : lds_for_groups(kEdqGroups);
 };
 
 // A dword of a stream holds one pair (2-byte elements) or two pairs (1-byte elements).
