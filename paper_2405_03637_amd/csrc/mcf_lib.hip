@@ -322,9 +322,13 @@ template <int VARIANT> struct StepStreams {
   static constexpr bool kDv = kBase == mcfd::V_PLUS;       // second component of v
   static constexpr bool kV = kBase != mcfd::V_SGD;         // second moment
   // Occupancy cap in workgroups per CU, from sweeps of 8..32 at the 7B-parameter set: the 9-stream
-  // kernels (light, Kahan) are fastest at 10, the 11-stream plus at 11 (23.18 ms against 23.38 at 10), the
-  // 7-stream plain variant, whose divide and root have less memory time to hide behind, at 12 (14.24 ms
-  // against 15.09 at 10), the 7-stream SGD at 10-11.  With the fp64 EDQ sums fused in there is more
+  // kernels (light, Kahan, both formats, either Grow) are fastest at 10 (light 18.53 ms against 18.75 at 9
+  // and 18.79 at 11); the 11-stream plus at 9 with bf16 components (23.08 ms; 23.20 at 10, 23.37 at 11,
+  // 24.05 at 8) and at 11 with fp16 components or Grow on TwoSum (fp16 23.11 against 23.26 at 10 and 24.2
+  // at 9); the 7-stream plain variant, whose divide and root have less memory time to hide behind, at 12
+  // (14.25 ms against 14.94 at 10); the 7-stream SGD at 11 (14.19 against 14.27 at 10).  The optimum
+  // moves with the kernel's instruction schedule, so it is re-swept when the arithmetic changes.
+  // With the fp64 EDQ sums fused in there is more
   // arithmetic to hide and more registers in use: light, Kahan and plus 12 (light 18.76 ms against 19.13
   // at 14 and 19.30 at 11; plus 23.3 against 24.2 at 14, in both 16-bit formats), fp16 light, SGD and the
   // TwoSum flavours 14 (SGD 14.32 against 15.15 at 12), the plain variant 16.
@@ -334,7 +338,9 @@ template <int VARIANT> struct StepStreams {
 #ifdef MCF_STEP_LDS
   static constexpr uint32_t kLds = MCF_STEP_LDS;
 #else
-  static constexpr uint32_t kLds = kEB == 1 ? 0 : lds_for_groups(kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? 11 : 10);
+  static constexpr int kGroups = kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? (kBf16 && !kGrow2 ? 9 : 11)
+                                 : kBase == mcfd::V_SGD ? 11 : 10;
+  static constexpr uint32_t kLds = kEB == 1 ? 0 : lds_for_groups(kGroups);
 #endif
   static constexpr int kEdqGroups = kBase == mcfd::V_BF16 ? 16 : (kGrow2 || kBase == mcfd::V_SGD) ? 14
                                     : (kBase == mcfd::V_PLUS || kBf16) ? 12 : 14;
