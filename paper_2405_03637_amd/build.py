@@ -45,5 +45,22 @@ def build(force=True, extra=(), out=LIB, verbose=False):
     return out
 
 
+DEMO_SRC = os.path.join(HERE, "csrc", "abi_demo.c")
+DEMO = os.path.join(HERE, "mcf_abi_demo")
+
+
+def build_demo(verbose=False):
+    """Compile csrc/abi_demo.c, a plain C99 consumer of the library, with gcc against the HIP runtime."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(rocm, "include"), DEMO_SRC,
+           "-L" + HERE, "-lmcf_adamw", "-L" + os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", DEMO]
+    if verbose:
+        print(" ".join(cmd), file=sys.stderr)
+    subprocess.run(cmd, check=True)
+    return DEMO
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_demo(verbose=True))

@@ -213,3 +213,11 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_plain_c_consumer_compiles():
+    """csrc/abi_demo.c is C99 and needs nothing but the header, the library and the HIP runtime."""
+    from paper_2405_03637_amd import build as lib_build
+    mcf.lib()                                   # the library it links against is built
+    path = lib_build.build_demo()
+    assert os.path.exists(path) and os.access(path, os.X_OK)
