@@ -155,8 +155,9 @@ int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *
  * (FP8 patterns in the low byte).
  * Each is computed in fp64 and cast once.  Host-only: no GPU is touched.  restricted_mode_ok (may be
  * NULL) receives 1 when the step kernels may use their reciprocal-based arithmetic for these scalars
- * and 0 when they will use the IEEE sequences (bf16 only: bias corrections below 2^-60, or a non-zero
- * epsilon outside [2^-100, 2^60]); the results are the same bits either way. */
+ * and 0 when they will use the slower exact sequences (bf16: bias corrections below 2^-60, or a non-zero
+ * epsilon outside [2^-100, 2^60]; FP8 E5M2: a bias correction of +-2^-16, whose reciprocal is no fp16
+ * number); the results are the same bits either way. */
 int mcf_step_scalars(int component, const mcf_hyper *hyper, uint64_t step, uint16_t *out, int *restricted_mode_ok);
 
 /* The same step over a single flat tensor, no plan, no allocation.  n == 0 is a no-op. */

@@ -1225,7 +1225,10 @@ int mcf_step_scalars(int component, const mcf_hyper *hyper, uint64_t step, uint1
   for (int i = 0; i < mcfh::K_COUNT; ++i) out[i] = b.v[i];
   if (restricted_mode_ok) {
     StepScalars unused;
-    *restricted_mode_ok = component != MCF_COMPONENT_BF16 ? 1 : (mcfh::derive_scalars(*hyper, step, unused) && !force_exact()) ? 1 : 0;
+    StepScalarsF8 unused8;
+    if (component == MCF_COMPONENT_BF16) *restricted_mode_ok = (mcfh::derive_scalars(*hyper, step, unused) && !force_exact()) ? 1 : 0;
+    else if (component == MCF_COMPONENT_FP16) *restricted_mode_ok = 1;
+    else *restricted_mode_ok = mcfh::derive_scalars_fp8(*hyper, step, component == MCF_COMPONENT_FP8_E4M3, unused8) ? 1 : 0;
   }
   return MCF_OK;
 }

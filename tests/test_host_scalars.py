@@ -118,6 +118,11 @@ def test_restricted_mode_report_and_errors():
     assert ok((3e-4, 0.0, 0.0, 1e-8, 0.1))                       # beta = 0: bias corrections are 1
     assert ok((3e-4, 1.0 - 2.0 ** -53, 0.95, 1e-8, 0.1))         # the smallest 1 - beta an fp64 beta < 1 allows is still sane
     assert ok((3e-4, 0.9, 0.95, 1e-40, 0.1), c=HF)               # fp16 arithmetic has no restricted mode
+    tiny = 1.0 - 2.0 ** -16                                      # first-step bias correction 2^-16
+    assert not ok((2.0 ** -6, tiny, 0.5, 2.0 ** -6, 0.125), c=2)  # E5M2: its reciprocal 2^16 is no fp16 number
+    assert not ok((2.0 ** -6, 0.5, tiny, 2.0 ** -6, 0.125), c=2)
+    assert ok((2.0 ** -6, tiny, 0.5, 2.0 ** -6, 0.125), t=2, c=2)  # second step: 2^-15
+    assert ok((2.0 ** -6, tiny, tiny, 2.0 ** -6, 0.125), c=3)     # E4M3 rounds that correction to 0: a * inf is IEEE's a / 0
     import ctypes
     lib = mcf.lib()
     out = (ctypes.c_uint16 * 10)()
