@@ -614,8 +614,9 @@ def test_config5_stress_64m():
 
 
 def test_flat_tensor_longer_than_2_pow_32():
-    """One flat tensor of 2^32 + 70,001 elements through the flat entry point (64-bit element offsets):
-    windows at the start, across the 2^32 boundary and at the ragged end are followed by the oracle."""
+    """One flat tensor of 2^32 + 70,001 elements through the flat entry point and through a plan (64-bit
+    element offsets in both): windows at the start, across the 2^31 and 2^32 boundaries and at the ragged end
+    are followed by the oracle."""
     n = (1 << 32) + 70_001
     _say("flat > 2^32: allocating")
     z = lambda: torch.zeros(n, dtype=torch.bfloat16, device=DEV)
@@ -628,11 +629,16 @@ def test_flat_tensor_longer_than_2_pow_32():
                                     np.arange((1 << 32) - w, (1 << 32) + w), np.arange(n - w, n)]).astype(np.int64))
     idx_dev = torch.from_numpy(idx).to(DEV)
     host = {k: H.torch_to_u16(v[idx_dev]) for k, v in st.items()}
-    for t in range(1, 4):
+    plan = mcf.Plan([(st["theta"], st["dtheta"], st["m"], st["v"], None, grad)], mcf.LIGHT)     # 2^26 + 1095 chunks of one tensor
+    for t in range(1, 5):
         W.fill_grads("flat_1m", [("x", n)], [0], grad, t)
         orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], None, H.torch_to_u16(grad[idx_dev]), 0,
                        W.HYPER_LIGHT, t)
-        mcf.adamw_step_flat(st["theta"], st["dtheta"], st["m"], st["v"], None, grad, mcf.LIGHT, W.HYPER_LIGHT, t)
+        if t <= 2:
+            mcf.adamw_step_flat(st["theta"], st["dtheta"], st["m"], st["v"], None, grad, mcf.LIGHT, W.HYPER_LIGHT, t)
+        else:
+            plan.step(W.HYPER_LIGHT, t)                 # the same tensor through the chunk table
+    plan.destroy()
     for k, v in st.items():
         assert np.array_equal(H.torch_to_u16(v[idx_dev]), host[k]), k
     # and the step really ran everywhere: m is non-zero wherever the gradient is
