@@ -111,7 +111,8 @@ def _ptr(t):
         return None
     if isinstance(t, int):
         return t
-    assert t.is_contiguous(), "buffers must be contiguous"
+    if not t.is_contiguous():
+        raise ValueError("buffers must be contiguous")
     return t.data_ptr()
 
 
@@ -137,7 +138,7 @@ class Plan:
         for i, (th, dth, m, v, dv, g) in enumerate(tensors):
             n = th.numel() if hasattr(th, "numel") else None
             if n is None:
-                raise TypeError("pass torch tensors; use raw_plan for raw addresses")
+                raise TypeError("pass torch tensors; use Plan.raw for raw addresses")
             arr[i] = Tensor(_ptr(th), _ptr(dth), _ptr(m), _ptr(v), _ptr(dv), _ptr(g), n)
         self._h = _vp()
         _check(lib().mcf_plan_create(ctypes.byref(self._h), arr, len(tensors), int(variant)), "mcf_plan_create")
