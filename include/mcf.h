@@ -37,9 +37,11 @@
  *     memory.  "host" pointers are ordinary process memory, read during the
  *     call only.
  *   - bf16 and fp16 buffers need 2-byte alignment (FP8 buffers none), fp32 buffers 4-byte, double
- *     buffers 8-byte (else MCF_ERR_ALIGN).  Any such alignment is accepted; 128-bit
- *     accesses are used when all buffers of one tensor share the same offset
- *     modulo 16 bytes, element-wise accesses otherwise.
+ *     buffers 8-byte (else MCF_ERR_ALIGN).  Any such alignment is accepted.  The step
+ *     and the primitives use 128-bit accesses cut on the first buffer's (theta's) 16-byte grid:
+ *     fastest when all buffers of one tensor share the same offset modulo 16 bytes; a
+ *     buffer at another offset is accessed unaligned, which the hardware splits (the fp32-master
+ *     baseline goes element by element instead when its buffers are not mutually aligned).
  *   - Updates are in place.  Buffers of different roles or tensors must not
  *     overlap (not checked; the result is undefined if they do).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -133,9 +135,8 @@ uint64_t mcf_plan_params(const mcf_plan *plan);
 /* Point an existing plan at other buffers of the same sizes (for callers whose gradient or parameter
  * buffers are reallocated between steps) without rebuilding it: no allocation.  `tensors` must
  * have the `count` of mcf_plan_create, every n unchanged (else MCF_ERR_SIZE), and each tensor's
- * buffers must sit at the same offset modulo 128 bytes, and be mutually aligned or not, as the buffers
- * they replace (else MCF_ERR_ALIGN: the plan's work split was cut for that alignment; create a new
- * plan).  The new table is copied in `stream` order, after the steps already enqueued there, and
+ * theta must sit at the same offset modulo 128 bytes as the theta it replaces (else MCF_ERR_ALIGN:
+ * the plan's work split was cut for that offset; create a new plan).  The new table is copied in `stream` order, after the steps already enqueued there, and
  * the call returns once the copy is done (it waits for that stream).  On an error the plan is unchanged. */
 int mcf_plan_update(mcf_plan *plan, const mcf_tensor *tensors, uint32_t count, void *stream);
 

@@ -95,7 +95,7 @@ struct TensorDesc {
   uint64_t p[kMaxStreams];   // the streams' device addresses, as integers
   uint64_t n;                // elements
   uint32_t phase;            // elements between the MCF_CHUNK_ALIGN-byte boundary below p[0] and p[0]
-  uint32_t scalar_only;      // 1: streams are not mutually aligned, every slot goes element by element
+  uint32_t skewed;           // 1: the streams do not share theta's offset modulo 16 bytes (their 128-bit accesses are unaligned)
 };
 static_assert(sizeof(TensorDesc) == 64, "descriptor is one 64-byte scalar load");
 
@@ -117,15 +117,21 @@ __device__ __forceinline__ Slot classify(const TensorDesc &d, uint64_t slot) {
   s.c0 = slot * kEps;
   const uint64_t lo = d.phase, hi = d.phase + d.n;
   s.any = (s.c0 + kEps > lo) && (s.c0 < hi);
-  s.full = (s.c0 >= lo) && (s.c0 + kEps <= hi) && !d.scalar_only;
+  s.full = (s.c0 >= lo) && (s.c0 + kEps <= hi);
   return s;
 }
 
 // 128-bit access to the 16 bytes at byte offset `off` of the buffer at p.
 // The pointers are device-memory addresses, so the accesses are typed as global (address
 // space 1): global_load/global_store instead of the generic flat instructions.
+// Slots are cut on theta's 16-byte grid.  A stream whose buffer sits at another offset modulo 16 is
+// accessed at addresses that are only element-aligned: the vector type says so (alignment 1), the
+// compiler emits the same global_load/store_dwordx4 for it (global memory takes unaligned accesses on
+// this target), and the hardware splits an access that straddles a line.  That costs bandwidth on the
+// skewed streams only; the alternative, element by element, costs a factor of three on everything.
 #define MCF_GLOBAL __attribute__((address_space(1)))
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_aligned_t __attribute__((ext_vector_type(4)));
+typedef u32x4_aligned_t u32x4_t __attribute__((aligned(1)));
 template <class T> __device__ __forceinline__ MCF_GLOBAL T *gptr(uint64_t p) { return (MCF_GLOBAL T *)p; }
 
 __device__ __forceinline__ void load_vec(uint64_t p, uint64_t off, uint32_t (&w)[4]) {
@@ -402,8 +408,7 @@ __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], u
 }
 
 // Cold path: one slot element by element in the variant's element mode (bf16: Exact), as a rolled loop so that it costs code
-// size once.  Serves the slots that straddle a tensor's ends, tensors whose buffers are not
-// mutually aligned, (bf16) slots the hot path asked to redo (their inputs are still in memory:
+// size once.  Serves the slots that straddle a tensor's ends, (bf16) slots the hot path asked to redo (their inputs are still in memory:
 // nothing of the slot has been stored yet), and every slot of a launch with MCF_EPS_INSIDE_SQRT: that
 // reading of line 12 is kept for reference, and keeping it out of the vector path keeps the vector
 // path's code and registers as they are (a compiled second copy of the chain there cost the default
@@ -584,7 +589,7 @@ enum PrimOp { P_FAST2SUM, P_TWOSUM, P_GROW, P_ADD, P_SUB, P_MUL, P_DIV, P_SQRT, 
 struct PrimArgs {
   uint64_t p[kMaxStreams];
   uint64_t n;
-  uint32_t phase, scalar_only;
+  uint32_t phase, skewed;
 };
 
 // One pair of elements of one primitive: inputs i[0..3] (and i[4] for EDQ), results (x, y).
@@ -671,7 +676,7 @@ __global__ void __launch_bounds__(kBlock) prim_kernel(PrimArgs a, uint32_t has_d
   TensorDesc d;
 #pragma unroll
   for (int s = 0; s < kMaxStreams; ++s) d.p[s] = a.p[s];
-  d.n = a.n; d.phase = a.phase; d.scalar_only = a.scalar_only;
+  d.n = a.n; d.phase = a.phase; d.skewed = a.skewed;
   const Slot s = classify<EB>(d, (uint64_t)blockIdx.x * kBlock + threadIdx.x);
   EdqAcc acc = {0.0, 0.0, 0u};
   if (s.any) {
@@ -834,7 +839,7 @@ fp32mw_kernel(const Fp32Desc *__restrict__ descs, const Chunk *__restrict__ chun
   // Chunks at a tensor's ends, and tensors whose buffers are not mutually aligned: slot by slot,
   // element by element where a slot is not whole.
   TensorDesc t;
-  t.n = d.n; t.phase = d.phase; t.scalar_only = d.scalar_only;
+  t.n = d.n; t.phase = d.phase; t.skewed = d.scalar_only;
 #pragma unroll 1
   for (int j = 0; j < kUnroll; ++j) {
     const Slot s = classify<2>(t, (uint64_t)c.slot0 + (uint64_t)j * kStepBlock + threadIdx.x);
@@ -858,15 +863,15 @@ fp32mw_kernel(const Fp32Desc *__restrict__ descs, const Chunk *__restrict__ chun
 
 inline bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
-// Alignment class of a set of 16-bit-element pointers: common phase (elements above the boundary)
-// or scalar_only when they disagree.
-inline void phase_of(const uint64_t *ptrs, int count, uint32_t &phase, uint32_t &scalar_only, uint64_t boundary = 16,
+// Where the slots of a set of streams are cut: phase = elements between the `boundary`-byte boundary at or
+// below the first stream's pointer and that pointer.  skewed = 1 when some other stream sits at another
+// offset modulo 16 bytes (its 128-bit accesses will be unaligned; nothing else depends on it).
+inline void phase_of(const uint64_t *ptrs, int count, uint32_t &phase, uint32_t &skewed, uint64_t boundary = 16,
                      uint32_t elem_bytes = 2) {
   phase = (uint32_t)((ptrs[0] & (boundary - 1)) / elem_bytes);
-  scalar_only = 0;
+  skewed = 0;
   for (int i = 1; i < count; ++i)
-    if ((ptrs[i] & 15) != (ptrs[0] & 15)) scalar_only = 1;
-  if (scalar_only) phase = 0;
+    if ((ptrs[i] & 15) != (ptrs[0] & 15)) skewed = 1;
 }
 
 inline uint64_t slots_of(uint64_t n, uint32_t phase, uint32_t elem_bytes = 2) {
@@ -912,7 +917,7 @@ void fill_desc(const mcf_tensor &t, int variant, TensorDesc &d) {
   d.p[S_G] = (uint64_t)(uintptr_t)t.grad;
   d.p[S_DV] = variant == MCF_PLUS ? (uint64_t)(uintptr_t)t.dv : d.p[S_V];
   d.n = t.n;
-  phase_of(d.p, 6, d.phase, d.scalar_only, MCF_CHUNK_ALIGN, eb);
+  phase_of(d.p, 6, d.phase, d.skewed, MCF_CHUNK_ALIGN, eb);
 }
 
 // Scalars of one step for both formats; fast = the bf16 Fast mode may be used with them.
@@ -1048,7 +1053,7 @@ int prim_launch(int format, int op, const void *p0, const void *p1, const void *
   }
   if (n > kMaxTensorElems) return MCF_ERR_SIZE;
   a.n = n;
-  phase_of(al, na, a.phase, a.scalar_only, 16, eb);
+  phase_of(al, na, a.phase, a.skewed, 16, eb);
   const uint64_t slots = slots_of(n, a.phase, eb);
   const dim3 g((uint32_t)((slots + kBlock - 1) / kBlock)), b(kBlock);
   hipStream_t st = (hipStream_t)stream;
@@ -1180,8 +1185,8 @@ int mcf_plan_update(mcf_plan *plan, const mcf_tensor *tensors, uint32_t count, v
     TensorDesc d;
     fill_desc(tensors[i], plan->variant, d);
     const TensorDesc &old = plan->h_descs[descs.size()];
-    // the chunk table was cut for the old buffers' alignment class: the new ones must share it
-    if (d.phase != old.phase || d.scalar_only != old.scalar_only) return MCF_ERR_ALIGN;
+    // the chunk table was cut for the old theta's offset within its 128-byte line: the new one must share it
+    if (d.phase != old.phase) return MCF_ERR_ALIGN;
     descs.push_back(d);
   }
   if (!descs.empty()) {
@@ -1375,7 +1380,7 @@ int mcf_edq_component(int component, const void *delta, const void *th0, const v
   }
   if (n > kMaxTensorElems) return MCF_ERR_SIZE;
   a.n = n;
-  phase_of(al, na, a.phase, a.scalar_only, 16, eb);
+  phase_of(al, na, a.phase, a.skewed, 16, eb);
   const uint64_t blocks = (slots_of(n, a.phase, eb) + kBlock - 1) / kBlock;
   const dim3 g((uint32_t)blocks), b(kBlock);
   hipStream_t st = (hipStream_t)stream;

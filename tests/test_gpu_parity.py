@@ -187,19 +187,44 @@ def test_many_small_and_ragged_tensors(variant):
         wl.close()
 
 
-def test_mutually_misaligned_tensor_goes_elementwise():
-    n = 20_000
-    mk = lambda off: torch.zeros(n + 8, dtype=torch.bfloat16, device=DEV)[off:off + n]
-    th, dth, m, v, g = mk(0), mk(1), mk(2), mk(3), mk(5)
-    th.copy_(W.normal_bf16(n, 0.02, (9, 0), device=DEV))
-    plan = mcf.Plan([(th, dth, m, v, None, g)], mcf.LIGHT)
-    host = [H.torch_to_u16(t) for t in (th, dth, m, v)]
-    for t in range(1, 4):
-        g.copy_(W.normal_bf16(n, 1e-3, (9, 1, t), device=DEV))
-        orc.adamw_step(host[0], host[1], host[2], host[3], None, H.torch_to_u16(g), 0, W.HYPER_LIGHT, t)
-        plan.step(W.HYPER_LIGHT, t)
-    for h, d in zip(host, (th, dth, m, v)):
-        assert np.array_equal(h, H.torch_to_u16(d))
+@pytest.mark.parametrize("variant,fmt", [("light", 0), ("plus", 0), ("light", 1), ("plus", 2), ("light", 3)])
+def test_buffers_at_different_offsets_modulo_16_bytes(variant, fmt):
+    """Every stream of a tensor at its own offset from a 16-byte boundary (a gradient that is a view into a
+    bucket, say): the slots are cut on theta's grid and the other streams are read and written with
+    unaligned 128-bit accesses.  Two tensors, several chunks each; then the plan is pointed at gradients
+    with yet another offset."""
+    sizes = (200_003, 4_099)
+    dtype = (torch.bfloat16, torch.float16, torch.float8_e5m2, torch.float8_e4m3fn)[fmt]
+    code = {"light": mcf.LIGHT, "plus": mcf.PLUS}[variant] | (fmt << 12)
+    hyper = W.HYPER_FP8 if fmt >= 2 else W.fp16_hyper(W.HYPER_LIGHT) if fmt == 1 else W.HYPER_LIGHT
+    names = ["theta", "dtheta", "m", "v"] + (["dv"] if variant == "plus" else [])
+    offsets = {"theta": 3, "dtheta": 0, "m": 5, "v": 2, "dv": 7, "grad": 1, "grad2": 6}
+    dev, host = {}, {}
+    for k in names + ["grad", "grad2"]:
+        dev[k] = [torch.zeros(n + 16, dtype=torch.uint8 if fmt >= 2 else dtype, device=DEV).view(dtype)[offsets[k]:offsets[k] + n] for n in sizes]
+    for i, n in enumerate(sizes):
+        dev["theta"][i].copy_(W.normal_bf16(n, 0.02, (11, i), device=DEV).to(dtype))
+    host = {k: [H.torch_to_u16(x) for x in dev[k]] for k in names}
+    assert len({x.data_ptr() % 16 for k in names + ["grad"] for x in dev[k][:1]}) >= 4
+    tensors = lambda g: [(dev["theta"][i], dev["dtheta"][i], dev["m"][i], dev["v"][i], dev["dv"][i] if variant == "plus" else None, dev[g][i])
+                         for i in range(len(sizes))]
+    plan = mcf.Plan(tensors("grad"), code)
+    scale = W.FP16_LOSS_SCALE if fmt else 1.0
+    for t in range(1, 5):
+        gname = "grad" if t <= 2 else "grad2"
+        if t == 3:
+            plan.update(tensors("grad2"))
+        for i, n in enumerate(sizes):
+            dev[gname][i].copy_((W.normal_bf16(n, 1e-3, (11, 7, t, i), device=DEV).float() * scale).to(dtype))
+            orc.adamw_step(host["theta"][i], host["dtheta"][i], host["m"][i], host["v"][i], host["dv"][i] if variant == "plus" else None,
+                           H.torch_to_u16(dev[gname][i]), code, hyper, t)
+        plan.step(hyper, t)
+    torch.cuda.synchronize()
+    for k in names:
+        for i in range(len(sizes)):
+            got = H.torch_to_u16(dev[k][i])
+            bad = np.flatnonzero(got != host[k][i])
+            assert bad.size == 0, f"{k}[{i}]: {bad.size} mismatches, first at {int(bad[0])}"
     plan.destroy()
 
 
