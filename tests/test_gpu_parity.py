@@ -228,6 +228,68 @@ def test_buffers_at_different_offsets_modulo_16_bytes(variant, fmt):
     plan.destroy()
 
 
+@pytest.mark.parametrize("seed", range(48))
+def test_seeded_mix_of_shapes_offsets_variants_and_formats(seed):
+    """Plans drawn from a seed: 1 to 12 tensors of 1 to 60,000 elements (a few empty), every buffer of
+    every tensor at its own element offset, any variant with any flag in any component format, one to
+    three steps with the fused EDQ on the last.  Every element and the EDQ outputs against the oracle."""
+    rng = np.random.default_rng(7000 + seed)
+    fmt = int(rng.integers(0, 4))
+    base = ["light", "plus", "bf16", "kahan", "sgd"][int(rng.integers(0, 5))]
+    code = {"light": mcf.LIGHT, "plus": mcf.PLUS, "bf16": mcf.BF16, "kahan": mcf.KAHAN, "sgd": mcf.SGD}[base]
+    if base in ("light", "plus") and rng.integers(0, 2):
+        code |= mcf.GROW_TWOSUM
+    if base != "sgd" and rng.integers(0, 4) == 0:
+        code |= mcf.EPS_INSIDE_SQRT
+    code |= fmt << 12
+    dtype = (torch.bfloat16, torch.float16, torch.float8_e5m2, torch.float8_e4m3fn)[fmt]
+    hyper = W.HYPER_FP8 if fmt >= 2 else W.fp16_hyper(W.HYPER_LIGHT) if fmt == 1 else W.HYPER_LIGHT
+    names = ["theta"] + (["dtheta"] if base != "bf16" else []) + ["m"] + (["v"] if base != "sgd" else []) + (["dv"] if base == "plus" else [])
+    sizes = [int(x) for x in rng.choice([0, 1, 7, 8, 9, 63, 64, 65, 511, 512, 513, 4097, 20_011, 60_000], int(rng.integers(1, 13)))]
+    _say(f"seed {seed}: fmt {fmt} variant {code:#x} sizes {sizes}")
+    aligned = bool(rng.integers(0, 2))               # half of the plans keep the buffers of a tensor mutually aligned
+    dev = {k: [] for k in names + ["grad"]}
+    for n in sizes:
+        common = int(rng.integers(0, 16))
+        for k in names + ["grad"]:
+            off = common if aligned else int(rng.integers(0, 16))
+            dev[k].append(torch.zeros(n + 32, dtype=torch.uint8 if fmt >= 2 else dtype, device=DEV).view(dtype)[off:off + n])
+    for i, n in enumerate(sizes):
+        if n:
+            dev["theta"][i].copy_(W.normal_bf16(n, 0.02, (12, seed, i), device=DEV).to(dtype))
+    host = {k: [H.torch_to_u16(x) for x in dev[k]] for k in names}
+    get = lambda d, k, i: d[k][i] if k in d else None
+    plan = mcf.Plan([(dev["theta"][i], get(dev, "dtheta", i), dev["m"][i], get(dev, "v", i), get(dev, "dv", i), dev["grad"][i])
+                     for i in range(len(sizes))], code)
+    assert plan.params == sum(sizes)
+    steps = int(rng.integers(1, 4))
+    scale = W.FP16_LOSS_SCALE if fmt else 1.0
+    edq = torch.zeros(4, dtype=torch.float64, device=DEV)
+    acc = orc.EdqAccumulator(fmt=fmt)
+    for t in range(1, steps + 1):
+        for i, n in enumerate(sizes):
+            if not n:
+                continue
+            dev["grad"][i].copy_((W.normal_bf16(n, 1e-3, (12, seed, t, i), device=DEV).float() * scale).to(dtype))
+            th0 = host["theta"][i].copy()
+            dth0 = host["dtheta"][i].copy() if "dtheta" in host else None
+            d = np.empty(n, np.uint16)
+            orc.adamw_step(host["theta"][i], get(host, "dtheta", i), host["m"][i], get(host, "v", i), get(host, "dv", i),
+                           H.torch_to_u16(dev["grad"][i]), code, hyper, t, delta_out=d)
+            if t == steps:
+                acc.add(d, th0, dth0, host["theta"][i], get(host, "dtheta", i))
+        plan.step(hyper, t, edq_out=edq if t == steps else None)
+    torch.cuda.synchronize()
+    for k in names:
+        for i in range(len(sizes)):
+            got = H.torch_to_u16(dev[k][i])
+            bad = np.flatnonzero(got != host[k][i])
+            assert bad.size == 0, f"seed {seed} {k}[{i}] (n={sizes[i]}): {bad.size} mismatches, first at {int(bad[0])}"
+    got = edq.cpu().numpy()
+    assert abs(got[0] - acc.value()) <= 1e-5 * abs(acc.value()) + 1e-300 and int(got[3]) == acc.lost.value
+    plan.destroy()
+
+
 @pytest.mark.parametrize("variant", ["light", "plus", "bf16", "kahan", "sgd", "light+twosum", "plus+twosum"])
 def test_special_values_take_the_exact_path(variant):
     """State and gradients drawn from all bit patterns (NaN, infinities, zeros, subnormals, huge and tiny
