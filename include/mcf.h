@@ -46,8 +46,9 @@
  *     overlap (not checked; the result is undefined if they do).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Work is enqueued on it and the call returns without waiting.
- *   - The library owns only plan objects (a host struct, one device table and
- *     one device buffer of reduction partials) between create and destroy.
+ *   - The library owns only plan objects (a host struct, device tables with a
+ *     small pinned host staging block for them, and one device buffer of
+ *     reduction partials) between create and destroy.
  *   - Calls on one plan must not overlap in time; distinct plans are independent.
  */
 #ifndef MCF_H
@@ -136,8 +137,14 @@ uint64_t mcf_plan_params(const mcf_plan *plan);
  * buffers are reallocated between steps) without rebuilding it: no allocation.  `tensors` must
  * have the `count` of mcf_plan_create, every n unchanged (else MCF_ERR_SIZE), and each tensor's
  * theta must sit at the same offset modulo 128 bytes as the theta it replaces (else MCF_ERR_ALIGN:
- * the plan's work split was cut for that offset; create a new plan).  The new table is copied in `stream` order, after the steps already enqueued there, and
- * the call returns once the copy is done (it waits for that stream).  On an error the plan is unchanged. */
+ * the plan's work split was cut for that offset; create a new plan).  Asynchronous like the step: the new
+ * table is staged in pinned host memory owned by the plan and copied in `stream` order, behind the steps
+ * already enqueued there, into the one of the plan's two device tables that those steps do not read; the
+ * call returns without waiting for the copy, and steps enqueued after it use the new buffers.  (The host
+ * only waits if it runs two updates ahead of the device: the staging block of the update before the
+ * previous one must have been copied.)  `tensors` is read during the call only.  Not for use while
+ * `stream` is being captured into a graph (MCF_ERR_HIP): a captured copy would be replayed from whatever
+ * the staging memory holds later.  On an error the plan is unchanged. */
 int mcf_plan_update(mcf_plan *plan, const mcf_tensor *tensors, uint32_t count, void *stream);
 
 /* One optimizer step, Alg. 2 lines 8-13, over every tensor of the plan: one launch.

@@ -28,6 +28,7 @@
 #include <stdint.h>
 
 #include <cstdlib>
+#include <cstring>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -1071,6 +1072,38 @@ int prim_launch(int format, int op, const void *p0, const void *p1, const void *
 
 inline bool known_component(int c) { return c >= MCF_COMPONENT_BF16 && c <= MCF_COMPONENT_FP8_E4M3; }
 
+// The stand-alone EDQ reduction (Def. 3.3) over n > 0 elements with `partials` as its scratch memory:
+// one partial per workgroup of the first kernel, then the two-kernel tail.
+int edq_launch(int component, const void *delta, const void *th0, const void *dth0, const void *th1,
+               const void *dth1, uint64_t n, double *partials, hipStream_t st, double *edq_dev) {
+  // stream order: delta, th0, th1, dth0, dth1 (absent second components are not read)
+  const void *ps[5] = {delta, th0, th1, dth0, dth1};
+  const uint32_t eb = elem_bytes_of(component);
+  for (int i = 0; i < 5; ++i)
+    if (ps[i] && misaligned(ps[i], eb)) return MCF_ERR_ALIGN;
+  PrimArgs a = {};
+  uint64_t al[5];
+  int na = 0;
+  for (int i = 0; i < 5; ++i) {
+    a.p[i] = (uint64_t)(uintptr_t)ps[i];
+    if (ps[i]) al[na++] = a.p[i];
+  }
+  if (n > kMaxTensorElems) return MCF_ERR_SIZE;
+  a.n = n;
+  phase_of(al, na, a.phase, a.skewed, 16, eb);
+  const uint64_t blocks = (slots_of(n, a.phase, eb) + kBlock - 1) / kBlock;
+  const dim3 g((uint32_t)blocks), b(kBlock);
+  const uint32_t h0 = dth0 ? 1u : 0u, h1 = dth1 ? 1u : 0u;
+  switch (component) {
+    case MCF_COMPONENT_FP16: hipLaunchKernelGGL((prim_kernel<P_EDQ, MCF_COMPONENT_FP16>), g, b, 0, st, a, h0, h1, partials); break;
+    case MCF_COMPONENT_FP8_E5M2: hipLaunchKernelGGL((prim_kernel<P_EDQ, MCF_COMPONENT_FP8_E5M2>), g, b, 0, st, a, h0, h1, partials); break;
+    case MCF_COMPONENT_FP8_E4M3: hipLaunchKernelGGL((prim_kernel<P_EDQ, MCF_COMPONENT_FP8_E4M3>), g, b, 0, st, a, h0, h1, partials); break;
+    default: hipLaunchKernelGGL((prim_kernel<P_EDQ, MCF_COMPONENT_BF16>), g, b, 0, st, a, h0, h1, partials); break;
+  }
+  MCF_HIP(hipGetLastError());
+  return launch_edq_tail(partials, blocks, partials + kEdqVals * blocks, edq_dev, st);
+}
+
 }  // namespace
 
 struct mcf_plan {
@@ -1078,10 +1111,18 @@ struct mcf_plan {
   uint32_t n_tensors;
   uint32_t n_chunks;
   uint64_t n_params;
-  TensorDesc *d_descs;
+  // Two descriptor tables in one device allocation; steps read d_descs[cur].  mcf_plan_update fills the
+  // other one through its own block of pinned host memory and then makes it current, so it never has to
+  // wait for the copy: the pinned block is only written again two updates later, after `staged` of that
+  // block (recorded behind its copy) has completed.
+  TensorDesc *d_descs[2];
+  TensorDesc *h_stage[2];            // pinned host memory, n_tensors descriptors each
+  hipEvent_t staged[2];
+  bool have_events;
+  int cur;
   Chunk *d_chunks;
   double *d_partials;   // kEdqVals*n_chunks doubles, then kEdqVals*kStage1Blocks doubles
-  std::vector<TensorDesc> h_descs;   // host copy of the descriptor table (for mcf_plan_update)
+  std::vector<uint32_t> phases;      // phase of every non-empty tensor's theta (mcf_plan_update must keep it)
   std::vector<uint64_t> in_n;        // n of every tensor given at creation, empty ones included
 };
 
@@ -1137,18 +1178,33 @@ int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, i
   p->n_tensors = (uint32_t)descs.size();
   p->n_chunks = (uint32_t)chunks.size();
   p->n_params = params;
-  p->d_descs = nullptr;
+  p->d_descs[0] = p->d_descs[1] = nullptr;
+  p->h_stage[0] = p->h_stage[1] = nullptr;
+  p->have_events = false;
+  p->cur = 0;
   p->d_chunks = nullptr;
   p->d_partials = nullptr;
-  p->h_descs = descs;
+  p->phases.resize(descs.size());
+  for (size_t i = 0; i < descs.size(); ++i) p->phases[i] = descs[i].phase;
   p->in_n.resize(count);
   for (uint32_t i = 0; i < count; ++i) p->in_n[i] = tensors[i].n;
   if (p->n_chunks) {
-    bool ok = hipMalloc((void **)&p->d_descs, descs.size() * sizeof(TensorDesc)) == hipSuccess &&
-              hipMalloc((void **)&p->d_chunks, chunks.size() * sizeof(Chunk)) == hipSuccess &&
-              hipMalloc((void **)&p->d_partials, (uint64_t)kEdqVals * ((uint64_t)p->n_chunks + kStage1Blocks) * sizeof(double)) == hipSuccess &&
-              hipMemcpy(p->d_descs, descs.data(), descs.size() * sizeof(TensorDesc), hipMemcpyHostToDevice) == hipSuccess &&
-              hipMemcpy(p->d_chunks, chunks.data(), chunks.size() * sizeof(Chunk), hipMemcpyHostToDevice) == hipSuccess;
+    const size_t table = descs.size() * sizeof(TensorDesc);
+    bool ok = hipMalloc((void **)&p->d_descs[0], 2 * table) == hipSuccess &&
+              hipHostMalloc((void **)&p->h_stage[0], 2 * table, hipHostMallocDefault) == hipSuccess &&
+              hipEventCreateWithFlags(&p->staged[0], hipEventDisableTiming) == hipSuccess;
+    if (ok) {
+      if (hipEventCreateWithFlags(&p->staged[1], hipEventDisableTiming) == hipSuccess) p->have_events = true;
+      else { (void)hipEventDestroy(p->staged[0]); ok = false; }
+    }
+    if (ok) {
+      p->d_descs[1] = p->d_descs[0] + descs.size();
+      p->h_stage[1] = p->h_stage[0] + descs.size();
+    }
+    ok = ok && hipMalloc((void **)&p->d_chunks, chunks.size() * sizeof(Chunk)) == hipSuccess &&
+         hipMalloc((void **)&p->d_partials, (uint64_t)kEdqVals * ((uint64_t)p->n_chunks + kStage1Blocks) * sizeof(double)) == hipSuccess &&
+         hipMemcpy(p->d_descs[0], descs.data(), table, hipMemcpyHostToDevice) == hipSuccess &&
+         hipMemcpy(p->d_chunks, chunks.data(), chunks.size() * sizeof(Chunk), hipMemcpyHostToDevice) == hipSuccess;
     if (!ok) {
       (void)hipGetLastError();
       mcf_plan_destroy(p);
@@ -1162,9 +1218,18 @@ int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, i
 int mcf_plan_destroy(mcf_plan *plan) {
   if (!plan) return MCF_OK;
   int rc = MCF_OK;
-  if (plan->d_descs && hipFree(plan->d_descs) != hipSuccess) rc = MCF_ERR_HIP;
+  if (plan->have_events) {
+    // a copy out of the pinned block may still be queued
+    for (hipEvent_t ev : plan->staged) {
+      if (hipEventSynchronize(ev) != hipSuccess) rc = MCF_ERR_HIP;
+      if (hipEventDestroy(ev) != hipSuccess) rc = MCF_ERR_HIP;
+    }
+  }
+  if (plan->d_descs[0] && hipFree(plan->d_descs[0]) != hipSuccess) rc = MCF_ERR_HIP;
+  if (plan->h_stage[0] && hipHostFree(plan->h_stage[0]) != hipSuccess) rc = MCF_ERR_HIP;
   if (plan->d_chunks && hipFree(plan->d_chunks) != hipSuccess) rc = MCF_ERR_HIP;
   if (plan->d_partials && hipFree(plan->d_partials) != hipSuccess) rc = MCF_ERR_HIP;
+  if (rc != MCF_OK) (void)hipGetLastError();
   delete plan;
   return rc;
 }
@@ -1176,7 +1241,7 @@ int mcf_plan_update(mcf_plan *plan, const mcf_tensor *tensors, uint32_t count, v
   if (count != plan->in_n.size()) return MCF_ERR_SIZE;
   if (count && !tensors) return MCF_ERR_NULL;
   std::vector<TensorDesc> descs;
-  descs.reserve(plan->h_descs.size());
+  descs.reserve(plan->phases.size());
   for (uint32_t i = 0; i < count; ++i) {
     if (tensors[i].n != plan->in_n[i]) return MCF_ERR_SIZE;
     const int rc = check_tensor(tensors[i], plan->variant);
@@ -1184,17 +1249,26 @@ int mcf_plan_update(mcf_plan *plan, const mcf_tensor *tensors, uint32_t count, v
     if (tensors[i].n == 0) continue;
     TensorDesc d;
     fill_desc(tensors[i], plan->variant, d);
-    const TensorDesc &old = plan->h_descs[descs.size()];
     // the chunk table was cut for the old theta's offset within its 128-byte line: the new one must share it
-    if (d.phase != old.phase) return MCF_ERR_ALIGN;
+    if (d.phase != plan->phases[descs.size()]) return MCF_ERR_ALIGN;
     descs.push_back(d);
   }
-  if (!descs.empty()) {
-    // the descriptor table is read by kernels already enqueued on `stream`; the copy is ordered after them
-    MCF_HIP(hipMemcpyAsync(plan->d_descs, descs.data(), descs.size() * sizeof(TensorDesc), hipMemcpyHostToDevice, (hipStream_t)stream));
-    MCF_HIP(hipStreamSynchronize((hipStream_t)stream));      // descs is a local: the copy must have read it before it goes
-  }
-  plan->h_descs.swap(descs);
+  if (descs.empty()) return MCF_OK;
+  hipStream_t st = (hipStream_t)stream;
+  // A captured copy would read the pinned block again at every replay, whatever it holds by then.
+  hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+  MCF_HIP(hipStreamIsCapturing(st, &capturing));
+  if (capturing != hipStreamCaptureStatusNone) return MCF_ERR_HIP;
+  const int nxt = plan->cur ^ 1;
+  // The pinned block of table `nxt` was last read by the copy of the update before the previous one;
+  // this returns at once unless the host has run two updates ahead of the device.
+  MCF_HIP(hipEventSynchronize(plan->staged[nxt]));
+  const size_t table = descs.size() * sizeof(TensorDesc);
+  memcpy(plan->h_stage[nxt], descs.data(), table);
+  // ordered on `stream` behind the steps already enqueued there (they read the other table anyway)
+  MCF_HIP(hipMemcpyAsync(plan->d_descs[nxt], plan->h_stage[nxt], table, hipMemcpyHostToDevice, st));
+  MCF_HIP(hipEventRecord(plan->staged[nxt], st));
+  plan->cur = nxt;
   return MCF_OK;
 }
 
@@ -1207,7 +1281,7 @@ int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *
   hipStream_t st = (hipStream_t)stream;
   const TensorDesc none = {};
   if (plan->n_chunks) {
-    launch_variant<true>(plan->variant, edq_dev != nullptr, plan->n_chunks, st, plan->d_descs, plan->d_chunks, none, hs,
+    launch_variant<true>(plan->variant, edq_dev != nullptr, plan->n_chunks, st, plan->d_descs[plan->cur], plan->d_chunks, none, hs,
                          plan->d_partials);
     MCF_HIP(hipGetLastError());
   }
@@ -1365,34 +1439,7 @@ int mcf_edq_component(int component, const void *delta, const void *th0, const v
   if (n == 0) return launch_edq_tail(nullptr, 0, nullptr, edq_dev, (hipStream_t)stream);
   if (!delta || !th0 || !th1 || !scratch_dev) return MCF_ERR_NULL;
   if (misaligned(scratch_dev, 8)) return MCF_ERR_ALIGN;
-  double *partials = (double *)scratch_dev;
-  // stream order: delta, th0, th1, dth0, dth1 (absent second components are not read)
-  const void *ps[5] = {delta, th0, th1, dth0, dth1};
-  const uint32_t eb = elem_bytes_of(component);
-  for (int i = 0; i < 5; ++i)
-    if (ps[i] && misaligned(ps[i], eb)) return MCF_ERR_ALIGN;
-  PrimArgs a = {};
-  uint64_t al[5];
-  int na = 0;
-  for (int i = 0; i < 5; ++i) {
-    a.p[i] = (uint64_t)(uintptr_t)ps[i];
-    if (ps[i]) al[na++] = a.p[i];
-  }
-  if (n > kMaxTensorElems) return MCF_ERR_SIZE;
-  a.n = n;
-  phase_of(al, na, a.phase, a.skewed, 16, eb);
-  const uint64_t blocks = (slots_of(n, a.phase, eb) + kBlock - 1) / kBlock;
-  const dim3 g((uint32_t)blocks), b(kBlock);
-  hipStream_t st = (hipStream_t)stream;
-  const uint32_t h0 = dth0 ? 1u : 0u, h1 = dth1 ? 1u : 0u;
-  switch (component) {
-    case MCF_COMPONENT_FP16: hipLaunchKernelGGL((prim_kernel<P_EDQ, MCF_COMPONENT_FP16>), g, b, 0, st, a, h0, h1, partials); break;
-    case MCF_COMPONENT_FP8_E5M2: hipLaunchKernelGGL((prim_kernel<P_EDQ, MCF_COMPONENT_FP8_E5M2>), g, b, 0, st, a, h0, h1, partials); break;
-    case MCF_COMPONENT_FP8_E4M3: hipLaunchKernelGGL((prim_kernel<P_EDQ, MCF_COMPONENT_FP8_E4M3>), g, b, 0, st, a, h0, h1, partials); break;
-    default: hipLaunchKernelGGL((prim_kernel<P_EDQ, MCF_COMPONENT_BF16>), g, b, 0, st, a, h0, h1, partials); break;
-  }
-  MCF_HIP(hipGetLastError());
-  return launch_edq_tail(partials, blocks, partials + kEdqVals * blocks, edq_dev, (hipStream_t)stream);
+  return edq_launch(component, delta, th0, dth0, th1, dth1, n, (double *)scratch_dev, (hipStream_t)stream, edq_dev);
 }
 
 int mcf_edq(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
