@@ -8,6 +8,7 @@ import pytest
 import torch
 
 import helpers as H
+from conftest import say as _say
 from gpu_harness import SampledOracle, Workload, assert_bitwise, full_oracle_run, sample_indices
 from oracle import oracle as orc
 from paper_2405_03637_amd import binding as mcf
@@ -17,10 +18,6 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 F16 = orc.FMT_FP16
 C16 = mcf.COMPONENT_FP16
-
-
-def _say(msg):
-    print(msg, flush=True)
 
 
 def _dev(u16):

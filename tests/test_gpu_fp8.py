@@ -7,6 +7,7 @@ import pytest
 import torch
 
 import helpers as H
+from conftest import say as _say
 from gpu_harness import SampledOracle, Workload, assert_bitwise, full_oracle_run, sample_indices
 from oracle import oracle as orc
 from paper_2405_03637_amd import binding as mcf
@@ -17,10 +18,6 @@ DEV = "cuda"
 FMTS = [2, 3]              # mcf_component and oracle format id: FP8 E5M2, FP8 E4M3
 NAN = {2: 0x7E, 3: 0x7F}
 ALL = np.arange(256, dtype=np.uint16)
-
-
-def _say(msg):
-    print(msg, flush=True)
 
 
 def _dev(patterns):

@@ -338,3 +338,25 @@ def test_small_quotients_by_a_bias_correction(orc):
         r = (1.0 / _bf16_as_f32(B).astype(np.float64)).astype(np.float32)
         got = orc.R_array((_bf16_as_f32(A) * r).astype(np.float32))
     assert np.array_equal(got, orc.binop(orc.DIV, A, B))
+
+
+def test_every_quotient_by_a_bias_correction_through_its_reciprocal(orc):
+    """Lines 10-11 of Alg. 2 in the GPU's restricted arithmetic mode, exhaustively: for EVERY bf16 pattern a
+    (zeros, subnormals, infinities and NaN included) and every bf16 bias correction bc in [2^-60, 1] -- the
+    range in which the host lets that mode run -- the product of a with the correctly rounded fp32
+    reciprocal of bc, rounded to bf16, is F(a / bc).  5.0e8 pairs of pure IEEE fp32 arithmetic; a NaN on one
+    side must be a NaN on the other (the kernel then redoes the slot and stores the one NaN pattern)."""
+    a_bits = np.arange(1 << 16, dtype=np.uint16)
+    fa = _bf16_as_f32(a_bits)
+    bc_all = np.arange((127 - 60) << 7, (127 << 7) + 1, dtype=np.uint16)
+    assert bc_all.size == 60 * 128 + 1
+    bad = checked = 0
+    with np.errstate(all="ignore"):
+        for i in range(0, bc_all.size, 64):
+            bc = bc_all[i:i + 64]
+            r = (1.0 / _bf16_as_f32(bc).astype(np.float64)).astype(np.float32)           # what the host passes
+            got = orc.R_array((fa[None, :] * r[:, None]).astype(np.float32).ravel())
+            want = orc.binop(orc.DIV, np.tile(a_bits, bc.size), np.repeat(bc, a_bits.size))
+            bad += int(np.count_nonzero(got != want))
+            checked += got.size
+    assert checked == (60 * 128 + 1) * 65536 and bad == 0
