@@ -20,11 +20,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor peak
 
-# HBM traffic per parameter per step measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
-# what the same counters read for a plain copy of known size (FETCH_SIZE x2.0000, WRITE_SIZE x1.0000);
-# the figures and commands are in profiles/*_llama_7b.md.  None = not measured.
-MEASURED_TRAFFIC_BYTES_PER_PARAM = {"light": 18.250, "plus": 22.250, "kahan": 18.250, "bf16": 14.250, "sgd": 14.250,
-                                    "fp32mw": 28.250}      # the same with fp16 components (same bytes, same table)
+# HBM traffic per parameter per step as rocprofv3 --pmc measured it (FETCH_SIZE, WRITE_SIZE, each scaled by what the
+# same counter reads for a plain copy of known size: FETCH_SIZE x2.0000, WRITE_SIZE x1.0000).  These are NOT measured
+# in this run: they are copied from the summaries under profiles/ (the commands are in those files), keyed by the
+# full variant name; a variant with no such summary reports null.
+PROFILED_TRAFFIC_BYTES_PER_PARAM = {"light": 18.250, "plus": 22.250, "kahan": 18.250, "bf16": 14.250, "sgd": 14.250,
+                                    "light+twosum": 18.250, "plus+twosum": 22.250, "light+fp16": 18.250, "plus+fp16": 22.250,
+                                    "light+e5m2": 9.125, "light+e4m3": 9.125, "plus+e5m2": 11.125, "fp32mw": 28.250}
 
 
 def log(msg):
@@ -93,19 +95,16 @@ def build_state(name, variant, arenas):
     return st, plan, W.total_params(shapes), len(shapes)
 
 
-def cpu_baseline(name, variant, hyper, sample=32 * 1024 * 1024, min_seconds=1.5):
-    """The oracle as it stands, on the host cores, over the first `sample` parameters of the workload."""
+def _oracle_rate(name, variant, hyper, n, threads, min_seconds):
+    """params/s of the oracle's step over n parameters drawn like the workload's, on `threads` host threads."""
     import numpy as np
-    import torch
     from oracle import oracle as orc
     from paper_2405_03637_amd import workloads as W
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     import helpers as H
-    n = min(sample, W.total_params(W.shapes(name)))
     theta = H.torch_to_u16(W.normal_bf16(n, 0.02, (0, 0, 0)))
     z = lambda: np.zeros(n, np.uint16)
     dth, m, v, dv = z(), z(), z(), (z() if variant.startswith("plus") else None)
-    threads = orc.default_threads()
     grads = [H.torch_to_u16(W.normal_bf16(n, 1e-3, (0, 1, t))) for t in (1, 2)]
     code = {"light": orc.LIGHT, "plus": orc.PLUS, "bf16": orc.BF16, "kahan": orc.KAHAN, "sgd": orc.SGD}[variant.split("+")[0]]
     if "+twosum" in variant:
@@ -121,8 +120,25 @@ def cpu_baseline(name, variant, hyper, sample=32 * 1024 * 1024, min_seconds=1.5)
         orc.adamw_step(theta, dth, m, v, dv, grads[steps & 1], code, hyper, steps + 2, nthreads=threads)
         steps += 1
     el = time.perf_counter() - t0
-    return {"value": n * steps / el, "unit": "params/s", "cores": threads, "kind": "oracle",
-            "sample": f"first {n} parameters of {name}, {steps} {variant} steps, {el:.2f} s wall on {threads} threads"}
+    return n * steps / el, steps, el
+
+
+def cpu_baseline(name, variant, hyper, sample=32 * 1024 * 1024, min_seconds=1.5):
+    """The oracle as it stands on the host cores: over the first `sample` parameters of the workload on every
+    core the process may use, and on ONE thread over the 2^20-parameter flat tensor of the smallest
+    configuration (the per-core figure)."""
+    from oracle import oracle as orc
+    from paper_2405_03637_amd import workloads as W
+    n = min(sample, W.total_params(W.shapes(name)))
+    threads = orc.default_threads()
+    rate, steps, el = _oracle_rate(name, variant, hyper, n, threads, min_seconds)
+    n1 = 1 << 20
+    rate1, steps1, el1 = _oracle_rate("flat_1m", variant, hyper, n1, 1, 0.5)
+    return {"value": rate, "unit": "params/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {n} parameters of {name}, {steps} {variant} steps, {el:.2f} s wall on {threads} threads",
+            "per_core": rate / threads,
+            "single_thread": {"value": rate1, "unit": "params/s", "cores": 1,
+                              "sample": f"flat_1m ({n1} parameters), {steps1} {variant} steps, {el1:.2f} s wall on 1 thread"}}
 
 
 def main():
@@ -171,7 +187,7 @@ def main():
     bpp = W.bytes_per_param(variant.split("+")[0]) * (0.5 if ("+e5m2" in variant or "+e4m3" in variant) else 1.0)
     kern_s = gpu_s / args.steps
     achieved = bpp * n_params / kern_s / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES_PER_PARAM.get(variant.split("+")[0])
+    traffic = PROFILED_TRAFFIC_BYTES_PER_PARAM.get(variant)
     result = {
         "metric": "MCF-AdamW params updated/sec and % of HBM roofline (GB/s) at 7B, 1 GPU",
         "value": n_params * args.steps / wall,
@@ -186,6 +202,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": (traffic * n_params) if traffic else None,
+                     "traffic_source": "rocprofv3 --pmc summaries under profiles/ (not measured in this run)" if traffic else None,
                      "kernel_ms": kern_s * 1e3, "algorithmic_bytes": bpp * n_params},
     }
     extras = {}
@@ -201,12 +218,31 @@ def main():
     plan.destroy()
     if not args.no_extras:
         try:
-            # plain copy of one arena as the achievable streaming ceiling (reads n*2, writes n*2 bytes)
+            # Streaming ceilings measured in this run, on the arenas the step just used.
+            # (a) a plain copy of one arena in the step's own launch shape (reads n*2, writes n*2 bytes)
             src, dst = st["theta"], st["dv"]
             nb = src.numel() // 8 * 8
             _, s = time_steps(lambda t: mcf.stream_copy(dst[:nb], src[:nb]), 10, 2)
             extras["copy_GBps"] = 4 * nb * 10 / s / 1e9
+            # (b) the same copy in other launch shapes and through the runtime's own device-to-device copy
+            shapes_tried = {}
+            for threads, vec, cap in ((64, 1, 0), (64, 2, 0), (64, 4, 0), (256, 1, 0), (256, 2, 0), (256, 4, 0), (64, 1, 16), (64, 2, 16)):
+                _, s = time_steps(lambda t: mcf.stream_mix([src[:nb]], [dst[:nb]], 2 * nb, threads, vec, cap), 6, 2)
+                shapes_tried[f"{threads}x{vec}" + (f"/cap{cap}" if cap else "")] = round(4 * nb * 6 / s / 1e9, 1)
+            extras["copy_shapes_GBps"] = shapes_tried
+            extras["copy_best_GBps"] = max(max(shapes_tried.values()), extras["copy_GBps"])
+            _, s = time_steps(lambda t: dst[:nb].copy_(src[:nb]), 6, 2)
+            extras["hipMemcpyDtoD_GBps"] = 4 * nb * 6 / s / 1e9
             del src, dst
+            # (c) the step's own mix of streams with no arithmetic: 5 arenas read, 4 of them written back in place
+            rd = [st[k][:nb] for k in ("theta", "dtheta", "m", "v", "grad")]
+            mix_tried = {}
+            for threads, vec, cap in ((64, 1, 10), (64, 1, 12), (64, 1, 16), (64, 1, 0), (64, 2, 8), (64, 2, 0), (256, 1, 0), (256, 2, 0)):
+                _, s = time_steps(lambda t: mcf.stream_mix(rd, rd[:4], 2 * nb, threads, vec, cap), 5, 2)
+                mix_tried[f"{threads}x{vec}" + (f"/cap{cap}" if cap else "")] = round(18 * nb * 5 / s / 1e9, 1)
+            extras["stream_5r4w_shapes_GBps"] = mix_tried
+            extras["stream_5r4w_GBps"] = max(mix_tried.values())
+            del rd
             # the other strategies on the same shapes
             for other in ("plus", "light", "kahan", "bf16", "sgd", "light+twosum", "plus+twosum", "light+fp16", "plus+fp16",
                           "light+e5m2", "plus+e5m2", "light+e4m3"):
@@ -248,8 +284,10 @@ def main():
     torch.cuda.empty_cache()
     if extras:
         result["extras"] = extras
-        if "copy_GBps" in extras:
-            result["roofline"]["frac_of_copy"] = achieved / extras["copy_GBps"]
+        if "copy_best_GBps" in extras:
+            result["roofline"]["frac_of_copy"] = achieved / extras["copy_best_GBps"]
+        if "stream_5r4w_GBps" in extras and variant.split("+")[0] in ("light", "kahan") and bpp == 18:
+            result["roofline"]["frac_of_mix"] = achieved / extras["stream_5r4w_GBps"]
 
     if not args.no_cpu:
         log("bench: timing the CPU oracle")

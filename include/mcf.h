@@ -246,6 +246,16 @@ int mcf_fp32mw_step(mcf_fp32mw_plan *plan, const mcf_hyper *hyper, uint64_t step
  * profiler byte counters (the step moves 18 or 22 bytes per parameter: Table 1's state, read and
  * written, plus the gradient). ---- */
 int mcf_stream_copy(void *dst, const void *src, uint64_t bytes, void *stream);
+/* ---- measurement aid: the memory traffic of a step without its arithmetic.  Every 16 bytes of each of the
+ * n_read buffers reads[] (host array of device pointers, 16-byte aligned, `bytes` bytes each, a multiple of
+ * 16) are loaded, and write j (j < n_write <= n_read) receives what read j brought in -- unchanged, so passing
+ * the same buffers for reads and writes, as the step does, leaves their contents as they are.  The launch
+ * shape is the caller's: threads per workgroup (64 or 256), 128-bit vectors per lane (1, 2 or 4; each wave
+ * instruction covers one contiguous run) and groups_per_cu, a cap on the workgroups resident per compute
+ * unit (0 = none).  Supported mixes (n_read, n_write): (1,1) a copy, (1,0), (4,3), (5,4) the light step,
+ * (6,5) the plus step; others are MCF_ERR_VARIANT.  bench.py reports the step against what this reaches. ---- */
+int mcf_stream_mix(const void *const *reads, uint32_t n_read, void *const *writes, uint32_t n_write, uint64_t bytes,
+                   uint32_t threads, uint32_t vectors_per_lane, uint32_t groups_per_cu, void *stream);
 
 #ifdef __cplusplus
 }

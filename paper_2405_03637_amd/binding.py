@@ -92,6 +92,8 @@ def lib():
     L.mcf_fp32mw_plan_destroy.argtypes = [_vp]
     L.mcf_fp32mw_step.argtypes = [_vp, ctypes.POINTER(Hyper), _u64, _vp]
     L.mcf_stream_copy.argtypes = [_vp, _vp, _u64, _vp]
+    L.mcf_stream_mix.argtypes = [ctypes.POINTER(_vp), ctypes.c_uint32, ctypes.POINTER(_vp), ctypes.c_uint32, _u64,
+                                 ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32, _vp]
     _lib = L
     return L
 
@@ -305,6 +307,14 @@ def stream_copy(dst, src, stream=None):
     _check(lib().mcf_stream_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "mcf_stream_copy")
 
 
+def stream_mix(reads, writes, nbytes, threads=64, vectors_per_lane=1, groups_per_cu=0, stream=None):
+    """reads, writes: lists of device tensors (or addresses); write j receives read j's data."""
+    r = (_vp * max(1, len(reads)))(*[_ptr(t) for t in reads])
+    w = (_vp * max(1, len(writes)))(*[_ptr(t) for t in writes])
+    _check(lib().mcf_stream_mix(r, len(reads), w, len(writes), int(nbytes), int(threads), int(vectors_per_lane),
+                                int(groups_per_cu), _stream(stream)), "mcf_stream_mix")
+
+
 # ---- the C names, one to one (each returns nothing and raises McfError on a non-zero status) ----
 def mcf_plan_create(tensors, variant):
     return Plan(tensors, variant)
@@ -344,6 +354,7 @@ mcf_component_op = component_op
 mcf_round_f32_to = round_f32_to
 mcf_edq_component = edq_component
 mcf_stream_copy = stream_copy
+mcf_stream_mix = stream_mix
 mcf_status_string = status_string
 
 

@@ -62,6 +62,15 @@ using mcfd::StepScalarsT;
 #ifndef MCF_REMAP
 #define MCF_REMAP 0                  // 1: give each XCD (blocks are dealt round-robin to the 8 XCDs) a contiguous run of chunks
 #endif
+#ifndef MCF_PERSIST
+#define MCF_PERSIST 0                // 1: fixed grid of workgroups that walk the chunk table (see adamw_kernel)
+#endif
+#ifndef MCF_DEPTH
+#define MCF_DEPTH 1                  // MCF_PERSIST: chunks whose loads are issued ahead of the one being computed (0 or 1)
+#endif
+#ifndef MCF_WAVES_PER_CU
+#define MCF_WAVES_PER_CU 8           // MCF_PERSIST: workgroups of the fixed grid per compute unit
+#endif
 #ifndef MCF_CHUNK_ALIGN
 #define MCF_CHUNK_ALIGN 128          // bytes: a tensor's slots are counted from this address boundary below its first element
 #endif
@@ -347,11 +356,11 @@ template <int VARIANT> struct StepStreams {
 #else
   static constexpr int kGroups = kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? (kBf16 && !kGrow2 ? 9 : 11)
                                  : kBase == mcfd::V_SGD ? 11 : 10;
-  static constexpr uint32_t kLds = kEB == 1 ? 0 : lds_for_groups(kGroups);
+  static constexpr uint32_t kLds = (kEB == 1 || MCF_PERSIST) ? 0 : lds_for_groups(kGroups);
 #endif
   static constexpr int kEdqGroups = kBase == mcfd::V_BF16 ? 16 : (kGrow2 || kBase == mcfd::V_SGD) ? 14
                                     : (kBase == mcfd::V_PLUS || kBf16) ? 12 : 14;
-  static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : kEB == 1 ? 0 : lds_for_groups(kEdqGroups);
+  static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : (kEB == 1 || MCF_PERSIST) ? 0 : lds_for_groups(kEdqGroups);
 };
 
 // A dword of a stream holds one pair (2-byte elements) or two pairs (1-byte elements).
@@ -449,66 +458,63 @@ __device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, cons
   }
 }
 
-template <int VARIANT, bool FAST, bool EDQ, bool TABLE>
-__global__ void __launch_bounds__(kStepBlock) MCF_STEP_ATTR
-adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, TensorDesc flat,
-             typename StepStreams<VARIANT>::Scalars sc, double *__restrict__ partials, uint32_t n_chunks) {
-  using SS = StepStreams<VARIANT>;
-  using Mode = typename SS::template Hot<FAST>;
-  TensorDesc d;
+// One chunk in flight: where it is and the 16 bytes per stream and slot that its loads bring in.
+template <int VARIANT> struct ChunkIn {
+  TensorDesc d;                               // wave-uniform (SGPRs)
   uint64_t slot0;
-  uint32_t chunk_id = blockIdx.x;
-#if MCF_REMAP
-  {
-    const uint32_t per = gridDim.x / 8;            // the grid is rounded up to a multiple of 8
-    chunk_id = (blockIdx.x % 8) * per + blockIdx.x / 8;
-    if (chunk_id >= n_chunks) return;
-  }
-#endif
-  if (TABLE) {
-    const Chunk c = chunks[chunk_id];
-    d = descs[c.tensor];
-    slot0 = c.slot0;
-  } else {
-    d = flat;
-    slot0 = (uint64_t)chunk_id * kSlotsPerChunk;
-  }
-
-  // Phase 1 issues every 128-bit load of the chunk, phase 2 computes and stores: the stores go to
-  // the buffers the loads read, so the compiler would not move a later slot's loads above them.
   Slot slot[kUnroll];
   uint32_t in[kUnroll][kMaxStreams][4];
-  const bool elementwise = sc.elementwise != 0;      // uniform over the launch
+};
+
+// Issues every 128-bit load of chunk `chunk_id` (nothing waits for them here).
+template <int VARIANT, bool TABLE>
+__device__ __forceinline__ void issue_chunk(uint32_t chunk_id, const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks,
+                                            const TensorDesc &flat, bool elementwise, ChunkIn<VARIANT> &c) {
+  using SS = StepStreams<VARIANT>;
+  if (TABLE) {
+    const Chunk e = chunks[chunk_id];
+    c.d = descs[e.tensor];
+    c.slot0 = e.slot0;
+  } else {
+    c.d = flat;
+    c.slot0 = (uint64_t)chunk_id * kSlotsPerChunk;
+  }
   static_for<0, kUnroll>([&](auto jc) {
     constexpr int j = decltype(jc)::value;
-    slot[j] = classify<SS::kEB>(d, slot0 + (uint64_t)j * kStepBlock + threadIdx.x);
-    if (elementwise) slot[j].full = false;
-    if (slot[j].full) {
-      const uint64_t e0 = (slot[j].c0 - d.phase) * SS::kEB;       // byte offset
-      load_vec(d.p[S_TH], e0, in[j][S_TH]);
-      if (SS::kDth) load_vec(d.p[S_DTH], e0, in[j][S_DTH]);
-      load_vec(d.p[S_M], e0, in[j][S_M]);
-      if (SS::kV) load_vec(d.p[S_V], e0, in[j][S_V]);
-      load_vec(d.p[S_G], e0, in[j][S_G]);
-      if (SS::kDv) load_vec(d.p[S_DV], e0, in[j][S_DV]);
+    c.slot[j] = classify<SS::kEB>(c.d, c.slot0 + (uint64_t)j * kStepBlock + threadIdx.x);
+    if (elementwise) c.slot[j].full = false;
+    if (c.slot[j].full) {
+      const uint64_t e0 = (c.slot[j].c0 - c.d.phase) * SS::kEB;       // byte offset
+      load_vec(c.d.p[S_TH], e0, c.in[j][S_TH]);
+      if (SS::kDth) load_vec(c.d.p[S_DTH], e0, c.in[j][S_DTH]);
+      load_vec(c.d.p[S_M], e0, c.in[j][S_M]);
+      if (SS::kV) load_vec(c.d.p[S_V], e0, c.in[j][S_V]);
+      load_vec(c.d.p[S_G], e0, c.in[j][S_G]);
+      if (SS::kDv) load_vec(c.d.p[S_DV], e0, c.in[j][S_DV]);
     }
   });
+}
 
-  EdqAcc acc = {0.0, 0.0, 0u};
+// Computes and stores a chunk whose loads were issued by issue_chunk; adds its EDQ terms to acc.
+template <int VARIANT, bool FAST, bool EDQ>
+__device__ __forceinline__ void finish_chunk(ChunkIn<VARIANT> &c, const typename StepStreams<VARIANT>::Scalars &sc, EdqAcc &acc) {
+  using SS = StepStreams<VARIANT>;
+  using Mode = typename SS::template Hot<FAST>;
+  const TensorDesc &d = c.d;
   uint32_t cold = 0;          // bit j: slot j still has to go through the cold path
   static_for<0, kUnroll>([&](auto jc) {
     constexpr int j = decltype(jc)::value;
-    if (slot[j].full) {
+    if (c.slot[j].full) {
       uint32_t out[kMaxStreams][4];
       EdqAcc local = {0.0, 0.0, 0u};
-      bool redo = hot_slot<Mode, VARIANT, EDQ>(in[j], out, sc, local);
+      bool redo = hot_slot<Mode, VARIANT, EDQ>(c.in[j], out, sc, local);
       if constexpr (!SS::kBf16) {
         // fp16, FP8: the first pass found a NaN among its results.  The same slot again, still from registers,
         // in the mode that stores the format's one NaN: the arithmetic is the same packed code, so a
         // diverged tensor costs 18% more time, not a serial loop (21.8 against 65.5 ms for an all-NaN 7B set).
         if (redo) {
           local = {0.0, 0.0, 0u};
-          (void)hot_slot<typename SS::Cold, VARIANT, EDQ>(in[j], out, sc, local);
+          (void)hot_slot<typename SS::Cold, VARIANT, EDQ>(c.in[j], out, sc, local);
           redo = false;
         }
       }
@@ -517,7 +523,7 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
         // the root that scales such operands; what still asks for a redo after that has a NaN.
         if (redo) {
           local = {0.0, 0.0, 0u};
-          redo = hot_slot<mcfd::FastScaled, VARIANT, EDQ>(in[j], out, sc, local);
+          redo = hot_slot<mcfd::FastScaled, VARIANT, EDQ>(c.in[j], out, sc, local);
         }
       }
       // bf16: a slot that produced a NaN in Fast mode goes to the element loop below.  Redoing it from
@@ -527,7 +533,7 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
       if (redo) {
         cold |= 1u << j;
       } else {
-        const uint64_t e0 = (slot[j].c0 - d.phase) * SS::kEB;
+        const uint64_t e0 = (c.slot[j].c0 - d.phase) * SS::kEB;
         store_vec(d.p[S_TH], e0, out[S_TH]);
         if (SS::kDth) store_vec(d.p[S_DTH], e0, out[S_DTH]);
         store_vec(d.p[S_M], e0, out[S_M]);
@@ -535,7 +541,7 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
         if (SS::kDv) store_vec(d.p[S_DV], e0, out[S_DV]);
         if (EDQ) { acc.s1 += local.s1; acc.s2 += local.s2; acc.lost += local.lost; }
       }
-    } else if (slot[j].any) {
+    } else if (c.slot[j].any) {
       cold |= 1u << j;
     }
   });
@@ -544,11 +550,63 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
     for (int j = 0; j < kUnroll; ++j) {
       if (!((cold >> j) & 1u)) continue;
       EdqAcc local = {0.0, 0.0, 0u};
-      cold_slot<VARIANT, EDQ>(d, (slot0 + (uint64_t)j * kStepBlock + threadIdx.x) * SS::kEps, sc, local);
+      cold_slot<VARIANT, EDQ>(d, (c.slot0 + (uint64_t)j * kStepBlock + threadIdx.x) * SS::kEps, sc, local);
       if (EDQ) { acc.s1 += local.s1; acc.s2 += local.s2; acc.lost += local.lost; }
     }
   }
+}
+
+// The step kernel.  Two work distributions, chosen at compile time (MCF_PERSIST):
+//   0  one chunk per single-wave workgroup, the grid covers the chunk table;
+//   1  a fixed grid of single-wave workgroups (a few per CU), each walking the chunk table with the grid as
+//      its stride and, with MCF_DEPTH 1, issuing the loads of its next chunk before it computes the current
+//      one.  The eight XCDs (workgroups are dealt to them round-robin) each take a contiguous eighth of
+//      every grid-sized stretch of the table, so a line of the table is fetched by one L2 only.
+template <int VARIANT, bool FAST, bool EDQ, bool TABLE>
+__global__ void __launch_bounds__(kStepBlock) MCF_STEP_ATTR
+adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, TensorDesc flat,
+             typename StepStreams<VARIANT>::Scalars sc, double *__restrict__ partials, uint32_t n_chunks) {
+  const bool elementwise = sc.elementwise != 0;      // uniform over the launch
+  EdqAcc acc = {0.0, 0.0, 0u};
+#if MCF_PERSIST
+  const uint32_t grid = gridDim.x;
+  uint32_t chunk_id = (grid & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
+  ChunkIn<VARIANT> cur;
+  if (chunk_id < n_chunks) issue_chunk<VARIANT, TABLE>(chunk_id, descs, chunks, flat, elementwise, cur);
+  while (chunk_id < n_chunks) {
+    const uint32_t next_id = chunk_id + grid;
+#if MCF_DEPTH
+    ChunkIn<VARIANT> nxt;
+    const bool more = next_id < n_chunks && next_id > chunk_id;
+    if (more) issue_chunk<VARIANT, TABLE>(next_id, descs, chunks, flat, elementwise, nxt);
+    __builtin_amdgcn_sched_barrier(0);             // the next chunk's loads stay ahead of this chunk's arithmetic
+    finish_chunk<VARIANT, FAST, EDQ>(cur, sc, acc);
+    if (!more) break;
+    cur = nxt;
+#else
+    finish_chunk<VARIANT, FAST, EDQ>(cur, sc, acc);
+    if (!(next_id < n_chunks && next_id > chunk_id)) break;
+    issue_chunk<VARIANT, TABLE>(next_id, descs, chunks, flat, elementwise, cur);
+#endif
+    chunk_id = next_id;
+  }
+  if (EDQ) edq_store_partial<kStepBlock>(acc, partials, blockIdx.x);
+#else
+  uint32_t chunk_id = blockIdx.x;
+#if MCF_REMAP
+  {
+    const uint32_t per = gridDim.x / 8;            // the grid is rounded up to a multiple of 8
+    chunk_id = (blockIdx.x % 8) * per + blockIdx.x / 8;
+    if (chunk_id >= n_chunks) return;
+  }
+#endif
+  // Phase 1 issues every 128-bit load of the chunk, phase 2 computes and stores: the stores go to
+  // the buffers the loads read, so the compiler would not move a later slot's loads above them.
+  ChunkIn<VARIANT> cur;
+  issue_chunk<VARIANT, TABLE>(chunk_id, descs, chunks, flat, elementwise, cur);
+  finish_chunk<VARIANT, FAST, EDQ>(cur, sc, acc);
   if (EDQ) edq_store_partial<kStepBlock>(acc, partials, chunk_id);
+#endif
 }
 
 // ---------------------------------------------------------------- EDQ reduction tail
@@ -751,6 +809,45 @@ copy_kernel(uint64_t dst, uint64_t src, uint64_t nvec) {
   store_vec(dst, 16 * i, w);
 }
 
+// The step's memory traffic without its arithmetic: every lane loads one 128-bit vector (VEC of them,
+// THREADS * 16 bytes apart) from each of NR buffers and stores NW of them back, write j receiving what read j
+// brought in (in place when the caller passes the same buffer for both, as the step does).  The reads that
+// have no write are folded in through `mask`, which the host passes as zero: the loads stay, the data
+// does not change.  Measures what the memory system gives this mix of streams in a given launch shape.
+constexpr int kMaxMix = 8;
+struct MixArgs {
+  uint64_t rd[kMaxMix], wr[kMaxMix];
+  uint64_t nvec;        // 128-bit vectors per buffer
+  uint32_t mask;
+};
+
+template <int NR, int NW, int THREADS, int VEC>
+__global__ void __launch_bounds__(THREADS) mix_kernel(MixArgs a) {
+  static_assert(NW <= NR && NR <= kMaxMix, "a write needs its read");
+  const uint64_t base = (uint64_t)blockIdx.x * (THREADS * VEC) + threadIdx.x;
+  uint32_t w[VEC][NR][4];
+  static_for<0, VEC>([&](auto vc) {
+    constexpr int v = decltype(vc)::value;
+    const uint64_t i = base + (uint64_t)v * THREADS;
+    if (i < a.nvec) static_for<0, NR>([&](auto rc) { load_vec(a.rd[decltype(rc)::value], 16 * i, w[v][decltype(rc)::value]); });
+  });
+  static_for<0, VEC>([&](auto vc) {
+    constexpr int v = decltype(vc)::value;
+    const uint64_t i = base + (uint64_t)v * THREADS;
+    if (i < a.nvec) {
+      uint32_t extra = 0;
+      static_for<NW, NR>([&](auto rc) { constexpr int r = decltype(rc)::value; extra ^= w[v][r][0] ^ w[v][r][1] ^ w[v][r][2] ^ w[v][r][3]; });
+      extra &= a.mask;
+      static_for<0, NW>([&](auto rc) {
+        constexpr int r = decltype(rc)::value;
+        if (NR > NW) w[v][r][0] ^= extra;
+        store_vec(a.wr[r], 16 * i, w[v][r]);
+      });
+      if (NW == 0 && extra == 0x9e3779b9u) store_vec(a.rd[0], 16 * i, w[v][0]);      // never taken: keeps a read-only launch's loads
+    }
+  });
+}
+
 // ---------------------------------------------------------------- option D (fp32 master weights)
 struct Fp32Desc {
   uint64_t theta, master, m, v, grad;   // pointers as integers
@@ -929,14 +1026,30 @@ struct HostScalars {
   bool fast;
 };
 
+// Workgroups of a step launch over `n_chunks` chunks (also the number of EDQ partials it writes).
+uint32_t step_grid(uint32_t n_chunks) {
+#if MCF_PERSIST
+  static const uint32_t per_cu = [] {                // MCF_WAVES_PER_CU in the environment overrides the built-in figure (for sweeps)
+    const char *e = getenv("MCF_WAVES_PER_CU");
+    const int v = e ? atoi(e) : 0;
+    return (uint32_t)(v > 0 && v <= 64 ? v : MCF_WAVES_PER_CU);
+  }();
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    cus = 256;
+  const uint32_t g = (uint32_t)cus * per_cu;
+  return n_chunks < g ? n_chunks : g;
+#elif MCF_REMAP
+  return (n_chunks + 7) / 8 * 8;
+#else
+  return n_chunks;
+#endif
+}
+
 template <int VARIANT, bool TABLE>
 void launch_step(bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs, const Chunk *chunks,
                  const TensorDesc &flat, const HostScalars &hs, double *partials) {
-#if MCF_REMAP
-  const dim3 g((blocks + 7) / 8 * 8), b(kStepBlock);
-#else
-  const dim3 g(blocks), b(kStepBlock);
-#endif
+  const dim3 g(step_grid(blocks)), b(kStepBlock);
   using SS = StepStreams<VARIANT>;
   if constexpr (SS::kFmt == MCF_COMPONENT_FP16) {          // one first-pass mode
     if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, SS::kLdsEdq, st, descs, chunks, flat, hs.hf, partials, blocks);
@@ -1068,6 +1181,23 @@ int prim_launch(int format, int op, const void *p0, const void *p1, const void *
   if (rc != MCF_OK) return rc;
   MCF_HIP(hipGetLastError());
   return MCF_OK;
+}
+
+template <int NR, int NW, int THREADS>
+void launch_mix_vec(uint32_t vec, uint32_t lds, hipStream_t st, const MixArgs &a) {
+  const uint64_t per = (uint64_t)THREADS * vec;
+  const dim3 g((uint32_t)((a.nvec + per - 1) / per)), b(THREADS);
+  switch (vec) {
+    case 1: hipLaunchKernelGGL((mix_kernel<NR, NW, THREADS, 1>), g, b, lds, st, a); break;
+    case 2: hipLaunchKernelGGL((mix_kernel<NR, NW, THREADS, 2>), g, b, lds, st, a); break;
+    default: hipLaunchKernelGGL((mix_kernel<NR, NW, THREADS, 4>), g, b, lds, st, a); break;
+  }
+}
+
+template <int NR, int NW>
+void launch_mix(uint32_t threads, uint32_t vec, uint32_t lds, hipStream_t st, const MixArgs &a) {
+  if (threads == 64) launch_mix_vec<NR, NW, 64>(vec, lds, st, a);
+  else launch_mix_vec<NR, NW, 256>(vec, lds, st, a);
 }
 
 inline bool known_component(int c) { return c >= MCF_COMPONENT_BF16 && c <= MCF_COMPONENT_FP8_E4M3; }
@@ -1287,7 +1417,12 @@ int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *
   }
   if (edq_dev) {
     // with no chunks the tail sums nothing and writes zeros
-    return launch_edq_tail(plan->d_partials, plan->n_chunks, plan->d_partials + (uint64_t)kEdqVals * plan->n_chunks, edq_dev, st);
+#if MCF_PERSIST
+    const uint64_t n_partials = plan->n_chunks ? step_grid(plan->n_chunks) : 0;      // one per workgroup
+#else
+    const uint64_t n_partials = plan->n_chunks;                                      // one per chunk
+#endif
+    return launch_edq_tail(plan->d_partials, n_partials, plan->d_partials + (uint64_t)kEdqVals * plan->n_chunks, edq_dev, st);
   }
   return MCF_OK;
 }
@@ -1422,6 +1557,43 @@ int mcf_stream_copy(void *dst, const void *src, uint64_t bytes, void *stream) {
   if (blocks > 0x7fffffffull) return MCF_ERR_SIZE;
   hipLaunchKernelGGL(copy_kernel, dim3((uint32_t)blocks), dim3(kStepBlock), MCF_COPY_LDS, (hipStream_t)stream,
                      (uint64_t)(uintptr_t)dst, (uint64_t)(uintptr_t)src, nvec);
+  MCF_HIP(hipGetLastError());
+  return MCF_OK;
+}
+
+int mcf_stream_mix(const void *const *reads, uint32_t n_read, void *const *writes, uint32_t n_write, uint64_t bytes,
+                   uint32_t threads, uint32_t vectors_per_lane, uint32_t groups_per_cu, void *stream) {
+  if (bytes == 0) return MCF_OK;
+  if (!reads || (n_write && !writes)) return MCF_ERR_NULL;
+  if (n_read > (uint32_t)kMaxMix || n_write > n_read) return MCF_ERR_SIZE;
+  if ((threads != 64 && threads != 256) || (vectors_per_lane != 1 && vectors_per_lane != 2 && vectors_per_lane != 4) || groups_per_cu > 128)
+    return MCF_ERR_VARIANT;
+  MixArgs a = {};
+  for (uint32_t i = 0; i < n_read; ++i) {
+    if (!reads[i]) return MCF_ERR_NULL;
+    if (misaligned(reads[i], 16)) return MCF_ERR_ALIGN;
+    a.rd[i] = (uint64_t)(uintptr_t)reads[i];
+  }
+  for (uint32_t i = 0; i < n_write; ++i) {
+    if (!writes[i]) return MCF_ERR_NULL;
+    if (misaligned(writes[i], 16)) return MCF_ERR_ALIGN;
+    a.wr[i] = (uint64_t)(uintptr_t)writes[i];
+  }
+  if (bytes & 15) return MCF_ERR_ALIGN;
+  a.nvec = bytes / 16;
+  a.mask = 0;
+  if ((a.nvec + (uint64_t)threads * vectors_per_lane - 1) / ((uint64_t)threads * vectors_per_lane) > 0x7fffffffull) return MCF_ERR_SIZE;
+  const uint32_t lds = groups_per_cu ? lds_for_groups(groups_per_cu) : 0;
+  hipStream_t st = (hipStream_t)stream;
+  const uint32_t key = n_read * 16 + n_write;
+  switch (key) {
+    case 1 * 16 + 1: launch_mix<1, 1>(threads, vectors_per_lane, lds, st, a); break;      // a copy
+    case 1 * 16 + 0: launch_mix<1, 0>(threads, vectors_per_lane, lds, st, a); break;      // read only
+    case 4 * 16 + 3: launch_mix<4, 3>(threads, vectors_per_lane, lds, st, a); break;      // plain bf16, MCF-SGD
+    case 5 * 16 + 4: launch_mix<5, 4>(threads, vectors_per_lane, lds, st, a); break;      // light, Kahan
+    case 6 * 16 + 5: launch_mix<6, 5>(threads, vectors_per_lane, lds, st, a); break;      // plus
+    default: return MCF_ERR_VARIANT;
+  }
   MCF_HIP(hipGetLastError());
   return MCF_OK;
 }
