@@ -225,6 +225,18 @@ int mcf_edq(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, co
 /* The same reduction over buffers of the given component format. */
 int mcf_edq_component(int component, const void *delta, const void *th0, const void *dth0, const void *th1,
                       const void *dth1, uint64_t n, void *scratch_dev, void *stream, double *edq_dev);
+/* mcf_edq_component for callers that cannot allocate device memory or pass a workspace: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without
+ * scratch_dev, same kernels, same results: the reduction partials live in a fixed array inside the
+ * library's device code (3.2 MB, held by every GPU the library runs on until the process ends), which
+ * bounds n at 2^28 elements (larger: MCF_ERR_SIZE; reduce in pieces, or use mcf_edq_component).  The call
+ * allocates and frees nothing.  Its first call on a device looks up that device's copy of the array (no
+ * allocation either; make that first call outside a capture).  All calls on one GPU share the one array:
+ * calls that overlap in time there, on different streams or from different threads, race on it and give
+ * wrong sums; calls on one stream, or otherwise ordered, are fine, and nothing has to be cleared between
+ * them. */
+int mcf_edq_noalloc(int component, const void *delta, const void *th0, const void *dth0, const void *th1,
+                    const void *dth1, uint64_t n, void *stream, double *edq_dev);
 
 /* ---- option D, the mixed-precision baseline the paper compares against (Sec. 2.1, Table 1):
  * bf16 parameter and gradient, fp32 moments and fp32 master weight; plain fp32 AdamW with the

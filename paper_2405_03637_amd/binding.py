@@ -85,6 +85,7 @@ def lib():
     L.mcf_component_op.argtypes = [_int, _int] + [_vp] * 3 + [_u64, _vp]
     L.mcf_round_f32_to.argtypes = [_int, _vp, _vp, _u64, _vp]
     L.mcf_edq_component.argtypes = [_int] + [_vp] * 5 + [_u64, _vp, _vp, _vp]
+    L.mcf_edq_noalloc.argtypes = [_int] + [_vp] * 5 + [_u64, _vp, _vp]
     L.mcf_edq_scratch_bytes.restype = _u64
     L.mcf_edq_scratch_bytes.argtypes = [_u64]
     L.mcf_edq.argtypes = [_vp] * 5 + [_u64, _vp, _vp, _vp]
@@ -293,6 +294,11 @@ def edq_component(component, delta, th0, dth0, th1, dth1, scratch, out, stream=N
                                    _ptr(scratch), _stream(stream), _ptr(out)), "mcf_edq_component")
 
 
+def edq_noalloc(component, delta, th0, dth0, th1, dth1, out, stream=None, n=None):
+    _check(lib().mcf_edq_noalloc(int(component), _ptr(delta), _ptr(th0), _ptr(dth0), _ptr(th1), _ptr(dth1),
+                                 delta.numel() if n is None else int(n), _stream(stream), _ptr(out)), "mcf_edq_noalloc")
+
+
 def edq_scratch_bytes(n):
     return int(lib().mcf_edq_scratch_bytes(int(n)))
 
@@ -353,6 +359,7 @@ mcf_primitive = primitive
 mcf_component_op = component_op
 mcf_round_f32_to = round_f32_to
 mcf_edq_component = edq_component
+mcf_edq_noalloc = edq_noalloc
 mcf_stream_copy = stream_copy
 mcf_stream_mix = stream_mix
 mcf_status_string = status_string

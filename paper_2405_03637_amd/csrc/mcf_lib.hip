@@ -29,6 +29,7 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -1236,6 +1237,39 @@ int edq_launch(int component, const void *delta, const void *th0, const void *dt
 
 }  // namespace
 
+// Reduction partials of mcf_edq_noalloc: a fixed array in device memory instead of a buffer somebody
+// allocated.  Every GPU the library's code object is loaded on holds its own copy at its own address.
+constexpr uint64_t kNoAllocMaxElems = 1ull << 28;
+constexpr uint64_t edq_partial_doubles(uint64_t n) {        // for 2-byte elements at the worst phase; 1-byte elements need fewer
+  return (uint64_t)kEdqVals * (((n + 7 + 7) / 8 + kBlock - 1) / kBlock + 1 + kStage1Blocks);
+}
+static __device__ __align__(256) double edq_scratch[edq_partial_doubles(kNoAllocMaxElems)];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double *g_scratch_ptr[kMaxDevices];      // device address of edq_scratch per device, resolved on the first call there
+
+// In host code `edq_scratch` is only a handle for the runtime, not an address a kernel could use: the
+// address on the current device comes from hipGetSymbolAddress, once per device.
+int scratch_of_current_device(double **out) {
+  int dev = -1;
+  MCF_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return MCF_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    MCF_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(edq_scratch)));
+    if (!p) return MCF_ERR_HIP;
+    g_scratch_ptr[dev] = (double *)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MCF_OK;
+}
+
+}  // namespace
+
 struct mcf_plan {
   int variant;
   uint32_t n_tensors;
@@ -1599,8 +1633,7 @@ int mcf_stream_mix(const void *const *reads, uint32_t n_read, void *const *write
 }
 
 uint64_t mcf_edq_scratch_bytes(uint64_t n) {
-  const uint64_t blocks = (slots_of(n, 7) + kBlock - 1) / kBlock + 1;
-  return (uint64_t)kEdqVals * (blocks + kStage1Blocks) * sizeof(double);
+  return edq_partial_doubles(n) * sizeof(double);
 }
 
 int mcf_edq_component(int component, const void *delta, const void *th0, const void *dth0, const void *th1,
@@ -1612,6 +1645,22 @@ int mcf_edq_component(int component, const void *delta, const void *th0, const v
   if (!delta || !th0 || !th1 || !scratch_dev) return MCF_ERR_NULL;
   if (misaligned(scratch_dev, 8)) return MCF_ERR_ALIGN;
   return edq_launch(component, delta, th0, dth0, th1, dth1, n, (double *)scratch_dev, (hipStream_t)stream, edq_dev);
+}
+
+int mcf_edq_noalloc(int component, const void *delta, const void *th0, const void *dth0, const void *th1,
+                    const void *dth1, uint64_t n, void *stream, double *edq_dev) {
+  if (!known_component(component)) return MCF_ERR_VARIANT;
+  if (!edq_dev) return MCF_ERR_NULL;
+  if (misaligned(edq_dev, 8)) return MCF_ERR_ALIGN;
+  if (n > kNoAllocMaxElems) return MCF_ERR_SIZE;
+  if (n == 0) return launch_edq_tail(nullptr, 0, nullptr, edq_dev, (hipStream_t)stream);
+  if (!delta || !th0 || !th1) return MCF_ERR_NULL;
+  double *partials = nullptr;
+  const int rc = scratch_of_current_device(&partials);
+  if (rc != MCF_OK) return rc;
+  // Nothing in the array has to start at zero: the first kernel writes one partial for every one of its
+  // workgroups, and the two reduction kernels read exactly those and what they wrote themselves.
+  return edq_launch(component, delta, th0, dth0, th1, dth1, n, partials, (hipStream_t)stream, edq_dev);
 }
 
 int mcf_edq(const uint16_t *delta, const uint16_t *th0, const uint16_t *dth0, const uint16_t *th1,
