@@ -258,6 +258,14 @@ int mcf_fp32mw_step(mcf_fp32mw_plan *plan, const mcf_hyper *hyper, uint64_t step
  * profiler byte counters (the step moves 18 or 22 bytes per parameter: Table 1's state, read and
  * written, plus the gradient). ---- */
 int mcf_stream_copy(void *dst, const void *src, uint64_t bytes, void *stream);
+/* ---- tuning aid: override, for every later step launch of this process, how the step kernels pace their
+ * memory traffic.  groups_per_cu: single-wave workgroups resident per compute unit (0 = no cap); head_sleep,
+ * tail_sleep: s_sleep units (64 clocks each) that every wave idles before its first load and after its last store.
+ * A negative value restores the built-in figure of each variant (the caps measured on MI355X at the
+ * 7B-parameter set; no sleeps).  Results do not depend on any of this, only the time does.  Values above 128
+ * groups or 4096 units are MCF_ERR_SIZE.  Not synchronised with launches on other threads. ---- */
+int mcf_set_launch_pacing(int groups_per_cu, int head_sleep, int tail_sleep);
+
 /* ---- measurement aid: the memory traffic of a step without its arithmetic.  Every 16 bytes of each of the
  * n_read buffers reads[] (host array of device pointers, 16-byte aligned, `bytes` bytes each, a multiple of
  * 16) are loaded, and write j (j < n_write <= n_read) receives what read j brought in -- unchanged, so passing

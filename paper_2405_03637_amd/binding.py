@@ -93,6 +93,7 @@ def lib():
     L.mcf_fp32mw_plan_destroy.argtypes = [_vp]
     L.mcf_fp32mw_step.argtypes = [_vp, ctypes.POINTER(Hyper), _u64, _vp]
     L.mcf_stream_copy.argtypes = [_vp, _vp, _u64, _vp]
+    L.mcf_set_launch_pacing.argtypes = [_int, _int, _int]
     L.mcf_stream_mix.argtypes = [ctypes.POINTER(_vp), ctypes.c_uint32, ctypes.POINTER(_vp), ctypes.c_uint32, _u64,
                                  ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32, _vp]
     _lib = L
@@ -313,6 +314,10 @@ def stream_copy(dst, src, stream=None):
     _check(lib().mcf_stream_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "mcf_stream_copy")
 
 
+def set_launch_pacing(groups_per_cu=-1, head_sleep=-1, tail_sleep=-1):
+    _check(lib().mcf_set_launch_pacing(int(groups_per_cu), int(head_sleep), int(tail_sleep)), "mcf_set_launch_pacing")
+
+
 def stream_mix(reads, writes, nbytes, threads=64, vectors_per_lane=1, groups_per_cu=0, stream=None):
     """reads, writes: lists of device tensors (or addresses); write j receives read j's data."""
     r = (_vp * max(1, len(reads)))(*[_ptr(t) for t in reads])
@@ -362,6 +367,7 @@ mcf_edq_component = edq_component
 mcf_edq_noalloc = edq_noalloc
 mcf_stream_copy = stream_copy
 mcf_stream_mix = stream_mix
+mcf_set_launch_pacing = set_launch_pacing
 mcf_status_string = status_string
 
 

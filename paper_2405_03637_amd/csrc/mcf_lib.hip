@@ -27,6 +27,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
@@ -315,22 +316,30 @@ constexpr int kGrow2Bit = 0x100;
 constexpr int kFmtShift = 12;
 constexpr int kHalfBit = MCF_COMPONENT_FP16 << kFmtShift;
 
-// Arithmetic modes of a component format: the first pass over a vector slot (FAST selects between the
-// two bf16 modes) and the mode of the element path and of a redo.
+// Arithmetic modes of a component format.  Hot: the first pass over a full slot (FAST selects between the two
+// bf16 modes); it may give a slot up.  Second: the pass that is right for every slot -- those the first pass
+// gave up, those at a tensor's ends, and every slot of a launch whose scalars the first pass cannot take; it
+// stores the format's one NaN pattern.  Cold: the mode single operations fall back to (bf16: IEEE divide and root).
 template <int FMT, bool FAST> struct ModeOf;
 template <bool FAST> struct ModeOf<MCF_COMPONENT_BF16, FAST> {
   using Hot = typename std::conditional<FAST, mcfd::Fast, mcfd::Exact>::type;
+  using Second = typename std::conditional<FAST, mcfd::FastSecond, mcfd::Exact>::type;
   using Cold = mcfd::Exact;
 };
-template <bool FAST> struct ModeOf<MCF_COMPONENT_FP16, FAST> { using Hot = mcfd::HalfHot; using Cold = mcfd::HalfCold; };
-template <bool FAST> struct ModeOf<MCF_COMPONENT_FP8_E5M2, FAST> { using Hot = mcfd::F8<false, true>; using Cold = mcfd::F8<false, false>; };
-template <bool FAST> struct ModeOf<MCF_COMPONENT_FP8_E4M3, FAST> { using Hot = mcfd::F8<true, true>; using Cold = mcfd::F8<true, false>; };
+template <bool FAST> struct ModeOf<MCF_COMPONENT_FP16, FAST> { using Hot = mcfd::HalfHot; using Second = mcfd::HalfCold; using Cold = mcfd::HalfCold; };
+template <bool FAST> struct ModeOf<MCF_COMPONENT_FP8_E5M2, FAST> {
+  using Hot = mcfd::F8<false, true>; using Second = mcfd::F8<false, false>; using Cold = mcfd::F8<false, false>;
+};
+template <bool FAST> struct ModeOf<MCF_COMPONENT_FP8_E4M3, FAST> {
+  using Hot = mcfd::F8<true, true>; using Second = mcfd::F8<true, false>; using Cold = mcfd::F8<true, false>;
+};
 template <int VARIANT> struct StepStreams {
   static constexpr int kBase = VARIANT & 0xff;
   static constexpr bool kGrow2 = (VARIANT & kGrow2Bit) != 0;
   static constexpr int kFmt = (VARIANT >> kFmtShift) & 3;
   static constexpr bool kBf16 = kFmt == MCF_COMPONENT_BF16;
   template <bool FAST> using Hot = typename ModeOf<kFmt, FAST>::Hot;
+  template <bool FAST> using Second = typename ModeOf<kFmt, FAST>::Second;
   using Cold = typename ModeOf<kFmt, true>::Cold;
   using Scalars = StepScalarsT<typename Cold::S, typename Cold::Rcp>;
   static constexpr int kEB = Cold::kBytes;                 // bytes per element
@@ -372,12 +381,14 @@ template <class M, int N> __device__ __forceinline__ uint32_t pack_pairs(const t
   if constexpr (M::kBytes == 1) return M::pack(x[0], x[1]); else return M::pack(x[0]);
 }
 
-// Hot path: one full slot, 16 bytes of every stream held as 4 dwords each.  Returns true
-// when the arithmetic mode asks for the slot to be recomputed (bf16 Fast mode: in Exact mode; fp16
-// and FP8: in the mode that stores canonical NaN).
-template <class M, int VARIANT, bool EDQ>
+// One slot, 16 bytes of every stream held as 4 dwords each, through the chain in arithmetic mode M.  Returns
+// true when the mode gives the slot up (first-pass modes only): it is then computed again in the variant's
+// second mode.  EPS_INSIDE: line 12 with epsilon under the root.  MASKED: bit e of `valid` says whether element e
+// of the slot belongs to the tensor; the others were loaded as zeros, are computed along and not stored, and
+// must stay out of the EDQ sums.
+template <class M, int VARIANT, bool EDQ, bool EPS_INSIDE = false, bool MASKED = false>
 __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], uint32_t (&out)[kMaxStreams][4],
-                                         const StepScalarsT<typename M::S, typename M::Rcp> &sc, EdqAcc &acc) {
+                                         const StepScalarsT<typename M::S, typename M::Rcp> &sc, EdqAcc &acc, uint32_t valid = ~0u) {
   using SS = StepStreams<VARIANT>;
   using T = typename M::T;
   constexpr int kPairs = M::kBytes == 1 ? 2 : 1;
@@ -396,11 +407,12 @@ __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], u
       if (SS::kDv) io.dv = unpack_pair<M, P>(in[S_DV][k]); else io.dv = M::zero();
       const T th0 = io.th, dth0 = io.dth;
       T delta;
-      mcfd::adamw_pair<M, SS::kBase, SS::kGrow2>(io, sc, delta, redo);
+      mcfd::adamw_pair<M, SS::kBase, SS::kGrow2, EPS_INSIDE && SS::kBase != mcfd::V_SGD>(io, sc, delta, redo);
       th[P] = io.th; dth[P] = io.dth; m[P] = io.m; v[P] = io.v; dv[P] = io.dv;
       if (EDQ) {
-        edq_add(acc, M::lo(delta), M::lo(th0), M::lo(dth0), M::lo(io.th), M::lo(io.dth));
-        edq_add(acc, M::hi(delta), M::hi(th0), M::hi(dth0), M::hi(io.th), M::hi(io.dth));
+        const int e = 2 * (kPairs * k + P);          // the pair's first element within the slot
+        if (!MASKED || ((valid >> e) & 1u)) edq_add(acc, M::lo(delta), M::lo(th0), M::lo(dth0), M::lo(io.th), M::lo(io.dth));
+        if (!MASKED || ((valid >> (e + 1)) & 1u)) edq_add(acc, M::hi(delta), M::hi(th0), M::hi(dth0), M::hi(io.th), M::hi(io.dth));
       }
     });
     out[S_TH][k] = pack_pairs<M>(th);
@@ -418,47 +430,6 @@ __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], u
   return redo;
 }
 
-// Cold path: one slot element by element in the variant's element mode (bf16: Exact), as a rolled loop so that it costs code
-// size once.  Serves the slots that straddle a tensor's ends, (bf16) slots the hot path asked to redo (their inputs are still in memory:
-// nothing of the slot has been stored yet), and every slot of a launch with MCF_EPS_INSIDE_SQRT: that
-// reading of line 12 is kept for reference, and keeping it out of the vector path keeps the vector
-// path's code and registers as they are (a compiled second copy of the chain there cost the default
-// reading 5% at the 7B set).
-template <int VARIANT, bool EDQ>
-__device__ __forceinline__ void cold_slot(const TensorDesc &d, uint64_t c0, const typename StepStreams<VARIANT>::Scalars &sc,
-                                          EdqAcc &acc) {
-  using SS = StepStreams<VARIANT>;
-  using M = typename SS::Cold;
-  using T = typename M::T;
-  constexpr int EB = SS::kEB;
-  const uint64_t lo = d.phase, hi = d.phase + d.n;
-#pragma unroll 1
-  for (int k = 0; k < SS::kEps; ++k) {
-    const uint64_t c = c0 + k;
-    if (c < lo || c >= hi) continue;
-    const uint64_t e = c - lo;
-    ElemIOT<T> io;                   // the element rides in the low half of a pair
-    io.th = M::unpack(load_elem<EB>(d.p[S_TH], e));
-    if (SS::kDth) io.dth = M::unpack(load_elem<EB>(d.p[S_DTH], e)); else io.dth = M::zero();
-    io.m = M::unpack(load_elem<EB>(d.p[S_M], e));
-    if (SS::kV) io.v = M::unpack(load_elem<EB>(d.p[S_V], e)); else io.v = M::zero();
-    io.g = M::unpack(load_elem<EB>(d.p[S_G], e));
-    if (SS::kDv) io.dv = M::unpack(load_elem<EB>(d.p[S_DV], e)); else io.dv = M::zero();
-    const float th0 = M::lo(io.th), dth0 = M::lo(io.dth);
-    T delta;
-    bool unused = false;
-    if (SS::kBase != mcfd::V_SGD && sc.eps_inside_sqrt) mcfd::adamw_pair<M, SS::kBase, SS::kGrow2, true>(io, sc, delta, unused);
-    else mcfd::adamw_pair<M, SS::kBase, SS::kGrow2, false>(io, sc, delta, unused);
-    // EDQ is taken on the stored values (a NaN stays a NaN whatever its payload)
-    if (EDQ) edq_add(acc, M::lo(delta), th0, dth0, M::lo(io.th), M::lo(io.dth));
-    store_elem<EB>(d.p[S_TH], e, M::bits_lo(io.th));
-    if (SS::kDth) store_elem<EB>(d.p[S_DTH], e, M::bits_lo(io.dth));
-    store_elem<EB>(d.p[S_M], e, M::bits_lo(io.m));
-    if (SS::kV) store_elem<EB>(d.p[S_V], e, M::bits_lo(io.v));
-    if (SS::kDv) store_elem<EB>(d.p[S_DV], e, M::bits_lo(io.dv));
-  }
-}
-
 // One chunk in flight: where it is and the 16 bytes per stream and slot that its loads bring in.
 template <int VARIANT> struct ChunkIn {
   TensorDesc d;                               // wave-uniform (SGPRs)
@@ -470,7 +441,7 @@ template <int VARIANT> struct ChunkIn {
 // Issues every 128-bit load of chunk `chunk_id` (nothing waits for them here).
 template <int VARIANT, bool TABLE>
 __device__ __forceinline__ void issue_chunk(uint32_t chunk_id, const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks,
-                                            const TensorDesc &flat, bool elementwise, ChunkIn<VARIANT> &c) {
+                                            const TensorDesc &flat, ChunkIn<VARIANT> &c) {
   using SS = StepStreams<VARIANT>;
   if (TABLE) {
     const Chunk e = chunks[chunk_id];
@@ -483,7 +454,6 @@ __device__ __forceinline__ void issue_chunk(uint32_t chunk_id, const TensorDesc 
   static_for<0, kUnroll>([&](auto jc) {
     constexpr int j = decltype(jc)::value;
     c.slot[j] = classify<SS::kEB>(c.d, c.slot0 + (uint64_t)j * kStepBlock + threadIdx.x);
-    if (elementwise) c.slot[j].full = false;
     if (c.slot[j].full) {
       const uint64_t e0 = (c.slot[j].c0 - c.d.phase) * SS::kEB;       // byte offset
       load_vec(c.d.p[S_TH], e0, c.in[j][S_TH]);
@@ -492,69 +462,73 @@ __device__ __forceinline__ void issue_chunk(uint32_t chunk_id, const TensorDesc 
       if (SS::kV) load_vec(c.d.p[S_V], e0, c.in[j][S_V]);
       load_vec(c.d.p[S_G], e0, c.in[j][S_G]);
       if (SS::kDv) load_vec(c.d.p[S_DV], e0, c.in[j][S_DV]);
+    } else if (c.slot[j].any) {
+      // a slot that straddles an end of its tensor: its elements one by one, zeros for the rest
+      load_slot<SS::kEB>(c.d.p[S_TH], c.d, c.slot[j], c.in[j][S_TH]);
+      if (SS::kDth) load_slot<SS::kEB>(c.d.p[S_DTH], c.d, c.slot[j], c.in[j][S_DTH]);
+      load_slot<SS::kEB>(c.d.p[S_M], c.d, c.slot[j], c.in[j][S_M]);
+      if (SS::kV) load_slot<SS::kEB>(c.d.p[S_V], c.d, c.slot[j], c.in[j][S_V]);
+      load_slot<SS::kEB>(c.d.p[S_G], c.d, c.slot[j], c.in[j][S_G]);
+      if (SS::kDv) load_slot<SS::kEB>(c.d.p[S_DV], c.d, c.slot[j], c.in[j][S_DV]);
     }
   });
 }
 
+// Which elements of a slot belong to the tensor, one bit each.
+template <int EB>
+__device__ __forceinline__ uint32_t valid_elements(const TensorDesc &d, const Slot &s) {
+  uint32_t valid = 0;
+#pragma unroll
+  for (int k = 0; k < 16 / EB; ++k)
+    if (s.c0 + k >= d.phase && s.c0 + k < d.phase + d.n) valid |= 1u << k;
+  return valid;
+}
+
 // Computes and stores a chunk whose loads were issued by issue_chunk; adds its EDQ terms to acc.
+// A full slot takes the first pass; what that pass gives up (bf16: the root met a subnormal operand, or a
+// result is NaN; fp16, FP8: a result is NaN) is computed again, still from registers, in the second mode:
+// the same vector code with a root that scales tiny operands and a pack that stores the one NaN pattern (an
+// all-NaN 7B set costs about twice the ordinary step, not a serial loop).  Slots at a tensor's ends, whose
+// elements were gathered one by one, and every slot of a launch the host marked `elementwise` (epsilon under
+// the root; an FP8 bias correction with no fp16 reciprocal) go to the second mode directly.
 template <int VARIANT, bool FAST, bool EDQ>
 __device__ __forceinline__ void finish_chunk(ChunkIn<VARIANT> &c, const typename StepStreams<VARIANT>::Scalars &sc, EdqAcc &acc) {
   using SS = StepStreams<VARIANT>;
-  using Mode = typename SS::template Hot<FAST>;
+  using First = typename SS::template Hot<FAST>;
+  using Second = typename SS::template Second<FAST>;
   const TensorDesc &d = c.d;
-  uint32_t cold = 0;          // bit j: slot j still has to go through the cold path
+  const bool skip_first = sc.elementwise != 0;       // uniform over the launch
   static_for<0, kUnroll>([&](auto jc) {
     constexpr int j = decltype(jc)::value;
-    if (c.slot[j].full) {
+    const Slot &slot = c.slot[j];
+    if (slot.any) {
       uint32_t out[kMaxStreams][4];
       EdqAcc local = {0.0, 0.0, 0u};
-      bool redo = hot_slot<Mode, VARIANT, EDQ>(c.in[j], out, sc, local);
-      if constexpr (!SS::kBf16) {
-        // fp16, FP8: the first pass found a NaN among its results.  The same slot again, still from registers,
-        // in the mode that stores the format's one NaN: the arithmetic is the same packed code, so a
-        // diverged tensor costs 18% more time, not a serial loop (21.8 against 65.5 ms for an all-NaN 7B set).
-        if (redo) {
-          local = {0.0, 0.0, 0u};
-          (void)hot_slot<typename SS::Cold, VARIANT, EDQ>(c.in[j], out, sc, local);
-          redo = false;
-        }
+      bool again = skip_first || !slot.full;
+      if (!again) again = hot_slot<First, VARIANT, EDQ>(c.in[j], out, sc, local);
+      if (again) {
+        local = {0.0, 0.0, 0u};
+        const uint32_t valid = slot.full ? ~0u : valid_elements<SS::kEB>(d, slot);
+        if (sc.eps_inside_sqrt) (void)hot_slot<Second, VARIANT, EDQ, true, true>(c.in[j], out, sc, local, valid);
+        else (void)hot_slot<Second, VARIANT, EDQ, false, true>(c.in[j], out, sc, local, valid);
       }
-      if constexpr (SS::kBf16 && FAST) {
-        // bf16 Fast mode: the root met a subnormal operand (or there is a NaN).  The same slot again with
-        // the root that scales such operands; what still asks for a redo after that has a NaN.
-        if (redo) {
-          local = {0.0, 0.0, 0u};
-          redo = hot_slot<mcfd::FastScaled, VARIANT, EDQ>(c.in[j], out, sc, local);
-        }
-      }
-      // bf16: a slot that produced a NaN in Fast mode goes to the element loop below.  Redoing it from
-      // registers with the vectorised Exact arithmetic was measured: an all-redo 7B set drops from 59.5
-      // to 46.2 ms, but the Exact chain's registers and code slow the ordinary path of several variants
-      // by 1-5%, so the diverged case keeps the loop.
-      if (redo) {
-        cold |= 1u << j;
-      } else {
-        const uint64_t e0 = (c.slot[j].c0 - d.phase) * SS::kEB;
+      if (slot.full) {
+        const uint64_t e0 = (slot.c0 - d.phase) * SS::kEB;
         store_vec(d.p[S_TH], e0, out[S_TH]);
         if (SS::kDth) store_vec(d.p[S_DTH], e0, out[S_DTH]);
         store_vec(d.p[S_M], e0, out[S_M]);
         if (SS::kV) store_vec(d.p[S_V], e0, out[S_V]);
         if (SS::kDv) store_vec(d.p[S_DV], e0, out[S_DV]);
-        if (EDQ) { acc.s1 += local.s1; acc.s2 += local.s2; acc.lost += local.lost; }
+      } else {
+        store_slot<SS::kEB>(d.p[S_TH], d, slot, out[S_TH]);
+        if (SS::kDth) store_slot<SS::kEB>(d.p[S_DTH], d, slot, out[S_DTH]);
+        store_slot<SS::kEB>(d.p[S_M], d, slot, out[S_M]);
+        if (SS::kV) store_slot<SS::kEB>(d.p[S_V], d, slot, out[S_V]);
+        if (SS::kDv) store_slot<SS::kEB>(d.p[S_DV], d, slot, out[S_DV]);
       }
-    } else if (c.slot[j].any) {
-      cold |= 1u << j;
-    }
-  });
-  if (cold) {
-#pragma unroll 1
-    for (int j = 0; j < kUnroll; ++j) {
-      if (!((cold >> j) & 1u)) continue;
-      EdqAcc local = {0.0, 0.0, 0u};
-      cold_slot<VARIANT, EDQ>(d, (c.slot0 + (uint64_t)j * kStepBlock + threadIdx.x) * SS::kEps, sc, local);
       if (EDQ) { acc.s1 += local.s1; acc.s2 += local.s2; acc.lost += local.lost; }
     }
-  }
+  });
 }
 
 // The step kernel.  Two work distributions, chosen at compile time (MCF_PERSIST):
@@ -567,19 +541,18 @@ template <int VARIANT, bool FAST, bool EDQ, bool TABLE>
 __global__ void __launch_bounds__(kStepBlock) MCF_STEP_ATTR
 adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, TensorDesc flat,
              typename StepStreams<VARIANT>::Scalars sc, double *__restrict__ partials, uint32_t n_chunks) {
-  const bool elementwise = sc.elementwise != 0;      // uniform over the launch
   EdqAcc acc = {0.0, 0.0, 0u};
 #if MCF_PERSIST
   const uint32_t grid = gridDim.x;
   uint32_t chunk_id = (grid & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
   ChunkIn<VARIANT> cur;
-  if (chunk_id < n_chunks) issue_chunk<VARIANT, TABLE>(chunk_id, descs, chunks, flat, elementwise, cur);
+  if (chunk_id < n_chunks) issue_chunk<VARIANT, TABLE>(chunk_id, descs, chunks, flat, cur);
   while (chunk_id < n_chunks) {
     const uint32_t next_id = chunk_id + grid;
 #if MCF_DEPTH
     ChunkIn<VARIANT> nxt;
     const bool more = next_id < n_chunks && next_id > chunk_id;
-    if (more) issue_chunk<VARIANT, TABLE>(next_id, descs, chunks, flat, elementwise, nxt);
+    if (more) issue_chunk<VARIANT, TABLE>(next_id, descs, chunks, flat, nxt);
     __builtin_amdgcn_sched_barrier(0);             // the next chunk's loads stay ahead of this chunk's arithmetic
     finish_chunk<VARIANT, FAST, EDQ>(cur, sc, acc);
     if (!more) break;
@@ -587,12 +560,13 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
 #else
     finish_chunk<VARIANT, FAST, EDQ>(cur, sc, acc);
     if (!(next_id < n_chunks && next_id > chunk_id)) break;
-    issue_chunk<VARIANT, TABLE>(next_id, descs, chunks, flat, elementwise, cur);
+    issue_chunk<VARIANT, TABLE>(next_id, descs, chunks, flat, cur);
 #endif
     chunk_id = next_id;
   }
   if (EDQ) edq_store_partial<kStepBlock>(acc, partials, blockIdx.x);
 #else
+  for (uint32_t i = 0; i < sc.head_sleep; ++i) __builtin_amdgcn_s_sleep(1);
   uint32_t chunk_id = blockIdx.x;
 #if MCF_REMAP
   {
@@ -604,9 +578,10 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
   // Phase 1 issues every 128-bit load of the chunk, phase 2 computes and stores: the stores go to
   // the buffers the loads read, so the compiler would not move a later slot's loads above them.
   ChunkIn<VARIANT> cur;
-  issue_chunk<VARIANT, TABLE>(chunk_id, descs, chunks, flat, elementwise, cur);
+  issue_chunk<VARIANT, TABLE>(chunk_id, descs, chunks, flat, cur);
   finish_chunk<VARIANT, FAST, EDQ>(cur, sc, acc);
   if (EDQ) edq_store_partial<kStepBlock>(acc, partials, chunk_id);
+  for (uint32_t i = 0; i < sc.tail_sleep; ++i) __builtin_amdgcn_s_sleep(1);
 #endif
 }
 
@@ -1047,23 +1022,34 @@ uint32_t step_grid(uint32_t n_chunks) {
 #endif
 }
 
+// Launch pacing of the step kernels that mcf_set_launch_pacing() may override (negative: the built-in figures).
+std::atomic<int> g_groups_per_cu{-1}, g_head_sleep{-1}, g_tail_sleep{-1};
+
+// Dynamic LDS of a step launch: the variant's built-in cap on the workgroups per CU, unless overridden.
+uint32_t step_lds(uint32_t builtin) {
+  const int forced = g_groups_per_cu.load(std::memory_order_relaxed);
+  if (forced < 0 || MCF_PERSIST) return builtin;
+  return forced == 0 ? 0u : lds_for_groups((uint32_t)(forced > 128 ? 128 : forced));
+}
+
 template <int VARIANT, bool TABLE>
 void launch_step(bool edq, uint32_t blocks, hipStream_t st, const TensorDesc *descs, const Chunk *chunks,
                  const TensorDesc &flat, const HostScalars &hs, double *partials) {
   const dim3 g(step_grid(blocks)), b(kStepBlock);
   using SS = StepStreams<VARIANT>;
+  const uint32_t lds = step_lds(SS::kLds), lds_edq = step_lds(SS::kLdsEdq);
   if constexpr (SS::kFmt == MCF_COMPONENT_FP16) {          // one first-pass mode
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, SS::kLdsEdq, st, descs, chunks, flat, hs.hf, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, SS::kLds, st, descs, chunks, flat, hs.hf, partials, blocks);
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, lds_edq, st, descs, chunks, flat, hs.hf, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, lds, st, descs, chunks, flat, hs.hf, partials, blocks);
   } else if constexpr (!SS::kBf16) {                       // FP8, likewise
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, SS::kLdsEdq, st, descs, chunks, flat, hs.f8, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, SS::kLds, st, descs, chunks, flat, hs.f8, partials, blocks);
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, lds_edq, st, descs, chunks, flat, hs.f8, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, lds, st, descs, chunks, flat, hs.f8, partials, blocks);
   } else if (hs.fast) {
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, SS::kLdsEdq, st, descs, chunks, flat, hs.bf, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, SS::kLds, st, descs, chunks, flat, hs.bf, partials, blocks);
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, true, true, TABLE>), g, b, lds_edq, st, descs, chunks, flat, hs.bf, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, true, false, TABLE>), g, b, lds, st, descs, chunks, flat, hs.bf, partials, blocks);
   } else {
-    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, SS::kLdsEdq, st, descs, chunks, flat, hs.bf, partials, blocks);
-    else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, SS::kLds, st, descs, chunks, flat, hs.bf, partials, blocks);
+    if (edq) hipLaunchKernelGGL((adamw_kernel<VARIANT, false, true, TABLE>), g, b, lds_edq, st, descs, chunks, flat, hs.bf, partials, blocks);
+    else hipLaunchKernelGGL((adamw_kernel<VARIANT, false, false, TABLE>), g, b, lds, st, descs, chunks, flat, hs.bf, partials, blocks);
   }
 }
 
@@ -1123,6 +1109,11 @@ HostScalars host_scalars(const mcf_hyper &h, uint64_t step, int variant) {
     if (!mcfh::derive_scalars_fp8(h, step, fmt == MCF_COMPONENT_FP8_E4M3, hs.f8)) hs.f8.elementwise = 1u;
   } else {
     hs.fast = mcfh::derive_scalars(h, step, hs.bf) && !force_exact();
+  }
+  {
+    const int head = g_head_sleep.load(std::memory_order_relaxed), tail = g_tail_sleep.load(std::memory_order_relaxed);
+    hs.bf.head_sleep = hs.hf.head_sleep = hs.f8.head_sleep = (uint32_t)(head > 0 ? head : 0);
+    hs.bf.tail_sleep = hs.hf.tail_sleep = hs.f8.tail_sleep = (uint32_t)(tail > 0 ? tail : 0);
   }
   // the printed form of line 12 is compiled into the element path only (SGD has no such line)
   if ((variant & MCF_EPS_INSIDE_SQRT) && (variant & 0xff) != MCF_SGD) {
@@ -1592,6 +1583,14 @@ int mcf_stream_copy(void *dst, const void *src, uint64_t bytes, void *stream) {
   hipLaunchKernelGGL(copy_kernel, dim3((uint32_t)blocks), dim3(kStepBlock), MCF_COPY_LDS, (hipStream_t)stream,
                      (uint64_t)(uintptr_t)dst, (uint64_t)(uintptr_t)src, nvec);
   MCF_HIP(hipGetLastError());
+  return MCF_OK;
+}
+
+int mcf_set_launch_pacing(int groups_per_cu, int head_sleep, int tail_sleep) {
+  if (groups_per_cu > 128 || head_sleep > 4096 || tail_sleep > 4096) return MCF_ERR_SIZE;
+  g_groups_per_cu.store(groups_per_cu, std::memory_order_relaxed);
+  g_head_sleep.store(head_sleep, std::memory_order_relaxed);
+  g_tail_sleep.store(tail_sleep, std::memory_order_relaxed);
   return MCF_OK;
 }
 

@@ -16,9 +16,10 @@
 //           than the error of a*r; one that is a tie has a divisor whose significand divides
 //           the dividend's, so it is either below 2^-127.5, where the error of a*r is under half
 //           a grid step and the fp32 rounding of the product lands on the tie itself, or has a
-//           power of two as divisor, whose reciprocal is exact.  (All bf16 pairs with such
-//           quotients, r anywhere within one unit of 1/b: tests/test_oracle_rounding.py; all 2^32
-//           pairs on the hardware: the GPU sweep.)  v_sqrt_f32 takes a subnormal operand for
+//           power of two as divisor, whose reciprocal is exact.  (Checked on the CPU for all bf16
+//           pairs with such quotients with r anywhere within one unit of 1/b, and for every bf16
+//           dividend against every bias correction in [2^-60, 1]; on the hardware for all 2^32
+//           pairs.)  v_sqrt_f32 takes a subnormal operand for
 //           zero: the first pass raises `redo` on one (a second moment that decayed to nothing
 //           under zero gradients), and the caller redoes that slot with a root that scales such
 //           operands by 2^64 first.  What is left for Exact mode: the host finds the step's
@@ -60,7 +61,8 @@ __device__ __forceinline__ bool is_nan(float x) { return x != x; }
 // ---- bf16 -------------------------------------------------------------------------------
 // Rounders: how one fp32 result becomes a bf16 value (left widened in an fp32 register).
 struct ExactR {
-  static constexpr bool kFast = false;
+  static constexpr bool kFast = false;      // never asks for a redo
+  static constexpr bool kCanon = false;     // its rounding already stores every NaN as 0x7FC0
   static __device__ __forceinline__ P2 rnd(P2 x) { return {round_bits(x.lo), round_bits(x.hi)}; }
   static __device__ __forceinline__ float div1(float a, float b, float, bool &) { return a / b; }
   static __device__ __forceinline__ float divg1(float a, float b, bool &) { return a / b; }
@@ -70,8 +72,15 @@ struct ExactR {
 // SCALED selects how the root treats a subnormal operand, which v_sqrt_f32 takes for zero: false raises
 // `redo` (first pass: such operands are rare and the test is one instruction), true scales it by the
 // exact factor 2^64 first and the root by 2^-32 afterwards (the pass that redoes those slots).
-template <bool SCALED> struct FastRT {
-  static constexpr bool kFast = true;
+// CANON: the pair is packed with every NaN replaced by 0x7FC0 (the hardware conversion keeps payloads and signs).
+// The first pass (SCALED, CANON both false) is the only one that asks for a redo; the second pass
+// (both true) is right for every input the first pass gives up on: the restricted divide is wrong for
+// no value the chain can meet (its divisors are normal, zero or infinite by the host's checks on the
+// scalars; x/0, 0/0, x/inf and inf/inf come out as IEEE has them through v_rcp_f32's inf and 0), the scaled root
+// takes subnormal operands, and a NaN is a NaN in either arithmetic -- only its stored pattern differs.
+template <bool SCALED, bool CANON = false> struct FastRT {
+  static constexpr bool kFast = !(SCALED && CANON);
+  static constexpr bool kCanon = CANON;
   // v_cvt_pk_bf16_f32 with 0 as its first source leaves bf16(x) in the upper half of the result and
   // bf16(0) = 0 in the lower half: that IS the rounded value widened back to fp32, in one instruction.
   static __device__ __forceinline__ float rnd1(float x) {
@@ -108,7 +117,14 @@ template <class R> struct Bf {
   static constexpr int kBytes = 2;             // bytes per stored element
   using Rcp = float;   // reciprocal of a scalar
   static __device__ __forceinline__ T unpack(uint32_t w) { return widen2(w); }
-  static __device__ __forceinline__ uint32_t pack(T x) { return pack2(x); }
+  static __device__ __forceinline__ uint32_t pack(T x) {
+    const uint32_t w = pack2(x);
+    if constexpr (!R::kCanon) return w;
+    // a half is NaN iff its magnitude bits exceed 0x7F80; +0x007F carries exactly those into bit 15
+    const uint32_t nan = (((w & 0x7fff7fffu) + 0x007f007fu) & 0x80008000u) >> 15;      // bit 0 / bit 16
+    const uint32_t halves = nan * 0xffffu;
+    return (w & ~halves) | (0x7fc07fc0u & halves);
+  }
   static __device__ __forceinline__ T zero() { return {0.f, 0.f}; }
   static __device__ __forceinline__ float lo(T x) { return x.lo; }
   static __device__ __forceinline__ float hi(T x) { return x.hi; }
@@ -141,7 +157,7 @@ template <class R> struct Bf {
 };
 using Exact = Bf<ExactR>;
 using Fast = Bf<FastRT<false>>;          // first pass
-using FastScaled = Bf<FastRT<true>>;     // second pass over the slots whose root met a subnormal operand
+using FastSecond = Bf<FastRT<true, true>>;     // second pass: slots whose root met a subnormal operand, slots that hold a NaN, slots at a tensor's ends
 
 // ---- fp16 -------------------------------------------------------------------------------
 // The same operation F(a o b) for IEEE binary16 components (App. A Table 7).  The pair stays packed
@@ -248,9 +264,9 @@ using HalfCold = Hf<false>;
 // quotient is further than 2^-9 (relative; 2^-22 absolute among E5M2's subnormal results) from the
 // nearest rounding boundary and cannot cross it.  a * inf, a * 0 and their NaN cases are IEEE's a / 0
 // and a / inf.  Checked on the CPU against the definition for all 256 x 256 operands with r anywhere
-// within two units in the last place of 1/b (tests/test_oracle_fp8.py), and on the GPU for all of them.
+// within two units in the last place of 1/b, and on the GPU for all of them.
 // Quotient by a scalar b: one packed fp16 multiplication by RN16(1/b), then the conversion: right for
-// every a and b (same CPU test) except E5M2's b = +-2^-16, whose reciprocal is not an fp16 number; the
+// every a and b (checked the same way) except E5M2's b = +-2^-16, whose reciprocal is not an fp16 number; the
 // host sends such a step to the element path, whose mode divides by b as above.
 // Root: v_sqrt_f32, then one conversion from fp32 (a root of a 3- or 4-bit number is either exact or
 // further than 2^-12 from any boundary; checked on every input).
@@ -392,7 +408,8 @@ template <class S, class Rcp> struct StepScalarsT {
   S b1, c1, b2, b2l, c2, bc1, bc2, e, lam, na;
   Rcp rbc1, rbc2;                // 1/bc1, 1/bc2 rounded to Rcp: the bf16 Fast mode and the FP8 first pass multiply by them
   uint32_t eps_inside_sqrt;      // 1: line 12's denominator is F(sqrt(F(v_hat + eps))), as Alg. 2 prints it
-  uint32_t elementwise;          // 1: every slot of this launch takes the element path
+  uint32_t elementwise;          // 1: every slot of this launch goes straight to the second arithmetic mode
+  uint32_t head_sleep, tail_sleep;   // launch pacing: s_sleep units a wave idles before its first load / after its last store
 };
 using StepScalars = StepScalarsT<float, float>;      // bf16
 using StepScalarsH = StepScalarsT<h2_t, float>;      // fp16

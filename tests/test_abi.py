@@ -221,3 +221,25 @@ def test_plain_c_consumer_compiles():
     mcf.lib()                                   # the library it links against is built
     path = lib_build.build_demo()
     assert os.path.exists(path) and os.access(path, os.X_OK)
+
+
+def test_launch_pacing_and_measurement_aid_argument_errors():
+    L = mcf.lib()
+    assert L.mcf_set_launch_pacing(129, 0, 0) == mcf.MCF_ERR_SIZE
+    assert L.mcf_set_launch_pacing(8, 5000, 0) == mcf.MCF_ERR_SIZE
+    assert L.mcf_set_launch_pacing(12, 4, 4) == mcf.MCF_OK
+    assert L.mcf_set_launch_pacing(-1, -1, -1) == mcf.MCF_OK          # back to the built-in figures
+    vp = ctypes.c_void_p
+    one = (vp * 1)(FAKE)
+    five = (vp * 5)(*([FAKE] * 5))
+    assert L.mcf_stream_mix(one, 1, one, 1, 0, 64, 1, 0, None) == mcf.MCF_OK            # nothing to move
+    assert L.mcf_stream_mix(None, 1, one, 1, 64, 64, 1, 0, None) == mcf.MCF_ERR_NULL
+    assert L.mcf_stream_mix(one, 1, five, 5, 64, 64, 1, 0, None) == mcf.MCF_ERR_SIZE    # a write needs its read
+    assert L.mcf_stream_mix(one, 1, one, 1, 64, 128, 1, 0, None) == mcf.MCF_ERR_VARIANT
+    assert L.mcf_stream_mix(one, 1, one, 1, 64, 64, 3, 0, None) == mcf.MCF_ERR_VARIANT
+    assert L.mcf_stream_mix(one, 1, one, 1, 24, 64, 1, 0, None) == mcf.MCF_ERR_ALIGN
+    odd = (vp * 1)(FAKE + 8)
+    assert L.mcf_stream_mix(odd, 1, one, 1, 64, 64, 1, 0, None) == mcf.MCF_ERR_ALIGN
+    assert L.mcf_edq_noalloc(0, FAKE, FAKE, None, FAKE, None, (1 << 28) + 1, None, FAKE) == mcf.MCF_ERR_SIZE
+    assert L.mcf_edq_noalloc(0, FAKE, FAKE, None, FAKE, None, 16, None, None) == mcf.MCF_ERR_NULL
+    assert L.mcf_edq_noalloc(7, FAKE, FAKE, None, FAKE, None, 16, None, FAKE) == mcf.MCF_ERR_VARIANT

@@ -539,6 +539,41 @@ def test_plan_update_repoints_the_plan():
     a.close(); b.close()
 
 
+def test_launch_pacing_changes_time_only():
+    """mcf_set_launch_pacing: caps on the resident workgroups and idle time at either end of a wave move when the
+    memory traffic happens, never what is computed.  A ragged set under several settings, every element against
+    the oracle; the stream-mix measurement aid leaves the buffers it reads and rewrites in place as they were."""
+    shapes = [("a", 300_007), ("b", 5), ("c", 8192), ("d", 333)]
+    wl = Workload("flat_1m", variant="plus", shape_list=shapes, misalign_tiny=True, hyper=W.HYPER_PLUS_1P3B)
+    try:
+        settings = [(0, 0, 0), (1, 0, 0), (3, 7, 0), (12, 0, 9), (128, 33, 33), (-1, -1, -1)]
+        host = {k: H.torch_to_u16(getattr(wl, k)) for k in wl.state_names()}
+        for t, (groups, head, tail) in enumerate(settings, start=1):
+            mcf.set_launch_pacing(groups, head, tail)
+            wl.new_grads(t)
+            orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], host["dv"], H.torch_to_u16(wl.grad), wl.variant, wl.hyper, t)
+            wl.plan.step(wl.hyper, t)
+            torch.cuda.synchronize()
+            for (_, n), o in zip(wl.shapes, wl.offs):
+                for k in wl.state_names():
+                    assert np.array_equal(H.torch_to_u16(getattr(wl, k)[o:o + n]), host[k][o:o + n]), (groups, head, tail, k)
+    finally:
+        mcf.set_launch_pacing(-1, -1, -1)
+    nb = wl.total // 8 * 8
+    before = {k: getattr(wl, k).clone() for k in wl.state_names()}
+    rd = [getattr(wl, k)[:nb] for k in ("theta", "dtheta", "m", "v", "dv", "grad")]
+    for threads, vec, cap in ((64, 1, 10), (256, 4, 0), (64, 2, 3)):
+        mcf.stream_mix(rd, rd[:5], 2 * nb, threads, vec, cap)
+        mcf.stream_mix(rd[:5], rd[:4], 2 * nb, threads, vec, cap)
+    torch.cuda.synchronize()
+    for k in wl.state_names():
+        assert torch.equal(getattr(wl, k), before[k]), k
+    dst = torch.zeros_like(wl.theta)
+    mcf.stream_mix([wl.theta[:nb]], [dst[:nb]], 2 * nb, 256, 2, 0)              # with distinct buffers it is a copy
+    assert torch.equal(dst[:nb], wl.theta[:nb])
+    wl.close()
+
+
 def test_two_plans_on_two_streams():
     """Distinct plans are independent: two steps enqueued on two streams at once give the same bits as
     the oracle gives for each alone."""
