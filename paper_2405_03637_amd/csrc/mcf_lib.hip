@@ -347,29 +347,33 @@ template <int VARIANT> struct StepStreams {
   static constexpr bool kDth = kBase != mcfd::V_BF16;      // second component of theta / Kahan variable
   static constexpr bool kDv = kBase == mcfd::V_PLUS;       // second component of v
   static constexpr bool kV = kBase != mcfd::V_SGD;         // second moment
-  // Occupancy cap in workgroups per CU, from sweeps of 8..32 at the 7B-parameter set: the 9-stream
-  // kernels (light, Kahan, both formats, either Grow) are fastest at 10 (light 18.53 ms against 18.75 at 9
-  // and 18.79 at 11); the 11-stream plus at 9 with bf16 components (23.08 ms; 23.20 at 10, 23.37 at 11,
-  // 24.05 at 8) and at 11 with fp16 components or Grow on TwoSum (fp16 23.11 against 23.26 at 10 and 24.2
-  // at 9); the 7-stream plain variant, whose divide and root have less memory time to hide behind, at 12
-  // (14.25 ms against 14.94 at 10); the 7-stream SGD at 11 (14.19 against 14.27 at 10).  The optimum
-  // moves with the kernel's instruction schedule, so it is re-swept when the arithmetic changes.
-  // With the fp64 EDQ sums fused in there is more
-  // arithmetic to hide and more registers in use: light, Kahan and plus 12 (light 18.76 ms against 19.13
-  // at 14 and 19.30 at 11; plus 23.3 against 24.2 at 14, in both 16-bit formats), fp16 light, SGD and the
-  // TwoSum flavours 14 (SGD 14.32 against 15.15 at 12), the plain variant 16.
+  // Occupancy cap in workgroups per CU, from sweeps of 8..28 at the 7B-parameter set, all settings of a
+  // kernel timed in one process on the same arenas (two processes differ by more than two neighbouring caps
+  // do: where the allocator puts 80 GB matters at the 1-3% level).  ms per step, best cap first:
+  //   light 10: 18.56 (11: 18.75, 9: 18.94, 12: 18.92)       Kahan 10: 18.55 (9: 18.75, 11: 18.82)
+  //   plus   9: 23.12 (10: 23.13, 11: 23.30, 12: 23.53)      plus, fp16 components 9: 22.93 (8: 23.15, 10: 23.23)
+  //   plain bf16 12: 14.23 (11: 14.41, 14: 14.64)            SGD 11: 14.20 (12: 14.32, 10: 14.43)
+  //   light on TwoSum 11: 18.64 (10: 18.68, 12: 18.89)       plus on TwoSum 12: 24.14 (13/14: 24.24, 11: 24.27, 10: 24.4)
+  //   light, fp16 components 10: 18.55 (11: 18.65, 12: 18.89)
+  // The plain variant and SGD have less memory time per wave to hide their divide and root behind and take
+  // more waves.  The optimum moves with a kernel's instruction schedule, so the table is re-measured when the
+  // arithmetic or the kernel's structure changes (mcf_set_launch_pacing does that without rebuilding).
+  // With the fp64 EDQ sums fused in there is more arithmetic per wave: light 16: 18.80 (18: 19.46, 13: 19.38,
+  // no cap: 19.94); plus 16: 23.58 (18: 23.72, 14: 24.38); Kahan 13-16: 18.95; plain bf16 18: 14.57 (20: 14.78,
+  // 16: 14.97); SGD 18: 14.29 (16: 14.52, 20: 14.89); light on TwoSum 16-18: 19.55; plus on TwoSum 16 and up:
+  // 25.5-25.6; light with fp16 components 18: 19.62 (16: 19.67); plus with fp16 components 16: 23.60.
   // The FP8 kernels move half the bytes with about the same arithmetic (a conversion to and from the
-  // 8-bit format around every operation): their vector-ALU time is level with their HBM time and they run
-  // uncapped (light E5M2, 7B set: 10.5 ms uncapped, 10.7-10.9 at 12 to 24 groups per CU).
+  // 8-bit format around every operation): they are bound by vector-ALU issue and run uncapped (light E5M2,
+  // 7B set: 10.5 ms uncapped, 10.7-10.9 at 12 to 24 groups per CU).
 #ifdef MCF_STEP_LDS
   static constexpr uint32_t kLds = MCF_STEP_LDS;
 #else
-  static constexpr int kGroups = kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? (kBf16 && !kGrow2 ? 9 : 11)
+  static constexpr int kGroups = kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? (kGrow2 ? 12 : 9)
                                  : kBase == mcfd::V_SGD ? 11 : 10;
   static constexpr uint32_t kLds = (kEB == 1 || MCF_PERSIST) ? 0 : lds_for_groups(kGroups);
 #endif
-  static constexpr int kEdqGroups = kBase == mcfd::V_BF16 ? 16 : (kGrow2 || kBase == mcfd::V_SGD) ? 14
-                                    : (kBase == mcfd::V_PLUS || kBf16) ? 12 : 14;
+  static constexpr int kEdqGroups = (kBase == mcfd::V_BF16 || kBase == mcfd::V_SGD || (kBase == mcfd::V_LIGHT && !kBf16 && !kGrow2)) ? 18
+                                    : kBase == mcfd::V_KAHAN ? 14 : 16;
   static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : (kEB == 1 || MCF_PERSIST) ? 0 : lds_for_groups(kEdqGroups);
 };
 
@@ -532,11 +536,26 @@ __device__ __forceinline__ void finish_chunk(ChunkIn<VARIANT> &c, const typename
 }
 
 // The step kernel.  Two work distributions, chosen at compile time (MCF_PERSIST):
-//   0  one chunk per single-wave workgroup, the grid covers the chunk table;
+//   0  one chunk per single-wave workgroup, the grid covers the chunk table (the default);
 //   1  a fixed grid of single-wave workgroups (a few per CU), each walking the chunk table with the grid as
 //      its stride and, with MCF_DEPTH 1, issuing the loads of its next chunk before it computes the current
 //      one.  The eight XCDs (workgroups are dealt to them round-robin) each take a contiguous eighth of
 //      every grid-sized stretch of the table, so a line of the table is fetched by one L2 only.
+// Measured on MI355X, same process and arenas (ms per step; the default shape first):
+//   7B set, light          19.19 | persistent, k workgroups per CU = 4 / 6 / 8 / 10 / 12 / 16:
+//                                  depth 0: 26.6 / 23.4 / 24.2 / 24.9 / 24.9 / 25.4    depth 1: 29.1 / 24.5 / 23.7 / 24.7 / 24.8 / 26.8
+//                                  depth 1, two slots per lane: 25.4 / 24.9 / 24.7 / 27.5 / 24.8 / 24.2;  depth 0, four slots: 27.9 ... 24.1
+//   7B set, plus           24.00 | 29.4 - 34.4 over the same grid of settings
+//   7B set, light FP8 E5M2 10.31 | 12.5 - 18.6      plus FP8 E5M2 14.53 | 16.8 - 24.6
+//   64Mi stress set, plus   0.302 | 0.307 - 0.382     GPT-2-125M set, light 0.373 | 0.384 - 0.532
+// (that build of the default shape was 3% off its best cap; the comparison does not hinge on it).  The fixed grid loses
+// everywhere, by a quarter at the 7B set, and issuing loads a chunk ahead does not help it.  Two reasons.  A static
+// stride gives every wave the same amount of work, so the launch ends with its slowest wave (k = 6 and 10, which
+// cannot spread evenly over a CU's four SIMDs, stand out), while the hardware dispatcher hands the next chunk
+// to whichever CU has room.  And that dispatcher is an in-order ticket counter: the chunks in flight at any
+// time are neighbours in every stream, which keeps the DRAM pages in use few; persistent waves drift apart.
+// Making the ticket explicit (an atomic counter) would cost 13 million atomics on one address per step to
+// rebuild what the hardware does for nothing.
 template <int VARIANT, bool FAST, bool EDQ, bool TABLE>
 __global__ void __launch_bounds__(kStepBlock) MCF_STEP_ATTR
 adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, TensorDesc flat,
@@ -568,10 +587,18 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
 #else
   for (uint32_t i = 0; i < sc.head_sleep; ++i) __builtin_amdgcn_s_sleep(1);
   uint32_t chunk_id = blockIdx.x;
-#if MCF_REMAP
+#if MCF_REMAP == 1
   {
     const uint32_t per = gridDim.x / 8;            // the grid is rounded up to a multiple of 8
     chunk_id = (blockIdx.x % 8) * per + blockIdx.x / 8;
+    if (chunk_id >= n_chunks) return;
+  }
+#elif MCF_REMAP == 2
+  {
+    // within every run of 128 workgroups, XCD x (workgroups are dealt round-robin) takes chunks 16x .. 16x+15:
+    // one 128-byte line of the chunk table per XCD instead of every line in all eight L2s
+    const uint32_t b = blockIdx.x;
+    chunk_id = (b & ~127u) | ((b & 7u) << 4) | ((b >> 3) & 15u);
     if (chunk_id >= n_chunks) return;
   }
 #endif
@@ -1015,8 +1042,10 @@ uint32_t step_grid(uint32_t n_chunks) {
     cus = 256;
   const uint32_t g = (uint32_t)cus * per_cu;
   return n_chunks < g ? n_chunks : g;
-#elif MCF_REMAP
+#elif MCF_REMAP == 1
   return (n_chunks + 7) / 8 * 8;
+#elif MCF_REMAP == 2
+  return (n_chunks + 127) / 128 * 128;
 #else
   return n_chunks;
 #endif
