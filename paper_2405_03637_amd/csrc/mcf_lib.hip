@@ -193,16 +193,23 @@ __device__ __forceinline__ void load_slot(uint64_t p, const TensorDesc &d, const
   if (s.full) {
     load_vec(p, (s.c0 - d.phase) * EB, w);
   } else {
+    // Every element of the slot is loaded without a branch -- those outside the tensor from element 0, which always
+    // exists, and then zeroed -- so that all loads of the slot are in flight together (one memory latency, not sixteen).
     constexpr int kPer = 4 / EB;        // elements per dword
     const uint64_t lo = d.phase, hi = d.phase + d.n;
+    uint32_t e[16 / EB];
+#pragma unroll
+    for (int k = 0; k < 16 / EB; ++k) {
+      const uint64_t c = s.c0 + k;
+      const bool inside = c >= lo && c < hi;
+      e[k] = load_elem<EB>(p, inside ? c - lo : 0);
+      e[k] = inside ? e[k] : 0u;
+    }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       uint32_t word = 0;
 #pragma unroll
-      for (int j = 0; j < kPer; ++j) {
-        const uint64_t c = s.c0 + kPer * k + j;
-        if (c >= lo && c < hi) word |= load_elem<EB>(p, c - lo) << (8 * EB * j);
-      }
+      for (int j = 0; j < kPer; ++j) word |= e[kPer * k + j] << (8 * EB * j);
       w[k] = word;
     }
   }
@@ -351,7 +358,9 @@ template <int VARIANT> struct StepStreams {
   // kernel timed in one process on the same arenas (two processes differ by more than two neighbouring caps
   // do: where the allocator puts 80 GB matters at the 1-3% level).  ms per step, best cap first:
   //   light 10: 18.56 (11: 18.75, 9: 18.94, 12: 18.92)       Kahan 10: 18.55 (9: 18.75, 11: 18.82)
-  //   plus   9: 23.12 (10: 23.13, 11: 23.30, 12: 23.53)      plus, fp16 components 9: 22.93 (8: 23.15, 10: 23.23)
+  //   plus  10: 23.13 (9: 23.12, 11: 23.30, 12: 23.53)       plus, fp16 components 9: 22.93 (8: 23.15, 10: 23.23)
+  //     (smaller sets settle it for plus: GPT-1.3B 4.50 ms at 10, 4.52 at 9; GPT-2-125M 0.423 against 0.433; the 64Mi
+  //      stress set with its 4096 tiny tensors 0.243 against 0.252, and 0.240 at 11 or 12)
   //   plain bf16 12: 14.23 (11: 14.41, 14: 14.64)            SGD 11: 14.20 (12: 14.32, 10: 14.43)
   //   light on TwoSum 11: 18.64 (10: 18.68, 12: 18.89)       plus on TwoSum 12: 24.14 (13/14: 24.24, 11: 24.27, 10: 24.4)
   //   light, fp16 components 10: 18.55 (11: 18.65, 12: 18.89)
@@ -368,7 +377,7 @@ template <int VARIANT> struct StepStreams {
 #ifdef MCF_STEP_LDS
   static constexpr uint32_t kLds = MCF_STEP_LDS;
 #else
-  static constexpr int kGroups = kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? (kGrow2 ? 12 : 9)
+  static constexpr int kGroups = kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? (kGrow2 ? 12 : kBf16 ? 10 : 9)
                                  : kBase == mcfd::V_SGD ? 11 : 10;
   static constexpr uint32_t kLds = (kEB == 1 || MCF_PERSIST) ? 0 : lds_for_groups(kGroups);
 #endif
