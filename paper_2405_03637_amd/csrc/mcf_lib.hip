@@ -5,7 +5,8 @@
 // slot is one 128-bit access per stream whatever the tensor's own alignment and every
 // wave's 1 KiB run covers whole cache lines (counting from the 16-byte boundary instead, waves of
 // neighbouring workgroups share lines: a set of tensors at odd offsets ran at 5.2 instead of 5.8 TB/s); the slots
-// that straddle the ends of the tensor are handled element by element.  A CHUNK is
+// that straddle the ends of the tensor are gathered and scattered element by element (and computed by the same
+// vector arithmetic as the others).  A CHUNK is
 // kStepBlock*kUnroll consecutive slots of one tensor, done by one workgroup; lane l takes
 // slots l, l+kStepBlock, ... so each wave's access is one contiguous 1 KiB run per stream.
 // The chunk table {tensor, first slot} and the tensor descriptors live in device memory

@@ -20,10 +20,12 @@
 //           pairs with such quotients with r anywhere within one unit of 1/b, and for every bf16
 //           dividend against every bias correction in [2^-60, 1]; on the hardware for all 2^32
 //           pairs.)  v_sqrt_f32 takes a subnormal operand for
-//           zero: the first pass raises `redo` on one (a second moment that decayed to nothing
-//           under zero gradients), and the caller redoes that slot with a root that scales such
-//           operands by 2^64 first.  What is left for Exact mode: the host finds the step's
-//           scalars outside the ranges above, or a pair produces a NaN, which also raises `redo`.
+//           zero, and the hardware conversion keeps a NaN's payload where 0x7FC0 is to be stored: the first
+//           pass over a slot raises `redo` on either (a second moment that decayed to nothing under zero
+//           gradients; any NaN), and the caller computes that slot again in the second-pass flavour of this
+//           mode, whose root scales tiny operands by 2^64 and whose pack stores the one NaN pattern.  What is
+//           left for Exact mode: launches whose scalars the host finds outside the ranges above, and the
+//           fallback of the single-operation primitives.
 // The same chains run over three more component formats (App. A Table 7), each with a first-pass mode
 // and a mode that stores the format's one NaN: fp16 in packed half arithmetic (Hf), and FP8 E5M2 and
 // E4M3 through the hardware conversions (F8).  Every mode offers the same static interface (T, S,
