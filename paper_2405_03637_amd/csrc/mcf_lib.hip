@@ -98,7 +98,7 @@ constexpr int kStepBlock = MCF_BLOCK;
 constexpr int kUnroll = MCF_UNROLL;
 constexpr uint32_t kSlotsPerChunk = kStepBlock * kUnroll;
 constexpr int kBlock = 256;          // threads per workgroup of the primitives and reduction tails
-constexpr uint64_t kMaxTensorElems = (1ull << 35) - 128;   // keeps a tensor's slot count, phase included, below 2^32
+constexpr uint64_t kMaxTensorElems = (1ull << 35) - (MCF_CHUNK_ALIGN > 128 ? MCF_CHUNK_ALIGN : 128);   // keeps a tensor's slot count, phase included, below 2^32
 constexpr int kMaxStreams = 6;
 
 // Streams of the Collage step, in descriptor order.

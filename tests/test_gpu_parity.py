@@ -539,6 +539,41 @@ def test_plan_update_repoints_the_plan():
     a.close(); b.close()
 
 
+def test_plan_update_in_bursts_without_synchronising():
+    """mcf_plan_update is asynchronous: many updates and steps enqueued back to back, the gradients alternating
+    between two buffers (as a framework that double-buffers them would), with no host synchronisation until the
+    end.  Every step must have seen the table that was current when it was enqueued."""
+    shapes = [("a", 200_003), ("b", 5), ("c", 8192)]
+    wl = Workload("flat_1m", variant="light", shape_list=shapes, misalign_tiny=True)
+    other = torch.zeros_like(wl.grad)
+    grads = [wl.grad, other]
+    def tensors(g):
+        return [(wl.theta[o:o + n], wl.dtheta[o:o + n], wl.m[o:o + n], wl.v[o:o + n], None, g[o:o + n])
+                for (_, n), o in zip(wl.shapes, wl.offs)]
+    host = {k: H.torch_to_u16(getattr(wl, k)) for k in wl.state_names()}
+    steps = 24
+    host_grads = []
+    for t in range(1, steps + 1):                     # draw every gradient first: nothing below waits for the device
+        wl.new_grads(t)
+        host_grads.append(H.torch_to_u16(wl.grad))
+    dev_grads = [H.u16_to_torch(g, DEV) for g in host_grads]
+    torch.cuda.synchronize()
+    for t in range(1, steps + 1):
+        g = grads[t & 1]
+        g.copy_(dev_grads[t - 1], non_blocking=True)  # stream-ordered, like everything else here
+        wl.plan.update(tensors(g))
+        if t % 5 == 0:
+            wl.plan.update(tensors(g))                # two updates in a row: the second reuses the first one's staging slot early
+        wl.plan.step(wl.hyper, t)
+    for t in range(1, steps + 1):
+        orc.adamw_step(host["theta"], host["dtheta"], host["m"], host["v"], None, host_grads[t - 1], wl.variant, wl.hyper, t)
+    torch.cuda.synchronize()
+    for (_, n), o in zip(wl.shapes, wl.offs):
+        for k in wl.state_names():
+            assert np.array_equal(H.torch_to_u16(getattr(wl, k)[o:o + n]), host[k][o:o + n]), k
+    wl.close()
+
+
 def test_launch_pacing_changes_time_only():
     """mcf_set_launch_pacing: caps on the resident workgroups and idle time at either end of a wave move when the
     memory traffic happens, never what is computed.  A ragged set under several settings, every element against
