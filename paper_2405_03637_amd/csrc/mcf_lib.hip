@@ -435,9 +435,10 @@ __device__ __forceinline__ bool hot_slot(const uint32_t (&in)[kMaxStreams][4], u
     if (SS::kV) out[S_V][k] = pack_pairs<M>(v);
     if (SS::kDv) out[S_DV][k] = pack_pairs<M>(dv);
     if constexpr (M::kFast && M::kNanOnWords) {
-      // any NaN produced or consumed by the chain reaches theta' or dtheta' (or dv')
-      redo |= M::word_has_nan(out[S_TH][k]);
-      if (SS::kDth) redo |= M::word_has_nan(out[S_DTH][k]);
+      // Any NaN produced or consumed by the chain reaches theta', and a NaN in theta' makes the second component NaN
+      // as well (it is computed from theta' - u), so where there is a second component that is the one to look at:
+      // it also catches the NaN that inf - inf leaves there when theta' itself is an infinity.  Likewise for (v', dv').
+      if (SS::kDth) redo |= M::word_has_nan(out[S_DTH][k]); else redo |= M::word_has_nan(out[S_TH][k]);
       if (SS::kDv) redo |= M::word_has_nan(out[S_DV][k]);
     }
   }
