@@ -226,7 +226,7 @@ def main():
             extras["copy_GBps"] = 4 * nb * 10 / s / 1e9
             # (b) the same copy in other launch shapes and through the runtime's own device-to-device copy
             shapes_tried = {}
-            for threads, vec, cap in ((64, 1, 0), (64, 2, 0), (64, 4, 0), (256, 1, 0), (256, 2, 0), (256, 4, 0), (64, 1, 16), (64, 2, 16)):
+            for threads, vec, cap in ((64, 1, 0), (64, 2, 0), (64, 4, 0), (256, 1, 0), (256, 2, 0), (256, 4, 0), (64, 1, 20), (256, 1, 5)):
                 _, s = time_steps(lambda t: mcf.stream_mix([src[:nb]], [dst[:nb]], 2 * nb, threads, vec, cap), 6, 2)
                 shapes_tried[f"{threads}x{vec}" + (f"/cap{cap}" if cap else "")] = round(4 * nb * 6 / s / 1e9, 1)
             extras["copy_shapes_GBps"] = shapes_tried
@@ -237,7 +237,7 @@ def main():
             # (c) the step's own mix of streams with no arithmetic: 5 arenas read, 4 of them written back in place
             rd = [st[k][:nb] for k in ("theta", "dtheta", "m", "v", "grad")]
             mix_tried = {}
-            for threads, vec, cap in ((64, 1, 10), (64, 1, 12), (64, 1, 16), (64, 1, 0), (64, 2, 8), (64, 2, 0), (256, 1, 0), (256, 2, 0)):
+            for threads, vec, cap in ((64, 1, 6), (64, 1, 8), (64, 1, 10), (64, 1, 12), (64, 1, 0), (64, 2, 4), (256, 1, 1), (256, 2, 0)):
                 _, s = time_steps(lambda t: mcf.stream_mix(rd, rd[:4], 2 * nb, threads, vec, cap), 5, 2)
                 mix_tried[f"{threads}x{vec}" + (f"/cap{cap}" if cap else "")] = round(18 * nb * 5 / s / 1e9, 1)
             extras["stream_5r4w_shapes_GBps"] = mix_tried
