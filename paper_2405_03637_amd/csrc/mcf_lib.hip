@@ -66,10 +66,13 @@ using mcfd::StepScalarsT;
 #define MCF_REMAP 0                  // 1: give each XCD (blocks are dealt round-robin to the 8 XCDs) a contiguous run of chunks
 #endif
 #ifndef MCF_PERSIST
-#define MCF_PERSIST 0                // 1: fixed grid of workgroups that walk the chunk table (see adamw_kernel)
+#define MCF_PERSIST 0                // 1: fixed grid of workgroups that walk the chunk table; 2: MCF_RUN consecutive chunks per workgroup (see adamw_kernel)
 #endif
 #ifndef MCF_DEPTH
 #define MCF_DEPTH 1                  // MCF_PERSIST: chunks whose loads are issued ahead of the one being computed (0 or 1)
+#endif
+#ifndef MCF_RUN
+#define MCF_RUN 4                    // MCF_PERSIST 2: consecutive chunks per workgroup
 #endif
 #ifndef MCF_WAVES_PER_CU
 #define MCF_WAVES_PER_CU 8           // MCF_PERSIST: workgroups of the fixed grid per compute unit
@@ -380,11 +383,11 @@ template <int VARIANT> struct StepStreams {
 #else
   static constexpr int kGroups = kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? (kGrow2 ? 12 : kBf16 ? 10 : 9)
                                  : kBase == mcfd::V_SGD ? 11 : 10;
-  static constexpr uint32_t kLds = (kEB == 1 || MCF_PERSIST) ? 0 : lds_for_groups(kGroups);
+  static constexpr uint32_t kLds = (kEB == 1 || MCF_PERSIST == 1) ? 0 : lds_for_groups(kGroups);
 #endif
   static constexpr int kEdqGroups = (kBase == mcfd::V_BF16 || kBase == mcfd::V_SGD || (kBase == mcfd::V_LIGHT && !kBf16 && !kGrow2)) ? 18
                                     : kBase == mcfd::V_KAHAN ? 14 : 16;
-  static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : (kEB == 1 || MCF_PERSIST) ? 0 : lds_for_groups(kEdqGroups);
+  static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : (kEB == 1 || MCF_PERSIST == 1) ? 0 : lds_for_groups(kEdqGroups);
 };
 
 // A dword of a stream holds one pair (2-byte elements) or two pairs (1-byte elements).
@@ -567,21 +570,34 @@ __device__ __forceinline__ void finish_chunk(ChunkIn<VARIANT> &c, const typename
 // time are neighbours in every stream, which keeps the DRAM pages in use few; persistent waves drift apart.
 // Making the ticket explicit (an atomic counter) would cost 13 million atomics on one address per step to
 // rebuild what the hardware does for nothing.
+//   2  the middle ground: MCF_RUN consecutive chunks per workgroup, the next chunk's loads issued before the current
+//      chunk's arithmetic, the runs still handed out in order by the dispatcher and capped like the default shape.
+//      7B set, best cap of 2..12 and none, same process (default shape: light 18.58, plus 23.23, plain bf16 14.28,
+//      light FP8 10.06): runs of 2: 19.31 / 24.58 / 14.97 / 10.79; of 4: 20.08 / 25.64 / 15.21 / 10.96; of 8: 22.12 /
+//      27.74 / 16.43 / 11.17; of 16: 22.65 / 28.08 / 17.24 / 11.37; runs of 4 without the prefetch 25.99 / 31.94 / 18.57 /
+//      12.46.  The longer a wave lives, the worse: one chunk per wave, born and retired in table order, is the shape.
 template <int VARIANT, bool FAST, bool EDQ, bool TABLE>
 __global__ void __launch_bounds__(kStepBlock) MCF_STEP_ATTR
 adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chunks, TensorDesc flat,
              typename StepStreams<VARIANT>::Scalars sc, double *__restrict__ partials, uint32_t n_chunks) {
   EdqAcc acc = {0.0, 0.0, 0u};
 #if MCF_PERSIST
-  const uint32_t grid = gridDim.x;
-  uint32_t chunk_id = (grid & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
+#if MCF_PERSIST == 2
+  // a short run of consecutive chunks per workgroup; the dispatcher still hands the runs out in order
+  const uint32_t stride = 1;
+  uint32_t chunk_id = blockIdx.x * (uint32_t)MCF_RUN;
+  const uint32_t end = n_chunks - chunk_id < (uint32_t)MCF_RUN ? n_chunks : chunk_id + (uint32_t)MCF_RUN;
+#else
+  const uint32_t stride = gridDim.x, end = n_chunks;
+  uint32_t chunk_id = (stride & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (stride >> 3) + (blockIdx.x >> 3);
+#endif
   ChunkIn<VARIANT> cur;
-  if (chunk_id < n_chunks) issue_chunk<VARIANT, TABLE>(chunk_id, descs, chunks, flat, cur);
-  while (chunk_id < n_chunks) {
-    const uint32_t next_id = chunk_id + grid;
+  if (chunk_id < end) issue_chunk<VARIANT, TABLE>(chunk_id, descs, chunks, flat, cur);
+  while (chunk_id < end) {
+    const uint32_t next_id = chunk_id + stride;
 #if MCF_DEPTH
     ChunkIn<VARIANT> nxt;
-    const bool more = next_id < n_chunks && next_id > chunk_id;
+    const bool more = next_id < end && next_id > chunk_id;
     if (more) issue_chunk<VARIANT, TABLE>(next_id, descs, chunks, flat, nxt);
     __builtin_amdgcn_sched_barrier(0);             // the next chunk's loads stay ahead of this chunk's arithmetic
     finish_chunk<VARIANT, FAST, EDQ>(cur, sc, acc);
@@ -589,7 +605,7 @@ adamw_kernel(const TensorDesc *__restrict__ descs, const Chunk *__restrict__ chu
     cur = nxt;
 #else
     finish_chunk<VARIANT, FAST, EDQ>(cur, sc, acc);
-    if (!(next_id < n_chunks && next_id > chunk_id)) break;
+    if (!(next_id < end && next_id > chunk_id)) break;
     issue_chunk<VARIANT, TABLE>(next_id, descs, chunks, flat, cur);
 #endif
     chunk_id = next_id;
@@ -1042,7 +1058,9 @@ struct HostScalars {
 
 // Workgroups of a step launch over `n_chunks` chunks (also the number of EDQ partials it writes).
 uint32_t step_grid(uint32_t n_chunks) {
-#if MCF_PERSIST
+#if MCF_PERSIST == 2
+  return (n_chunks + (uint32_t)MCF_RUN - 1) / (uint32_t)MCF_RUN;
+#elif MCF_PERSIST
   static const uint32_t per_cu = [] {                // MCF_WAVES_PER_CU in the environment overrides the built-in figure (for sweeps)
     const char *e = getenv("MCF_WAVES_PER_CU");
     const int v = e ? atoi(e) : 0;
@@ -1068,7 +1086,7 @@ std::atomic<int> g_groups_per_cu{-1}, g_head_sleep{-1}, g_tail_sleep{-1};
 // Dynamic LDS of a step launch: the variant's built-in cap on the workgroups per CU, unless overridden.
 uint32_t step_lds(uint32_t builtin) {
   const int forced = g_groups_per_cu.load(std::memory_order_relaxed);
-  if (forced < 0 || MCF_PERSIST) return builtin;
+  if (forced < 0 || MCF_PERSIST == 1) return builtin;
   return forced == 0 ? 0u : lds_for_groups((uint32_t)(forced > 128 ? 128 : forced));
 }
 
