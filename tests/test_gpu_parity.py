@@ -843,6 +843,23 @@ def test_step_replays_in_a_hip_graph():
         for k in wl.state_names():
             assert torch.equal(getattr(wl, k), want[k]), (rep, k)
         assert torch.equal(e_graph, e_eager), rep
+    # mcf_plan_update refuses to be captured: its table copy would be replayed from whatever the staging memory holds later
+    tensors = [(wl.theta[o:o + n], wl.dtheta[o:o + n], wl.m[o:o + n], wl.v[o:o + n], wl.dv[o:o + n], wl.grad[o:o + n])
+               for (_, n), o in zip(wl.shapes, wl.offs)]
+    scratch = torch.zeros(8, device=DEV)
+    other = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(other):
+        scratch.add_(1.0)                                # something to capture
+        with pytest.raises(mcf.McfError) as err:
+            wl.plan.update(tensors)
+    assert err.value.status == mcf.MCF_ERR_HIP
+    wl.plan.update(tensors)                              # outside a capture it is an ordinary call
+    for k, v in snap.items():
+        getattr(wl, k).copy_(v)
+    wl.plan.step(wl.hyper, 1)
+    torch.cuda.synchronize()
+    for k in wl.state_names():
+        assert torch.equal(getattr(wl, k), want[k]), k
     wl.close()
 
 
