@@ -694,22 +694,49 @@ def test_config3_gpt_1p3b_plus_edq():
 def test_config4_llama_7b():
     """Config 4: 291 tensors, 6,738,415,616 parameters, light, 10 steps, in the launch configuration the
     benchmark times.  Steps 1 and 2: every element of every state tensor, streamed through the oracle piece by
-    piece (the initial parameters, both gradient arenas and the state after step 1 stay on the device).  Steps
-    3 to 10: sampled elements (all small tensors, heads, tails and random windows of the large ones), which the
-    oracle follows from step 0 on."""
+    piece (the initial parameters, both gradient arenas and the state after step 1 stay on the device).  All 10
+    steps: one seeded tensor of each large size (16.7 M, 45 M and 131 M elements) whole, and sampled elements of
+    everything else (all small tensors, heads, tails and random windows of the large ones); the oracle follows
+    both from step 0 on, compared at steps 1, 2, 5 and 10."""
     wl = Workload("llama_7b")
+    names = wl.state_names()
     idx = sample_indices(wl.shapes, wl.offs)
     so = SampledOracle(wl, idx)
-    _say(f"llama_7b: {wl.n_params} params in {len(wl.shapes)} tensors, {idx.size} sampled")
+    by_size = {}
+    for i, (_, n) in enumerate(wl.shapes):
+        by_size.setdefault(n, []).append(i)
+    rng = np.random.default_rng(4)
+    chosen = [int(rng.choice(v)) for n, v in sorted(by_size.items()) if n > 16384]
+    whole = {i: {k: H.torch_to_u16(getattr(wl, k)[wl.offs[i]:wl.offs[i] + wl.shapes[i][1]]) for k in names} for i in chosen}
+    _say(f"llama_7b: {wl.n_params} params in {len(wl.shapes)} tensors, {idx.size} sampled, whole tensors "
+         + ", ".join(f"{wl.shapes[i][0]} ({wl.shapes[i][1]})" for i in chosen))
+
+    def follow(t):
+        so.step(t)
+        for i in chosen:
+            o, n = wl.offs[i], wl.shapes[i][1]
+            st = whole[i]
+            orc.adamw_step(st["theta"], st["dtheta"], st["m"], st["v"], None, H.torch_to_u16(wl.grad[o:o + n]), wl.variant, wl.hyper, t)
+
+    def check(t):
+        assert_bitwise(so.mismatches(), f"llama_7b step {t}")
+        for i in chosen:
+            o, n = wl.offs[i], wl.shapes[i][1]
+            for k in names:
+                got = H.torch_to_u16(getattr(wl, k)[o:o + n])
+                bad = np.flatnonzero(got != whole[i][k])
+                assert bad.size == 0, f"llama_7b step {t} {wl.shapes[i][0]} {k}: {bad.size} of {n} differ, first at {int(bad[0])}"
+        _say(f"llama_7b: step {t}: {idx.size} sampled elements and {len(chosen)} whole tensors identical")
+
     theta0 = wl.theta.clone()
     grads, snaps = [], []
     for t in (1, 2):
         wl.new_grads(t)
-        so.step(t)
+        follow(t)
         grads.append(wl.grad.clone() if t == 1 else wl.grad)
         wl.plan.step(wl.hyper, t)
-        snaps.append({k: (getattr(wl, k).clone() if t == 1 else getattr(wl, k)) for k in wl.state_names()})
-        assert_bitwise(so.mismatches(), f"llama_7b step {t}")
+        snaps.append({k: (getattr(wl, k).clone() if t == 1 else getattr(wl, k)) for k in names})
+        check(t)
         if t == 1:
             # no chunk was skipped: after the first step m = F(c1 * g) is non-zero exactly where the gradient is (the
             # normal draws hold a few hundred exact zeros among 6.7e9; the arenas of this set have no padding)
@@ -720,7 +747,12 @@ def test_config4_llama_7b():
     assert done == wl.n_params
     del theta0, grads, snaps
     torch.cuda.empty_cache()
-    _sampled_steps(wl, so, 3, 10, {5, 10})
+    for t in range(3, 11):
+        wl.new_grads(t)
+        follow(t)
+        wl.plan.step(wl.hyper, t)
+        if t in (5, 10):
+            check(t)
     wl.close()
 
 
@@ -744,9 +776,9 @@ def test_llama_7b_other_strategies_sampled(variant):
 
 def test_config5_stress_64m():
     """Config 5: 64 Mi parameters incl. 4096 tensors of 1..256 elements at odd offsets, plus, lr = 2^-20,
-    1000 steps.  Steps 1 to 10: the oracle over every element, whole state compared at steps 1 and 10.  All
+    1000 steps.  Steps 1 to 100: the oracle over every element, whole state compared at steps 1, 10 and 100.  All
     1000 steps: every tiny tensor and windows of the large ones are followed by the oracle, compared at
-    steps 1, 10, 100, 500 and 1000, with the drift of theta + dtheta against the exact sum of the updates
+    steps 10, 100, 500 and 1000, with the drift of theta + dtheta against the exact sum of the updates
     (Sec. 4: Grow keeps what a plain bf16 addition loses)."""
     name, steps = "stress_64m", 1000
     wl = Workload(name, misalign_tiny=True)
@@ -762,9 +794,9 @@ def test_config5_stress_64m():
         track["ideal"] += H.u16_to_f64(delta)
         track["plain"] = orc.binop(orc.ADD, track["plain"], delta)
 
-    whole_state_run(wl, 10, {1, 10}, _say, on_grads=follow)
-    assert_bitwise(so.mismatches(), f"{name} step 10")
-    _sampled_steps(wl, so, 11, steps, {100, 500, 1000}, on_grads=follow)
+    whole_state_run(wl, 100, {1, 10, 100}, _say, on_grads=follow)
+    assert_bitwise(so.mismatches(), f"{name} step 100")
+    _sampled_steps(wl, so, 101, steps, {500, 1000}, on_grads=follow)
     # Drift of the DEVICE's expansion against the exact sum of the updates it was given.  Each Grow loses at
     # most half an ulp of the second component, i.e. at most 2^-16 of |theta| per step; plain bf16 never moves
     # because every update is below ulp/2.
