@@ -92,7 +92,10 @@ constexpr uint32_t lds_for_groups(uint32_t groups) { return (128u / groups) * 12
 #define MCF_STEP_LDS_EDQ 0           // 0: per variant (StepStreams::kLdsEdq); else bytes for every EDQ-fused step kernel
 #endif
 #ifndef MCF_FP32MW_LDS
-#define MCF_FP32MW_LDS lds_for_groups(12)   // fp32-master baseline kernel: 10 groups 28.90 ms, 11: 28.84, 12: 28.82, 14: 29.31
+#define MCF_FP32MW_LDS lds_for_groups(10)   // fp32-master baseline kernel: 9 groups 29.15 ms, 10: 29.14, 11: 29.38, 12: 29.72, 14: 30.40
+#endif
+#ifndef MCF_FP32MW_STORE
+#define MCF_FP32MW_STORE ST_AGENT_NT // StorePolicy of the fp32-master baseline kernel (10 groups: 29.14 ms; ST_AGENT 29.22; ST_NT 29.75)
 #endif
 #ifndef MCF_COPY_LDS
 #define MCF_COPY_LDS 0               // the plain copy (2 streams) is fastest uncapped: 6.66 TB/s against 4.4 TB/s with the cap
@@ -158,13 +161,33 @@ __device__ __forceinline__ void load_vec(uint64_t p, uint64_t off, uint32_t (&w)
 #endif
   w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
 }
+// How a 128-bit store is marked for the caches.  ST_NT: non-temporal.  ST_AGENT: agent scope -- the data is
+// written through to memory instead of waiting in the XCD's L2 for an eviction; ST_AGENT_NT: both.  Measured at the
+// 7B set, each kernel at its best cap, same process: light 18.53 ms with ST_NT, 18.17 with ST_AGENT_NT, 17.94 with
+// ST_AGENT; plus 23.10 / 22.73 / 22.34; SGD 14.16 / 14.05 / 13.82; the kernels with the fp64 EDQ sums fused in prefer
+// ST_AGENT_NT (light 18.70 against 19.23 with ST_AGENT), the ALU-bound FP8 kernels ST_NT (9.80 against 9.99).  In an
+// arithmetic-free 5-read/4-write probe every combination of sc0, sc1 and nt on the loads leaves the rate where it is;
+// on the stores, any with sc1 gives 6.81-6.83 TB/s against 6.63 for nt alone and 5.7-6.3 for none or sc0.
+enum StorePolicy { ST_NT = 0, ST_AGENT = 1, ST_AGENT_NT = 2, ST_PLAIN = 3 };
+#ifndef MCF_STORE_POLICY
+#define MCF_STORE_POLICY -1          // -1: per kernel (see finish_chunk); else one StorePolicy for every step kernel
+#endif
+
+// The scope bits have no builtin, so those stores are written as the instruction.  The s_nop keeps the two wait
+// states this target wants between a store of more than 64 bits and a write to its data registers: the compiler's
+// hazard pass provides them for instructions it knows and cannot for this one.
+template <int POLICY = (MCF_NT_STORE ? ST_NT : ST_PLAIN)>
 __device__ __forceinline__ void store_vec(uint64_t p, uint64_t off, const uint32_t (&w)[4]) {
   const u32x4_t q = {w[0], w[1], w[2], w[3]};
-#if MCF_NT_STORE
-  __builtin_nontemporal_store(q, gptr<u32x4_t>(p + off));
-#else
-  *gptr<u32x4_t>(p + off) = q;
-#endif
+  if constexpr (POLICY == ST_AGENT) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p + off), "v"(q) : "memory");
+  } else if constexpr (POLICY == ST_AGENT_NT) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p + off), "v"(q) : "memory");
+  } else if constexpr (POLICY == ST_NT) {
+    __builtin_nontemporal_store(q, gptr<u32x4_t>(p + off));
+  } else {
+    *gptr<u32x4_t>(p + off) = q;
+  }
 }
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -175,12 +198,18 @@ __device__ __forceinline__ f32x4_t load_f4(const MCF_GLOBAL float *p) {
   return *(const MCF_GLOBAL f32x4_t *)p;
 #endif
 }
+template <int POLICY>
 __device__ __forceinline__ void store_f4(MCF_GLOBAL float *p, f32x4_t q) {
-#if MCF_NT_STORE
-  __builtin_nontemporal_store(q, (MCF_GLOBAL f32x4_t *)p);
-#else
-  *(MCF_GLOBAL f32x4_t *)p = q;
-#endif
+  const uint64_t at = (uint64_t)p;
+  if constexpr (POLICY == ST_AGENT) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(at), "v"(q) : "memory");
+  } else if constexpr (POLICY == ST_AGENT_NT) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(at), "v"(q) : "memory");
+  } else if constexpr (POLICY == ST_NT) {
+    __builtin_nontemporal_store(q, (MCF_GLOBAL f32x4_t *)p);
+  } else {
+    *(MCF_GLOBAL f32x4_t *)p = q;
+  }
 }
 
 // One element of EB bytes.
@@ -358,35 +387,31 @@ template <int VARIANT> struct StepStreams {
   static constexpr bool kDth = kBase != mcfd::V_BF16;      // second component of theta / Kahan variable
   static constexpr bool kDv = kBase == mcfd::V_PLUS;       // second component of v
   static constexpr bool kV = kBase != mcfd::V_SGD;         // second moment
-  // Occupancy cap in workgroups per CU, from sweeps of 8..28 at the 7B-parameter set, all settings of a
+  // Occupancy cap in workgroups per CU, from sweeps of 7..20 at the 7B-parameter set, all settings of a
   // kernel timed in one process on the same arenas (two processes differ by more than two neighbouring caps
-  // do: where the allocator puts 80 GB matters at the 1-3% level).  ms per step, best cap first:
-  //   light 10: 18.56 (11: 18.75, 9: 18.94, 12: 18.92)       Kahan 10: 18.55 (9: 18.75, 11: 18.82)
-  //   plus  10: 23.13 (9: 23.12, 11: 23.30, 12: 23.53)       plus, fp16 components 9: 22.93 (8: 23.15, 10: 23.23)
-  //     (smaller sets settle it for plus: GPT-1.3B 4.50 ms at 10, 4.52 at 9; GPT-2-125M 0.423 against 0.433; the 64Mi
-  //      stress set with its 4096 tiny tensors 0.243 against 0.252, and 0.240 at 11 or 12)
-  //   plain bf16 12: 14.23 (11: 14.41, 14: 14.64)            SGD 11: 14.20 (12: 14.32, 10: 14.43)
-  //   light on TwoSum 11: 18.64 (10: 18.68, 12: 18.89)       plus on TwoSum 12: 24.14 (13/14: 24.24, 11: 24.27, 10: 24.4)
-  //   light, fp16 components 10: 18.55 (11: 18.65, 12: 18.89)
+  // do: where the allocator puts 80 GB matters at the 1-3% level).  ms per step, best cap first, with the store
+  // policy each kernel uses (see StorePolicy):
+  //   light 11: 17.94 (10: 18.27, 12: 18.68, 9: 18.96)       Kahan 11: 18.02 (10: 18.10, 12: 18.68)
+  //   plus  10: 22.34 (9: 22.88, 11: 23.02, 12: 23.54)       plus, fp16 components 10: 22.14 (9: 22.35, 11: 23.10)
+  //   plain bf16 12: 14.05 (13: 14.36, 11: 14.50)            SGD 12: 13.82 (11: 14.10, 13: 14.44)
+  //   light on TwoSum 12: 18.04 (11: 18.21, 10: 18.69)       plus on TwoSum 12: 23.29 (11: 23.38, 13: 23.48)
+  //   light, fp16 components 11: 18.08 (12: 18.39, 10: 18.47)
   // The plain variant and SGD have less memory time per wave to hide their divide and root behind and take
   // more waves.  The optimum moves with a kernel's instruction schedule, so the table is re-measured when the
   // arithmetic or the kernel's structure changes (mcf_set_launch_pacing does that without rebuilding).
-  // With the fp64 EDQ sums fused in there is more arithmetic per wave: light 16: 18.80 (18: 19.46, 13: 19.38,
-  // no cap: 19.94); plus 16: 23.58 (18: 23.72, 14: 24.38); Kahan 13-16: 18.95; plain bf16 18: 14.57 (20: 14.78,
-  // 16: 14.97); SGD 18: 14.29 (16: 14.52, 20: 14.89); light on TwoSum 16-18: 19.55; plus on TwoSum 16 and up:
-  // 25.5-25.6; light with fp16 components 18: 19.62 (16: 19.67); plus with fp16 components 16: 23.60.
+  // With the fp64 EDQ sums fused in there is more arithmetic per wave: light 13: 18.70 (16: 18.73, 12: 19.30);
+  // plus 16: 23.40 (14: 23.44, 13: 23.46); Kahan 13: 18.40; plain bf16 18: 14.34 (16: 14.65); SGD 16: 14.22
+  // (18: 14.29, 14: 14.67); light on TwoSum 16-18: 19.35; plus on TwoSum 20: 25.42 (18: 25.60); light with fp16
+  // components 16: 19.37; plus with fp16 components 14: 23.05.
   // The FP8 kernels move half the bytes with about the same arithmetic (a conversion to and from the
   // 8-bit format around every operation): they are bound by vector-ALU issue and run uncapped (light E5M2,
-  // 7B set: 10.5 ms uncapped, 10.7-10.9 at 12 to 24 groups per CU).
-#ifdef MCF_STEP_LDS
-  static constexpr uint32_t kLds = MCF_STEP_LDS;
-#else
-  static constexpr int kGroups = kBase == mcfd::V_BF16 ? 12 : kBase == mcfd::V_PLUS ? (kGrow2 ? 12 : kBf16 ? 10 : 9)
-                                 : kBase == mcfd::V_SGD ? 11 : 10;
+  // 7B set: 9.80 ms uncapped, 10.06-10.54 at 12 to 14 groups per CU).
+  static constexpr int kGroups = (kBase == mcfd::V_BF16 || kBase == mcfd::V_SGD || kGrow2) ? 12 : kBase == mcfd::V_PLUS ? 10 : 11;
   static constexpr uint32_t kLds = (kEB == 1 || MCF_PERSIST == 1) ? 0 : lds_for_groups(kGroups);
 #endif
-  static constexpr int kEdqGroups = (kBase == mcfd::V_BF16 || kBase == mcfd::V_SGD || (kBase == mcfd::V_LIGHT && !kBf16 && !kGrow2)) ? 18
-                                    : kBase == mcfd::V_KAHAN ? 14 : 16;
+  static constexpr int kEdqGroups = kBase == mcfd::V_BF16 ? 18 : kBase == mcfd::V_KAHAN ? 13
+                                    : kBase == mcfd::V_PLUS ? (kGrow2 ? 20 : kBf16 ? 16 : 14)
+                                    : kBase == mcfd::V_LIGHT && kBf16 && !kGrow2 ? 13 : 16;
   static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : (kEB == 1 || MCF_PERSIST == 1) ? 0 : lds_for_groups(kEdqGroups);
 };
 
@@ -515,6 +540,8 @@ __device__ __forceinline__ void finish_chunk(ChunkIn<VARIANT> &c, const typename
   using First = typename SS::template Hot<FAST>;
   using Second = typename SS::template Second<FAST>;
   const TensorDesc &d = c.d;
+  // ALU-bound FP8 kernels: non-temporal; with the EDQ sums fused in: agent scope and non-temporal; else agent scope
+  constexpr int kStore = MCF_STORE_POLICY >= 0 ? MCF_STORE_POLICY : SS::kEB == 1 ? ST_NT : EDQ ? ST_AGENT_NT : ST_AGENT;
   const bool skip_first = sc.elementwise != 0;       // uniform over the launch
   static_for<0, kUnroll>([&](auto jc) {
     constexpr int j = decltype(jc)::value;
@@ -532,11 +559,11 @@ __device__ __forceinline__ void finish_chunk(ChunkIn<VARIANT> &c, const typename
       }
       if (slot.full) {
         const uint64_t e0 = (slot.c0 - d.phase) * SS::kEB;
-        store_vec(d.p[S_TH], e0, out[S_TH]);
-        if (SS::kDth) store_vec(d.p[S_DTH], e0, out[S_DTH]);
-        store_vec(d.p[S_M], e0, out[S_M]);
-        if (SS::kV) store_vec(d.p[S_V], e0, out[S_V]);
-        if (SS::kDv) store_vec(d.p[S_DV], e0, out[S_DV]);
+        store_vec<kStore>(d.p[S_TH], e0, out[S_TH]);
+        if (SS::kDth) store_vec<kStore>(d.p[S_DTH], e0, out[S_DTH]);
+        store_vec<kStore>(d.p[S_M], e0, out[S_M]);
+        if (SS::kV) store_vec<kStore>(d.p[S_V], e0, out[S_V]);
+        if (SS::kDv) store_vec<kStore>(d.p[S_DV], e0, out[S_DV]);
       } else {
         store_slot<SS::kEB>(d.p[S_TH], d, slot, out[S_TH]);
         if (SS::kDth) store_slot<SS::kEB>(d.p[S_DTH], d, slot, out[S_DTH]);
@@ -952,15 +979,15 @@ fp32mw_kernel(const Fp32Desc *__restrict__ descs, const Chunk *__restrict__ chun
       fp32mw_elem(g0.hi, m[1], v[1], w[1], sc);
       fp32mw_elem(g1.lo, m[2], v[2], w[2], sc);
       fp32mw_elem(g1.hi, m[3], v[3], w[3], sc);
-      store_f4(mp + e0, f32x4_t{m[0], m[1], m[2], m[3]});
-      store_f4(vp + e0, f32x4_t{v[0], v[1], v[2], v[3]});
-      store_f4(master + e0, f32x4_t{w[0], w[1], w[2], w[3]});
+      store_f4<MCF_FP32MW_STORE>(mp + e0, f32x4_t{m[0], m[1], m[2], m[3]});
+      store_f4<MCF_FP32MW_STORE>(vp + e0, f32x4_t{v[0], v[1], v[2], v[3]});
+      store_f4<MCF_FP32MW_STORE>(master + e0, f32x4_t{w[0], w[1], w[2], w[3]});
       const u32x2_t tw = {mcfd::pack2(mcfd::Exact::round_f32(w[0], w[1])), mcfd::pack2(mcfd::Exact::round_f32(w[2], w[3]))};
-#if MCF_NT_STORE
-      __builtin_nontemporal_store(tw, (MCF_GLOBAL u32x2_t *)(theta + e0));
-#else
-      *(MCF_GLOBAL u32x2_t *)(theta + e0) = tw;
-#endif
+      const uint64_t theta_at = (uint64_t)(theta + e0);
+      if (MCF_FP32MW_STORE == ST_AGENT) asm volatile("global_store_dwordx2 %0, %1, off sc1" : : "v"(theta_at), "v"(tw) : "memory");
+      else if (MCF_FP32MW_STORE == ST_AGENT_NT) asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" : : "v"(theta_at), "v"(tw) : "memory");
+      else if (MCF_FP32MW_STORE == ST_NT) __builtin_nontemporal_store(tw, (MCF_GLOBAL u32x2_t *)(theta + e0));
+      else *(MCF_GLOBAL u32x2_t *)(theta + e0) = tw;
     });
     return;
   }
@@ -1809,7 +1836,7 @@ int mcf_fp32mw_step(mcf_fp32mw_plan *plan, const mcf_hyper *hyper, uint64_t step
   s.e = (float)hyper->eps;
   s.lam = (float)hyper->weight_decay;
   s.na = (float)(-hyper->lr);
-  hipLaunchKernelGGL(fp32mw_kernel, dim3(plan->n_chunks), dim3(kStepBlock), MCF_FP32MW_LDS, (hipStream_t)stream, plan->d_descs, plan->d_chunks, s);
+  hipLaunchKernelGGL(fp32mw_kernel, dim3(plan->n_chunks), dim3(kStepBlock), step_lds(MCF_FP32MW_LDS), (hipStream_t)stream, plan->d_descs, plan->d_chunks, s);
   MCF_HIP(hipGetLastError());
   return MCF_OK;
 }
