@@ -406,6 +406,9 @@ template <int VARIANT> struct StepStreams {
   // The FP8 kernels move half the bytes with about the same arithmetic (a conversion to and from the
   // 8-bit format around every operation): they are bound by vector-ALU issue and run uncapped (light E5M2,
   // 7B set: 9.80 ms uncapped, 10.06-10.54 at 12 to 14 groups per CU).
+#ifdef MCF_STEP_LDS
+  static constexpr uint32_t kLds = MCF_STEP_LDS;
+#else
   static constexpr int kGroups = (kBase == mcfd::V_BF16 || kBase == mcfd::V_SGD || kGrow2) ? 12 : kBase == mcfd::V_PLUS ? 10 : 11;
   static constexpr uint32_t kLds = (kEB == 1 || MCF_PERSIST == 1) ? 0 : lds_for_groups(kGroups);
 #endif
