@@ -226,9 +226,11 @@ def main():
             extras["copy_GBps"] = 4 * nb * 10 / s / 1e9
             # (b) the same copy in other launch shapes and through the runtime's own device-to-device copy
             shapes_tried = {}
-            for threads, vec, cap in ((64, 1, 0), (64, 2, 0), (64, 4, 0), (256, 1, 0), (256, 2, 0), (256, 4, 0), (64, 1, 20), (256, 1, 5)):
-                _, s = time_steps(lambda t: mcf.stream_mix([src[:nb]], [dst[:nb]], 2 * nb, threads, vec, cap), 6, 2)
-                shapes_tried[f"{threads}x{vec}" + (f"/cap{cap}" if cap else "")] = round(4 * nb * 6 / s / 1e9, 1)
+            tag = lambda threads, vec, cap, store: f"{threads}x{vec}" + (f"/cap{cap}" if cap else "") + ("", "/agent", "/agent+nt")[store]
+            for threads, vec, cap, store in ((64, 1, 0, 0), (64, 2, 0, 0), (64, 4, 0, 0), (256, 1, 0, 0), (256, 2, 0, 0), (256, 4, 0, 0),
+                                             (64, 1, 20, 0), (256, 1, 5, 0), (64, 1, 0, 1), (256, 1, 0, 1), (64, 1, 0, 2), (64, 1, 20, 1)):
+                _, s = time_steps(lambda t: mcf.stream_mix([src[:nb]], [dst[:nb]], 2 * nb, threads, vec, cap, store), 6, 2)
+                shapes_tried[tag(threads, vec, cap, store)] = round(4 * nb * 6 / s / 1e9, 1)
             extras["copy_shapes_GBps"] = shapes_tried
             extras["copy_best_GBps"] = max(max(shapes_tried.values()), extras["copy_GBps"])
             _, s = time_steps(lambda t: dst[:nb].copy_(src[:nb]), 6, 2)
@@ -237,9 +239,10 @@ def main():
             # (c) the step's own mix of streams with no arithmetic: 5 arenas read, 4 of them written back in place
             rd = [st[k][:nb] for k in ("theta", "dtheta", "m", "v", "grad")]
             mix_tried = {}
-            for threads, vec, cap in ((64, 1, 6), (64, 1, 8), (64, 1, 10), (64, 1, 12), (64, 1, 0), (64, 2, 4), (256, 1, 1), (256, 2, 0)):
-                _, s = time_steps(lambda t: mcf.stream_mix(rd, rd[:4], 2 * nb, threads, vec, cap), 5, 2)
-                mix_tried[f"{threads}x{vec}" + (f"/cap{cap}" if cap else "")] = round(18 * nb * 5 / s / 1e9, 1)
+            for threads, vec, cap, store in ((64, 1, 6, 0), (64, 1, 10, 0), (64, 1, 0, 0), (256, 2, 0, 0), (64, 1, 5, 1), (64, 1, 6, 1), (64, 1, 7, 1),
+                                             (64, 1, 8, 1), (64, 1, 10, 1), (64, 1, 6, 2), (64, 1, 8, 2), (64, 2, 4, 1), (256, 1, 1, 1), (256, 1, 2, 1)):
+                _, s = time_steps(lambda t: mcf.stream_mix(rd, rd[:4], 2 * nb, threads, vec, cap, store), 5, 2)
+                mix_tried[tag(threads, vec, cap, store)] = round(18 * nb * 5 / s / 1e9, 1)
             extras["stream_5r4w_shapes_GBps"] = mix_tried
             extras["stream_5r4w_GBps"] = max(mix_tried.values())
             del rd

@@ -271,11 +271,13 @@ int mcf_set_launch_pacing(int groups_per_cu, int head_sleep, int tail_sleep);
  * 16) are loaded, and write j (j < n_write <= n_read) receives what read j brought in -- unchanged, so passing
  * the same buffers for reads and writes, as the step does, leaves their contents as they are.  The launch
  * shape is the caller's: threads per workgroup (64 or 256), 128-bit vectors per lane (1, 2 or 4; each wave
- * instruction covers one contiguous run) and groups_per_cu, a cap on the workgroups resident per compute
- * unit (0 = none).  Supported mixes (n_read, n_write): (1,1) a copy, (1,0), (4,3), (5,4) the light step,
+ * instruction covers one contiguous run), groups_per_cu, a cap on the workgroups resident per compute
+ * unit (0 = none), and store_policy, how the stores are marked for the caches: 0 non-temporal, 1 agent scope
+ * (written through to memory), 2 both -- the step kernels use 1, 2 with the EDQ sums fused in, 0 for FP8.
+ * Supported mixes (n_read, n_write): (1,1) a copy, (1,0), (4,3), (5,4) the light step,
  * (6,5) the plus step; others are MCF_ERR_VARIANT.  bench.py reports the step against what this reaches. ---- */
 int mcf_stream_mix(const void *const *reads, uint32_t n_read, void *const *writes, uint32_t n_write, uint64_t bytes,
-                   uint32_t threads, uint32_t vectors_per_lane, uint32_t groups_per_cu, void *stream);
+                   uint32_t threads, uint32_t vectors_per_lane, uint32_t groups_per_cu, uint32_t store_policy, void *stream);
 
 #ifdef __cplusplus
 }

@@ -95,7 +95,7 @@ def lib():
     L.mcf_stream_copy.argtypes = [_vp, _vp, _u64, _vp]
     L.mcf_set_launch_pacing.argtypes = [_int, _int, _int]
     L.mcf_stream_mix.argtypes = [ctypes.POINTER(_vp), ctypes.c_uint32, ctypes.POINTER(_vp), ctypes.c_uint32, _u64,
-                                 ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32, _vp]
+                                 ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32, _vp]
     _lib = L
     return L
 
@@ -318,12 +318,13 @@ def set_launch_pacing(groups_per_cu=-1, head_sleep=-1, tail_sleep=-1):
     _check(lib().mcf_set_launch_pacing(int(groups_per_cu), int(head_sleep), int(tail_sleep)), "mcf_set_launch_pacing")
 
 
-def stream_mix(reads, writes, nbytes, threads=64, vectors_per_lane=1, groups_per_cu=0, stream=None):
-    """reads, writes: lists of device tensors (or addresses); write j receives read j's data."""
+def stream_mix(reads, writes, nbytes, threads=64, vectors_per_lane=1, groups_per_cu=0, store_policy=0, stream=None):
+    """reads, writes: lists of device tensors (or addresses); write j receives read j's data.
+    store_policy: 0 non-temporal stores, 1 agent scope, 2 both."""
     r = (_vp * max(1, len(reads)))(*[_ptr(t) for t in reads])
     w = (_vp * max(1, len(writes)))(*[_ptr(t) for t in writes])
     _check(lib().mcf_stream_mix(r, len(reads), w, len(writes), int(nbytes), int(threads), int(vectors_per_lane),
-                                int(groups_per_cu), _stream(stream)), "mcf_stream_mix")
+                                int(groups_per_cu), int(store_policy), _stream(stream)), "mcf_stream_mix")
 
 
 # ---- the C names, one to one (each returns nothing and raises McfError on a non-zero status) ----

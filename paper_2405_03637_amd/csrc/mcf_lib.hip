@@ -881,7 +881,7 @@ struct MixArgs {
   uint32_t mask;
 };
 
-template <int NR, int NW, int THREADS, int VEC>
+template <int NR, int NW, int THREADS, int VEC, int STORE>
 __global__ void __launch_bounds__(THREADS) mix_kernel(MixArgs a) {
   static_assert(NW <= NR && NR <= kMaxMix, "a write needs its read");
   const uint64_t base = (uint64_t)blockIdx.x * (THREADS * VEC) + threadIdx.x;
@@ -901,7 +901,7 @@ __global__ void __launch_bounds__(THREADS) mix_kernel(MixArgs a) {
       static_for<0, NW>([&](auto rc) {
         constexpr int r = decltype(rc)::value;
         if (NR > NW) w[v][r][0] ^= extra;
-        store_vec(a.wr[r], 16 * i, w[v][r]);
+        store_vec<STORE>(a.wr[r], 16 * i, w[v][r]);
       });
       if (NW == 0 && extra == 0x9e3779b9u) store_vec(a.rd[0], 16 * i, w[v][0]);      // never taken: keeps a read-only launch's loads
     }
@@ -1263,21 +1263,28 @@ int prim_launch(int format, int op, const void *p0, const void *p1, const void *
   return MCF_OK;
 }
 
-template <int NR, int NW, int THREADS>
+template <int NR, int NW, int THREADS, int STORE>
 void launch_mix_vec(uint32_t vec, uint32_t lds, hipStream_t st, const MixArgs &a) {
   const uint64_t per = (uint64_t)THREADS * vec;
   const dim3 g((uint32_t)((a.nvec + per - 1) / per)), b(THREADS);
   switch (vec) {
-    case 1: hipLaunchKernelGGL((mix_kernel<NR, NW, THREADS, 1>), g, b, lds, st, a); break;
-    case 2: hipLaunchKernelGGL((mix_kernel<NR, NW, THREADS, 2>), g, b, lds, st, a); break;
-    default: hipLaunchKernelGGL((mix_kernel<NR, NW, THREADS, 4>), g, b, lds, st, a); break;
+    case 1: hipLaunchKernelGGL((mix_kernel<NR, NW, THREADS, 1, STORE>), g, b, lds, st, a); break;
+    case 2: hipLaunchKernelGGL((mix_kernel<NR, NW, THREADS, 2, STORE>), g, b, lds, st, a); break;
+    default: hipLaunchKernelGGL((mix_kernel<NR, NW, THREADS, 4, STORE>), g, b, lds, st, a); break;
   }
 }
 
 template <int NR, int NW>
-void launch_mix(uint32_t threads, uint32_t vec, uint32_t lds, hipStream_t st, const MixArgs &a) {
-  if (threads == 64) launch_mix_vec<NR, NW, 64>(vec, lds, st, a);
-  else launch_mix_vec<NR, NW, 256>(vec, lds, st, a);
+void launch_mix(uint32_t threads, uint32_t vec, uint32_t lds, uint32_t store, hipStream_t st, const MixArgs &a) {
+  if (threads == 64) {
+    if (store == ST_AGENT) launch_mix_vec<NR, NW, 64, ST_AGENT>(vec, lds, st, a);
+    else if (store == ST_AGENT_NT) launch_mix_vec<NR, NW, 64, ST_AGENT_NT>(vec, lds, st, a);
+    else launch_mix_vec<NR, NW, 64, ST_NT>(vec, lds, st, a);
+  } else {
+    if (store == ST_AGENT) launch_mix_vec<NR, NW, 256, ST_AGENT>(vec, lds, st, a);
+    else if (store == ST_AGENT_NT) launch_mix_vec<NR, NW, 256, ST_AGENT_NT>(vec, lds, st, a);
+    else launch_mix_vec<NR, NW, 256, ST_NT>(vec, lds, st, a);
+  }
 }
 
 inline bool known_component(int c) { return c >= MCF_COMPONENT_BF16 && c <= MCF_COMPONENT_FP8_E4M3; }
@@ -1683,11 +1690,12 @@ int mcf_set_launch_pacing(int groups_per_cu, int head_sleep, int tail_sleep) {
 }
 
 int mcf_stream_mix(const void *const *reads, uint32_t n_read, void *const *writes, uint32_t n_write, uint64_t bytes,
-                   uint32_t threads, uint32_t vectors_per_lane, uint32_t groups_per_cu, void *stream) {
+                   uint32_t threads, uint32_t vectors_per_lane, uint32_t groups_per_cu, uint32_t store_policy, void *stream) {
   if (bytes == 0) return MCF_OK;
   if (!reads || (n_write && !writes)) return MCF_ERR_NULL;
   if (n_read > (uint32_t)kMaxMix || n_write > n_read) return MCF_ERR_SIZE;
-  if ((threads != 64 && threads != 256) || (vectors_per_lane != 1 && vectors_per_lane != 2 && vectors_per_lane != 4) || groups_per_cu > 128)
+  if ((threads != 64 && threads != 256) || (vectors_per_lane != 1 && vectors_per_lane != 2 && vectors_per_lane != 4) || groups_per_cu > 128 ||
+      store_policy > (uint32_t)ST_AGENT_NT)
     return MCF_ERR_VARIANT;
   MixArgs a = {};
   for (uint32_t i = 0; i < n_read; ++i) {
@@ -1708,11 +1716,11 @@ int mcf_stream_mix(const void *const *reads, uint32_t n_read, void *const *write
   hipStream_t st = (hipStream_t)stream;
   const uint32_t key = n_read * 16 + n_write;
   switch (key) {
-    case 1 * 16 + 1: launch_mix<1, 1>(threads, vectors_per_lane, lds, st, a); break;      // a copy
-    case 1 * 16 + 0: launch_mix<1, 0>(threads, vectors_per_lane, lds, st, a); break;      // read only
-    case 4 * 16 + 3: launch_mix<4, 3>(threads, vectors_per_lane, lds, st, a); break;      // plain bf16, MCF-SGD
-    case 5 * 16 + 4: launch_mix<5, 4>(threads, vectors_per_lane, lds, st, a); break;      // light, Kahan
-    case 6 * 16 + 5: launch_mix<6, 5>(threads, vectors_per_lane, lds, st, a); break;      // plus
+    case 1 * 16 + 1: launch_mix<1, 1>(threads, vectors_per_lane, lds, store_policy, st, a); break;      // a copy
+    case 1 * 16 + 0: launch_mix<1, 0>(threads, vectors_per_lane, lds, store_policy, st, a); break;      // read only
+    case 4 * 16 + 3: launch_mix<4, 3>(threads, vectors_per_lane, lds, store_policy, st, a); break;      // plain bf16, MCF-SGD
+    case 5 * 16 + 4: launch_mix<5, 4>(threads, vectors_per_lane, lds, store_policy, st, a); break;      // light, Kahan
+    case 6 * 16 + 5: launch_mix<6, 5>(threads, vectors_per_lane, lds, store_policy, st, a); break;      // plus
     default: return MCF_ERR_VARIANT;
   }
   MCF_HIP(hipGetLastError());

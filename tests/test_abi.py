@@ -232,14 +232,15 @@ def test_launch_pacing_and_measurement_aid_argument_errors():
     vp = ctypes.c_void_p
     one = (vp * 1)(FAKE)
     five = (vp * 5)(*([FAKE] * 5))
-    assert L.mcf_stream_mix(one, 1, one, 1, 0, 64, 1, 0, None) == mcf.MCF_OK            # nothing to move
-    assert L.mcf_stream_mix(None, 1, one, 1, 64, 64, 1, 0, None) == mcf.MCF_ERR_NULL
-    assert L.mcf_stream_mix(one, 1, five, 5, 64, 64, 1, 0, None) == mcf.MCF_ERR_SIZE    # a write needs its read
-    assert L.mcf_stream_mix(one, 1, one, 1, 64, 128, 1, 0, None) == mcf.MCF_ERR_VARIANT
-    assert L.mcf_stream_mix(one, 1, one, 1, 64, 64, 3, 0, None) == mcf.MCF_ERR_VARIANT
-    assert L.mcf_stream_mix(one, 1, one, 1, 24, 64, 1, 0, None) == mcf.MCF_ERR_ALIGN
+    assert L.mcf_stream_mix(one, 1, one, 1, 0, 64, 1, 0, 0, None) == mcf.MCF_OK            # nothing to move
+    assert L.mcf_stream_mix(None, 1, one, 1, 64, 64, 1, 0, 0, None) == mcf.MCF_ERR_NULL
+    assert L.mcf_stream_mix(one, 1, five, 5, 64, 64, 1, 0, 0, None) == mcf.MCF_ERR_SIZE    # a write needs its read
+    assert L.mcf_stream_mix(one, 1, one, 1, 64, 128, 1, 0, 0, None) == mcf.MCF_ERR_VARIANT
+    assert L.mcf_stream_mix(one, 1, one, 1, 64, 64, 3, 0, 0, None) == mcf.MCF_ERR_VARIANT
+    assert L.mcf_stream_mix(one, 1, one, 1, 24, 64, 1, 0, 0, None) == mcf.MCF_ERR_ALIGN
+    assert L.mcf_stream_mix(one, 1, one, 1, 64, 64, 1, 0, 3, None) == mcf.MCF_ERR_VARIANT      # unknown store policy
     odd = (vp * 1)(FAKE + 8)
-    assert L.mcf_stream_mix(odd, 1, one, 1, 64, 64, 1, 0, None) == mcf.MCF_ERR_ALIGN
+    assert L.mcf_stream_mix(odd, 1, one, 1, 64, 64, 1, 0, 0, None) == mcf.MCF_ERR_ALIGN
     assert L.mcf_edq_noalloc(0, FAKE, FAKE, None, FAKE, None, (1 << 28) + 1, None, FAKE) == mcf.MCF_ERR_SIZE
     assert L.mcf_edq_noalloc(0, FAKE, FAKE, None, FAKE, None, 16, None, None) == mcf.MCF_ERR_NULL
     assert L.mcf_edq_noalloc(7, FAKE, FAKE, None, FAKE, None, 16, None, FAKE) == mcf.MCF_ERR_VARIANT

@@ -597,14 +597,14 @@ def test_launch_pacing_changes_time_only():
     nb = wl.total // 8 * 8
     before = {k: getattr(wl, k).clone() for k in wl.state_names()}
     rd = [getattr(wl, k)[:nb] for k in ("theta", "dtheta", "m", "v", "dv", "grad")]
-    for threads, vec, cap in ((64, 1, 10), (256, 4, 0), (64, 2, 3)):
-        mcf.stream_mix(rd, rd[:5], 2 * nb, threads, vec, cap)
-        mcf.stream_mix(rd[:5], rd[:4], 2 * nb, threads, vec, cap)
+    for threads, vec, cap, store in ((64, 1, 10, 0), (256, 4, 0, 1), (64, 2, 3, 2)):
+        mcf.stream_mix(rd, rd[:5], 2 * nb, threads, vec, cap, store)
+        mcf.stream_mix(rd[:5], rd[:4], 2 * nb, threads, vec, cap, store)
     torch.cuda.synchronize()
     for k in wl.state_names():
         assert torch.equal(getattr(wl, k), before[k]), k
     dst = torch.zeros_like(wl.theta)
-    mcf.stream_mix([wl.theta[:nb]], [dst[:nb]], 2 * nb, 256, 2, 0)              # with distinct buffers it is a copy
+    mcf.stream_mix([wl.theta[:nb]], [dst[:nb]], 2 * nb, 256, 2, 0, 1)           # with distinct buffers it is a copy
     assert torch.equal(dst[:nb], wl.theta[:nb])
     wl.close()
 
