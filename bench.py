@@ -239,8 +239,8 @@ def main():
             # (c) the step's own mix of streams with no arithmetic: 5 arenas read, 4 of them written back in place
             rd = [st[k][:nb] for k in ("theta", "dtheta", "m", "v", "grad")]
             mix_tried = {}
-            for threads, vec, cap, store in ((64, 1, 6, 0), (64, 1, 10, 0), (64, 1, 0, 0), (256, 2, 0, 0), (64, 1, 5, 1), (64, 1, 6, 1), (64, 1, 7, 1),
-                                             (64, 1, 8, 1), (64, 1, 10, 1), (64, 1, 6, 2), (64, 1, 8, 2), (64, 2, 4, 1), (256, 1, 1, 1), (256, 1, 2, 1)):
+            for threads, vec, cap, store in ((64, 1, 6, 0), (64, 1, 10, 0), (64, 1, 0, 0), (256, 2, 0, 0), (64, 1, 8, 1), (64, 1, 10, 1), (64, 1, 11, 1),
+                                             (64, 1, 12, 1), (64, 1, 14, 1), (64, 1, 16, 1), (64, 1, 10, 2), (64, 1, 12, 2), (64, 2, 6, 1), (256, 1, 3, 1)):
                 _, s = time_steps(lambda t: mcf.stream_mix(rd, rd[:4], 2 * nb, threads, vec, cap, store), 5, 2)
                 mix_tried[tag(threads, vec, cap, store)] = round(18 * nb * 5 / s / 1e9, 1)
             extras["stream_5r4w_shapes_GBps"] = mix_tried

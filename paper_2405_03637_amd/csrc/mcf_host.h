@@ -190,7 +190,7 @@ inline bool derive_scalars(const mcf_hyper &h, uint64_t step, mcfd::StepScalars 
   s.e = bf16_to_f32(b.v[K_EPS]);
   s.lam = bf16_to_f32(b.v[K_LAM]);
   s.na = bf16_to_f32(b.v[K_NA]);
-  s.eps_inside_sqrt = s.elementwise = s.head_sleep = s.tail_sleep = 0;
+  s.eps_inside_sqrt = s.elementwise = s.head_sleep = s.tail_sleep = s.write_through = 0;
   auto sane_bc = [](float x) { return x >= 0x1p-60f && x <= 1.0f; };
   const bool eps_ok = (s.e == 0.0f) || (s.e >= 0x1p-100f && s.e <= 0x1p60f);
   return sane_bc(s.bc1) && sane_bc(s.bc2) && eps_ok;
@@ -212,7 +212,7 @@ inline void derive_scalars_fp16(const mcf_hyper &h, uint64_t step, mcfd::StepSca
   s.e = splat(b.v[K_EPS]);
   s.lam = splat(b.v[K_LAM]);
   s.na = splat(b.v[K_NA]);
-  s.eps_inside_sqrt = s.elementwise = s.head_sleep = s.tail_sleep = 0;
+  s.eps_inside_sqrt = s.elementwise = s.head_sleep = s.tail_sleep = s.write_through = 0;
 }
 
 // FP8 scalars as fp16 values (every FP8 number is one; infinities and NaN carry over: a scalar that
@@ -252,7 +252,7 @@ inline bool derive_scalars_fp8(const mcf_hyper &h, uint64_t step, bool e4m3, mcf
   s.e = splat(b.v[K_EPS]);
   s.lam = splat(b.v[K_LAM]);
   s.na = splat(b.v[K_NA]);
-  s.eps_inside_sqrt = s.elementwise = s.head_sleep = s.tail_sleep = 0;
+  s.eps_inside_sqrt = s.elementwise = s.head_sleep = s.tail_sleep = s.write_through = 0;
   return ok;
 }
 

@@ -168,7 +168,12 @@ __device__ __forceinline__ void load_vec(uint64_t p, uint64_t off, uint32_t (&w)
 // ST_AGENT_NT (light 18.70 against 19.23 with ST_AGENT), the ALU-bound FP8 kernels ST_NT (9.80 against 9.99).  In an
 // arithmetic-free 5-read/4-write probe every combination of sc0, sc1 and nt on the loads leaves the rate where it is;
 // on the stores, any with sc1 gives 6.81-6.83 TB/s against 6.63 for nt alone and 5.7-6.3 for none or sc0.
+// That holds where the streams are far larger than the caches.  At small sets the write-through costs: the 64Mi stress
+// set (128 MB per stream) takes 0.261 ms with ST_AGENT against 0.241 with ST_NT, the 125M set is level (0.418 / 0.423),
+// the 1.3B set (2.6 GB per stream) gains 2.4% like the 7B set.  So the host picks per launch: write-through policies
+// from kWriteThroughBytes per stream on, ST_NT below.
 enum StorePolicy { ST_NT = 0, ST_AGENT = 1, ST_AGENT_NT = 2, ST_PLAIN = 3 };
+constexpr uint64_t kWriteThroughBytes = 512ull << 20;
 #ifndef MCF_STORE_POLICY
 #define MCF_STORE_POLICY -1          // -1: per kernel (see finish_chunk); else one StorePolicy for every step kernel
 #endif
@@ -543,7 +548,8 @@ __device__ __forceinline__ void finish_chunk(ChunkIn<VARIANT> &c, const typename
   using First = typename SS::template Hot<FAST>;
   using Second = typename SS::template Second<FAST>;
   const TensorDesc &d = c.d;
-  // ALU-bound FP8 kernels: non-temporal; with the EDQ sums fused in: agent scope and non-temporal; else agent scope
+  // Large sets (sc.write_through): agent scope; with the EDQ sums fused in: agent scope and non-temporal; the
+  // ALU-bound FP8 kernels and small sets: non-temporal
   constexpr int kStore = MCF_STORE_POLICY >= 0 ? MCF_STORE_POLICY : SS::kEB == 1 ? ST_NT : EDQ ? ST_AGENT_NT : ST_AGENT;
   const bool skip_first = sc.elementwise != 0;       // uniform over the launch
   static_for<0, kUnroll>([&](auto jc) {
@@ -562,11 +568,19 @@ __device__ __forceinline__ void finish_chunk(ChunkIn<VARIANT> &c, const typename
       }
       if (slot.full) {
         const uint64_t e0 = (slot.c0 - d.phase) * SS::kEB;
-        store_vec<kStore>(d.p[S_TH], e0, out[S_TH]);
-        if (SS::kDth) store_vec<kStore>(d.p[S_DTH], e0, out[S_DTH]);
-        store_vec<kStore>(d.p[S_M], e0, out[S_M]);
-        if (SS::kV) store_vec<kStore>(d.p[S_V], e0, out[S_V]);
-        if (SS::kDv) store_vec<kStore>(d.p[S_DV], e0, out[S_DV]);
+        if (kStore != ST_NT && sc.write_through) {          // uniform over the launch
+          store_vec<kStore>(d.p[S_TH], e0, out[S_TH]);
+          if (SS::kDth) store_vec<kStore>(d.p[S_DTH], e0, out[S_DTH]);
+          store_vec<kStore>(d.p[S_M], e0, out[S_M]);
+          if (SS::kV) store_vec<kStore>(d.p[S_V], e0, out[S_V]);
+          if (SS::kDv) store_vec<kStore>(d.p[S_DV], e0, out[S_DV]);
+        } else {
+          store_vec<ST_NT>(d.p[S_TH], e0, out[S_TH]);
+          if (SS::kDth) store_vec<ST_NT>(d.p[S_DTH], e0, out[S_DTH]);
+          store_vec<ST_NT>(d.p[S_M], e0, out[S_M]);
+          if (SS::kV) store_vec<ST_NT>(d.p[S_V], e0, out[S_V]);
+          if (SS::kDv) store_vec<ST_NT>(d.p[S_DV], e0, out[S_DV]);
+        }
       } else {
         store_slot<SS::kEB>(d.p[S_TH], d, slot, out[S_TH]);
         if (SS::kDth) store_slot<SS::kEB>(d.p[S_DTH], d, slot, out[S_DTH]);
@@ -917,7 +931,7 @@ struct Fp32Desc {
 };
 static_assert(sizeof(Fp32Desc) == 64, "descriptor is one 64-byte scalar load");
 
-struct Fp32Scalars { float b1, c1, b2, c2, bc1, bc2, e, lam, na; };
+struct Fp32Scalars { float b1, c1, b2, c2, bc1, bc2, e, lam, na; uint32_t write_through; };
 
 __device__ __forceinline__ void fp32mw_elem(float g, float &m, float &v, float &w, const Fp32Scalars &s) {
   const float t1 = s.b1 * m;
@@ -982,15 +996,20 @@ fp32mw_kernel(const Fp32Desc *__restrict__ descs, const Chunk *__restrict__ chun
       fp32mw_elem(g0.hi, m[1], v[1], w[1], sc);
       fp32mw_elem(g1.lo, m[2], v[2], w[2], sc);
       fp32mw_elem(g1.hi, m[3], v[3], w[3], sc);
-      store_f4<MCF_FP32MW_STORE>(mp + e0, f32x4_t{m[0], m[1], m[2], m[3]});
-      store_f4<MCF_FP32MW_STORE>(vp + e0, f32x4_t{v[0], v[1], v[2], v[3]});
-      store_f4<MCF_FP32MW_STORE>(master + e0, f32x4_t{w[0], w[1], w[2], w[3]});
       const u32x2_t tw = {mcfd::pack2(mcfd::Exact::round_f32(w[0], w[1])), mcfd::pack2(mcfd::Exact::round_f32(w[2], w[3]))};
       const uint64_t theta_at = (uint64_t)(theta + e0);
-      if (MCF_FP32MW_STORE == ST_AGENT) asm volatile("global_store_dwordx2 %0, %1, off sc1" : : "v"(theta_at), "v"(tw) : "memory");
-      else if (MCF_FP32MW_STORE == ST_AGENT_NT) asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" : : "v"(theta_at), "v"(tw) : "memory");
-      else if (MCF_FP32MW_STORE == ST_NT) __builtin_nontemporal_store(tw, (MCF_GLOBAL u32x2_t *)(theta + e0));
-      else *(MCF_GLOBAL u32x2_t *)(theta + e0) = tw;
+      if (MCF_FP32MW_STORE != ST_NT && sc.write_through) {       // uniform over the launch
+        store_f4<MCF_FP32MW_STORE>(mp + e0, f32x4_t{m[0], m[1], m[2], m[3]});
+        store_f4<MCF_FP32MW_STORE>(vp + e0, f32x4_t{v[0], v[1], v[2], v[3]});
+        store_f4<MCF_FP32MW_STORE>(master + e0, f32x4_t{w[0], w[1], w[2], w[3]});
+        if (MCF_FP32MW_STORE == ST_AGENT) asm volatile("global_store_dwordx2 %0, %1, off sc1" : : "v"(theta_at), "v"(tw) : "memory");
+        else asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" : : "v"(theta_at), "v"(tw) : "memory");
+      } else {
+        store_f4<ST_NT>(mp + e0, f32x4_t{m[0], m[1], m[2], m[3]});
+        store_f4<ST_NT>(vp + e0, f32x4_t{v[0], v[1], v[2], v[3]});
+        store_f4<ST_NT>(master + e0, f32x4_t{w[0], w[1], w[2], w[3]});
+        __builtin_nontemporal_store(tw, (MCF_GLOBAL u32x2_t *)(theta + e0));
+      }
     });
     return;
   }
@@ -1186,7 +1205,7 @@ bool force_exact() {
   return v;
 }
 
-HostScalars host_scalars(const mcf_hyper &h, uint64_t step, int variant) {
+HostScalars host_scalars(const mcf_hyper &h, uint64_t step, int variant, uint64_t n_params) {
   HostScalars hs = {};
   const int fmt = format_of(variant);
   if (fmt == MCF_COMPONENT_FP16) {
@@ -1199,6 +1218,8 @@ HostScalars host_scalars(const mcf_hyper &h, uint64_t step, int variant) {
     hs.fast = mcfh::derive_scalars(h, step, hs.bf) && !force_exact();
   }
   {
+    const uint32_t big = n_params * elem_bytes_of(fmt) >= kWriteThroughBytes ? 1u : 0u;
+    hs.bf.write_through = hs.hf.write_through = hs.f8.write_through = big;
     const int head = g_head_sleep.load(std::memory_order_relaxed), tail = g_tail_sleep.load(std::memory_order_relaxed);
     hs.bf.head_sleep = hs.hf.head_sleep = hs.f8.head_sleep = (uint32_t)(head > 0 ? head : 0);
     hs.bf.tail_sleep = hs.hf.tail_sleep = hs.f8.tail_sleep = (uint32_t)(tail > 0 ? tail : 0);
@@ -1378,6 +1399,7 @@ struct mcf_plan {
 
 struct mcf_fp32mw_plan {
   uint32_t n_chunks;
+  uint64_t n_params;
   Fp32Desc *d_descs;
   Chunk *d_chunks;
 };
@@ -1527,7 +1549,7 @@ int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *
   const int rc = mcfh::check_hyper(hyper, step);
   if (rc != MCF_OK) return rc;
   if (edq_dev && misaligned(edq_dev, 8)) return MCF_ERR_ALIGN;
-  const HostScalars hs = host_scalars(*hyper, step, plan->variant);
+  const HostScalars hs = host_scalars(*hyper, step, plan->variant, plan->n_params);
   hipStream_t st = (hipStream_t)stream;
   const TensorDesc none = {};
   if (plan->n_chunks) {
@@ -1580,7 +1602,7 @@ int mcf_adamw_step_flat(void *theta, void *dtheta, void *m, void *v, void *dv,
   TensorDesc d;
   fill_desc(t, variant, d);
   const uint64_t nch = (slots_of(d.n, d.phase, elem_bytes_of(format_of(variant))) + kSlotsPerChunk - 1) / kSlotsPerChunk;
-  const HostScalars hs = host_scalars(*hyper, step, variant);
+  const HostScalars hs = host_scalars(*hyper, step, variant, n);
   launch_variant<false>(variant, false, (uint32_t)nch, (hipStream_t)stream, nullptr, nullptr, d, hs, nullptr);
   MCF_HIP(hipGetLastError());
   return MCF_OK;
@@ -1805,6 +1827,8 @@ int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tenso
   mcf_fp32mw_plan *p = new (std::nothrow) mcf_fp32mw_plan();
   if (!p) return MCF_ERR_HIP;
   p->n_chunks = (uint32_t)chunks.size();
+  p->n_params = 0;
+  for (const Fp32Desc &d : descs) p->n_params += d.n;
   p->d_descs = nullptr;
   p->d_chunks = nullptr;
   if (p->n_chunks) {
@@ -1847,6 +1871,7 @@ int mcf_fp32mw_step(mcf_fp32mw_plan *plan, const mcf_hyper *hyper, uint64_t step
   s.e = (float)hyper->eps;
   s.lam = (float)hyper->weight_decay;
   s.na = (float)(-hyper->lr);
+  s.write_through = plan->n_params * 4 >= kWriteThroughBytes ? 1u : 0u;
   hipLaunchKernelGGL(fp32mw_kernel, dim3(plan->n_chunks), dim3(kStepBlock), step_lds(MCF_FP32MW_LDS), (hipStream_t)stream, plan->d_descs, plan->d_chunks, s);
   MCF_HIP(hipGetLastError());
   return MCF_OK;

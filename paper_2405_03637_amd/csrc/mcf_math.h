@@ -412,6 +412,7 @@ template <class S, class Rcp> struct StepScalarsT {
   uint32_t eps_inside_sqrt;      // 1: line 12's denominator is F(sqrt(F(v_hat + eps))), as Alg. 2 prints it
   uint32_t elementwise;          // 1: every slot of this launch goes straight to the second arithmetic mode
   uint32_t head_sleep, tail_sleep;   // launch pacing: s_sleep units a wave idles before its first load / after its last store
+  uint32_t write_through;        // 1: the set is far larger than the caches, and the kernel marks its stores to be written through
 };
 using StepScalars = StepScalarsT<float, float>;      // bf16
 using StepScalarsH = StepScalarsT<h2_t, float>;      // fp16
