@@ -219,7 +219,7 @@ inline void derive_scalars_fp16(const mcf_hyper &h, uint64_t step, mcfd::StepSca
 // left the format's range poisons the step exactly as it does in the definition), each copied into both
 // halves of a packed register, with the fp16 roundings of the reciprocals of the two bias corrections.
 // Returns false when one of those reciprocals is not an fp16 number (E5M2's +-2^-16): the first pass
-// multiplies by them, so such a step must take the element path.
+// multiplies by them, so such a step must take the second arithmetic pass (the caller sets `elementwise`).
 inline bool derive_scalars_fp8(const mcf_hyper &h, uint64_t step, bool e4m3, mcfd::StepScalarsF8 &s) {
   const ScalarBits b = e4m3 ? scalar_bits_e4m3(h, step) : scalar_bits_e5m2(h, step);
   auto half_bits = [e4m3](uint16_t x) -> uint16_t {

@@ -396,7 +396,7 @@ template <int VARIANT> struct StepStreams {
   // kernel timed in one process on the same arenas (two processes differ by more than two neighbouring caps
   // do: where the allocator puts 80 GB matters at the 1-3% level).  ms per step, best cap first, with the store
   // policy each kernel uses (see StorePolicy):
-  //   light 11: 17.94 (10: 18.27, 12: 18.68, 9: 18.96)       Kahan 11: 18.02 (10: 18.10, 12: 18.68)
+  //   light 11: 17.96 (10: 18.27, 12: 18.71, 9: 18.95)       Kahan 10: 18.11 (11: 18.22, 9: 18.69, 12: 18.73)
   //   plus  10: 22.34 (9: 22.88, 11: 23.02, 12: 23.54)       plus, fp16 components 10: 22.14 (9: 22.35, 11: 23.10)
   //   plain bf16 12: 14.05 (13: 14.36, 11: 14.50)            SGD 12: 13.82 (11: 14.10, 13: 14.44)
   //   light on TwoSum 12: 18.04 (11: 18.21, 10: 18.69)       plus on TwoSum 12: 23.29 (11: 23.38, 13: 23.48)
@@ -404,7 +404,7 @@ template <int VARIANT> struct StepStreams {
   // The plain variant and SGD have less memory time per wave to hide their divide and root behind and take
   // more waves.  The optimum moves with a kernel's instruction schedule, so the table is re-measured when the
   // arithmetic or the kernel's structure changes (mcf_set_launch_pacing does that without rebuilding).
-  // With the fp64 EDQ sums fused in there is more arithmetic per wave: light 13: 18.70 (16: 18.73, 12: 19.30);
+  // With the fp64 EDQ sums fused in there is more arithmetic per wave: light 16: 18.65 (13-14: 18.82, 12: 19.40, 18: 19.21);
   // plus 16: 23.40 (14: 23.44, 13: 23.46); Kahan 13: 18.40; plain bf16 18: 14.34 (16: 14.65); SGD 16: 14.22
   // (18: 14.29, 14: 14.67); light on TwoSum 16-18: 19.35; plus on TwoSum 20: 25.42 (18: 25.60); light with fp16
   // components 16: 19.37; plus with fp16 components 14: 23.05.
@@ -414,12 +414,11 @@ template <int VARIANT> struct StepStreams {
 #ifdef MCF_STEP_LDS
   static constexpr uint32_t kLds = MCF_STEP_LDS;
 #else
-  static constexpr int kGroups = (kBase == mcfd::V_BF16 || kBase == mcfd::V_SGD || kGrow2) ? 12 : kBase == mcfd::V_PLUS ? 10 : 11;
+  static constexpr int kGroups = (kBase == mcfd::V_BF16 || kBase == mcfd::V_SGD || kGrow2) ? 12 : (kBase == mcfd::V_PLUS || kBase == mcfd::V_KAHAN) ? 10 : 11;
   static constexpr uint32_t kLds = (kEB == 1 || MCF_PERSIST == 1) ? 0 : lds_for_groups(kGroups);
 #endif
   static constexpr int kEdqGroups = kBase == mcfd::V_BF16 ? 18 : kBase == mcfd::V_KAHAN ? 13
-                                    : kBase == mcfd::V_PLUS ? (kGrow2 ? 20 : kBf16 ? 16 : 14)
-                                    : kBase == mcfd::V_LIGHT && kBf16 && !kGrow2 ? 13 : 16;
+                                    : kBase == mcfd::V_PLUS ? (kGrow2 ? 20 : kBf16 ? 16 : 14) : 16;
   static constexpr uint32_t kLdsEdq = MCF_STEP_LDS_EDQ ? MCF_STEP_LDS_EDQ : (kEB == 1 || MCF_PERSIST == 1) ? 0 : lds_for_groups(kEdqGroups);
 };
 
@@ -1224,7 +1223,7 @@ HostScalars host_scalars(const mcf_hyper &h, uint64_t step, int variant, uint64_
     hs.bf.head_sleep = hs.hf.head_sleep = hs.f8.head_sleep = (uint32_t)(head > 0 ? head : 0);
     hs.bf.tail_sleep = hs.hf.tail_sleep = hs.f8.tail_sleep = (uint32_t)(tail > 0 ? tail : 0);
   }
-  // the printed form of line 12 is compiled into the element path only (SGD has no such line)
+  // the printed form of line 12 is compiled into the second arithmetic pass only (SGD has no such line)
   if ((variant & MCF_EPS_INSIDE_SQRT) && (variant & 0xff) != MCF_SGD) {
     hs.bf.eps_inside_sqrt = hs.hf.eps_inside_sqrt = hs.f8.eps_inside_sqrt = 1u;
     hs.bf.elementwise = hs.hf.elementwise = hs.f8.elementwise = 1u;
@@ -1420,11 +1419,17 @@ const char *mcf_status_string(int status) {
   }
 }
 
+// The host-side tables are std::vectors: a failed allocation there must not leave through the C boundary.
+#define MCF_NO_THROW_BEGIN try {
+#define MCF_NO_THROW_END(cleanup) } catch (...) { cleanup; return MCF_ERR_HIP; }
+
 int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, int variant) {
   if (!out) return MCF_ERR_NULL;
   *out = nullptr;
   if (count && !tensors) return MCF_ERR_NULL;
   if (!known_variant(variant)) return MCF_ERR_VARIANT;
+  mcf_plan *p = nullptr;
+  MCF_NO_THROW_BEGIN
   for (uint32_t i = 0; i < count; ++i) {
     const int rc = check_tensor(tensors[i], variant);
     if (rc != MCF_OK) return rc;
@@ -1444,7 +1449,7 @@ int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, i
     for (uint64_t c = 0; c < nch; ++c) chunks.push_back(Chunk{id, (uint32_t)(c * kSlotsPerChunk)});
     params += d.n;
   }
-  mcf_plan *p = new (std::nothrow) mcf_plan();
+  p = new (std::nothrow) mcf_plan();
   if (!p) return MCF_ERR_HIP;
   p->variant = variant;
   p->n_tensors = (uint32_t)descs.size();
@@ -1485,6 +1490,7 @@ int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, i
   }
   *out = p;
   return MCF_OK;
+  MCF_NO_THROW_END(mcf_plan_destroy(p))
 }
 
 int mcf_plan_destroy(mcf_plan *plan) {
@@ -1512,6 +1518,7 @@ int mcf_plan_update(mcf_plan *plan, const mcf_tensor *tensors, uint32_t count, v
   if (!plan) return MCF_ERR_NULL;
   if (count != plan->in_n.size()) return MCF_ERR_SIZE;
   if (count && !tensors) return MCF_ERR_NULL;
+  MCF_NO_THROW_BEGIN
   std::vector<TensorDesc> descs;
   descs.reserve(plan->phases.size());
   for (uint32_t i = 0; i < count; ++i) {
@@ -1542,6 +1549,7 @@ int mcf_plan_update(mcf_plan *plan, const mcf_tensor *tensors, uint32_t count, v
   MCF_HIP(hipEventRecord(plan->staged[nxt], st));
   plan->cur = nxt;
   return MCF_OK;
+  MCF_NO_THROW_END((void)0)
 }
 
 int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *stream, double *edq_dev) {
@@ -1789,6 +1797,8 @@ int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tenso
   if (!out) return MCF_ERR_NULL;
   *out = nullptr;
   if (count && !tensors) return MCF_ERR_NULL;
+  mcf_fp32mw_plan *p = nullptr;
+  MCF_NO_THROW_BEGIN
   std::vector<Fp32Desc> descs;
   std::vector<Chunk> chunks;
   for (uint32_t i = 0; i < count; ++i) {
@@ -1824,7 +1834,7 @@ int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tenso
     descs.push_back(d);
     for (uint64_t c = 0; c < nch; ++c) chunks.push_back(Chunk{id, (uint32_t)(c * kSlotsPerChunk)});
   }
-  mcf_fp32mw_plan *p = new (std::nothrow) mcf_fp32mw_plan();
+  p = new (std::nothrow) mcf_fp32mw_plan();
   if (!p) return MCF_ERR_HIP;
   p->n_chunks = (uint32_t)chunks.size();
   p->n_params = 0;
@@ -1844,6 +1854,7 @@ int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tenso
   }
   *out = p;
   return MCF_OK;
+  MCF_NO_THROW_END(mcf_fp32mw_plan_destroy(p))
 }
 
 int mcf_fp32mw_plan_destroy(mcf_fp32mw_plan *plan) {

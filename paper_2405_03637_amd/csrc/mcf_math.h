@@ -269,7 +269,7 @@ using HalfCold = Hf<false>;
 // within two units in the last place of 1/b, and on the GPU for all of them.
 // Quotient by a scalar b: one packed fp16 multiplication by RN16(1/b), then the conversion: right for
 // every a and b (checked the same way) except E5M2's b = +-2^-16, whose reciprocal is not an fp16 number; the
-// host sends such a step to the element path, whose mode divides by b as above.
+// host sends such a step straight to the second arithmetic pass, whose mode divides by b as above.
 // Root: v_sqrt_f32, then one conversion from fp32 (a root of a 3- or 4-bit number is either exact or
 // further than 2^-12 from any boundary; checked on every input).
 // NaN: as for fp16, the first pass detects, the redo stores the format's one NaN (0x7E, 0x7F).
@@ -430,7 +430,7 @@ enum : int { V_LIGHT = 0, V_PLUS = 1, V_BF16 = 2, V_KAHAN = 3, V_SGD = 4 };
 
 // Alg. 2 lines 8-13 on one pair.  GROW2 builds every Grow on TwoSum, EPS_INSIDE puts epsilon under the root.  On return io holds the new theta, dtheta, m, v (and dv);
 // delta receives line 12's update.  redo is raised (modes with kFast) when this pair must be
-// recomputed element by element.
+// recomputed in the second-pass mode.
 template <class M, int VARIANT, bool GROW2 = false, bool EPS_INSIDE = false>
 __device__ __forceinline__ void adamw_pair(ElemIOT<typename M::T> &io, const StepScalarsT<typename M::S, typename M::Rcp> &s,
                                            typename M::T &delta, bool &redo) {
