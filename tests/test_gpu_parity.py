@@ -657,6 +657,35 @@ def test_fp32_master_baseline():
     plan.destroy()
 
 
+def test_fp32_master_baseline_large_set():
+    """The baseline over a set large enough (4 bytes x parameters >= 512 MiB) for the library to switch its stores to
+    the write-through policy it uses on multi-gigabyte sets: two steps, every element of all four tensors."""
+    shapes = [("big", (1 << 27) + 1003), ("b", 77), ("c", 12_345)]
+    offs, total = W.layout(shapes)
+    th = torch.zeros(total, dtype=torch.bfloat16, device=DEV)
+    W.init_theta("flat_1m", shapes, offs, th)
+    master = th.float()
+    m = torch.zeros(total, dtype=torch.float32, device=DEV)
+    v = torch.zeros_like(m)
+    g = torch.zeros_like(th)
+    plan = mcf.Fp32MwPlan([(th[o:o + n], master[o:o + n], m[o:o + n], v[o:o + n], g[o:o + n]) for (_, n), o in zip(shapes, offs)])
+    h_th, h_w, h_m, h_v = H.torch_to_u16(th), master.cpu().numpy().copy(), m.cpu().numpy().copy(), v.cpu().numpy().copy()
+    for t in (1, 2):
+        W.fill_grads("flat_1m", shapes, offs, g, t)
+        orc.fp32mw_step(h_th, h_w, h_m, h_v, H.torch_to_u16(g), W.HYPER_LIGHT, t)
+        plan.step(W.HYPER_LIGHT, t)
+        _say(f"fp32-master baseline, {total} elements: step {t} done")
+    live = np.zeros(total, bool)
+    for (_, n), o in zip(shapes, offs):
+        live[o:o + n] = True
+    for name, host, dev in (("master", h_w, master), ("m", h_m, m), ("v", h_v, v)):
+        d = dev.cpu().numpy()
+        assert np.array_equal(d.view(np.uint32)[live], host.view(np.uint32)[live]), name
+    assert np.array_equal(H.torch_to_u16(th)[live], h_th[live])
+    assert np.count_nonzero(h_m[live]) > 0.99 * live.sum()
+    plan.destroy()
+
+
 # ------------------------------------------------------------------ the paper-shaped configurations
 def _sampled_steps(wl, so, first, last, check_at, on_grads=None):
     """Steps first..last of the library with the oracle following the sampled elements."""
