@@ -127,7 +127,9 @@ typedef struct mcf_plan mcf_plan;
  * them, however many and however small.  `tensors` is a host array of `count` entries,
  * copied; the device buffers it names must stay valid while the plan is used.  Tensors
  * with n == 0 are allowed and skipped; count == 0 gives a plan whose step does nothing.
- * Allocates device memory for the table (MCF_ERR_HIP if that fails). */
+ * Allocates device memory for the table (MCF_ERR_HIP if that fails) on the device that is current
+ * during the call; the plan belongs to that device, and mcf_plan_update and mcf_adamw_step return
+ * MCF_ERR_HIP, launching nothing, when another device is current. */
 int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, int variant);
 int mcf_plan_destroy(mcf_plan *plan);      /* NULL is accepted */
 /* Number of parameters the plan covers (0 for NULL). */
@@ -248,6 +250,7 @@ typedef struct {
   uint64_t n;
 } mcf_fp32mw_tensor;
 typedef struct mcf_fp32mw_plan mcf_fp32mw_plan;
+/* Plans of the baseline belong to the device current at creation, like mcf_plan. */
 int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tensors, uint32_t count);
 int mcf_fp32mw_plan_destroy(mcf_fp32mw_plan *plan);
 int mcf_fp32mw_step(mcf_fp32mw_plan *plan, const mcf_hyper *hyper, uint64_t step, void *stream);

@@ -1377,6 +1377,7 @@ int scratch_of_current_device(double **out) {
 }  // namespace
 
 struct mcf_plan {
+  int device;           // the device that was current at creation: its tables live there
   int variant;
   uint32_t n_tensors;
   uint32_t n_chunks;
@@ -1397,11 +1398,22 @@ struct mcf_plan {
 };
 
 struct mcf_fp32mw_plan {
+  int device;
   uint32_t n_chunks;
   uint64_t n_params;
   Fp32Desc *d_descs;
   Chunk *d_chunks;
 };
+
+namespace {
+// A plan's tables are memory of one device; a step launched with another device current would hand its kernel
+// pointers that device cannot reach.
+int on_plan_device(int plan_device) {
+  int dev = -1;
+  MCF_HIP(hipGetDevice(&dev));
+  return dev == plan_device ? MCF_OK : MCF_ERR_HIP;
+}
+}  // namespace
 
 extern "C" {
 
@@ -1451,6 +1463,7 @@ int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, i
   }
   p = new (std::nothrow) mcf_plan();
   if (!p) return MCF_ERR_HIP;
+  p->device = -1;
   p->variant = variant;
   p->n_tensors = (uint32_t)descs.size();
   p->n_chunks = (uint32_t)chunks.size();
@@ -1465,6 +1478,11 @@ int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, i
   for (size_t i = 0; i < descs.size(); ++i) p->phases[i] = descs[i].phase;
   p->in_n.resize(count);
   for (uint32_t i = 0; i < count; ++i) p->in_n[i] = tensors[i].n;
+  if (p->n_chunks && hipGetDevice(&p->device) != hipSuccess) {       // an empty plan owns nothing on any device
+    (void)hipGetLastError();
+    mcf_plan_destroy(p);
+    return MCF_ERR_HIP;
+  }
   if (p->n_chunks) {
     const size_t table = descs.size() * sizeof(TensorDesc);
     bool ok = hipMalloc((void **)&p->d_descs[0], 2 * table) == hipSuccess &&
@@ -1533,6 +1551,8 @@ int mcf_plan_update(mcf_plan *plan, const mcf_tensor *tensors, uint32_t count, v
     descs.push_back(d);
   }
   if (descs.empty()) return MCF_OK;
+  const int where = on_plan_device(plan->device);
+  if (where != MCF_OK) return where;
   hipStream_t st = (hipStream_t)stream;
   // A captured copy would read the pinned block again at every replay, whatever it holds by then.
   hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
@@ -1557,6 +1577,8 @@ int mcf_adamw_step(mcf_plan *plan, const mcf_hyper *hyper, uint64_t step, void *
   const int rc = mcfh::check_hyper(hyper, step);
   if (rc != MCF_OK) return rc;
   if (edq_dev && misaligned(edq_dev, 8)) return MCF_ERR_ALIGN;
+  const int where = plan->n_chunks ? on_plan_device(plan->device) : MCF_OK;
+  if (where != MCF_OK) return where;
   const HostScalars hs = host_scalars(*hyper, step, plan->variant, plan->n_params);
   hipStream_t st = (hipStream_t)stream;
   const TensorDesc none = {};
@@ -1836,6 +1858,14 @@ int mcf_fp32mw_plan_create(mcf_fp32mw_plan **out, const mcf_fp32mw_tensor *tenso
   }
   p = new (std::nothrow) mcf_fp32mw_plan();
   if (!p) return MCF_ERR_HIP;
+  p->d_descs = nullptr;
+  p->d_chunks = nullptr;
+  p->device = -1;
+  if (!chunks.empty() && hipGetDevice(&p->device) != hipSuccess) {
+    (void)hipGetLastError();
+    mcf_fp32mw_plan_destroy(p);
+    return MCF_ERR_HIP;
+  }
   p->n_chunks = (uint32_t)chunks.size();
   p->n_params = 0;
   for (const Fp32Desc &d : descs) p->n_params += d.n;
@@ -1871,6 +1901,8 @@ int mcf_fp32mw_step(mcf_fp32mw_plan *plan, const mcf_hyper *hyper, uint64_t step
   const int rc = mcfh::check_hyper(hyper, step);
   if (rc != MCF_OK) return rc;
   if (!plan->n_chunks) return MCF_OK;
+  const int where = on_plan_device(plan->device);
+  if (where != MCF_OK) return where;
   const double t = (double)step;
   Fp32Scalars s;
   s.b1 = (float)hyper->beta1;
