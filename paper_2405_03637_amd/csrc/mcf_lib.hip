@@ -1096,6 +1096,37 @@ void fill_desc(const mcf_tensor &t, int variant, TensorDesc &d) {
   phase_of(d.p, 6, d.phase, d.skewed, MCF_CHUNK_ALIGN, eb);
 }
 
+// Order of the chunk table.  A chunk that holds a slot straddling one of its tensor's ends gathers that slot element
+// by element and sends it through the second arithmetic pass: its wave lives several times as long as a wave of
+// whole slots and moves fewer bytes.  A set with thousands of tiny tensors hands the dispatcher long runs of such
+// chunks, and while they fill the CUs little memory traffic flows.  So they are dealt out evenly among the other
+// chunks (which keep their order, and with it the neighbourhood of the addresses in flight), leaving the last
+// eighth of the table to whole chunks so that the launch does not end on a slow wave.  Chunks are independent:
+// the order changes when a chunk runs, never what it computes.
+#ifndef MCF_SPREAD_RAGGED
+#define MCF_SPREAD_RAGGED 1
+#endif
+void spread_ragged_chunks(std::vector<Chunk> &chunks, const std::vector<TensorDesc> &descs, uint32_t elem_bytes) {
+  if (!MCF_SPREAD_RAGGED) return;
+  const uint64_t eps = 16 / elem_bytes;
+  auto ragged = [&](const Chunk &c) {
+    const TensorDesc &d = descs[c.tensor];
+    const uint64_t first = (uint64_t)c.slot0 * eps, last = first + (uint64_t)kSlotsPerChunk * eps;      // elements from the boundary
+    const uint64_t end = d.n + d.phase;
+    return (first < d.phase && d.phase % eps != 0) || (end > first && end < last && end % eps != 0);
+  };
+  std::vector<Chunk> whole, rag;
+  for (const Chunk &c : chunks) (ragged(c) ? rag : whole).push_back(c);
+  if (rag.empty() || whole.size() < 8 * rag.size()) return;       // nothing to hide, or nothing to hide it behind
+  const size_t span = whole.size() - whole.size() / 8, n_rag = rag.size();
+  size_t r = 0, out = 0;
+  for (size_t w = 0; w < whole.size(); ++w) {
+    while (r < n_rag && r * span / n_rag <= w) chunks[out++] = rag[r++];
+    chunks[out++] = whole[w];
+  }
+  while (r < n_rag) chunks[out++] = rag[r++];
+}
+
 // Scalars of one step for both formats; fast = the bf16 Fast mode may be used with them.
 struct HostScalars {
   StepScalars bf;
@@ -1461,6 +1492,7 @@ int mcf_plan_create(mcf_plan **out, const mcf_tensor *tensors, uint32_t count, i
     for (uint64_t c = 0; c < nch; ++c) chunks.push_back(Chunk{id, (uint32_t)(c * kSlotsPerChunk)});
     params += d.n;
   }
+  spread_ragged_chunks(chunks, descs, elem_bytes_of(format_of(variant)));
   p = new (std::nothrow) mcf_plan();
   if (!p) return MCF_ERR_HIP;
   p->device = -1;
