@@ -1115,9 +1115,13 @@ void spread_ragged_chunks(std::vector<Chunk> &chunks, const std::vector<TensorDe
     const uint64_t end = d.n + d.phase;
     return (first < d.phase && d.phase % eps != 0) || (end > first && end < last && end % eps != 0);
   };
+  size_t count = 0;
+  for (const Chunk &c : chunks) count += ragged(c) ? 1 : 0;
+  if (count == 0 || chunks.size() - count < 8 * count) return;    // nothing to hide, or nothing to hide it behind
   std::vector<Chunk> whole, rag;
+  whole.reserve(chunks.size() - count);
+  rag.reserve(count);
   for (const Chunk &c : chunks) (ragged(c) ? rag : whole).push_back(c);
-  if (rag.empty() || whole.size() < 8 * rag.size()) return;       // nothing to hide, or nothing to hide it behind
   const size_t span = whole.size() - whole.size() / 8, n_rag = rag.size();
   size_t r = 0, out = 0;
   for (size_t w = 0; w < whole.size(); ++w) {
