@@ -245,7 +245,13 @@ def main():
                 mix_tried[tag(threads, vec, cap, store)] = round(18 * nb * 5 / s / 1e9, 1)
             extras["stream_5r4w_shapes_GBps"] = mix_tried
             extras["stream_5r4w_GBps"] = max(mix_tried.values())
-            del rd
+            # (d) the stand-alone EDQ reduction (Def. 3.3) over whole arenas: five streams read, 24 bytes per 2048 elements written
+            scratch = torch.empty(mcf.edq_scratch_bytes(nb) // 8, dtype=torch.float64, device=dev)
+            edq4 = torch.zeros(4, dtype=torch.float64, device=dev)
+            _, s = time_steps(lambda t: mcf.edq(rd[4], rd[0], rd[1], rd[2], rd[3], scratch, edq4), 5, 2)
+            extras["edq_standalone_GBps"] = 10 * nb * 5 / s / 1e9
+            extras["edq_standalone_ms"] = s / 5 * 1e3
+            del rd, scratch, edq4
             # the other strategies on the same shapes
             for other in ("plus", "light", "kahan", "bf16", "sgd", "light+twosum", "plus+twosum", "light+fp16", "plus+fp16",
                           "light+e5m2", "plus+e5m2", "light+e4m3"):
