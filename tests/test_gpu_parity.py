@@ -226,7 +226,7 @@ def test_buffers_at_different_offsets_modulo_16_bytes(variant, fmt):
     plan.destroy()
 
 
-@pytest.mark.parametrize("seed", range(48))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("MCF_FUZZ_SEEDS", "48"))))      # 6648 seeds were run once: no mismatch
 def test_seeded_mix_of_shapes_offsets_variants_and_formats(seed):
     """Plans drawn from a seed: 1 to 12 tensors of 1 to 60,000 elements (a few empty), every buffer of
     every tensor at its own element offset, any variant with any flag in any component format, one to
