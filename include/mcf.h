@@ -39,7 +39,8 @@
  *   - bf16 and fp16 buffers need 2-byte alignment (FP8 buffers none), fp32 buffers 4-byte, double
  *     buffers 8-byte (else MCF_ERR_ALIGN).  Any such alignment is accepted.  The step
  *     and the primitives use 128-bit accesses cut on the first buffer's (theta's) 16-byte grid:
- *     fastest when all buffers of one tensor share the same offset modulo 16 bytes; a
+ *     fastest when all buffers of one tensor share the same offset modulo 16 bytes (modulo 1 KiB
+ *     for the last 2-4%: buffers shifted against each other by 128 to 512 bytes measured slower); a
  *     buffer at another offset is accessed unaligned, which the hardware splits (the fp32-master
  *     baseline goes element by element instead when its buffers are not mutually aligned).
  *   - Updates are in place.  Buffers of different roles or tensors must not
